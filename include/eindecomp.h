@@ -1,0 +1,224 @@
+/*
+ * eindecomp.h - C ABI of the MI355X tensor-relational einsum executor.
+ *
+ * The library runs an already-decomposed graph of extended Einstein-summation
+ * vertices (arxiv 2410.02682) on one GPU.  Per vertex it follows the rewrite of
+ * Section 4.3 of the paper: the inputs are tensor relations (Section 4.1: keyed
+ * blocks fixed by a bound vector b and a partitioning vector d); a join matches
+ * blocks whose keys agree on shared labels and runs the per-block kernel K on
+ * every matched pair; an aggregation reduces, with the vertex's (+), the partial
+ * blocks that belong to the same output key, in ascending order of the key over
+ * the aggregated labels.
+ *
+ * Conventions
+ *   - All functions return EG_OK (0) or a negative eg_status.  No exception
+ *     crosses the ABI; eg_last_error() gives a thread-local message for the
+ *     last failing call.
+ *   - "host" / "device" is stated for every pointer.  Device buffers and the HIP
+ *     stream always belong to the caller; the library never allocates, frees or
+ *     synchronises device memory.  Handles (eg_graph, eg_relation) own host
+ *     memory only and are released by their *_destroy call.
+ *   - All validation happens on the host before any launch: a failing call
+ *     leaves device memory untouched.
+ *   - Tensors are dense with element strides (row-major unless strides are
+ *     given).  A block of a relation is a strided view into that buffer, so
+ *     partitioning and repartitioning move no data.
+ *   - A partitioning vector is given per UNIQUE label of the vertex, in order of
+ *     first appearance over l_X then l_Y (the schema of the natural join,
+ *     Section 4.3): for "ij,jk->ik" the vector (2,2,2) is the paper's
+ *     d = [2,2,2,2] with the co-partitioning constraint of Section 6 applied.
+ *   - Tuple order (the paper leaves it open): row-major over I(d) on that
+ *     schema, last label fastest.  aggIdx is the row-major rank of the key
+ *     restricted to the aggregated labels; group is the rank of the key
+ *     restricted to l_Z (in l_Z order) within I(d_Z).
+ */
+#ifndef EINDECOMP_H
+#define EINDECOMP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EG_MAX_RANK 8      /* dimensions per tensor */
+#define EG_MAX_LABELS 12   /* unique labels per vertex */
+
+typedef enum {
+    EG_OK = 0,
+    EG_ERR_NULL = -1,            /* a required pointer is NULL */
+    EG_ERR_BAD_SPEC = -2,        /* spec string malformed, operand count mismatch */
+    EG_ERR_REPEATED_LABEL = -3,  /* a label occurs twice inside one operand (Section 3 excludes it) */
+    EG_ERR_BROADCAST = -4,       /* an output label occurs in no input (Section 3 excludes it) */
+    EG_ERR_BAD_BOUND = -5,       /* rank/bound mismatch, or a shared label with two different bounds */
+    EG_ERR_BAD_PARTITION = -6,   /* wrong length, entry < 1 */
+    EG_ERR_INDIVISIBLE = -7,     /* d[i] does not divide b[i] */
+    EG_ERR_DTYPE = -8,           /* unsupported dtype or dtype mismatch with a bound relation */
+    EG_ERR_WORKSPACE = -9,       /* workspace missing, misaligned or too small */
+    EG_ERR_BAD_VERTEX = -10,     /* vertex id out of range / not an einsum vertex / wrong binding count */
+    EG_ERR_BAD_OP = -11,         /* (x)/(+) combination not valid for this spec */
+    EG_ERR_HIP = -12,            /* a HIP runtime call failed */
+    EG_ERR_LIMIT = -13           /* exceeds EG_MAX_RANK / EG_MAX_LABELS / 32-bit tile grid limits */
+} eg_status;
+
+typedef enum { EG_F32 = 0, EG_BF16 = 1 } eg_dtype;
+
+/* (+): the aggregation operator; must be associative and commutative (Section 3). */
+typedef enum { EG_AGG_NONE = 0, EG_AGG_SUM = 1, EG_AGG_MAX = 2 } eg_agg;
+
+/* (x): the scalar function applied to joined values (Section 3).  alpha is the one scalar
+ * parameter a vertex carries.  Binary: */
+typedef enum {
+    EG_MUL = 0,        /* alpha * x * y      (with EG_AGG_SUM: a contraction)            */
+    EG_ADD = 1,        /* alpha * x + y      (scale then add: scaled scores + mask)      */
+    EG_SUB = 2,        /* alpha * (x - y)                                                */
+    EG_DIV = 3,        /* x / y                                                          */
+    EG_SQDIFF = 4,     /* (x - y)^2          (squared L2 distance, Section 3)            */
+    EG_ABSDIFF = 5,    /* |x - y|            (L-infinity distance with EG_AGG_MAX)       */
+    EG_EXP_SUB = 6,    /* exp(x - y)         (softmax numerator, Section 3)              */
+    EG_RELU_GRAD = 7,  /* x if y > 0 else 0                                              */
+    EG_SILU_MUL = 8,   /* x * sigmoid(x) * y                                             */
+    /* unary maps: */
+    EG_IDENT = 32,     /* x                                                              */
+    EG_SCALE = 33,     /* alpha * x                                                      */
+    EG_RELU = 34,      /* max(x, 0)                                                      */
+    EG_EXP = 35,       /* exp(x)                                                         */
+    EG_LOG = 36        /* log(x)                                                         */
+} eg_join;
+
+typedef struct eg_graph eg_graph;        /* an EinGraph annotated with partitioning vectors (Sections 5-6) */
+typedef struct eg_relation eg_relation;  /* a tensor relation: b, d, dtype and a borrowed device pointer   */
+
+/* Which device kernel family a vertex is routed to (reported by einsum_graph_plan). */
+typedef enum {
+    EG_KERNEL_NONE = 0,
+    EG_KERNEL_CONTRACT_MFMA = 1,   /* (x)=mul, (+)=sum as a strided batched matrix product on MFMA   */
+    EG_KERNEL_MAP = 2,             /* no aggregated label: elementwise map / binary join             */
+    EG_KERNEL_REDUCE_ROW = 3,      /* aggregated labels are the contiguous tail of X: wave reductions */
+    EG_KERNEL_GENERIC = 4          /* any EinSum: one output element per lane, loop over l_agg       */
+} eg_kernel_kind;
+
+/* Read-only view of one vertex's plan.  All pointers are host memory owned by the graph and stay
+ * valid until the vertex's partition changes or the graph is destroyed. */
+typedef struct {
+    int32_t n_labels;                    /* unique labels (schema of the join) */
+    char    labels[EG_MAX_LABELS];       /* their characters, schema order */
+    int64_t bound[EG_MAX_LABELS];        /* b per unique label */
+    int32_t d[EG_MAX_LABELS];            /* partitioning per unique label */
+    int32_t rank_x, rank_y, rank_z;      /* rank_y = 0 for a unary vertex */
+    int32_t d_x[EG_MAX_RANK], d_y[EG_MAX_RANK], d_z[EG_MAX_RANK];   /* d[l_X; l_XY] etc. (Section 4.3) */
+    int64_t bound_z[EG_MAX_RANK];        /* b_Z = b_XY[l_Z; l_XY] */
+    int64_t block_x[EG_MAX_RANK], block_y[EG_MAX_RANK], block_z[EG_MAX_RANK];  /* sub-tensor bounds b/d */
+    int64_t n_tuples;                    /* N = prod d over the schema (Section 6) */
+    int64_t n_agg;                       /* prod d over the aggregated labels (Section 7) */
+    int64_t n_groups;                    /* N / n_agg = number of output blocks */
+    int32_t kernel;                      /* eg_kernel_kind */
+    int32_t repart_x, repart_y;          /* 1 if the producer's d_Z differs from this vertex's d_X / d_Y (Section 5) */
+    /* per tuple, tuple-major, host: */
+    const int32_t *key;                  /* [n_tuples][n_labels] key over the schema */
+    const int32_t *key_x;                /* [n_tuples][rank_x] */
+    const int32_t *key_y;                /* [n_tuples][rank_y] */
+    const int32_t *key_z;                /* [n_tuples][rank_z] */
+    const int32_t *agg_idx;              /* [n_tuples] */
+    const int32_t *group;                /* [n_tuples] */
+    const int64_t *off_x;                /* [n_tuples] element offset of the X block in a dense row-major X */
+    const int64_t *off_y;                /* [n_tuples] likewise for Y (0 if unary) */
+    const int64_t *off_z;                /* [n_tuples] likewise for the Z block in a dense row-major Z */
+} eg_plan_view;
+
+/* ---- EinGraph construction (Section 5: one triple (bound, EinSum, inputs) per vertex) ------------------- */
+
+/* Creates an empty graph.  *g (host) receives the handle. */
+int einsum_graph_create(eg_graph **g);
+
+/* Adds a graph input (a vertex with empty EinSum and no inputs).  bound: host, `rank` entries, each >= 1.
+ * *vertex receives its id.  Vertex ids count up from 0 in insertion order, which is a topological order. */
+int einsum_graph_add_input(eg_graph *g, int rank, const int64_t *bound, eg_dtype dtype, int *vertex);
+
+/* Adds an EinSum vertex.  spec (host, NUL-terminated): "ij,jk->ik" (binary) or "ij->i" (unary); one
+ * character per label; "->" followed by nothing denotes a rank-0 output.  inputs (host): n_inputs (1 or 2)
+ * ids of earlier vertices, ordered as in the spec (the EinSum need not be commutative).  The output bound
+ * is deduced (b_Z = b_XY[l_Z; l_XY]).  oplus must be SUM or MAX when some input label is missing from the
+ * output and is ignored otherwise.  The partitioning defaults to all ones. */
+int einsum_graph_add_einsum(eg_graph *g, const char *spec, eg_join otimes, eg_agg oplus, double alpha,
+                            const int *inputs, int n_inputs, eg_dtype out_dtype, int *vertex);
+
+/* Annotates a vertex with its partitioning vector (Section 6), one entry per unique label in schema order.
+ * d: host.  Rejects entries < 1 (EG_ERR_BAD_PARTITION) and entries that do not divide the label's bound
+ * (EG_ERR_INDIVISIBLE; the paper only ever divides evenly). */
+int einsum_graph_set_partition(eg_graph *g, int vertex, const int32_t *d, int n_unique_labels);
+
+/* Marks a vertex as a graph output: tr_execute writes it into a caller-provided relation instead of the
+ * workspace.  Outputs are bound in the order they were marked. */
+int einsum_graph_mark_output(eg_graph *g, int vertex);
+
+/* Fills *out (host, caller-owned struct) with the vertex's plan tables; see eg_plan_view. */
+int einsum_graph_plan(eg_graph *g, int vertex, eg_plan_view *out);
+
+/* Number of vertices, or a negative status. */
+int einsum_graph_num_vertices(const eg_graph *g);
+
+void einsum_graph_destroy(eg_graph *g);
+
+/* ---- Tensor relations (Section 4.1) ---------------------------------------------------------------------- */
+
+/* Views the dense tensor at dev_ptr (device, borrowed) as the tensor relation with bound `bound` and
+ * partitioning `d` (host arrays, `rank` entries).  strides_or_null: element strides (host) or NULL for
+ * row-major.  No data moves: block <k> is the strided view starting at sum_i k[i]*(b[i]/d[i])*stride[i]. */
+int tensor_partition(void *dev_ptr, eg_dtype dtype, int rank, const int64_t *bound,
+                     const int64_t *strides_or_null, const int32_t *d, eg_relation **rel);
+
+/* Descriptor of block `key` (host, rank entries): element offset, block bound and strides (host outputs,
+ * rank entries each; any may be NULL). */
+int tensor_relation_block(const eg_relation *rel, const int32_t *key,
+                          int64_t *offset, int64_t *bound, int64_t *strides);
+
+/* Releases the handle; never touches the device buffer. */
+void tensor_relation_destroy(eg_relation *rel);
+
+/* ---- Execution (Sections 4.2-4.3, 5) ----------------------------------------------------------------------- */
+
+/* Bytes of device workspace tr_execute needs for the graph as currently annotated: fp32 partial slabs
+ * ([n_agg][dense Z] per vertex with a partitioned aggregated label) plus every intermediate vertex that
+ * is not a marked output, with buffers reused once their last consumer has run. */
+int tr_workspace_bytes(eg_graph *g, size_t *bytes);
+
+/* Runs every vertex in topological order on `hip_stream` (a hipStream_t, may be NULL for the default
+ * stream), asynchronously.  inputs: one relation per graph input in insertion order; outputs: one relation
+ * per marked output in marking order (both host arrays of handles).  Bounds and dtypes must match the
+ * graph's.  A relation whose d differs from what the consuming vertex needs is repartitioned (Section 5);
+ * with strided-view blocks that is a change of tables only.  workspace: device, 256-byte aligned, at least
+ * tr_workspace_bytes(). */
+int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs,
+               eg_relation *const *outputs, int n_outputs,
+               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* The aggregation operator of Section 4.2 on its own: out[e] = (+)_{a = 0 .. n_agg-1} partials[a][e],
+ * reduced sequentially in ascending a in fp32, then cast once to out's dtype.  partials: device,
+ * fp32, slab-major [n_agg][slab_elems] where a slab is the dense row-major tensor of out's bound.
+ * out may be strided.  oplus is SUM or MAX.  Also called inside tr_execute. */
+int tr_aggregate(eg_agg oplus, const void *partials, int64_t n_agg, int64_t slab_elems,
+                 eg_relation *out, void *hip_stream);
+
+/* ---- Timing of the launches inside tr_execute (for roofline reports) ----------------------------------- */
+
+/* When enabled, tr_execute brackets every kernel launch with HIP events on the given stream.  The events
+ * are created here (not in tr_execute). */
+int tr_profile_enable(eg_graph *g, int enable);
+
+/* After the stream has been synchronised by the caller: number of launches recorded by the last
+ * tr_execute, or a negative status. */
+int tr_profile_count(eg_graph *g);
+
+/* Launch i of the last tr_execute: its vertex, whether it was the join kernel (0) or the aggregation (1),
+ * its eg_kernel_kind and elapsed milliseconds.  Host outputs, any may be NULL. */
+int tr_profile_get(eg_graph *g, int i, int *vertex, int *stage, int *kernel, float *ms);
+
+/* Message for the last error on this thread (host, valid until the next failing call on the thread). */
+const char *eg_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EINDECOMP_H */

@@ -1,0 +1,77 @@
+"""Loads libeindecomp.so and declares the C ABI of include/eindecomp.h for ctypes.
+
+There is no fallback: if the library has not been built, importing the binding raises.
+"""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libeindecomp.so")
+
+EG_MAX_RANK = 8
+EG_MAX_LABELS = 12
+
+c_i32p = ctypes.POINTER(ctypes.c_int32)
+c_i64p = ctypes.POINTER(ctypes.c_int64)
+
+
+class PlanView(ctypes.Structure):
+    _fields_ = [
+        ("n_labels", ctypes.c_int32),
+        ("labels", ctypes.c_char * EG_MAX_LABELS),
+        ("bound", ctypes.c_int64 * EG_MAX_LABELS),
+        ("d", ctypes.c_int32 * EG_MAX_LABELS),
+        ("rank_x", ctypes.c_int32), ("rank_y", ctypes.c_int32), ("rank_z", ctypes.c_int32),
+        ("d_x", ctypes.c_int32 * EG_MAX_RANK), ("d_y", ctypes.c_int32 * EG_MAX_RANK), ("d_z", ctypes.c_int32 * EG_MAX_RANK),
+        ("bound_z", ctypes.c_int64 * EG_MAX_RANK),
+        ("block_x", ctypes.c_int64 * EG_MAX_RANK), ("block_y", ctypes.c_int64 * EG_MAX_RANK), ("block_z", ctypes.c_int64 * EG_MAX_RANK),
+        ("n_tuples", ctypes.c_int64), ("n_agg", ctypes.c_int64), ("n_groups", ctypes.c_int64),
+        ("kernel", ctypes.c_int32), ("repart_x", ctypes.c_int32), ("repart_y", ctypes.c_int32),
+        ("key", c_i32p), ("key_x", c_i32p), ("key_y", c_i32p), ("key_z", c_i32p),
+        ("agg_idx", c_i32p), ("group", c_i32p),
+        ("off_x", c_i64p), ("off_y", c_i64p), ("off_z", c_i64p),
+    ]
+
+
+EXPORTS = {
+    # name: (restype, argtypes)
+    "einsum_graph_create": (ctypes.c_int, [ctypes.POINTER(ctypes.c_void_p)]),
+    "einsum_graph_add_input": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, c_i64p, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]),
+    "einsum_graph_add_einsum": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_char_p, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                               ctypes.POINTER(ctypes.c_int), ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]),
+    "einsum_graph_set_partition": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, c_i32p, ctypes.c_int]),
+    "einsum_graph_mark_output": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int]),
+    "einsum_graph_plan": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(PlanView)]),
+    "einsum_graph_num_vertices": (ctypes.c_int, [ctypes.c_void_p]),
+    "einsum_graph_destroy": (None, [ctypes.c_void_p]),
+    "tensor_partition": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, c_i64p, c_i64p, c_i32p, ctypes.POINTER(ctypes.c_void_p)]),
+    "tensor_relation_block": (ctypes.c_int, [ctypes.c_void_p, c_i32p, c_i64p, c_i64p, c_i64p]),
+    "tensor_relation_destroy": (None, [ctypes.c_void_p]),
+    "tr_workspace_bytes": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_size_t)]),
+    "tr_execute": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
+                                  ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "tr_aggregate": (ctypes.c_int, [ctypes.c_int, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]),
+    "tr_profile_enable": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int]),
+    "tr_profile_count": (ctypes.c_int, [ctypes.c_void_p]),
+    "tr_profile_get": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int),
+                                      ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]),
+    "eg_last_error": (ctypes.c_char_p, []),
+}
+
+_lib = None
+
+
+def load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                f"{LIB_PATH} is missing: build it first (python -m paper_2410_02682_amd.build, or "
+                "__graft_entry__.build()).  There is no CPU fallback.")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(lib, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = lib
+    return _lib

@@ -1,0 +1,116 @@
+// Device helpers shared by the kernels: dtype conversion, the scalar functions (x), tuple decoding.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "eg_internal.h"
+
+namespace eg {
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// fp32 -> bf16, round to nearest, ties to even; infinities pass through, NaN stays NaN.
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7f800000u) == 0x7f800000u) return (uint16_t)((u >> 16) | ((u & 0xffffu) ? 0x40u : 0u));
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float load_elem(const void *p, int dt, int64_t off)
+{
+    return dt == EG_BF16 ? bf16_to_f32(((const uint16_t *)p)[off]) : ((const float *)p)[off];
+}
+
+__device__ __forceinline__ void store_elem(void *p, int dt, int64_t off, float v)
+{
+    if (dt == EG_BF16) ((uint16_t *)p)[off] = f32_to_bf16(v);
+    else ((float *)p)[off] = v;
+}
+
+// Loads 8 consecutive elements as fp32 (16-byte aligned start).
+__device__ __forceinline__ void load8(const void *p, int dt, int64_t off, float (&v)[8])
+{
+    if (dt == EG_BF16) {
+        uint4 r = *(const uint4 *)((const uint16_t *)p + off);
+        v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
+        v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xffff0000u);
+        v[4] = __uint_as_float(r.z << 16); v[5] = __uint_as_float(r.z & 0xffff0000u);
+        v[6] = __uint_as_float(r.w << 16); v[7] = __uint_as_float(r.w & 0xffff0000u);
+    } else {
+        float4 a = *(const float4 *)((const float *)p + off);
+        float4 b = *(const float4 *)((const float *)p + off + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+}
+
+__device__ __forceinline__ void store8(void *p, int dt, int64_t off, const float (&v)[8])
+{
+    if (dt == EG_BF16) {
+        uint4 r;
+        r.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+        r.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+        r.z = (uint32_t)f32_to_bf16(v[4]) | ((uint32_t)f32_to_bf16(v[5]) << 16);
+        r.w = (uint32_t)f32_to_bf16(v[6]) | ((uint32_t)f32_to_bf16(v[7]) << 16);
+        *(uint4 *)((uint16_t *)p + off) = r;
+    } else {
+        *(float4 *)((float *)p + off) = make_float4(v[0], v[1], v[2], v[3]);
+        *(float4 *)((float *)p + off + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    }
+}
+
+// The scalar function (x) of a vertex (Section 3 of the paper: any scalar function of the joined values).
+__device__ __forceinline__ float otimes_eval(int op, float x, float y, float alpha)
+{
+    switch (op) {
+    case EG_MUL: return alpha * (x * y);
+    case EG_ADD: return alpha * x + y;
+    case EG_SUB: return alpha * (x - y);
+    case EG_DIV: return x / y;
+    case EG_SQDIFF: return (x - y) * (x - y);
+    case EG_ABSDIFF: return fabsf(x - y);
+    case EG_EXP_SUB: return expf(x - y);
+    case EG_RELU_GRAD: return y > 0.f ? x : 0.f;
+    case EG_SILU_MUL: return (x / (1.f + expf(-x))) * y;
+    case EG_IDENT: return x;
+    case EG_SCALE: return alpha * x;
+    case EG_RELU: return x > 0.f ? x : 0.f;
+    case EG_EXP: return expf(x);
+    case EG_LOG: return logf(x);
+    default: return 0.f;
+    }
+}
+
+__device__ __forceinline__ float oplus_identity(int oplus) { return oplus == EG_AGG_MAX ? -INFINITY : 0.f; }
+__device__ __forceinline__ float oplus_eval(int oplus, float a, float b) { return oplus == EG_AGG_MAX ? fmaxf(a, b) : a + b; }
+
+// Tuple t -> base offsets of its X / Y / Z blocks and its aggIdx (row-major over I(d), last label fastest).
+__device__ __forceinline__ void decode_tuple(const TupleSpace &ts, int64_t t, int64_t &ox, int64_t &oy, int64_t &oz, int64_t &agg)
+{
+    ox = oy = oz = agg = 0;
+    uint32_t rem = (uint32_t)t;
+    for (int l = ts.n - 1; l >= 0; l--) {
+        uint32_t dd = (uint32_t)ts.d[l];
+        uint32_t q = rem / dd, k = rem - q * dd;
+        rem = q;
+        ox += (int64_t)k * ts.step_x[l];
+        oy += (int64_t)k * ts.step_y[l];
+        oz += (int64_t)k * ts.step_z[l];
+        agg += (int64_t)k * ts.agg_w[l];
+    }
+}
+
+// Flat index within a collapsed index space -> offsets in X / Y / Z.
+__device__ __forceinline__ void decode_dims(const StridedDims &d, int64_t e, int64_t &ox, int64_t &oy, int64_t &oz)
+{
+    for (int i = d.n - 1; i >= 0; i--) {
+        int64_t q = e / d.ext[i], k = e - q * d.ext[i];
+        e = q;
+        ox += k * d.sx[i];
+        oy += k * d.sy[i];
+        oz += k * d.sz[i];
+    }
+}
+
+}  // namespace eg

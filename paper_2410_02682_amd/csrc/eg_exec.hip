@@ -1,0 +1,670 @@
+// Executor: routes every annotated vertex to a kernel family, lays out the workspace and launches
+// join kernel + aggregation per vertex in topological order.
+//
+// Paper passages: a vertex runs as a join followed by an aggregation, with an optional repartition
+// between vertices when the producer's output partitioning differs from the consumer's input
+// partitioning (Section 5); the two-step form temp <- join, res <- aggregation is the end of Section
+// 4.3.  Blocks are strided views of dense buffers here, so a repartition rewrites tables only.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <map>
+
+#include "eg_internal.h"
+
+namespace eg {
+
+static inline int64_t dtype_size(int dt) { return dt == EG_BF16 ? 2 : 4; }
+static inline int64_t align_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+struct Operand {
+    const void *ptr = nullptr;
+    int dtype = EG_F32;
+    std::vector<int64_t> stride;     // per dimension of the tensor
+};
+
+static std::vector<int64_t> dense_strides(const std::vector<int64_t> &bound)
+{
+    std::vector<int64_t> st(bound.size());
+    int64_t acc = 1;
+    for (int i = (int)bound.size() - 1; i >= 0; i--) {
+        st[i] = acc;
+        acc *= bound[i];
+    }
+    return st;
+}
+
+static int64_t numel(const std::vector<int64_t> &bound)
+{
+    int64_t n = 1;
+    for (int64_t b : bound) n *= b;
+    return n;
+}
+
+// Per schema label: stride in each operand (0 when the label is absent), block extent.
+struct LabelInfo {
+    int nl = 0;
+    int64_t sx[kMaxLabels] = {0}, sy[kMaxLabels] = {0}, sz[kMaxLabels] = {0};
+    bool inx[kMaxLabels] = {false}, iny[kMaxLabels] = {false}, inz[kMaxLabels] = {false};
+    int64_t ext[kMaxLabels] = {0};
+};
+
+static LabelInfo label_info(const Vertex &v, const Operand &X, const Operand *Y, const std::vector<int64_t> &zstride)
+{
+    LabelInfo li;
+    li.nl = (int)v.labels.size();
+    for (int l = 0; l < li.nl; l++) li.ext[l] = v.lbound[l] / v.d[l];
+    for (size_t i = 0; i < v.lx.size(); i++) { li.sx[v.lx[i]] = X.stride[i]; li.inx[v.lx[i]] = true; }
+    if (Y)
+        for (size_t i = 0; i < v.ly.size(); i++) { li.sy[v.ly[i]] = Y->stride[i]; li.iny[v.ly[i]] = true; }
+    for (size_t i = 0; i < v.lz.size(); i++) { li.sz[v.lz[i]] = zstride[i]; li.inz[v.lz[i]] = true; }
+    return li;
+}
+
+static TupleSpace tuple_space(const Vertex &v, const LabelInfo &li)
+{
+    TupleSpace ts;
+    memset(&ts, 0, sizeof ts);
+    ts.n = li.nl;
+    for (int l = 0; l < li.nl; l++) {
+        ts.d[l] = v.d[l];
+        ts.step_x[l] = li.ext[l] * li.sx[l];
+        ts.step_y[l] = li.ext[l] * li.sy[l];
+        ts.step_z[l] = li.ext[l] * li.sz[l];
+    }
+    int64_t w = 1;
+    for (int i = (int)v.agg.size() - 1; i >= 0; i--) {
+        ts.agg_w[v.agg[i]] = (int32_t)w;
+        w *= v.d[v.agg[i]];
+    }
+    return ts;
+}
+
+// Builds a collapsed index space from schema labels (outermost first): extent-1 labels are dropped and
+// neighbours are fused when, in every operand, the outer stride equals inner stride * inner extent.
+static bool collapse(const LabelInfo &li, const std::vector<int> &labs, StridedDims &out)
+{
+    memset(&out, 0, sizeof out);
+    struct D { int64_t e, x, y, z; };
+    std::vector<D> ds;
+    for (int l : labs)
+        if (li.ext[l] > 1) ds.push_back({li.ext[l], li.sx[l], li.sy[l], li.sz[l]});
+    std::vector<D> m;
+    for (const D &c : ds) {
+        if (!m.empty()) {
+            D &p = m.back();
+            if (p.x == c.x * c.e && p.y == c.y * c.e && p.z == c.z * c.e && p.e * c.e < (1ll << 31)) {
+                p.e *= c.e; p.x = c.x; p.y = c.y; p.z = c.z;
+                continue;
+            }
+        }
+        m.push_back(c);
+    }
+    if ((int)m.size() > kMaxDims) return false;
+    out.n = (int)m.size();
+    for (int i = 0; i < out.n; i++) {
+        if (m[i].e >= (1ll << 31)) return false;
+        out.ext[i] = (int32_t)m[i].e; out.sx[i] = m[i].x; out.sy[i] = m[i].y; out.sz[i] = m[i].z;
+    }
+    return true;
+}
+
+static bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+// Can an operand be read with 16-byte vectors along collapsed dim `vd` of `dims`?  which: 0 = X, 1 = Y.
+static bool vec_ok(const StridedDims &dims, int which, int vd, int vec, const void *ptr, const TupleSpace &ts, bool allow_bcast)
+{
+    const int64_t *s = which == 0 ? dims.sx : dims.sy;
+    if (!aligned16(ptr)) return false;
+    if (s[vd] == 0) return allow_bcast;
+    if (s[vd] != 1) return false;
+    for (int i = 0; i < dims.n; i++)
+        if (i != vd && s[i] % vec) return false;
+    const int64_t *step = which == 0 ? ts.step_x : ts.step_y;
+    for (int l = 0; l < ts.n; l++)
+        if (step[l] % vec) return false;
+    return true;
+}
+
+// ------------------------------------------------------------------------------------------------
+// contraction eligibility and parameter construction
+// ------------------------------------------------------------------------------------------------
+static bool build_contract(const Vertex &v, const LabelInfo &li, const Operand &X, const Operand &Y, ContractParams &cp)
+{
+    if (v.otimes != EG_MUL || v.oplus != EG_AGG_SUM || v.n_in != 2) return false;
+    if (X.dtype != Y.dtype) return false;
+    const int epc = X.dtype == EG_BF16 ? 8 : 4;
+    if (!aligned16(X.ptr) || !aligned16(Y.ptr)) return false;
+    std::vector<int> gb, gm, gn, gk;
+    for (int l = 0; l < li.nl; l++) {
+        const bool x = li.inx[l], y = li.iny[l], z = li.inz[l];
+        if (x && y && z) gb.push_back(l);
+        else if (x && z) gm.push_back(l);
+        else if (y && z) gn.push_back(l);
+        else if (x && y) gk.push_back(l);
+        else return false;                     // a label summed out of one operand alone: not a matrix product
+    }
+    auto live = [&](std::vector<int> &g) { g.erase(std::remove_if(g.begin(), g.end(), [&](int l) { return li.ext[l] <= 1; }), g.end()); };
+    live(gb); live(gm); live(gn); live(gk);
+    if (gm.empty() || gn.empty() || gk.empty()) return false;
+    // the label each operand is contiguous along (stride 1, extent > 1)
+    int cx = -1, cy = -1;
+    for (int l = 0; l < li.nl; l++) {
+        if (li.inx[l] && li.ext[l] > 1 && li.sx[l] == 1) cx = l;
+        if (li.iny[l] && li.ext[l] > 1 && li.sy[l] == 1) cy = l;
+    }
+    if (cx < 0 || cy < 0) return false;
+    auto in = [](const std::vector<int> &g, int l) { return std::find(g.begin(), g.end(), l) != g.end(); };
+    const bool a_k = in(gk, cx), a_m = in(gm, cx);
+    const bool b_k = in(gk, cy), b_n = in(gn, cy);
+    if (!(a_k || a_m) || !(b_k || b_n)) return false;
+    if (a_k && b_k && cx != cy) return false;
+    if (li.ext[cx] % epc || li.ext[cy] % epc) return false;
+    for (int l = 0; l < li.nl; l++) {
+        if (li.inx[l] && l != cx && li.ext[l] > 1 && li.sx[l] % epc) return false;
+        if (li.iny[l] && l != cy && li.ext[l] > 1 && li.sy[l] % epc) return false;
+        if ((li.ext[l] * li.sx[l]) % epc || (li.ext[l] * li.sy[l]) % epc) return false;   // block steps keep alignment
+    }
+    // order each group outermost-first by stride in its leading operand, contiguous label last
+    auto order = [&](std::vector<int> &g, const int64_t *s, int last) {
+        std::sort(g.begin(), g.end(), [&](int a, int b) { return s[a] > s[b]; });
+        if (last >= 0 && in(g, last)) {
+            g.erase(std::find(g.begin(), g.end(), last));
+            g.push_back(last);
+        }
+    };
+    order(gb, li.sx, -1);
+    order(gm, li.sx, a_m ? cx : -1);
+    order(gn, li.sy, b_n ? cy : -1);
+    order(gk, li.sx, a_k ? cx : (b_k ? cy : -1));
+    // fuse neighbours where every operand that carries the group allows it
+    auto fill = [&](const std::vector<int> &g, DimList &dl, const int64_t *s0, const int64_t *s1, const int64_t *s2) -> bool {
+        struct D { int64_t e, a, b, c; };
+        std::vector<D> m;
+        for (int l : g) {
+            D c{li.ext[l], s0 ? s0[l] : 0, s1 ? s1[l] : 0, s2 ? s2[l] : 0};
+            if (!m.empty()) {
+                D &p = m.back();
+                if (p.a == c.a * c.e && p.b == c.b * c.e && p.c == c.c * c.e && p.e * c.e < (1ll << 31)) {
+                    p.e *= c.e; p.a = c.a; p.b = c.b; p.c = c.c;
+                    continue;
+                }
+            }
+            m.push_back(c);
+        }
+        if ((int)m.size() > kMaxGroup) return false;
+        memset(&dl, 0, sizeof dl);
+        dl.n = (int)m.size();
+        for (int i = 0; i < dl.n; i++) {
+            if (m[i].e >= (1ll << 31)) return false;
+            dl.ext[i] = (int32_t)m[i].e; dl.s0[i] = m[i].a; dl.s1[i] = m[i].b; dl.s2[i] = m[i].c;
+        }
+        return true;
+    };
+    memset(&cp, 0, sizeof cp);
+    if (!fill(gb, cp.batch, li.sx, li.sy, li.sz)) return false;
+    if (!fill(gm, cp.m, li.sx, li.sz, nullptr)) return false;
+    if (!fill(gn, cp.n, li.sy, li.sz, nullptr)) return false;
+    if (!fill(gk, cp.k, li.sx, li.sy, nullptr)) return false;
+    auto size = [](const DimList &d) { int64_t p = 1; for (int i = 0; i < d.n; i++) p *= d.ext[i]; return p; };
+    cp.M = size(cp.m); cp.N = size(cp.n); cp.K = size(cp.k); cp.n_batch = size(cp.batch);
+    if (cp.M >= (1ll << 31) || cp.N >= (1ll << 31) || cp.K >= (1ll << 31)) return false;
+    cp.a_kcontig = a_k ? 1 : 0;
+    cp.b_kcontig = b_k ? 1 : 0;
+    // after fusing, the innermost entry of the vectorised group must still be the stride-1 run
+    if (a_k && cp.k.s0[cp.k.n - 1] != 1) return false;
+    if (!a_k && cp.m.s0[cp.m.n - 1] != 1) return false;
+    if (b_k && cp.k.s1[cp.k.n - 1] != 1) return false;
+    if (!b_k && cp.n.s0[cp.n.n - 1] != 1) return false;
+    if (a_k && cp.k.ext[cp.k.n - 1] % epc) return false;
+    if (!a_k && cp.m.ext[cp.m.n - 1] % epc) return false;
+    if (b_k && cp.k.ext[cp.k.n - 1] % epc) return false;
+    if (!b_k && cp.n.ext[cp.n.n - 1] % epc) return false;
+    cp.in_dtype = X.dtype;
+    cp.alpha = (float)v.alpha;
+    cp.x = X.ptr;
+    cp.y = Y.ptr;
+    return true;
+}
+
+// ------------------------------------------------------------------------------------------------
+// routing of one vertex given the real strides of its operands
+// ------------------------------------------------------------------------------------------------
+struct Routed {
+    int kind = EG_KERNEL_NONE;
+    ContractParams cp;
+    MapParams mp;
+    ReduceParams rp;
+    GenericParams gp;
+};
+
+static int route(const Vertex &v, const Operand &X, const Operand *Y, const std::vector<int64_t> &zstride,
+                 const OutSpec &out, Routed &r)
+{
+    LabelInfo li = label_info(v, X, Y, zstride);
+    TupleSpace ts = tuple_space(v, li);
+    const int64_t n_tuples = v.plan.n_tuples;
+    const bool binary = v.n_in == 2;
+
+    if (v.agg.empty()) {                                        // element-wise: no aggregated label
+        MapParams &p = r.mp;
+        memset(&p, 0, sizeof p);
+        std::vector<int> zl(v.lz.begin(), v.lz.end());
+        if (!collapse(li, zl, p.dims)) return fail(EG_ERR_LIMIT, "map: too many dimensions after collapsing");
+        if (p.dims.n == 0) { p.dims.n = 1; p.dims.ext[0] = 1; }
+        p.ts = ts; p.binary = binary; p.otimes = v.otimes; p.alpha = (float)v.alpha;
+        p.dtx = X.dtype; p.dty = Y ? Y->dtype : EG_F32;
+        p.x = X.ptr; p.y = Y ? Y->ptr : nullptr; p.out = out; p.n_tuples = n_tuples;
+        const int vd = p.dims.n - 1;
+        bool vz = p.dims.sz[vd] == 1 && aligned16(out.ptr) && p.dims.ext[vd] % 8 == 0;
+        for (int i = 0; i < p.dims.n && vz; i++)
+            if (i != vd && p.dims.sz[i] % 8) vz = false;
+        for (int l = 0; l < ts.n && vz; l++)
+            if (ts.step_z[l] % 8) vz = false;
+        if (out.slab_elems % 8) vz = false;
+        bool vx = vec_ok(p.dims, 0, vd, 8, X.ptr, ts, true);
+        bool vy = !binary || vec_ok(p.dims, 1, vd, 8, Y->ptr, ts, true);
+        p.vec = (vz && vx && vy) ? 8 : 1;
+        int64_t rows = 1;
+        for (int i = 0; i < vd; i++) rows *= p.dims.ext[i];
+        p.vecs_per_block = rows * ((p.dims.ext[vd] + p.vec - 1) / p.vec);
+        r.kind = EG_KERNEL_MAP;
+        return EG_OK;
+    }
+
+    if (binary && build_contract(v, li, X, *Y, r.cp)) {
+        r.cp.ts = ts;
+        r.cp.out = out;
+        r.cp.n_tuples = n_tuples;
+        r.kind = EG_KERNEL_CONTRACT_MFMA;
+        return EG_OK;
+    }
+
+    // output and reduction index spaces
+    std::vector<int> zl(v.lz.begin(), v.lz.end());
+    // row reduction: the aggregated labels are the trailing dimensions of X, and Y has no label outside X
+    bool tail = v.lx.size() >= v.agg.size();
+    std::vector<int> rl;
+    if (tail) {
+        for (size_t i = v.lx.size() - v.agg.size(); i < v.lx.size(); i++) {
+            if (li.inz[v.lx[i]]) tail = false;
+            rl.push_back(v.lx[i]);
+        }
+        for (int a : v.agg)
+            if (!li.inx[a]) tail = false;
+    }
+    if (tail) {                                  // short reductions are better served one lane per output
+        int64_t red = 1;
+        for (int a : v.agg) red *= li.ext[a];
+        if (red < 64) tail = false;
+    }
+    if (tail) {
+        ReduceParams &p = r.rp;
+        memset(&p, 0, sizeof p);
+        if (collapse(li, zl, p.zdims) && collapse(li, rl, p.rdims)) {
+            if (p.rdims.n == 0) { p.rdims.n = 1; p.rdims.ext[0] = 1; }
+            p.ts = ts; p.binary = binary; p.otimes = v.otimes; p.oplus = v.oplus; p.alpha = (float)v.alpha;
+            p.dtx = X.dtype; p.dty = Y ? Y->dtype : EG_F32;
+            p.x = X.ptr; p.y = Y ? Y->ptr : nullptr; p.out = out; p.n_tuples = n_tuples;
+            p.outs_per_block = 1;
+            for (int i = 0; i < p.zdims.n; i++) p.outs_per_block *= p.zdims.ext[i];
+            p.red_elems = 1;
+            for (int i = 0; i < p.rdims.n; i++) p.red_elems *= p.rdims.ext[i];
+            const int vd = p.rdims.n - 1;
+            bool vx = p.rdims.ext[vd] % 8 == 0 && vec_ok(p.rdims, 0, vd, 8, X.ptr, ts, false);
+            bool vy = !binary || vec_ok(p.rdims, 1, vd, 8, Y->ptr, ts, true);
+            // the output index also moves the vector start: its strides must keep 16-byte alignment
+            for (int i = 0; i < p.zdims.n; i++) {
+                if (p.zdims.sx[i] % 8) vx = false;
+                if (binary && p.zdims.sy[i] % 8) vy = false;
+            }
+            p.vec = (vx && vy) ? 8 : 1;
+            r.kind = EG_KERNEL_REDUCE_ROW;
+            return EG_OK;
+        }
+    }
+
+    GenericParams &p = r.gp;
+    memset(&p, 0, sizeof p);
+    std::vector<int> al(v.agg.begin(), v.agg.end());
+    if (!collapse(li, zl, p.zdims) || !collapse(li, al, p.rdims))
+        return fail(EG_ERR_LIMIT, "generic: too many dimensions after collapsing");
+    p.ts = ts; p.binary = binary; p.otimes = v.otimes; p.oplus = v.oplus; p.alpha = (float)v.alpha;
+    p.dtx = X.dtype; p.dty = Y ? Y->dtype : EG_F32;
+    p.x = X.ptr; p.y = Y ? Y->ptr : nullptr; p.out = out; p.n_tuples = n_tuples;
+    p.outs_per_block = 1;
+    for (int i = 0; i < p.zdims.n; i++) p.outs_per_block *= p.zdims.ext[i];
+    p.red_elems = 1;
+    for (int i = 0; i < p.rdims.n; i++) p.red_elems *= p.rdims.ext[i];
+    r.kind = EG_KERNEL_GENERIC;
+    return EG_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// workspace layout: intermediates and partial slabs, first-fit with reuse after the last consumer
+// ------------------------------------------------------------------------------------------------
+struct Layout {
+    std::vector<int64_t> result_off;    // per vertex: byte offset of its tensor in the workspace (-1: not there)
+    std::vector<int64_t> partial_off;   // per vertex: byte offset of its partial slabs (-1: none)
+    int64_t total = 0;
+};
+
+class Arena {
+public:
+    int64_t alloc(int64_t bytes)
+    {
+        bytes = align_up(std::max<int64_t>(bytes, 1), 256);
+        for (auto it = free_.begin(); it != free_.end(); ++it) {
+            if (it->second >= bytes) {
+                int64_t off = it->first, rest = it->second - bytes;
+                free_.erase(it);
+                if (rest) free_[off + bytes] = rest;
+                size_[off] = bytes;
+                return off;
+            }
+        }
+        int64_t off = top_;
+        // grow from a trailing free block if there is one
+        if (!free_.empty()) {
+            auto last = std::prev(free_.end());
+            if (last->first + last->second == top_) {
+                off = last->first;
+                free_.erase(last);
+            }
+        }
+        top_ = off + bytes;
+        size_[off] = bytes;
+        return off;
+    }
+    void release(int64_t off)
+    {
+        int64_t bytes = size_[off];
+        size_.erase(off);
+        auto it = free_.emplace(off, bytes).first;
+        auto nx = std::next(it);
+        if (nx != free_.end() && it->first + it->second == nx->first) {
+            it->second += nx->second;
+            free_.erase(nx);
+        }
+        if (it != free_.begin()) {
+            auto pv = std::prev(it);
+            if (pv->first + pv->second == it->first) {
+                pv->second += it->second;
+                free_.erase(it);
+            }
+        }
+    }
+    int64_t top() const { return top_; }
+
+private:
+    std::map<int64_t, int64_t> free_, size_;
+    int64_t top_ = 0;
+};
+
+static Layout make_layout(const eg_graph *g)
+{
+    const int nv = (int)g->v.size();
+    Layout L;
+    L.result_off.assign(nv, -1);
+    L.partial_off.assign(nv, -1);
+    std::vector<int> last_use(nv, -1);
+    for (int i = 0; i < nv; i++)
+        for (int k = 0; k < g->v[i].n_in; k++) last_use[g->v[i].in[k]] = i;
+    Arena arena;
+    for (int i = 0; i < nv; i++) {
+        const Vertex &v = g->v[i];
+        if (v.is_input) continue;
+        if (!v.is_output) L.result_off[i] = arena.alloc(numel(v.bound) * dtype_size(v.dtype));
+        if (v.plan.n_agg > 1) {
+            L.partial_off[i] = arena.alloc(v.plan.n_agg * numel(v.bound) * 4);
+            arena.release(L.partial_off[i]);          // live only while this vertex runs
+        }
+        for (int k = 0; k < v.n_in; k++) {
+            int u = v.in[k];
+            if (last_use[u] == i && L.result_off[u] >= 0 && !(k == 1 && v.in[0] == u)) arena.release(L.result_off[u]);
+        }
+        if (!v.is_output && last_use[i] < 0) arena.release(L.result_off[i]);   // never consumed
+    }
+    L.total = arena.top();
+    return L;
+}
+
+}  // namespace eg
+
+using namespace eg;
+
+// Kernel family a vertex would use with dense row-major operands (what einsum_graph_plan reports).
+int eg_route_vertex(const eg_graph *g, int vertex)
+{
+    const Vertex &v = g->v[vertex];
+    static char dummy_buf[64];
+    void *aligned = (void *)(((uintptr_t)dummy_buf + 15) & ~(uintptr_t)15);
+    Operand X, Y;
+    X.ptr = aligned; X.dtype = g->v[v.in[0]].dtype; X.stride = dense_strides(g->v[v.in[0]].bound);
+    if (v.n_in > 1) { Y.ptr = aligned; Y.dtype = g->v[v.in[1]].dtype; Y.stride = dense_strides(g->v[v.in[1]].bound); }
+    OutSpec out{aligned, 0, (int32_t)v.dtype};
+    if (v.plan.n_agg > 1) { out.slab_elems = numel(v.bound); out.dtype = EG_F32; }
+    Routed r;
+    if (route(v, X, v.n_in > 1 ? &Y : nullptr, dense_strides(v.bound), out, r) != EG_OK) return EG_KERNEL_NONE;
+    return r.kind;
+}
+
+void eg_release_events(eg_graph *g)
+{
+    for (void *e : g->ev_start) (void)hipEventDestroy((hipEvent_t)e);
+    for (void *e : g->ev_stop) (void)hipEventDestroy((hipEvent_t)e);
+    g->ev_start.clear();
+    g->ev_stop.clear();
+}
+
+static int ensure_events(eg_graph *g, size_t n)
+{
+    while (g->ev_start.size() < n) {
+        hipEvent_t a, b;
+        if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return fail(EG_ERR_HIP, "hipEventCreate failed");
+        g->ev_start.push_back((void *)a);
+        g->ev_stop.push_back((void *)b);
+    }
+    return EG_OK;
+}
+
+static int launch_routed(Routed &r, void *stream)
+{
+    switch (r.kind) {
+    case EG_KERNEL_CONTRACT_MFMA: return launch_contract(r.cp, stream);
+    case EG_KERNEL_MAP: return launch_map(r.mp, stream);
+    case EG_KERNEL_REDUCE_ROW: return launch_reduce_row(r.rp, stream);
+    case EG_KERNEL_GENERIC: return launch_generic(r.gp, stream);
+    default: return fail(EG_ERR_BAD_OP, "vertex could not be routed to a kernel");
+    }
+}
+
+static int aggregate_into(int oplus, const void *partials, int64_t n_agg, int64_t slab_elems, void *out, int out_dtype,
+                          const std::vector<int64_t> &bound, const std::vector<int64_t> &stride, void *stream)
+{
+    AggregateParams ap;
+    memset(&ap, 0, sizeof ap);
+    ap.partials = (const float *)partials;
+    ap.n_agg = n_agg;
+    ap.slab_elems = slab_elems;
+    ap.oplus = oplus;
+    ap.out_dtype = out_dtype;
+    ap.out = out;
+    ap.contiguous = stride == dense_strides(bound) ? 1 : 0;
+    int nd = 0;
+    for (size_t i = 0; i < bound.size(); i++) {
+        if (bound[i] == 1) continue;
+        if (bound[i] >= (1ll << 31)) return fail(EG_ERR_LIMIT, "aggregate: bound above 2^31");
+        ap.dims.ext[nd] = (int32_t)bound[i];
+        ap.dims.sz[nd] = stride[i];
+        nd++;
+    }
+    ap.dims.n = nd;
+    return launch_aggregate(ap, stream);
+}
+
+extern "C" {
+
+int tr_workspace_bytes(eg_graph *g, size_t *bytes)
+{
+    if (!g || !bytes) return fail(EG_ERR_NULL, "tr_workspace_bytes: NULL argument");
+    *bytes = (size_t)make_layout(g).total;
+    return EG_OK;
+}
+
+int tr_profile_enable(eg_graph *g, int enable)
+{
+    if (!g) return fail(EG_ERR_NULL, "graph is NULL");
+    g->profile = enable != 0;
+    if (g->profile) {
+        size_t n = 0;
+        for (const Vertex &v : g->v)
+            if (!v.is_input) n += 2;
+        return ensure_events(g, n);
+    }
+    return EG_OK;
+}
+
+int tr_profile_count(eg_graph *g)
+{
+    if (!g) return fail(EG_ERR_NULL, "graph is NULL");
+    return g->profile ? (int)g->launches.size() : 0;
+}
+
+int tr_profile_get(eg_graph *g, int i, int *vertex, int *stage, int *kernel, float *ms)
+{
+    if (!g) return fail(EG_ERR_NULL, "graph is NULL");
+    if (!g->profile || i < 0 || i >= (int)g->launches.size()) return fail(EG_ERR_BAD_VERTEX, "no recorded launch %d", i);
+    if (vertex) *vertex = g->launches[i].vertex;
+    if (stage) *stage = g->launches[i].stage;
+    if (kernel) *kernel = g->launches[i].kernel;
+    if (ms) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, (hipEvent_t)g->ev_start[i], (hipEvent_t)g->ev_stop[i]) != hipSuccess)
+            return fail(EG_ERR_HIP, "hipEventElapsedTime failed (was the stream synchronised?)");
+        *ms = t;
+    }
+    return EG_OK;
+}
+
+int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relation *const *outputs, int n_outputs,
+               void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!g) return fail(EG_ERR_NULL, "graph is NULL");
+    if (n_inputs != (int)g->inputs.size() || n_outputs != (int)g->outputs.size())
+        return fail(EG_ERR_BAD_VERTEX, "graph has %zu inputs and %zu marked outputs; %d and %d relations were given",
+                    g->inputs.size(), g->outputs.size(), n_inputs, n_outputs);
+    if ((n_inputs && !inputs) || (n_outputs && !outputs)) return fail(EG_ERR_NULL, "relation array is NULL");
+    const int nv = (int)g->v.size();
+    std::vector<const eg_relation *> bound_rel(nv, nullptr);
+    auto check = [&](const eg_relation *r, const Vertex &v, const char *what, int idx) -> int {
+        if (!r) return fail(EG_ERR_NULL, "%s relation %d is NULL", what, idx);
+        if (r->dtype != v.dtype) return fail(EG_ERR_DTYPE, "%s relation %d: dtype differs from the graph's", what, idx);
+        if (r->bound != v.bound) return fail(EG_ERR_BAD_BOUND, "%s relation %d: bound differs from the graph's", what, idx);
+        return EG_OK;
+    };
+    for (int i = 0; i < n_inputs; i++) {
+        int rc = check(inputs[i], g->v[g->inputs[i]], "input", i);
+        if (rc) return rc;
+        bound_rel[g->inputs[i]] = inputs[i];
+    }
+    for (int i = 0; i < n_outputs; i++) {
+        int rc = check(outputs[i], g->v[g->outputs[i]], "output", i);
+        if (rc) return rc;
+        bound_rel[g->outputs[i]] = outputs[i];
+    }
+    Layout L = make_layout(g);
+    if (L.total > 0) {
+        if (!workspace) return fail(EG_ERR_WORKSPACE, "graph needs %lld workspace bytes but workspace is NULL", (long long)L.total);
+        if ((uintptr_t)workspace & 255) return fail(EG_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+        if ((int64_t)workspace_bytes < L.total)
+            return fail(EG_ERR_WORKSPACE, "workspace has %zu bytes, graph needs %lld", workspace_bytes, (long long)L.total);
+    }
+    char *ws = (char *)workspace;
+
+    // route everything first so that a failure launches nothing
+    struct Step { int vertex; Routed r; bool agg; const void *partials; void *dst; std::vector<int64_t> dst_stride; };
+    std::vector<Step> steps;
+    auto operand_of = [&](int u) {
+        Operand o;
+        const Vertex &pu = g->v[u];
+        o.dtype = pu.dtype;
+        if (bound_rel[u]) { o.ptr = bound_rel[u]->ptr; o.stride = bound_rel[u]->stride; }
+        else { o.ptr = ws + L.result_off[u]; o.stride = dense_strides(pu.bound); }
+        return o;
+    };
+    for (int i = 0; i < nv; i++) {
+        Vertex &v = g->v[i];
+        if (v.is_input) continue;
+        if (!v.plan.valid) return fail(EG_ERR_BAD_PARTITION, "vertex %d has no plan", i);
+        Step s;
+        s.vertex = i;
+        Operand X = operand_of(v.in[0]), Y;
+        if (v.n_in > 1) Y = operand_of(v.in[1]);
+        Operand Z = operand_of(i);
+        s.dst = (void *)Z.ptr;
+        s.dst_stride = Z.stride;
+        s.agg = v.plan.n_agg > 1;
+        OutSpec out;
+        std::vector<int64_t> zstride;
+        if (s.agg) {
+            s.partials = ws + L.partial_off[i];
+            out.ptr = (void *)s.partials;
+            out.slab_elems = numel(v.bound);
+            out.dtype = EG_F32;
+            zstride = dense_strides(v.bound);
+        } else {
+            s.partials = nullptr;
+            out.ptr = s.dst;
+            out.slab_elems = 0;
+            out.dtype = v.dtype;
+            zstride = Z.stride;
+        }
+        int rc = route(v, X, v.n_in > 1 ? &Y : nullptr, zstride, out, s.r);
+        if (rc) return rc;
+        steps.push_back(std::move(s));
+    }
+    if (g->profile) {
+        size_t n = 0;
+        for (const Step &s : steps) n += s.agg ? 2 : 1;
+        int rc = ensure_events(g, n);
+        if (rc) return rc;
+    }
+    g->launches.clear();
+    hipStream_t st = (hipStream_t)hip_stream;
+    auto timed = [&](int vertex, int stage, int kernel, auto &&fn) -> int {
+        size_t idx = g->launches.size();
+        if (g->profile && hipEventRecord((hipEvent_t)g->ev_start[idx], st) != hipSuccess) return fail(EG_ERR_HIP, "hipEventRecord failed");
+        int rc = fn();
+        if (rc) return rc;
+        if (g->profile && hipEventRecord((hipEvent_t)g->ev_stop[idx], st) != hipSuccess) return fail(EG_ERR_HIP, "hipEventRecord failed");
+        g->launches.push_back({vertex, stage, kernel});
+        return EG_OK;
+    };
+    for (Step &s : steps) {
+        const Vertex &v = g->v[s.vertex];
+        int rc = timed(s.vertex, 0, s.r.kind, [&] { return launch_routed(s.r, hip_stream); });
+        if (rc) return rc;
+        if (s.agg) {
+            rc = timed(s.vertex, 1, EG_KERNEL_NONE, [&] {
+                return aggregate_into(v.oplus, s.partials, v.plan.n_agg, numel(v.bound), s.dst, v.dtype, v.bound, s.dst_stride, hip_stream);
+            });
+            if (rc) return rc;
+        }
+    }
+    return EG_OK;
+}
+
+int tr_aggregate(eg_agg oplus, const void *partials, int64_t n_agg, int64_t slab_elems, eg_relation *out, void *hip_stream)
+{
+    if (!partials || !out) return fail(EG_ERR_NULL, "tr_aggregate: NULL argument");
+    if (oplus != EG_AGG_SUM && oplus != EG_AGG_MAX) return fail(EG_ERR_BAD_OP, "tr_aggregate: (+) must be SUM or MAX");
+    if (n_agg < 1) return fail(EG_ERR_BAD_PARTITION, "tr_aggregate: n_agg must be >= 1");
+    if (slab_elems != numel(out->bound)) return fail(EG_ERR_BAD_BOUND, "tr_aggregate: slab_elems %lld differs from the output's %lld elements",
+                                                      (long long)slab_elems, (long long)numel(out->bound));
+    if ((uintptr_t)partials & 15) return fail(EG_ERR_WORKSPACE, "tr_aggregate: partials must be 16-byte aligned");
+    return aggregate_into((int)oplus, partials, n_agg, slab_elems, out->ptr, out->dtype, out->bound, out->stride, hip_stream);
+}
+
+}  // extern "C"

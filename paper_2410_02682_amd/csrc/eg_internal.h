@@ -1,0 +1,189 @@
+// Internal declarations shared by the host planner, the executor and the kernel launchers.
+// Nothing in here is part of the public ABI (see include/eindecomp.h).
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "eindecomp.h"
+
+namespace eg {
+
+// ------------------------------------------------------------------------------------------------
+// error reporting
+// ------------------------------------------------------------------------------------------------
+int fail(int code, const char *fmt, ...);   // records a thread-local message, returns code
+
+// ------------------------------------------------------------------------------------------------
+// device-visible parameter blocks (plain data, passed to kernels by value)
+// ------------------------------------------------------------------------------------------------
+constexpr int kMaxLabels = EG_MAX_LABELS;
+constexpr int kMaxGroup = 4;     // labels per role group (batch / M / N / K) in the contraction kernel
+constexpr int kMaxDims = 8;      // collapsed dimensions in the map / reduce kernels
+
+// The join's tuple space (Section 4.3 of the paper): tuple t is the key over the schema in row-major
+// order of I(d).  step_* = block extent * element stride of the label in X / Y / Z (0 when absent), so a
+// block's base offset is sum_l key[l] * step[l].  agg_w[l] is the weight of key[l] in aggIdx.
+struct TupleSpace {
+    int32_t n;
+    int32_t d[kMaxLabels];
+    int32_t agg_w[kMaxLabels];
+    int64_t step_x[kMaxLabels];
+    int64_t step_y[kMaxLabels];
+    int64_t step_z[kMaxLabels];
+};
+
+// Output addressing: when a vertex has a partitioned aggregated label the join kernel writes fp32
+// partial blocks into slab aggIdx of the workspace ([n_agg][dense Z]); otherwise it writes the final
+// tensor in its own dtype and strides.
+struct OutSpec {
+    void *ptr;            // device: slab 0 (partials) or the destination tensor
+    int64_t slab_elems;   // elements per slab (partials only; 0 otherwise)
+    int32_t dtype;        // eg_dtype of what is stored through ptr
+};
+
+struct DimList {          // one role group of the contraction: block-level extents and strides
+    int32_t n;
+    int32_t ext[kMaxGroup];
+    int64_t s0[kMaxGroup];   // batch: X, M: X, N: Y, K: X
+    int64_t s1[kMaxGroup];   // batch: Y, M: Z, N: Z, K: Y
+    int64_t s2[kMaxGroup];   // batch: Z
+};
+
+struct ContractParams {
+    TupleSpace ts;
+    DimList batch, m, n, k;
+    int64_t M, N, K, n_batch;     // group sizes (products of block extents)
+    int32_t a_kcontig;            // 1: X is contiguous along the innermost K label, 0: along innermost M label
+    int32_t b_kcontig;            // 1: Y is contiguous along the innermost K label, 0: along innermost N label
+    int32_t in_dtype;             // dtype of X and Y
+    float alpha;
+    const void *x;
+    const void *y;
+    OutSpec out;
+    int64_t n_tuples;
+    int32_t tiles_m, tiles_n;     // filled by the launcher
+};
+
+struct StridedDims {              // collapsed index space with per-operand element strides
+    int32_t n;
+    int32_t ext[kMaxDims];
+    int64_t sx[kMaxDims], sy[kMaxDims], sz[kMaxDims];
+};
+
+struct MapParams {                // Z[z] = otimes(X[..], Y[..]) over one block per tuple
+    TupleSpace ts;
+    StridedDims dims;             // Z's block index space, outermost first; last dim is the vector dim
+    int32_t binary, otimes;
+    float alpha;
+    int32_t dtx, dty;
+    int32_t vec;                  // elements per lane along the last dim (1 = scalar path)
+    const void *x;
+    const void *y;
+    OutSpec out;
+    int64_t n_tuples;
+    int64_t vecs_per_block;       // prod(ext[0..n-2]) * ceil(ext[n-1] / vec)
+};
+
+struct ReduceParams {             // Z[z] = oplus over r of otimes(X[z, r], Y[z, r]); one wave-group per z
+    TupleSpace ts;
+    StridedDims zdims;            // output block index space (sz = destination strides)
+    StridedDims rdims;            // reduced index space (sz unused); last dim contiguous in X when vec > 1
+    int32_t binary, otimes, oplus;
+    float alpha;
+    int32_t dtx, dty;
+    int32_t vec;
+    const void *x;
+    const void *y;
+    OutSpec out;
+    int64_t n_tuples;
+    int64_t outs_per_block;
+    int64_t red_elems;            // prod(rdims.ext)
+};
+
+struct GenericParams {            // any EinSum: one output element per lane, sequential loop over l_agg
+    TupleSpace ts;
+    StridedDims zdims;
+    StridedDims rdims;
+    int32_t binary, otimes, oplus;
+    float alpha;
+    int32_t dtx, dty;
+    const void *x;
+    const void *y;
+    OutSpec out;
+    int64_t n_tuples;
+    int64_t outs_per_block;
+    int64_t red_elems;
+};
+
+struct AggregateParams {          // out[e] = oplus_a partials[a][e], ascending a, fp32, one final cast
+    const float *partials;
+    int64_t n_agg;
+    int64_t slab_elems;
+    int32_t oplus;
+    int32_t out_dtype;
+    void *out;
+    int32_t contiguous;           // 1: out is dense row-major (vector path)
+    StridedDims dims;             // out's index space (sz = out strides), used when not contiguous
+};
+
+// launchers (defined in the .hip files); each validates what its kernel assumes and returns eg_status
+int launch_contract(ContractParams &p, void *stream);
+int launch_map(const MapParams &p, void *stream);
+int launch_reduce_row(const ReduceParams &p, void *stream);
+int launch_generic(const GenericParams &p, void *stream);
+int launch_aggregate(const AggregateParams &p, void *stream);
+
+// ------------------------------------------------------------------------------------------------
+// host-side graph
+// ------------------------------------------------------------------------------------------------
+struct Plan {                      // integer tables of one annotated vertex
+    std::vector<int32_t> key, key_x, key_y, key_z, agg_idx, group;
+    std::vector<int64_t> off_x, off_y, off_z;
+    int64_t n_tuples = 0, n_agg = 1, n_groups = 1;
+    bool valid = false;
+};
+
+struct Vertex {
+    bool is_input = false;
+    eg_dtype dtype = EG_F32;
+    std::vector<int64_t> bound;            // b_Z (or the input's bound)
+    // einsum vertices:
+    std::string spec;
+    std::vector<int> lx, ly, lz;           // schema index of every dimension of X / Y / Z
+    std::vector<char> labels;              // schema: unique labels in first-appearance order
+    std::vector<int64_t> lbound;           // bound per schema label
+    std::vector<int32_t> d;                // partitioning per schema label
+    std::vector<int> agg;                  // schema indices of aggregated labels (schema order)
+    int otimes = EG_MUL, oplus = EG_AGG_SUM;
+    double alpha = 1.0;
+    int in[2] = {-1, -1};
+    int n_in = 0;
+    bool is_output = false;
+    Plan plan;
+};
+
+}  // namespace eg
+
+struct eg_graph {
+    std::vector<eg::Vertex> v;
+    std::vector<int> inputs;      // vertex ids of graph inputs, insertion order
+    std::vector<int> outputs;     // marked outputs, marking order
+    // executor state
+    bool profile = false;
+    std::vector<void *> ev_start, ev_stop;          // hipEvent_t pool
+    struct Launch { int vertex, stage, kernel; };
+    std::vector<Launch> launches;                   // of the last tr_execute
+};
+
+// defined in eg_exec.hip
+void eg_release_events(eg_graph *g);
+int eg_route_vertex(const eg_graph *g, int vertex);
+
+struct eg_relation {
+    void *ptr = nullptr;
+    eg_dtype dtype = EG_F32;
+    std::vector<int64_t> bound, stride;
+    std::vector<int32_t> d;
+};

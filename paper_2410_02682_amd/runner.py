@@ -1,0 +1,105 @@
+"""Binds a workload description (synth_inputs.workloads.Workload) to the C ABI: marshalling only.
+
+Builds the library's EinGraph from the vertex records, annotates it with one named set of
+partitioning vectors, views torch device tensors as tensor relations and calls tr_execute.
+torch is used for device memory and the stream handle only.
+"""
+from __future__ import annotations
+
+from typing import Dict, Iterable, Optional
+
+import numpy as np
+import torch
+
+from synth_inputs.prng import HostTensor
+from synth_inputs.workloads import Workload, d_vector, parse_spec
+from . import api
+
+TORCH_DTYPE = {"f32": torch.float32, "bf16": torch.bfloat16}
+
+
+def to_device(t: HostTensor, device="cuda") -> torch.Tensor:
+    if t.dtype == "f32":
+        return torch.from_numpy(np.ascontiguousarray(t.data)).to(device)
+    return torch.from_numpy(np.ascontiguousarray(t.data).view(np.int16)).to(device).view(torch.bfloat16)
+
+
+def to_host(x: torch.Tensor) -> HostTensor:
+    x = x.detach().contiguous().cpu()
+    if x.dtype == torch.float32:
+        return HostTensor(x.numpy().copy(), "f32")
+    return HostTensor(x.view(torch.int16).numpy().view(np.uint16).copy(), "bf16")
+
+
+class GraphRunner:
+    def __init__(self, w: Workload, partitioning: str, outputs: Optional[Iterable[str]] = None, device="cuda"):
+        self.w = w
+        self.device = device
+        self.g = api.einsum_graph_create()
+        self.vid: Dict[str, int] = {}
+        self.part = w.partitionings[partitioning]
+        self.out_names = list(outputs) if outputs is not None else list(w.outputs)
+        for v in w.vertices:
+            if v.is_input:
+                self.vid[v.name] = api.einsum_graph_add_input(self.g, v.bound, v.dtype)
+            else:
+                self.vid[v.name] = api.einsum_graph_add_einsum(self.g, v.spec, v.otimes, v.oplus, v.alpha,
+                                                               [self.vid[n] for n in v.inputs], v.dtype)
+                api.einsum_graph_set_partition(self.g, self.vid[v.name], d_vector(v.spec, self.part.get(v.name, {})))
+        for n in self.out_names:
+            api.einsum_graph_mark_output(self.g, self.vid[n])
+        self.rel_in, self.rel_out = [], []
+        self.tensors: Dict[str, torch.Tensor] = {}
+        self.workspace = None
+
+    def plan(self, name: str) -> dict:
+        return api.einsum_graph_plan(self.g, self.vid[name])
+
+    def _input_partition(self, name: str):
+        """Inputs are pre-partitioned the way their first consumer joins them (Section 8.2: inputs cost nothing)."""
+        for v in self.w.einsum_vertices():
+            for pos, n in enumerate(v.inputs):
+                if n == name:
+                    lX, lY, _ = parse_spec(v.spec)
+                    labs = lX if pos == 0 else lY
+                    part = self.part.get(v.name, {})
+                    return [int(part.get(l, 1)) for l in labs]
+        return [1] * len(self.w.vertex(name).bound)
+
+    def bind(self, inputs: Dict[str, torch.Tensor]):
+        self.release_relations()
+        for v in self.w.vertices:
+            if v.is_input:
+                t = inputs[v.name]
+                assert t.is_contiguous() and tuple(t.shape) == tuple(v.bound) and t.dtype == TORCH_DTYPE[v.dtype]
+                self.tensors[v.name] = t
+                self.rel_in.append(api.tensor_partition(t.data_ptr(), v.dtype, v.bound, self._input_partition(v.name)))
+        for n in self.out_names:
+            v = self.w.vertex(n)
+            pl = self.plan(n)
+            t = torch.empty(tuple(pl["bound_z"]), dtype=TORCH_DTYPE[v.dtype], device=self.device)
+            self.tensors[n] = t
+            self.rel_out.append(api.tensor_partition(t.data_ptr(), v.dtype, pl["bound_z"], pl["d_z"]))
+        nbytes = api.tr_workspace_bytes(self.g)
+        self.workspace_bytes = nbytes
+        self.workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
+        assert self.workspace.data_ptr() % 256 == 0
+        return self
+
+    def run(self, stream: Optional[torch.cuda.Stream] = None):
+        s = stream if stream is not None else torch.cuda.current_stream()
+        api.tr_execute(self.g, self.rel_in, self.rel_out, self.workspace.data_ptr(), self.workspace.numel(), s.cuda_stream)
+
+    def output(self, name: str) -> torch.Tensor:
+        return self.tensors[name]
+
+    def release_relations(self):
+        for r in self.rel_in + self.rel_out:
+            api.tensor_relation_destroy(r)
+        self.rel_in, self.rel_out = [], []
+
+    def close(self):
+        self.release_relations()
+        if self.g is not None:
+            api.einsum_graph_destroy(self.g)
+            self.g = None

@@ -1,0 +1,207 @@
+"""CPU-only tests of the C-ABI library: it loads without a GPU, exports every symbol the header
+declares, and its host-side planner reproduces the oracle's tuple tables bit for bit."""
+import itertools
+import os
+import re
+
+import pytest
+
+import paper_2410_02682_amd as E
+from paper_2410_02682_amd import _lib
+from oracle import tra_ref as T
+from synth_inputs import build_config
+from synth_inputs.workloads import d_vector
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "eindecomp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:const\s+)?(?:int|void|char)\s*\*?\s*([a-z_][a-z0-9_]*)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = _lib.load()
+    declared = _declared_symbols()
+    assert {"einsum_graph_create", "tensor_partition", "tr_execute", "tr_aggregate"} <= set(declared)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert set(_lib.EXPORTS) == set(declared)
+
+
+def _one_vertex_graph(spec, bx, by, dt="f32", otimes="mul", oplus="sum"):
+    g = E.einsum_graph_create()
+    ins = [E.einsum_graph_add_input(g, bx, dt)]
+    if by is not None:
+        ins.append(E.einsum_graph_add_input(g, by, dt))
+    v = E.einsum_graph_add_einsum(g, spec, otimes, oplus, 1.0, ins, dt)
+    return g, v
+
+
+PLAN_CASES = [
+    ("ij,jk->ik", (8, 8), (8, 8)),
+    ("ijb,jbk->ik", (4, 8, 2), (8, 2, 16)),
+    ("bshd,bthd->bhst", (2, 4, 2, 8), (2, 8, 2, 8)),
+    ("bhst,bthd->bshd", (2, 2, 4, 8), (2, 8, 2, 4)),
+    ("bc,bc->", (4, 8), (4, 8)),
+    ("ij->i", (8, 16), None),
+    ("ij,i->ij", (8, 4), (8,)),
+]
+
+
+@pytest.mark.parametrize("spec,bx,by", PLAN_CASES)
+def test_planner_tables_equal_the_literal_join(spec, bx, by):
+    lX, lY, lZ = T.split_spec(spec)
+    schema = T.concat_unique(lX, lY or [])
+    bmap = dict(zip(lX, bx))
+    if lY:
+        bmap.update(zip(lY, by))
+    otimes, oplus = ("mul", "sum") if lY else ("ident", "sum")
+    g, v = _one_vertex_graph(spec, bx, by, otimes=otimes, oplus=oplus)
+    checked = 0
+    for d in itertools.product([1, 2, 4], repeat=len(schema)):
+        if any(bmap[l] % dd for l, dd in zip(schema, d)):
+            continue
+        E.einsum_graph_set_partition(g, v, d)
+        got = E.einsum_graph_plan(g, v)
+        want = T.tuple_table(spec, d)
+        assert got["labels"] == want["schema"]
+        assert got["n_tuples"] == want["N"] and got["n_agg"] == want["n_agg"]
+        assert got["d_x"] == want["d_X"] and got["d_y"] == want["d_Y"] and got["d_z"] == want["d_Z"]
+        assert got["key"] == [r["key"] for r in want["rows"]]
+        assert got["key_x"] == [r["keyX"] for r in want["rows"]]
+        assert got["key_y"] == [r["keyY"] for r in want["rows"]]
+        assert got["key_z"] == [r["keyZ"] for r in want["rows"]]
+        assert got["agg_idx"] == [r["aggIdx"] for r in want["rows"]]
+        assert got["group"] == [r["group"] for r in want["rows"]]
+        # block offsets against the oracle's block descriptors
+        bz = [bmap[l] for l in lZ]
+        for t, r in enumerate(want["rows"]):
+            assert got["off_x"][t] == T.block_descriptor(bx, want["d_X"], r["keyX"])[0]
+            if lY:
+                assert got["off_y"][t] == T.block_descriptor(by, want["d_Y"], r["keyY"])[0]
+            assert got["off_z"][t] == T.block_descriptor(bz, want["d_Z"], r["keyZ"])[0]
+        assert got["block_x"] == [b // dd for b, dd in zip(bx, want["d_X"])]
+        checked += 1
+    assert checked >= 4
+    E.einsum_graph_destroy(g)
+
+
+def test_paper_join_counts_through_the_abi():
+    # Section 6: d = [16,2,2,4] gives 128 tuples; Figures 1-2: four vectors with 16 tuples each
+    g, v = _one_vertex_graph("ij,jk->ik", (16, 8), (8, 8))
+    E.einsum_graph_set_partition(g, v, [16, 2, 4])
+    assert E.einsum_graph_plan(g, v)["n_tuples"] == 128
+    E.einsum_graph_destroy(g)
+    g, v = _one_vertex_graph("ij,jk->ik", (8, 8), (8, 8))
+    for d, has_agg in (([4, 1, 4], False), ([2, 1, 8], False), ([2, 4, 2], True), ([2, 2, 4], True)):
+        E.einsum_graph_set_partition(g, v, d)
+        p = E.einsum_graph_plan(g, v)
+        assert p["n_tuples"] == 16 and (p["n_agg"] > 1) == has_agg
+    E.einsum_graph_destroy(g)
+
+
+def test_tensor_relation_blocks_of_the_u_example():
+    # Section 4.1: 4x4 U cut d = [2,2]: block <1,0> starts at row 2, column 0 and is 2x2
+    rel = E.tensor_partition(0x1000, "f32", [4, 4], [2, 2])
+    assert E.tensor_relation_block(rel, [1, 0]) == (8, [2, 2], [4, 1])
+    assert E.tensor_relation_block(rel, [0, 1]) == (2, [2, 2], [4, 1])
+    E.tensor_relation_destroy(rel)
+    rel = E.tensor_partition(0x1000, "f32", [4, 4], [2, 4])
+    assert E.tensor_relation_block(rel, [1, 3]) == (11, [2, 1], [4, 1])
+    with pytest.raises(E.EgError):
+        E.tensor_relation_block(rel, [2, 0])
+    E.tensor_relation_destroy(rel)
+
+
+def test_error_paths_are_detected_on_the_host():
+    g = E.einsum_graph_create()
+    a = E.einsum_graph_add_input(g, [4, 6], "f32")
+    b = E.einsum_graph_add_input(g, [6, 8], "f32")
+    c = E.einsum_graph_add_input(g, [5, 8], "f32")
+    cases = [
+        (dict(spec="ii,jk->ik", ins=[a, b]), -3),        # repeated label
+        (dict(spec="ij,jk->ikz", ins=[a, b]), -4),       # broadcast label
+        (dict(spec="ij,jk->ik", ins=[a, c]), -5),        # shared label, two bounds
+        (dict(spec="ij,jk,kl->il", ins=[a, b]), -2),     # more than two operands
+        (dict(spec="ij,jk->ik", ins=[a]), -2),           # operand count
+        (dict(spec="ijk,jk->ik", ins=[a, b]), -5),       # rank mismatch
+        (dict(spec="ij,jk->ik", ins=[a, 7]), -10),       # unknown input vertex
+        (dict(spec="ij,jk->ik", ins=[a, b], oplus="none"), -11),   # aggregated label, no (+)
+        (dict(spec="ij,jk->ik", ins=[a, b], otimes="relu"), -11),  # unary function on a binary spec
+    ]
+    for kw, code in cases:
+        with pytest.raises(E.EgError) as ei:
+            E.einsum_graph_add_einsum(g, kw["spec"], kw.get("otimes", "mul"), kw.get("oplus", "sum"), 1.0, kw["ins"], "f32")
+        assert ei.value.code == code, kw
+    v = E.einsum_graph_add_einsum(g, "ij,jk->ik", "mul", "sum", 1.0, [a, b], "f32")
+    for d, code in (([2, 2], -6), ([0, 1, 1], -6), ([3, 1, 1], -7), ([1, 4, 1], -7)):
+        with pytest.raises(E.EgError) as ei:
+            E.einsum_graph_set_partition(g, v, d)
+        assert ei.value.code == code
+    with pytest.raises(E.EgError):
+        E.einsum_graph_set_partition(g, a, [1, 1])       # not an einsum vertex
+    with pytest.raises(E.EgError):
+        E.tensor_partition(0x1000, "f32", [4, 6], [3, 2])
+    with pytest.raises(E.EgError):
+        E.tensor_partition(0, "f32", [4, 6], [2, 2])      # NULL device pointer
+    # binding errors are caught before any launch
+    E.einsum_graph_mark_output(g, v)
+    ra = E.tensor_partition(0x1000, "f32", [4, 6], [1, 1])
+    rb = E.tensor_partition(0x2000, "f32", [6, 8], [1, 1])
+    rc = E.tensor_partition(0x3000, "f32", [5, 8], [1, 1])
+    rz_bad = E.tensor_partition(0x4000, "f32", [4, 7], [1, 1])
+    with pytest.raises(E.EgError) as ei:
+        E.tr_execute(g, [ra, rb], [], 0, 0)
+    assert ei.value.code == -10
+    with pytest.raises(E.EgError) as ei:
+        E.tr_execute(g, [ra, rb, rc], [rz_bad], 0, 0)
+    assert ei.value.code == -5
+    for r in (ra, rb, rc, rz_bad):
+        E.tensor_relation_destroy(r)
+    E.einsum_graph_destroy(g)
+
+
+def test_workspace_accounts_for_partial_slabs_and_reuse():
+    g = E.einsum_graph_create()
+    a = E.einsum_graph_add_input(g, [64, 64], "bf16")
+    b = E.einsum_graph_add_input(g, [64, 64], "bf16")
+    ab = E.einsum_graph_add_einsum(g, "ij,jk->ik", "mul", "sum", 1.0, [a, b], "bf16")
+    abc = E.einsum_graph_add_einsum(g, "ik,kl->il", "mul", "sum", 1.0, [ab, b], "f32")
+    E.einsum_graph_mark_output(g, abc)
+    base = E.tr_workspace_bytes(g)
+    assert base == 64 * 64 * 2                                    # only the bf16 intermediate
+    E.einsum_graph_set_partition(g, ab, [2, 4, 1])                # 4 fp32 partial slabs for AB
+    assert E.tr_workspace_bytes(g) == 64 * 64 * 2 + 4 * 64 * 64 * 4
+    E.einsum_graph_set_partition(g, abc, [1, 2, 2])               # 2 slabs for ABC reuse AB's slab space
+    assert E.tr_workspace_bytes(g) == 64 * 64 * 2 + 4 * 64 * 64 * 4
+    p = E.einsum_graph_plan(g, abc)
+    assert p["repart_x"] == 1 and p["repart_y"] == 0              # AB produced as [2,1], consumed as [1,2]
+    E.einsum_graph_destroy(g)
+
+
+def test_kernel_routing_of_the_workload_vertices():
+    want = {
+        2: {"AB": "contract_mfma", "ABC": "contract_mfma"},
+        3: {"H1": "contract_mfma", "A1": "map", "L": "contract_mfma", "Cmax": "reduce_row", "E": "map", "S": "reduce_row",
+            "loss": "reduce_row", "dW2": "contract_mfma", "dA1": "contract_mfma", "dH1": "map", "dW1": "contract_mfma"},
+        4: {"Q": "contract_mfma", "T1": "contract_mfma", "T2": "map", "Cmax": "reduce_row", "O": "contract_mfma",
+            "Yatt": "contract_mfma", "Hh": "map", "Out": "contract_mfma"},
+        5: {"Z": "contract_mfma"},
+    }
+    for n, kinds in want.items():
+        w = build_config(n)
+        for pname, part in w.partitionings.items():
+            g = E.einsum_graph_create()
+            vid = {}
+            for v in w.vertices:
+                if v.is_input:
+                    vid[v.name] = E.einsum_graph_add_input(g, v.bound, v.dtype)
+                else:
+                    vid[v.name] = E.einsum_graph_add_einsum(g, v.spec, v.otimes, v.oplus, v.alpha, [vid[i] for i in v.inputs], v.dtype)
+                    E.einsum_graph_set_partition(g, vid[v.name], d_vector(v.spec, part.get(v.name, {})))
+            for name, kind in kinds.items():
+                assert E.einsum_graph_plan(g, vid[name])["kernel"] == kind, (n, pname, name)
+            E.einsum_graph_destroy(g)

@@ -1,0 +1,310 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element.
+
+Sizes are those the oracle finishes in seconds while every block still spans several kernel
+tiles with ragged tails.  Full-size checks live in test_gpu_fullsize.py."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+from tests._parity import RTOL_BF16, RTOL_F32, rtol_for, single_vertex, violations
+from oracle.einsum_ref import einsum_ref
+from oracle.graph_ref import make_inputs, run_graph, to_storage
+from synth_inputs import build_config
+from synth_inputs.prng import HostTensor, make_tensor, small_ints, uniform_pm1, normal
+
+pytestmark = pytest.mark.gpu
+
+
+def _gpu():
+    import torch
+    from paper_2410_02682_amd.runner import GraphRunner, to_device, to_host
+    return torch, GraphRunner, to_device, to_host
+
+
+def _run(w, pname, inputs, outputs=None):
+    torch, GraphRunner, to_device, to_host = _gpu()
+    r = GraphRunner(w, pname, outputs=outputs)
+    try:
+        r.bind({k: to_device(t) for k, t in inputs.items()})
+        r.run()
+        torch.cuda.synchronize()
+        return {n: to_host(r.output(n)) for n in r.out_names}
+    finally:
+        r.close()
+
+
+# ------------------------------------------------------------------ the five configurations, scaled down
+CASES = [(n, p) for n in range(1, 6) for p in build_config(n, small=True).partitionings]
+_ref_cache = {}
+
+
+def _reference(n):
+    if n not in _ref_cache:
+        w = build_config(n, small=True)
+        inp = make_inputs(w)
+        _ref_cache[n] = (w, inp, run_graph(w, inp))
+    return _ref_cache[n]
+
+
+@pytest.mark.parametrize("n,pname", CASES)
+def test_config_every_vertex_matches_oracle(n, pname):
+    w, inp, ref = _reference(n)
+    names = [v.name for v in w.einsum_vertices()]
+    print(f"config {n} partitioning {pname}: all vertices as outputs", flush=True)
+    got = _run(w, pname, inp, outputs=names)
+    for name in names:
+        bad, worst = violations(got[name].as_f64(), ref[name].as_f64(), rtol_for(w, name))
+        assert bad == 0, f"config {n} {pname} vertex {name}: {bad} elements out of tolerance (worst {worst:.2f}x)"
+
+
+@pytest.mark.parametrize("n,pname", CASES)
+def test_config_outputs_through_workspace_match_oracle(n, pname):
+    w, inp, ref = _reference(n)
+    print(f"config {n} partitioning {pname}: intermediates in the workspace", flush=True)
+    got = _run(w, pname, inp)
+    for name in w.outputs:
+        bad, worst = violations(got[name].as_f64(), ref[name].as_f64(), rtol_for(w, name))
+        assert bad == 0, f"config {n} {pname} output {name}: {bad} elements out of tolerance (worst {worst:.2f}x)"
+
+
+# ------------------------------------------------------------------ contraction layouts, tails, label groups
+LAYOUTS = [
+    # spec, bound X, bound Y: K-contiguous / M-contiguous A x K-contiguous / N-contiguous B, ragged tails
+    ("ij,jk->ik", (200, 328), (328, 136)),       # A k-contig, B n-contig
+    ("ij,kj->ik", (200, 328), (136, 328)),       # A k-contig, B k-contig
+    ("ji,jk->ik", (328, 200), (328, 136)),       # A m-contig, B n-contig
+    ("ji,kj->ik", (328, 200), (136, 328)),       # A m-contig, B k-contig
+    ("ij,jk->ki", (200, 328), (328, 136)),       # transposed output
+    ("bshd,bthd->bhst", (2, 72, 3, 40), (2, 56, 3, 40)),
+    ("bhst,bthd->bshd", (2, 3, 72, 56), (2, 56, 3, 40)),
+    ("bshd,ahd->bsa", (2, 72, 3, 40), (88, 3, 40)),
+    ("ijk,kl->ijl", (3, 40, 264), (264, 72)),
+    ("bf,bh->fh", (264, 136), (264, 72)),
+]
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("spec,bx,by", LAYOUTS)
+def test_contraction_layouts(spec, bx, by, dtype):
+    print(f"contraction {spec} {bx} {by} {dtype}", flush=True)
+    x = HostTensor.from_f32(uniform_pm1(11, 0, int(np.prod(bx))).reshape(bx), dtype)
+    y = HostTensor.from_f32(uniform_pm1(11, 1, int(np.prod(by))).reshape(by), dtype)
+    w = single_vertex(spec, x, y, "f32")
+    ref = run_graph(w, {"X": x, "Y": y})["Z"]
+    import paper_2410_02682_amd as E
+    got = _run(w, "whole", {"X": x, "Y": y})["Z"]
+    bad, worst = violations(got.as_f64(), ref.as_f64(), RTOL_F32)
+    assert bad == 0, f"{bad} elements out of tolerance (worst {worst:.2f}x)"
+
+
+def test_contraction_routes_to_mfma_and_bf16_output_rounds_once():
+    torch, GraphRunner, to_device, to_host = _gpu()
+    x = HostTensor.from_f32(normal(12, 0, 256 * 192, 1.0).reshape(256, 192), "bf16")
+    y = HostTensor.from_f32(normal(12, 1, 192 * 128, 1.0).reshape(192, 128), "bf16")
+    w = single_vertex("ij,jk->ik", x, y, "bf16", parts={"d": {"i": 2, "j": 2, "k": 2}})
+    r = GraphRunner(w, "d")
+    assert r.plan("Z")["kernel"] == "contract_mfma"
+    r.close()
+    ref = run_graph(w, {"X": x, "Y": y})["Z"]
+    got = _run(w, "d", {"X": x, "Y": y})["Z"]
+    bad, worst = violations(got.as_f64(), ref.as_f64(), RTOL_BF16)
+    assert bad == 0
+    # bf16 results differ from the oracle's by at most one bf16 ulp (a different tie), never more
+    ulp = np.abs(ref.as_f64()) * 2.0 ** -7 + 1e-30
+    assert np.all(np.abs(got.as_f64() - ref.as_f64()) <= ulp)
+
+
+# ------------------------------------------------------------------ exact cases
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_integer_inputs_are_bit_identical_under_every_partitioning(dtype):
+    # small-integer entries: every product and partial sum is exact in fp32, so every decomposition
+    # (Section 4.3) must give the same bits as the undecomposed EinSum
+    bx, by = (128, 256), (256, 64)
+    x = HostTensor.from_f32(small_ints(13, 0, bx[0] * bx[1]).reshape(bx), dtype)
+    y = HostTensor.from_f32(small_ints(13, 1, by[0] * by[1]).reshape(by), dtype)
+    parts = {"d%d%d%d" % d: {"i": d[0], "j": d[1], "k": d[2]} for d in itertools.product([1, 2, 4, 8], repeat=3) if math.prod(d) in (1, 8, 64)}
+    w = single_vertex("ij,jk->ik", x, y, "f32", parts=parts)
+    ref = run_graph(w, {"X": x, "Y": y})["Z"].data
+    for pname in parts:
+        print(f"integer invariant {dtype} {pname}", flush=True)
+        got = _run(w, pname, {"X": x, "Y": y})["Z"].data
+        assert np.array_equal(got, ref), pname
+
+
+def test_identity_and_all_ones_operands():
+    eye = make_tensor({"dist": "identity"}, (256, 256), "bf16", 0, 0)
+    x = HostTensor.from_f32(normal(14, 0, 128 * 256, 1.0).reshape(128, 256), "bf16")
+    w = single_vertex("ij,jk->ik", x, eye, "bf16", parts={"d": {"i": 2, "j": 4, "k": 1}})
+    got = _run(w, "d", {"X": x, "Y": eye})["Z"]
+    assert np.array_equal(got.data, x.data)                       # X.I = X, bit for bit
+    ones_a = make_tensor({"dist": "ones"}, (64, 8192), "bf16", 0, 0)
+    ones_b = make_tensor({"dist": "ones"}, (8192, 64), "bf16", 0, 0)
+    w = single_vertex("ij,jk->ik", ones_a, ones_b, "bf16", parts={"d": {"j": 16}})
+    got = _run(w, "d", {"X": ones_a, "Y": ones_b})["Z"]
+    assert np.all(got.as_f32() == 8192.0)
+
+
+def test_two_runs_are_bit_identical():
+    w, inp, _ = _reference(2)
+    a = _run(w, "mix", inp)["ABC"].data
+    b = _run(w, "mix", inp)["ABC"].data
+    assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------------ maps, reductions, extended operators
+UNARY = ["ident", "scale", "relu", "exp", "log"]
+BINARY = ["mul", "add", "sub", "div", "sqdiff", "absdiff", "exp_sub", "relu_grad", "silu_mul"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape,part", [((96, 200), {"i": 2, "j": 4}), ((7, 13), {}), ((4, 6, 40), {"k": 5})])
+def test_every_scalar_function_elementwise(shape, part, dtype):
+    labs = "ijk"[:len(shape)]
+    n = int(np.prod(shape))
+    x = HostTensor.from_f32((uniform_pm1(15, 0, n) * 3).reshape(shape), dtype)
+    y = HostTensor.from_f32((uniform_pm1(15, 1, n) * 3).reshape(shape), dtype)
+    xp = HostTensor.from_f32((np.abs(uniform_pm1(15, 2, n)) + 0.5).reshape(shape), dtype)
+    rtol = RTOL_F32 if dtype == "f32" else RTOL_BF16
+    for op in UNARY:
+        src = xp if op == "log" else x
+        w = single_vertex(f"{labs}->{labs}", src, None, dtype, otimes=op, oplus="none", alpha=0.75, parts={"p": part})
+        ref = run_graph(w, {"X": src})["Z"]
+        got = _run(w, "p", {"X": src})["Z"]
+        bad, worst = violations(got.as_f64(), ref.as_f64(), rtol)
+        assert bad == 0, (op, bad, worst)
+    for op in BINARY:
+        rhs = xp if op == "div" else y
+        w = single_vertex(f"{labs},{labs}->{labs}", x, rhs, dtype, otimes=op, oplus="none", alpha=0.75, parts={"p": part})
+        ref = run_graph(w, {"X": x, "Y": rhs})["Z"]
+        got = _run(w, "p", {"X": x, "Y": rhs})["Z"]
+        bad, worst = violations(got.as_f64(), ref.as_f64(), rtol)
+        assert bad == 0, (op, bad, worst)
+
+
+@pytest.mark.parametrize("spec,bx,by,otimes,oplus,part", [
+    ("ij,i->ij", (64, 136), (64,), "exp_sub", "none", {"i": 2, "j": 1}),
+    ("ij,j->ij", (64, 136), (136,), "add", "none", {"j": 17}),
+    ("bhst,st->bhst", (2, 3, 40, 48), (40, 48), "add", "none", {"h": 3, "t": 2}),
+    ("ij,ij->ji", (40, 72), (40, 72), "sub", "none", {"i": 2}),
+    ("ij->i", (96, 1000), None, "ident", "max", {"j": 8}),
+    ("ij->i", (96, 1000), None, "ident", "sum", {"i": 2, "j": 4}),
+    ("ij->j", (96, 1000), None, "ident", "sum", {"i": 4}),
+    ("ij->", (96, 1000), None, "exp", "sum", {"i": 2, "j": 2}),
+    ("bhst->bhs", (2, 3, 40, 256), None, "ident", "max", {"t": 4}),
+    ("bc,bc->", (64, 256), (64, 256), "mul", "sum", {"b": 8}),
+    ("ij,jk->ik", (40, 72), (72, 24), "sqdiff", "sum", {"i": 2, "j": 2, "k": 2}),
+    ("ij,jk->ik", (40, 72), (72, 24), "absdiff", "max", {"i": 2, "j": 2, "k": 2}),
+    ("ij,j->i", (40, 1024), (1024,), "mul", "sum", {"j": 2}),
+    ("ij,jk->ik", (37, 53), (53, 29), "mul", "sum", {}),          # nothing divides a vector: scalar paths
+])
+def test_maps_reductions_and_extended_operators(spec, bx, by, otimes, oplus, part):
+    print(f"{spec} {otimes}/{oplus} {part}", flush=True)
+    x = HostTensor.from_f32(uniform_pm1(16, 0, int(np.prod(bx))).reshape(bx), "f32")
+    y = None if by is None else HostTensor.from_f32(uniform_pm1(16, 1, int(np.prod(by))).reshape(by), "f32")
+    w = single_vertex(spec, x, y, "f32", otimes=otimes, oplus=oplus, alpha=0.5, parts={"p": part})
+    inputs = {"X": x} if y is None else {"X": x, "Y": y}
+    ref = run_graph(w, inputs)["Z"]
+    got = _run(w, "p", inputs)["Z"]
+    bad, worst = violations(got.as_f64(), ref.as_f64(), RTOL_F32)
+    assert bad == 0, f"{bad} elements out of tolerance (worst {worst:.2f}x)"
+
+
+def test_softmax_pins_on_the_gpu():
+    # constant rows of power-of-two length give exactly 1/n; rows sum to one; a row of 1000s needs the max subtraction
+    from synth_inputs.workloads import Vertex, Workload
+    rows = np.stack([np.full(64, 3.25), np.full(64, 1000.0), np.linspace(-4, 4, 64), -np.arange(64.0)]).astype(np.float32)
+    x = HostTensor(rows, "f32")
+    vs = [Vertex("X", "f32", bound=(4, 64)),
+          Vertex("C", "f32", spec="ij->i", otimes="ident", oplus="max", inputs=("X",)),
+          Vertex("E", "f32", spec="ij,i->ij", otimes="exp_sub", oplus="none", inputs=("X", "C")),
+          Vertex("S", "f32", spec="ij->i", otimes="ident", oplus="sum", inputs=("E",)),
+          Vertex("P", "f32", spec="ij,i->ij", otimes="div", oplus="none", inputs=("E", "S"))]
+    for part in ({}, {"j": 4}, {"i": 2, "j": 8}):
+        w = Workload("softmax", 0, vs, ["P"], {"p": {v.name: {l: d for l, d in part.items() if l in v.spec.split("->")[0]} for v in vs if not v.is_input}})
+        P = _run(w, "p", {"X": x})["P"].as_f64()
+        assert np.array_equal(P[0], np.full(64, 1 / 64))
+        assert np.array_equal(P[1], np.full(64, 1 / 64))
+        assert np.allclose(P.sum(axis=1), 1.0, atol=1e-6)
+        ref = run_graph(w, {"X": x})["P"].as_f64()
+        assert violations(P, ref, RTOL_F32)[0] == 0
+
+
+# ------------------------------------------------------------------ tr_aggregate on its own
+@pytest.mark.parametrize("out_dtype", ["f32", "bf16"])
+def test_tr_aggregate_sum_max_and_strided_output(out_dtype):
+    torch, GraphRunner, to_device, to_host = _gpu()
+    import paper_2410_02682_amd as E
+    n_agg, shape = 8, (48, 136)
+    slab = (np.round(uniform_pm1(17, 0, shape[0] * shape[1]) * 64) / 64).astype(np.float32).reshape(shape)   # short mantissas
+    parts = torch.from_numpy(np.stack([slab] * n_agg)).cuda()
+    tdt = torch.float32 if out_dtype == "f32" else torch.bfloat16
+    out = torch.zeros(shape, dtype=tdt, device="cuda")
+    rel = E.tensor_partition(out.data_ptr(), out_dtype, shape, [1, 1])
+    E.tr_aggregate("sum", parts.data_ptr(), n_agg, slab.size, rel, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    want = to_storage(n_agg * slab.astype(np.float64), out_dtype) if out_dtype == "f32" else HostTensor.from_f32((n_agg * slab).astype(np.float32), "bf16")
+    assert np.array_equal(to_host(out).data, want.data)            # eight copies: exactly 8x, then one rounding
+    E.tensor_relation_destroy(rel)
+    # max over different slabs, into a strided (transposed) destination
+    rnd = uniform_pm1(17, 1, n_agg * slab.size).reshape((n_agg,) + shape)
+    parts = torch.from_numpy(rnd).cuda()
+    buf = torch.zeros((shape[1], shape[0]), dtype=tdt, device="cuda")
+    rel = E.tensor_partition(buf.data_ptr(), out_dtype, shape, [1, 1], strides=[1, shape[0]])
+    E.tr_aggregate("max", parts.data_ptr(), n_agg, slab.size, rel, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    want = HostTensor.from_f32(rnd.max(axis=0), out_dtype)
+    assert np.array_equal(to_host(buf.t()).data, want.data)
+    E.tensor_relation_destroy(rel)
+    with pytest.raises(E.EgError):
+        rel = E.tensor_partition(out.data_ptr(), out_dtype, shape, [1, 1])
+        try:
+            E.tr_aggregate("sum", parts.data_ptr(), n_agg, slab.size + 1, rel, 0)
+        finally:
+            E.tensor_relation_destroy(rel)
+
+
+def test_strided_input_relation_and_small_workspace_is_rejected():
+    torch, GraphRunner, to_device, to_host = _gpu()
+    import paper_2410_02682_amd as E
+    xt = HostTensor.from_f32(uniform_pm1(18, 0, 96 * 64).reshape(96, 64), "f32")     # stored as [j, i]
+    y = HostTensor.from_f32(uniform_pm1(18, 1, 96 * 40).reshape(96, 40), "f32")
+    g = E.einsum_graph_create()
+    a = E.einsum_graph_add_input(g, [64, 96], "f32")
+    b = E.einsum_graph_add_input(g, [96, 40], "f32")
+    z = E.einsum_graph_add_einsum(g, "ij,jk->ik", "mul", "sum", 1.0, [a, b], "f32")
+    E.einsum_graph_set_partition(g, z, [2, 2, 1])
+    E.einsum_graph_mark_output(g, z)
+    dx, dy = to_device(xt), to_device(y)
+    out = torch.empty((64, 40), dtype=torch.float32, device="cuda")
+    ra = E.tensor_partition(dx.data_ptr(), "f32", [64, 96], [2, 2], strides=[1, 64])   # a transposed view
+    rb = E.tensor_partition(dy.data_ptr(), "f32", [96, 40], [2, 1])
+    rz = E.tensor_partition(out.data_ptr(), "f32", [64, 40], [2, 1])
+    need = E.tr_workspace_bytes(g)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    with pytest.raises(E.EgError) as ei:
+        E.tr_execute(g, [ra, rb], [rz], ws.data_ptr(), need - 256, torch.cuda.current_stream().cuda_stream)
+    assert ei.value.code == -9
+    E.tr_execute(g, [ra, rb], [rz], ws.data_ptr(), need, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    ref = einsum_ref("ji,jk->ik", xt.data, y.data, out_dtype="f32")
+    assert violations(to_host(out).as_f64(), ref, RTOL_F32)[0] == 0
+    for r in (ra, rb, rz):
+        E.tensor_relation_destroy(r)
+    E.einsum_graph_destroy(g)
+
+
+def test_profile_records_every_launch():
+    torch, GraphRunner, to_device, to_host = _gpu()
+    import paper_2410_02682_amd as E
+    w, inp, _ = _reference(2)
+    r = GraphRunner(w, "mix")
+    r.bind({k: to_device(t) for k, t in inp.items()})
+    E.tr_profile_enable(r.g, True)
+    r.run()
+    torch.cuda.synchronize()
+    rec = E.tr_profile_read(r.g)
+    assert [(x["stage"], x["kernel"]) for x in rec] == [("join", "contract_mfma"), ("aggregate", "none")] * 2
+    assert all(x["ms"] > 0 for x in rec)
+    r.close()
