@@ -203,16 +203,20 @@ int tr_aggregate(eg_agg oplus, const void *partials, int64_t n_agg, int64_t slab
 
 /* ---- Timing of the launches inside tr_execute (for roofline reports) ----------------------------------- */
 
-/* When enabled, tr_execute brackets every kernel launch with HIP events on the given stream.  The events
- * are created here (not in tr_execute). */
-int tr_profile_enable(eg_graph *g, int enable);
+/* max_launches > 0: from now on tr_execute brackets every kernel launch with a pair of HIP events recorded
+ * on its stream, appending to a log that holds up to max_launches launches (later ones are not recorded).
+ * The events are created here, never inside tr_execute.  max_launches = 0 switches recording off. */
+int tr_profile_enable(eg_graph *g, int max_launches);
 
-/* After the stream has been synchronised by the caller: number of launches recorded by the last
- * tr_execute, or a negative status. */
+/* Forgets the recorded launches (the events are kept for reuse). */
+int tr_profile_reset(eg_graph *g);
+
+/* Number of launches recorded since the last reset, or a negative status. */
 int tr_profile_count(eg_graph *g);
 
-/* Launch i of the last tr_execute: its vertex, whether it was the join kernel (0) or the aggregation (1),
- * its eg_kernel_kind and elapsed milliseconds.  Host outputs, any may be NULL. */
+/* Recorded launch i: its vertex, whether it was the join kernel (0) or the aggregation (1), its
+ * eg_kernel_kind (EG_KERNEL_NONE for the aggregation) and elapsed milliseconds.  The caller must have
+ * synchronised the stream.  Host outputs, any may be NULL. */
 int tr_profile_get(eg_graph *g, int i, int *vertex, int *stage, int *kernel, float *ms);
 
 /* Message for the last error on this thread (host, valid until the next failing call on the thread). */

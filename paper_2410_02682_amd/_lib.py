@@ -52,6 +52,7 @@ EXPORTS = {
                                   ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
     "tr_aggregate": (ctypes.c_int, [ctypes.c_int, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]),
     "tr_profile_enable": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int]),
+    "tr_profile_reset": (ctypes.c_int, [ctypes.c_void_p]),
     "tr_profile_count": (ctypes.c_int, [ctypes.c_void_p]),
     "tr_profile_get": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int),
                                       ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]),
@@ -68,6 +69,10 @@ def load():
             raise ImportError(
                 f"{LIB_PATH} is missing: build it first (python -m paper_2410_02682_amd.build, or "
                 "__graft_entry__.build()).  There is no CPU fallback.")
+        # torch ships its own HIP runtime; it must be the one already resident when this library's
+        # libamdhip64 dependency is resolved, or the process ends up with two runtimes that do not share
+        # device state (streams, allocations, code objects).
+        import torch  # noqa: F401
         lib = ctypes.CDLL(LIB_PATH)
         for name, (res, args) in EXPORTS.items():
             fn = getattr(lib, name)

@@ -130,8 +130,12 @@ def tr_aggregate(oplus: str, partials_ptr: int, n_agg: int, slab_elems: int, out
     _check(_lib.load().tr_aggregate(OPLUS[oplus], ctypes.c_void_p(partials_ptr), n_agg, slab_elems, out_rel, ctypes.c_void_p(stream)))
 
 
-def tr_profile_enable(g, enable: bool) -> None:
-    _check(_lib.load().tr_profile_enable(g, 1 if enable else 0))
+def tr_profile_enable(g, max_launches: int) -> None:
+    _check(_lib.load().tr_profile_enable(g, int(max_launches)))
+
+
+def tr_profile_reset(g) -> None:
+    _check(_lib.load().tr_profile_reset(g))
 
 
 def tr_profile_read(g) -> List[dict]:

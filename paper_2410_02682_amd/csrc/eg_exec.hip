@@ -513,16 +513,19 @@ int tr_workspace_bytes(eg_graph *g, size_t *bytes)
     return EG_OK;
 }
 
-int tr_profile_enable(eg_graph *g, int enable)
+int tr_profile_enable(eg_graph *g, int max_launches)
 {
     if (!g) return fail(EG_ERR_NULL, "graph is NULL");
-    g->profile = enable != 0;
-    if (g->profile) {
-        size_t n = 0;
-        for (const Vertex &v : g->v)
-            if (!v.is_input) n += 2;
-        return ensure_events(g, n);
-    }
+    if (max_launches < 0) return fail(EG_ERR_LIMIT, "max_launches must be >= 0");
+    g->profile = max_launches > 0;
+    g->launches.clear();
+    return g->profile ? ensure_events(g, (size_t)max_launches) : EG_OK;
+}
+
+int tr_profile_reset(eg_graph *g)
+{
+    if (!g) return fail(EG_ERR_NULL, "graph is NULL");
+    g->launches.clear();
     return EG_OK;
 }
 
@@ -625,21 +628,17 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
         if (rc) return rc;
         steps.push_back(std::move(s));
     }
-    if (g->profile) {
-        size_t n = 0;
-        for (const Step &s : steps) n += s.agg ? 2 : 1;
-        int rc = ensure_events(g, n);
-        if (rc) return rc;
-    }
-    g->launches.clear();
     hipStream_t st = (hipStream_t)hip_stream;
     auto timed = [&](int vertex, int stage, int kernel, auto &&fn) -> int {
-        size_t idx = g->launches.size();
-        if (g->profile && hipEventRecord((hipEvent_t)g->ev_start[idx], st) != hipSuccess) return fail(EG_ERR_HIP, "hipEventRecord failed");
+        const size_t idx = g->launches.size();
+        const bool rec = g->profile && idx < g->ev_start.size();
+        if (rec && hipEventRecord((hipEvent_t)g->ev_start[idx], st) != hipSuccess) return fail(EG_ERR_HIP, "hipEventRecord failed");
         int rc = fn();
         if (rc) return rc;
-        if (g->profile && hipEventRecord((hipEvent_t)g->ev_stop[idx], st) != hipSuccess) return fail(EG_ERR_HIP, "hipEventRecord failed");
-        g->launches.push_back({vertex, stage, kernel});
+        if (rec) {
+            if (hipEventRecord((hipEvent_t)g->ev_stop[idx], st) != hipSuccess) return fail(EG_ERR_HIP, "hipEventRecord failed");
+            g->launches.push_back({vertex, stage, kernel});
+        }
         return EG_OK;
     };
     for (Step &s : steps) {

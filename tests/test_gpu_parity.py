@@ -301,7 +301,7 @@ def test_profile_records_every_launch():
     w, inp, _ = _reference(2)
     r = GraphRunner(w, "mix")
     r.bind({k: to_device(t) for k, t in inp.items()})
-    E.tr_profile_enable(r.g, True)
+    E.tr_profile_enable(r.g, 16)
     r.run()
     torch.cuda.synchronize()
     rec = E.tr_profile_read(r.g)
