@@ -221,6 +221,10 @@ static bool build_contract(const Vertex &v, const LabelInfo &li, const Operand &
     if (!a_k && cp.m.ext[cp.m.n - 1] % epc) return false;
     if (b_k && cp.k.ext[cp.k.n - 1] % epc) return false;
     if (!b_k && cp.n.ext[cp.n.n - 1] % epc) return false;
+    for (int l = 0; l < li.nl; l++) {
+        cp.span_x += (li.ext[l] - 1) * li.sx[l];
+        cp.span_y += (li.ext[l] - 1) * li.sy[l];
+    }
     cp.in_dtype = X.dtype;
     cp.alpha = (float)v.alpha;
     cp.x = X.ptr;

@@ -63,6 +63,7 @@ struct ContractParams {
     const void *y;
     OutSpec out;
     int64_t n_tuples;
+    int64_t span_x, span_y;       // largest element offset inside one block of X / Y
     int32_t tiles_m, tiles_n;     // filled by the launcher
 };
 
@@ -130,6 +131,8 @@ struct AggregateParams {          // out[e] = oplus_a partials[a][e], ascending 
 
 // launchers (defined in the .hip files); each validates what its kernel assumes and returns eg_status
 int launch_contract(ContractParams &p, void *stream);
+int launch_contract_dma(ContractParams &p, void *stream);     // bf16, direct global->LDS staging; see k_contract_dma.hip
+bool contract_dma_eligible(const ContractParams &p);
 int launch_map(const MapParams &p, void *stream);
 int launch_reduce_row(const ReduceParams &p, void *stream);
 int launch_generic(const GenericParams &p, void *stream);

@@ -10,6 +10,9 @@
 // vertex dtype.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+#include <cstring>
+
 #include "eg_device.h"
 
 namespace eg {
@@ -330,6 +333,10 @@ int launch_contract(ContractParams &p, void *stream)
                                   : (p.n.s0[p.n.n - 1] == 1 && p.n.ext[p.n.n - 1] % epc == 0);
     if (!ok_a || !ok_b) return fail(EG_ERR_LIMIT, "contraction: operand is not vectorisable along its contiguous label");
     if (((uintptr_t)p.x & 15) || ((uintptr_t)p.y & 15)) return fail(EG_ERR_LIMIT, "contraction: operands must be 16-byte aligned");
+    // large bf16 blocks take the direct-to-LDS kernel; EINDECOMP_CONTRACT=staged|dma forces one of the two
+    static const char *force = getenv("EINDECOMP_CONTRACT");
+    const bool want_dma = force ? (strcmp(force, "dma") == 0) : (p.M >= 128 && p.N >= 128);
+    if (want_dma && !(force && strcmp(force, "staged") == 0) && contract_dma_eligible(p)) return launch_contract_dma(p, stream);
     if (p.in_dtype == EG_BF16) return launch_cfg<Cfg<128, 128, 64, 64, true>>(p, stream);
     return launch_cfg<Cfg<128, 128, 64, 64, false>>(p, stream);
 }

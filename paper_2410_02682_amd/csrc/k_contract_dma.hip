@@ -1,0 +1,319 @@
+// bf16 block contraction with direct global->LDS staging (no register round trip), 256x256x64 tiles.
+//
+// Same operation as k_contract.hip (the per-block kernel K of Section 4.3 of the paper for (x) = multiply,
+// (+) = sum, all tuples of the join in one launch), specialised for the large bf16 blocks:
+//   * 4 waves per workgroup, each owning a 128x128 output patch = 4x4 MFMA 32x32x16 tiles (fp32 accumulators);
+//   * every 16-byte chunk of both operand tiles travels global memory -> LDS directly; the chunk a lane
+//     fetches is chosen so that the contiguous 1 KiB an instruction deposits is already the swizzled layout;
+//   * an operand contiguous along K sits in LDS as [row][64 k] and is read with 16-byte reads; an operand
+//     contiguous along M or N sits as [k][256 mn] and is read with the 16-bit transposing LDS read, which
+//     hands every lane four consecutive k for its own column;
+//   * two LDS stages: the loads of stage t+1 are in flight while the MFMAs of stage t run.
+// Requirements (checked on the host): K is a multiple of 64 made of runs of 64 along the innermost K label,
+// in-block offsets fit 31 bits.  Anything else goes to the register-staged kernel.
+#include <hip/hip_runtime.h>
+
+#include "eg_device.h"
+
+namespace eg {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+
+namespace dma {
+
+constexpr int BM = 256, BN = 256, BK = 64, THREADS = 256;
+constexpr int TILE_BYTES = 256 * 64 * 2;          // one operand tile of one stage: 32 KiB
+constexpr int STAGE_BYTES = 2 * TILE_BYTES;
+constexpr int LDS_BYTES = 2 * STAGE_BYTES;        // 128 KiB
+
+#define EG_LDS(p) ((__attribute__((address_space(3))) void *)(p))
+#define EG_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
+
+__device__ __forceinline__ void decode_group2(const DimList &g, int64_t idx, int64_t &o0, int64_t &o1)
+{
+    o0 = o1 = 0;
+    if (g.n == 1) { o0 = idx * g.s0[0]; o1 = idx * g.s1[0]; return; }
+    uint32_t rem = (uint32_t)idx;
+    for (int i = g.n - 1; i >= 0; i--) {
+        uint32_t e = (uint32_t)g.ext[i], q = rem / e, k = rem - q * e;
+        rem = q;
+        o0 += (int64_t)k * g.s0[i];
+        o1 += (int64_t)k * g.s1[i];
+    }
+}
+
+// Per-lane source offsets (elements, relative to the operand's block base) of the 8 chunks this lane
+// fetches per stage, without the k advance.
+//   KC: instruction i of wave w deposits rows (4i+w)*8 .. +7, lane -> row +lane/8, physical chunk lane%8,
+//       logical chunk (lane%8) ^ (row&7) = (lane%8) ^ (lane/8).
+//   MC: instruction i of wave w deposits k-rows (4i+w)*2 .. +1, lane -> k-row +lane/32, physical chunk lane%32,
+//       logical chunk (lane%32) ^ 4*(krow%4), krow%4 = (2w + lane/32)%4.
+template <bool KC>
+struct Src {
+    uint32_t off[KC ? 8 : 1];
+    int64_t kstep;            // MC: element stride of one k-row in this operand (KC: unused)
+
+    __device__ __forceinline__ void init(const DimList &grp, int64_t first, int64_t extent, int64_t k_inner_stride, int wave, int lane)
+    {
+        if (KC) {
+            const int lc = (lane & 7) ^ (lane >> 3);
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                int64_t r = first + (4 * i + wave) * 8 + (lane >> 3);
+                r = r < extent ? r : extent - 1;
+                int64_t o0, o1;
+                decode_group2(grp, r, o0, o1);
+                off[i] = (uint32_t)(o0 + lc * 8);
+            }
+            kstep = 0;
+        } else {
+            const int kr4 = (2 * wave + (lane >> 5)) & 3;
+            const int lc = (lane & 31) ^ (4 * kr4);
+            int64_t m = first + lc * 8;
+            m = m + 8 <= extent ? m : extent - 8;
+            int64_t o0, o1;
+            decode_group2(grp, m, o0, o1);
+            off[0] = (uint32_t)(o0 + (2 * wave + (lane >> 5)) * k_inner_stride);
+            kstep = k_inner_stride;
+        }
+    }
+
+    // byte offset of the chunk instruction i fetches
+    __device__ __forceinline__ int64_t byte_off(int i) const
+    {
+        if (KC) return (int64_t)off[i] * 2;
+        return ((int64_t)off[0] + (int64_t)i * 8 * kstep) * 2;
+    }
+};
+
+// LDS byte address of the fragment chunk lane `lane` feeds to the MFMA for 32-row tile `t32` (rows t32*32..+31
+// of the wave's 128) at k-step ks (16 k per step).  KC layout: one 16-byte read.
+__device__ __forceinline__ int kc_frag_off(int row, int ks, int lane)
+{
+    const int lc = 2 * ks + (lane >> 5);
+    return row * 128 + ((lc ^ (row & 7)) << 4);
+}
+
+// MC layout: two transposing 8-byte reads (k = 8*(lane/32) + 0..3 and +4..7 of the k-step).
+__device__ __forceinline__ int mc_frag_off(int col0, int ks, int lane, int second)
+{
+    const int s = lane & 15;
+    const int kr = 16 * ks + 8 * (lane >> 5) + (s >> 2) + 4 * second;
+    const int n = col0 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
+    const int pc = (n >> 3) ^ (4 * (s >> 2));
+    return kr * 512 + (pc << 4) + ((n & 7) << 1);
+}
+
+// All MFMAs of one stage: 4 k-steps x (4 A fragments, 4 B fragments, 16 MFMAs) for this wave's 128x128 patch.
+template <bool A_KC, bool B_KC>
+__device__ __forceinline__ void compute_stage(const char *la, const char *lb, f32x16 (&acc)[4][4], int wm, int wn, int lane)
+{
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) {
+        bf16x8 a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            if (A_KC) {
+                a[i] = *(const bf16x8 *)(la + kc_frag_off(wm * 128 + i * 32 + (lane & 31), ks, lane));
+            } else {
+                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off(wm * 128 + i * 32, ks, lane, 0)));
+                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off(wm * 128 + i * 32, ks, lane, 1)));
+                short4v *dst = (short4v *)&a[i];
+                dst[0] = lo; dst[1] = hi;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            if (B_KC) {
+                b[j] = *(const bf16x8 *)(lb + kc_frag_off(wn * 128 + j * 32 + (lane & 31), ks, lane));
+            } else {
+                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off(wn * 128 + j * 32, ks, lane, 0)));
+                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off(wn * 128 + j * 32, ks, lane, 1)));
+                short4v *dst = (short4v *)&b[j];
+                dst[0] = lo; dst[1] = hi;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int j = 0; j < 4; j++)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+}
+
+template <bool A_KC, bool B_KC>
+__global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p)
+{
+    // Two separate LDS objects, one per stage: the compiler can then tell that the fragment reads of one
+    // stage never alias the direct loads in flight into the other, and does not wait for them.
+    __shared__ __attribute__((aligned(1024))) char lds0[STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char lds1[STAGE_BYTES];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // ---- workgroup -> (tuple, batch, tile); consecutive logical ids stay on one XCD -----------------
+    const int64_t total = (int64_t)gridDim.x;
+    int64_t logical;
+    {
+        const int64_t per = total / 8, rem = total % 8;
+        const int64_t x = blockIdx.x % 8, j = blockIdx.x / 8;
+        logical = x * per + (x < rem ? x : rem) + j;
+    }
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    const int64_t tb = logical / tiles;
+    const int tl = (int)(logical - tb * tiles);
+    constexpr int GM = 8;
+    const int span = GM * p.tiles_n;
+    const int grp = tl / span, first_m = grp * GM;
+    const int gsz = (p.tiles_m - first_m) < GM ? (p.tiles_m - first_m) : GM;
+    const int tile_m = first_m + (tl - grp * span) % gsz;
+    const int tile_n = (tl - grp * span) / gsz;
+    const int64_t tuple = tb / p.n_batch, bidx = tb - tuple * p.n_batch;
+
+    int64_t bx, by, bz, agg;
+    decode_tuple(p.ts, tuple, bx, by, bz, agg);
+    {
+        uint32_t rem = (uint32_t)bidx;
+        for (int i = p.batch.n - 1; i >= 0; i--) {
+            uint32_t e = (uint32_t)p.batch.ext[i], q = rem / e, k = rem - q * e;
+            rem = q;
+            bx += (int64_t)k * p.batch.s0[i];
+            by += (int64_t)k * p.batch.s1[i];
+            bz += (int64_t)k * p.batch.s2[i];
+        }
+    }
+    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
+    const char *xb = (const char *)p.x + bx * 2;
+    const char *yb = (const char *)p.y + by * 2;
+    const int kin = p.k.n - 1;                        // innermost K label: every 64-run of k lies inside it
+
+    Src<A_KC> sa;
+    Src<B_KC> sb;
+    sa.init(p.m, m0, p.M, p.k.s0[kin], wave, lane);
+    sb.init(p.n, n0, p.N, p.k.s1[kin], wave, lane);
+
+    // issues the 16 direct loads of the stage that starts at k0 into the LDS stage at `dst`
+    auto issue = [&](int64_t k0, char *dst) {
+        int64_t ka, kb;
+        decode_group2(p.k, k0, ka, kb);                // uniform: offset of the run's first k in X and in Y
+        const char *ga = xb + ka * 2, *gb = yb + kb * 2;
+#pragma unroll
+        for (int i = 0; i < 8; i++)
+            __builtin_amdgcn_global_load_lds(EG_GLB(ga + sa.byte_off(i)), EG_LDS(dst + (4 * i + wave) * 1024), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 8; i++)
+            __builtin_amdgcn_global_load_lds(EG_GLB(gb + sb.byte_off(i)), EG_LDS(dst + TILE_BYTES + (4 * i + wave) * 1024), 16, 0, 0);
+    };
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+
+    const int64_t nk = p.K / BK;
+    issue(0, lds0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0): this wave's deposits have landed
+    __syncthreads();
+    for (int64_t kt = 0; kt + 1 < nk; kt += 2) {
+        issue((kt + 1) * BK, lds1);
+        compute_stage<A_KC, B_KC>(lds0, lds0 + TILE_BYTES, acc, wm, wn, lane);
+        __builtin_amdgcn_s_waitcnt(0x0F70);           // the next stage's deposits of this wave have landed
+        __syncthreads();                              // ... and everybody's; everybody is done reading lds0
+        if (kt + 2 < nk) issue((kt + 2) * BK, lds0);
+        compute_stage<A_KC, B_KC>(lds1, lds1 + TILE_BYTES, acc, wm, wn, lane);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();
+    }
+    if (nk & 1) {                                      // odd number of stages: the last one sits in lds0
+        compute_stage<A_KC, B_KC>(lds0, lds0 + TILE_BYTES, acc, wm, wn, lane);
+        __syncthreads();
+    }
+
+    // ---- epilogue ---------------------------------------------------------------------------------
+    // Z offsets of the tile's 256 rows and 256 columns go through LDS (free now): one decode per thread.
+    int64_t *zrow = (int64_t *)lds0, *zcol = zrow + 256;
+    {
+        int64_t unused, z;
+        const int64_t m = m0 + tid, n = n0 + tid;
+        decode_group2(p.m, m < p.M ? m : 0, unused, z);
+        zrow[tid] = z;
+        decode_group2(p.n, n < p.N ? n : 0, unused, z);
+        zcol[tid] = z;
+    }
+    __syncthreads();
+    // lane holds column (lane % 32) and rows 8*(r/4) + 4*(lane/32) + r%4 of each 32x32 tile
+    char *zb = (char *)p.out.ptr + (p.out.slab_elems ? agg * p.out.slab_elems * 4 : 0);
+    const bool out_bf16 = p.out.dtype == EG_BF16;
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    int64_t zn[4];
+    bool nok[4];
+#pragma unroll
+    for (int j = 0; j < 4; j++) {
+        const int c = wn * 128 + j * 32 + lrow;
+        zn[j] = bz + zcol[c];
+        nok[j] = n0 + c < p.N;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const int rr = wm * 128 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+            if (m0 + rr >= p.M) continue;
+            const int64_t zm = zrow[rr];
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                if (!nok[j]) continue;
+                const float val = p.alpha * acc[i][j][r];
+                const int64_t off = zm + zn[j];
+                if (out_bf16) ((uint16_t *)zb)[off] = f32_to_bf16(val);
+                else ((float *)zb)[off] = val;
+            }
+            asm volatile("" ::: "memory");             // keep the scheduler from hoisting all 64 row lookups at once
+        }
+    }
+}
+
+template <bool A_KC, bool B_KC>
+static int launch_one(ContractParams &p, void *stream)
+{
+    const int64_t wgs = p.n_tuples * p.n_batch * p.tiles_m * p.tiles_n;
+    hipLaunchKernelGGL((k_contract_dma<A_KC, B_KC>), dim3((unsigned)wgs), dim3(THREADS), 0, (hipStream_t)stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(EG_ERR_HIP, "k_contract_dma launch failed: %s", hipGetErrorString(e));
+    return EG_OK;
+}
+
+}  // namespace dma
+
+bool contract_dma_eligible(const ContractParams &p)
+{
+    if (p.in_dtype != EG_BF16) return false;
+    if (p.m.n < 1 || p.n.n < 1 || p.k.n < 1) return false;
+    if (p.K % dma::BK || p.k.ext[p.k.n - 1] % dma::BK) return false;       // stages never straddle a K label
+    if (p.span_x >= (1ll << 30) || p.span_y >= (1ll << 30)) return false;  // 32-bit lane offsets (in bytes < 2^31)
+    if (p.a_kcontig ? p.k.s0[p.k.n - 1] != 1 : (p.m.s0[p.m.n - 1] != 1 || p.m.ext[p.m.n - 1] % 8)) return false;
+    if (p.b_kcontig ? p.k.s1[p.k.n - 1] != 1 : (p.n.s0[p.n.n - 1] != 1 || p.n.ext[p.n.n - 1] % 8)) return false;
+    if (!p.a_kcontig && p.M < 8) return false;
+    if (!p.b_kcontig && p.N < 8) return false;
+    if (((uintptr_t)p.x & 15) || ((uintptr_t)p.y & 15)) return false;
+    return true;
+}
+
+int launch_contract_dma(ContractParams &p, void *stream)
+{
+    if (!p.x || !p.y || !p.out.ptr) return fail(EG_ERR_NULL, "contraction: NULL operand");
+    if (!contract_dma_eligible(p)) return fail(EG_ERR_LIMIT, "contraction: shape not eligible for the direct-to-LDS kernel");
+    p.tiles_m = (int32_t)((p.M + dma::BM - 1) / dma::BM);
+    p.tiles_n = (int32_t)((p.N + dma::BN - 1) / dma::BN);
+    const int64_t wgs = p.n_tuples * p.n_batch * p.tiles_m * p.tiles_n;
+    if (wgs < 1 || wgs >= (1ll << 31)) return fail(EG_ERR_LIMIT, "contraction needs %lld workgroups", (long long)wgs);
+    if (p.a_kcontig) return p.b_kcontig ? dma::launch_one<true, true>(p, stream) : dma::launch_one<true, false>(p, stream);
+    return p.b_kcontig ? dma::launch_one<false, true>(p, stream) : dma::launch_one<false, false>(p, stream);
+}
+
+}  // namespace eg
