@@ -26,7 +26,6 @@ namespace dma {
 constexpr int BM = 256, BN = 256, BK = 64, THREADS = 256;
 constexpr int TILE_BYTES = 256 * 64 * 2;          // one operand tile of one stage: 32 KiB
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;
-constexpr int LDS_BYTES = 2 * STAGE_BYTES;        // 128 KiB
 
 #define EG_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 #define EG_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
@@ -52,8 +51,7 @@ __device__ __forceinline__ void decode_group2(const DimList &g, int64_t idx, int
 //       logical chunk (lane%32) ^ 4*(krow%4), krow%4 = (2w + lane/32)%4.
 template <bool KC>
 struct Src {
-    uint32_t off[KC ? 8 : 1];
-    int64_t kstep;            // MC: element stride of one k-row in this operand (KC: unused)
+    uint32_t boff[8];         // byte offset of the chunk instruction i fetches, relative to the stage's first k
 
     __device__ __forceinline__ void init(const DimList &grp, int64_t first, int64_t extent, int64_t k_inner_stride, int wave, int lane)
     {
@@ -65,9 +63,8 @@ struct Src {
                 r = r < extent ? r : extent - 1;
                 int64_t o0, o1;
                 decode_group2(grp, r, o0, o1);
-                off[i] = (uint32_t)(o0 + lc * 8);
+                boff[i] = (uint32_t)((o0 + lc * 8) * 2);
             }
-            kstep = 0;
         } else {
             const int kr4 = (2 * wave + (lane >> 5)) & 3;
             const int lc = (lane & 31) ^ (4 * kr4);
@@ -75,16 +72,10 @@ struct Src {
             m = m + 8 <= extent ? m : extent - 8;
             int64_t o0, o1;
             decode_group2(grp, m, o0, o1);
-            off[0] = (uint32_t)(o0 + (2 * wave + (lane >> 5)) * k_inner_stride);
-            kstep = k_inner_stride;
+#pragma unroll
+            for (int i = 0; i < 8; i++)
+                boff[i] = (uint32_t)((o0 + (8 * i + 2 * wave + (lane >> 5)) * k_inner_stride) * 2);
         }
-    }
-
-    // byte offset of the chunk instruction i fetches
-    __device__ __forceinline__ int64_t byte_off(int i) const
-    {
-        if (KC) return (int64_t)off[i] * 2;
-        return ((int64_t)off[0] + (int64_t)i * 8 * kstep) * 2;
     }
 };
 
@@ -106,44 +97,46 @@ __device__ __forceinline__ int mc_frag_off(int col0, int ks, int lane, int secon
     return kr * 512 + (pc << 4) + ((n & 7) << 1);
 }
 
-// All MFMAs of one stage: 4 k-steps x (4 A fragments, 4 B fragments, 16 MFMAs) for this wave's 128x128 patch.
+// Fragments of one k-step (16 k): four 32-row A fragments and four 32-column B fragments of this wave.
 template <bool A_KC, bool B_KC>
-__device__ __forceinline__ void compute_stage(const char *la, const char *lb, f32x16 (&acc)[4][4], int wm, int wn, int lane)
+__device__ __forceinline__ void load_frags(const char *la, const char *lb, int ks, bf16x8 (&a)[4], bf16x8 (&b)[4], int wm, int wn, int lane)
 {
 #pragma unroll
-    for (int ks = 0; ks < 4; ks++) {
-        bf16x8 a[4], b[4];
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            if (A_KC) {
-                a[i] = *(const bf16x8 *)(la + kc_frag_off(wm * 128 + i * 32 + (lane & 31), ks, lane));
-            } else {
-                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off(wm * 128 + i * 32, ks, lane, 0)));
-                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off(wm * 128 + i * 32, ks, lane, 1)));
-                short4v *dst = (short4v *)&a[i];
-                dst[0] = lo; dst[1] = hi;
-            }
+    for (int i = 0; i < 4; i++) {
+        if (A_KC) {
+            a[i] = *(const bf16x8 *)(la + kc_frag_off(wm * 128 + i * 32 + (lane & 31), ks, lane));
+        } else {
+            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off(wm * 128 + i * 32, ks, lane, 0)));
+            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off(wm * 128 + i * 32, ks, lane, 1)));
+            short4v *dst = (short4v *)&a[i];
+            dst[0] = lo; dst[1] = hi;
         }
+    }
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
-            if (B_KC) {
-                b[j] = *(const bf16x8 *)(lb + kc_frag_off(wn * 128 + j * 32 + (lane & 31), ks, lane));
-            } else {
-                short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off(wn * 128 + j * 32, ks, lane, 0)));
-                short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off(wn * 128 + j * 32, ks, lane, 1)));
-                short4v *dst = (short4v *)&b[j];
-                dst[0] = lo; dst[1] = hi;
-            }
+    for (int j = 0; j < 4; j++) {
+        if (B_KC) {
+            b[j] = *(const bf16x8 *)(lb + kc_frag_off(wn * 128 + j * 32 + (lane & 31), ks, lane));
+        } else {
+            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off(wn * 128 + j * 32, ks, lane, 0)));
+            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off(wn * 128 + j * 32, ks, lane, 1)));
+            short4v *dst = (short4v *)&b[j];
+            dst[0] = lo; dst[1] = hi;
         }
-#pragma unroll
-        for (int i = 0; i < 4; i++)
-#pragma unroll
-            for (int j = 0; j < 4; j++)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
 }
 
-template <bool A_KC, bool B_KC>
+// MFMAs of one k-step for rows [I0, I1) of this wave's 4x4 grid of 32x32 tiles.
+template <int I0, int I1>
+__device__ __forceinline__ void mfma_rows(const bf16x8 (&a)[4], const bf16x8 (&b)[4], f32x16 (&acc)[4][4])
+{
+#pragma unroll
+    for (int i = I0; i < I1; i++)
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+}
+
+template <bool A_KC, bool B_KC, bool ODD>
 __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p)
 {
     // Two separate LDS objects, one per stage: the compiler can then tell that the fragment reads of one
@@ -194,17 +187,22 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
     sa.init(p.m, m0, p.M, p.k.s0[kin], wave, lane);
     sb.init(p.n, n0, p.N, p.k.s1[kin], wave, lane);
 
-    // issues the 16 direct loads of the stage that starts at k0 into the LDS stage at `dst`
-    auto issue = [&](int64_t k0, char *dst) {
+    // uniform source pointers of the stage that starts at k0
+    auto stage_ptrs = [&](int64_t k0, const char *&ga, const char *&gb) {
         int64_t ka, kb;
-        decode_group2(p.k, k0, ka, kb);                // uniform: offset of the run's first k in X and in Y
-        const char *ga = xb + ka * 2, *gb = yb + kb * 2;
+        decode_group2(p.k, k0, ka, kb);                // offset of the run's first k in X and in Y
+        ga = xb + ka * 2;
+        gb = yb + kb * 2;
+    };
+    // issues the 16 direct loads of a stage into the LDS stage at `dst`: uniform base + 32-bit lane offset
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    auto issue = [&](const char *ga, const char *gb, char *dst) {
 #pragma unroll
         for (int i = 0; i < 8; i++)
-            __builtin_amdgcn_global_load_lds(EG_GLB(ga + sa.byte_off(i)), EG_LDS(dst + (4 * i + wave) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(EG_GLB(ga + sa.boff[i]), EG_LDS(dst + (4 * i + wave_u) * 1024), 16, 0, 0);
 #pragma unroll
         for (int i = 0; i < 8; i++)
-            __builtin_amdgcn_global_load_lds(EG_GLB(gb + sb.byte_off(i)), EG_LDS(dst + TILE_BYTES + (4 * i + wave) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(EG_GLB(gb + sb.boff[i]), EG_LDS(dst + TILE_BYTES + (4 * i + wave_u) * 1024), 16, 0, 0);
     };
 
     f32x16 acc[4][4];
@@ -215,24 +213,63 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
+    // Software pipeline.  Fragment registers alternate between two sets (f0 = a0/b0, f1 = a1/b1).  Each k-step
+    // issues its first 4 MFMAs, then the LDS reads of the next k-step, then its other 12 MFMAs, so the reads
+    // return while the matrix pipe is busy.  The last k-step of a stage runs after the barrier, together with
+    // the direct loads of the stage after next and the first fragment reads of the next stage.
+    // sched_barrier pins this order against the compiler's own scheduling.
     const int64_t nk = p.K / BK;
-    issue(0, lds0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);               // vmcnt(0): this wave's deposits have landed
+    bf16x8 a0[4], b0[4], a1[4], b1[4];
+#define EG_PIN() __builtin_amdgcn_sched_barrier(0)
+#define EG_KSTEP(FA, FB, NA, NB, BUF, KS_NEXT)                                                    \
+    mfma_rows<0, 1>(FA, FB, acc); EG_PIN();                                                       \
+    load_frags<A_KC, B_KC>(BUF, BUF + TILE_BYTES, KS_NEXT, NA, NB, wm, wn, lane); EG_PIN();       \
+    mfma_rows<1, 4>(FA, FB, acc); EG_PIN();
+#define EG_STAGE_NEXT(C, O, HAS_NEXT2, K_NEXT2) /* one stage; its successor is already in flight into O */ \
+    do {                                                                                          \
+        mfma_rows<0, 1>(a0, b0, acc); EG_PIN();                                                   \
+        stage_ptrs((HAS_NEXT2) ? (K_NEXT2) : 0, ga2, gb2);   /* scalar work rides under the MFMAs */ \
+        load_frags<A_KC, B_KC>(C, C + TILE_BYTES, 1, a1, b1, wm, wn, lane); EG_PIN();             \
+        mfma_rows<1, 4>(a0, b0, acc); EG_PIN();                                                   \
+        EG_KSTEP(a1, b1, a0, b0, C, 2)                                                            \
+        EG_KSTEP(a0, b0, a1, b1, C, 3)                                                            \
+        __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): this wave's deposits for O landed */     \
+        __syncthreads();                    /* everybody's landed; everybody has left C */        \
+        EG_PIN();                                                                                 \
+        mfma_rows<0, 1>(a1, b1, acc); EG_PIN();                                                   \
+        if (HAS_NEXT2) issue(ga2, gb2, C);                                                        \
+        load_frags<A_KC, B_KC>(O, O + TILE_BYTES, 0, a0, b0, wm, wn, lane); EG_PIN();             \
+        mfma_rows<1, 4>(a1, b1, acc); EG_PIN();                                                   \
+    } while (0)
+    // Every stage, the last one included, runs the same straight-line code (the last one pays for one idle
+    // barrier and twelve unused fragment reads): an MFMA under a branch inside the loop would make the
+    // compiler shuffle the 256 accumulator registers.  The stage count's parity is a template parameter.
+    const char *ga2, *gb2;
+    stage_ptrs(0, ga2, gb2);
+    issue(ga2, gb2, lds0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
-    for (int64_t kt = 0; kt + 1 < nk; kt += 2) {
-        issue((kt + 1) * BK, lds1);
-        compute_stage<A_KC, B_KC>(lds0, lds0 + TILE_BYTES, acc, wm, wn, lane);
-        __builtin_amdgcn_s_waitcnt(0x0F70);           // the next stage's deposits of this wave have landed
-        __syncthreads();                              // ... and everybody's; everybody is done reading lds0
-        if (kt + 2 < nk) issue((kt + 2) * BK, lds0);
-        compute_stage<A_KC, B_KC>(lds1, lds1 + TILE_BYTES, acc, wm, wn, lane);
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();
+    if (nk > 1) {
+        stage_ptrs(BK, ga2, gb2);
+        issue(ga2, gb2, lds1);
     }
-    if (nk & 1) {                                      // odd number of stages: the last one sits in lds0
-        compute_stage<A_KC, B_KC>(lds0, lds0 + TILE_BYTES, acc, wm, wn, lane);
-        __syncthreads();
+    load_frags<A_KC, B_KC>(lds0, lds0 + TILE_BYTES, 0, a0, b0, wm, wn, lane);
+    if (ODD) {
+        EG_STAGE_NEXT(lds0, lds1, 2 < nk, 2 * BK);
+        for (int64_t st = 1; st < nk; st += 2) {
+            EG_STAGE_NEXT(lds1, lds0, st + 2 < nk, (st + 2) * BK);
+            EG_STAGE_NEXT(lds0, lds1, st + 3 < nk, (st + 3) * BK);
+        }
+    } else {
+        for (int64_t st = 0; st < nk; st += 2) {
+            EG_STAGE_NEXT(lds0, lds1, st + 2 < nk, (st + 2) * BK);
+            EG_STAGE_NEXT(lds1, lds0, st + 3 < nk, (st + 3) * BK);
+        }
     }
+    __syncthreads();
+#undef EG_STAGE_NEXT
+#undef EG_KSTEP
+#undef EG_PIN
 
     // ---- epilogue ---------------------------------------------------------------------------------
     // Z offsets of the tile's 256 rows and 256 columns go through LDS (free now): one decode per thread.
@@ -278,14 +315,20 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
     }
 }
 
-template <bool A_KC, bool B_KC>
+template <bool A_KC, bool B_KC, bool ODD>
 static int launch_one(ContractParams &p, void *stream)
 {
     const int64_t wgs = p.n_tuples * p.n_batch * p.tiles_m * p.tiles_n;
-    hipLaunchKernelGGL((k_contract_dma<A_KC, B_KC>), dim3((unsigned)wgs), dim3(THREADS), 0, (hipStream_t)stream, p);
+    hipLaunchKernelGGL((k_contract_dma<A_KC, B_KC, ODD>), dim3((unsigned)wgs), dim3(THREADS), 0, (hipStream_t)stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(EG_ERR_HIP, "k_contract_dma launch failed: %s", hipGetErrorString(e));
     return EG_OK;
+}
+
+template <bool A_KC, bool B_KC>
+static int launch_parity(ContractParams &p, void *stream)
+{
+    return ((p.K / BK) & 1) ? launch_one<A_KC, B_KC, true>(p, stream) : launch_one<A_KC, B_KC, false>(p, stream);
 }
 
 }  // namespace dma
@@ -312,8 +355,8 @@ int launch_contract_dma(ContractParams &p, void *stream)
     p.tiles_n = (int32_t)((p.N + dma::BN - 1) / dma::BN);
     const int64_t wgs = p.n_tuples * p.n_batch * p.tiles_m * p.tiles_n;
     if (wgs < 1 || wgs >= (1ll << 31)) return fail(EG_ERR_LIMIT, "contraction needs %lld workgroups", (long long)wgs);
-    if (p.a_kcontig) return p.b_kcontig ? dma::launch_one<true, true>(p, stream) : dma::launch_one<true, false>(p, stream);
-    return p.b_kcontig ? dma::launch_one<false, true>(p, stream) : dma::launch_one<false, false>(p, stream);
+    if (p.a_kcontig) return p.b_kcontig ? dma::launch_parity<true, true>(p, stream) : dma::launch_parity<true, false>(p, stream);
+    return p.b_kcontig ? dma::launch_parity<false, true>(p, stream) : dma::launch_parity<false, false>(p, stream);
 }
 
 }  // namespace eg
