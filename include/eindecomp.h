@@ -219,6 +219,16 @@ int tr_profile_count(eg_graph *g);
  * synchronised the stream.  Host outputs, any may be NULL. */
 int tr_profile_get(eg_graph *g, int i, int *vertex, int *stage, int *kernel, float *ms);
 
+/* ---- Measured ceilings of the machine (context for roofline reports; not part of the einsum path) ------- */
+
+/* Enqueues a register-resident loop of bf16 32x32x16 MFMAs (no memory traffic): `waves_per_simd` (1 or 2)
+ * waves on each SIMD of `cus` compute units, iters*8 MFMAs per wave.  sink: device, >= 4 bytes, never
+ * written.  *flops (host) receives the launch's operation count; the caller times it. */
+int eg_ceiling_mfma_bf16(void *sink, int cus, int waves_per_simd, int iters, double *flops, void *hip_stream);
+
+/* Enqueues a plain device-to-device copy of `bytes` (multiple of 16; dst/src device, 16-byte aligned). */
+int eg_ceiling_copy(void *dst, const void *src, int64_t bytes, void *hip_stream);
+
 /* Message for the last error on this thread (host, valid until the next failing call on the thread). */
 const char *eg_last_error(void);
 

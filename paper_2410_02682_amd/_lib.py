@@ -6,7 +6,7 @@ import ctypes
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libeindecomp.so")
+LIB_PATH = os.environ.get("EINDECOMP_LIB") or os.path.join(HERE, "libeindecomp.so")   # override: an alternate build of the same ABI
 
 EG_MAX_RANK = 8
 EG_MAX_LABELS = 12
@@ -56,6 +56,8 @@ EXPORTS = {
     "tr_profile_count": (ctypes.c_int, [ctypes.c_void_p]),
     "tr_profile_get": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int),
                                       ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]),
+    "eg_ceiling_mfma_bf16": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]),
+    "eg_ceiling_copy": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]),
     "eg_last_error": (ctypes.c_char_p, []),
 }
 

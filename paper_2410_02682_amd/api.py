@@ -147,3 +147,14 @@ def tr_profile_read(g) -> List[dict]:
         _check(lib.tr_profile_get(g, i, ctypes.byref(v), ctypes.byref(s), ctypes.byref(k), ctypes.byref(ms)))
         out.append(dict(vertex=v.value, stage="join" if s.value == 0 else "aggregate", kernel=KERNEL_NAMES[k.value], ms=ms.value))
     return out
+
+
+def eg_ceiling_mfma_bf16(sink_ptr: int, cus: int, waves_per_simd: int, iters: int, stream: int = 0) -> float:
+    """Enqueues the register-resident MFMA loop; returns its operation count (the caller times it)."""
+    fl = ctypes.c_double()
+    _check(_lib.load().eg_ceiling_mfma_bf16(ctypes.c_void_p(sink_ptr), cus, waves_per_simd, iters, ctypes.byref(fl), ctypes.c_void_p(stream)))
+    return fl.value
+
+
+def eg_ceiling_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:
+    _check(_lib.load().eg_ceiling_copy(ctypes.c_void_p(dst_ptr), ctypes.c_void_p(src_ptr), nbytes, ctypes.c_void_p(stream)))

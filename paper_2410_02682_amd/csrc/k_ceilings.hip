@@ -1,0 +1,63 @@
+// Measured ceilings of the box, reported next to the datasheet peaks: a register-resident bf16 MFMA loop
+// (no memory traffic at all) and a plain 16-byte-per-lane copy.  Neither is part of the einsum path.
+#include <hip/hip_runtime.h>
+
+#include "eg_internal.h"
+
+namespace eg {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__global__ __launch_bounds__(256) void k_mfma_ceiling(float *sink, int iters)
+{
+    bf16x8 a, b;
+    for (int i = 0; i < 8; i++) { a[i] = (__bf16)(float)(threadIdx.x & 3); b[i] = (__bf16)(float)(i & 1); }
+    f32x16 acc[8];
+    for (int t = 0; t < 8; t++)
+        for (int r = 0; r < 16; r++) acc[t][r] = 0.f;
+    for (int it = 0; it < iters; it++) {
+#pragma unroll
+        for (int t = 0; t < 8; t++) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[t], 0, 0, 0);
+    }
+    float s = 0.f;
+    for (int t = 0; t < 8; t++)
+        for (int r = 0; r < 16; r++) s += acc[t][r];
+    if (s == -1.f) sink[0] = s;      // never true: keeps the loop alive
+}
+
+__global__ __launch_bounds__(256) void k_copy_ceiling(uint4 *dst, const uint4 *src, int64_t n16)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+}  // namespace eg
+
+extern "C" {
+
+// Launches `waves_per_simd` waves on every SIMD of `cus` compute units, each issuing iters*8 independent
+// 32x32x16 bf16 MFMAs from registers.  *flops receives the floating-point operation count of the launch.
+// sink: device, at least 4 bytes (never written).
+int eg_ceiling_mfma_bf16(void *sink, int cus, int waves_per_simd, int iters, double *flops, void *hip_stream)
+{
+    if (!sink || !flops) return eg::fail(EG_ERR_NULL, "eg_ceiling_mfma_bf16: NULL argument");
+    if (cus < 1 || waves_per_simd < 1 || waves_per_simd > 2 || iters < 1) return eg::fail(EG_ERR_LIMIT, "eg_ceiling_mfma_bf16: bad launch shape");
+    const int wgs = cus * waves_per_simd;
+    hipLaunchKernelGGL(eg::k_mfma_ceiling, dim3(wgs), dim3(256), 0, (hipStream_t)hip_stream, (float *)sink, iters);
+    if (hipGetLastError() != hipSuccess) return eg::fail(EG_ERR_HIP, "k_mfma_ceiling launch failed");
+    *flops = (double)wgs * 4.0 * iters * 8.0 * (2.0 * 32 * 32 * 16);
+    return EG_OK;
+}
+
+// Copies `bytes` (a multiple of 16, both pointers 16-byte aligned, device) with a grid-stride loop.
+int eg_ceiling_copy(void *dst, const void *src, int64_t bytes, void *hip_stream)
+{
+    if (!dst || !src) return eg::fail(EG_ERR_NULL, "eg_ceiling_copy: NULL argument");
+    if (bytes < 16 || bytes % 16 || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return eg::fail(EG_ERR_LIMIT, "eg_ceiling_copy: size/alignment");
+    hipLaunchKernelGGL(eg::k_copy_ceiling, dim3(256 * 16), dim3(256), 0, (hipStream_t)hip_stream, (uint4 *)dst, (const uint4 *)src, bytes / 16);
+    if (hipGetLastError() != hipSuccess) return eg::fail(EG_ERR_HIP, "k_copy_ceiling launch failed");
+    return EG_OK;
+}
+
+}  // extern "C"
