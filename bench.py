@@ -1,11 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the tensor-relational einsum hot path on one MI355X.
 
-A step is one pass of the whole path over one batch of synthetic input: tr_execute of the
-matrix-chain graph (A.B).C with i=j=k=l=8192, bf16 storage, fp32 accumulation, the first product
-cut (2,2,2) and the second (1,2,4): two joins of 8 block contractions each on MFMA, each followed
-by the aggregation of two fp32 partial slabs, with a repartition of A.B in between.  Inputs are
-resident in HBM before the timed region.  Prints one JSON line.
+A step is one pass of the whole path over one batch of synthetic input: tr_execute of a workload graph,
+i.e. for every vertex the join kernel over all block tuples and, where a contracted label is partitioned,
+the aggregation of the fp32 partial slabs.  The default workload is the matrix chain (A.B).C with
+i=j=k=l=8192, bf16 storage, fp32 accumulation, first product cut (2,2,2), second cut (1,2,4) (so a
+repartition of A.B sits between them).  Inputs are resident in HBM before the timed region.
+Prints one JSON line.
 """
 import argparse
 import json
@@ -17,29 +18,82 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
-PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA (datasheet)
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E (datasheet)
+DEFAULT_PART = {1: "d222", 2: "mix", 3: "batch8", 4: "heads8", 5: "k16"}
+# HBM bytes per launch of the dominant kernel of the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
+# (see profiles/); None until measured for the chosen workload.
+MEASURED_TRAFFIC = {("c2", "mix"): None}
 
 
-def cpu_baseline(w, inp, budget_s=15.0):
-    """Times the oracle as it stands on a bounded sample: R rows of the first product at full reduction length."""
+def prod(xs):
+    p = 1
+    for x in xs:
+        p *= int(x)
+    return p
+
+
+def cpu_baseline(w, dev, budget_s=15.0):
+    """Times the oracle as it stands on a bounded sample: R rows of the first contraction at full reduction length."""
     import numpy as np
+    import torch
     from oracle.einsum_ref import einsum_ref
-    A, B = inp["A"].data, inp["B"].data
-    j, k = B.shape
+    from synth_inputs.workloads import parse_spec
+    v = next(v for v in w.einsum_vertices() if v.otimes == "mul" and v.oplus == "sum" and len(v.inputs) == 2
+             and all(w.vertex(i).is_input for i in v.inputs))
+
+    def host(t):
+        t = t.detach().contiguous().cpu()
+        return t.view(torch.int16).numpy().view(np.uint16) if t.dtype == torch.bfloat16 else t.numpy()
+
+    X, Y = host(dev[v.inputs[0]]), host(dev[v.inputs[1]])
+    lX, lY, lZ = parse_spec(v.spec)
+    per_row = 2.0 * prod(X.shape[1:]) * prod(n for l, n in zip(lY, Y.shape) if l not in lX)
 
     def run(rows):
         t0 = time.perf_counter()
-        einsum_ref("ij,jk->ik", A[:rows], B, out_dtype="bf16", x_dtype="bf16", y_dtype="bf16")
+        einsum_ref(v.spec, X[:rows], Y, out_dtype=v.dtype)
         return time.perf_counter() - t0
 
-    t = run(8)                                        # calibration
-    rows = int(max(8, min(A.shape[0], 8 * budget_s / max(t, 1e-3))))
+    r0 = max(1, min(X.shape[0], 4))
+    t = run(r0)
+    rows = int(max(r0, min(X.shape[0], r0 * budget_s / max(t, 1e-3))))
     t = run(rows)
-    flops = 2.0 * rows * j * k
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return {"value": flops / t / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": f"{rows} of {A.shape[0]} rows of A.B at full reduction length {j} (einsum_ref, double accumulation), {t:.1f} s"}
+    return {"value": per_row * rows / t / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": f"vertex {v.name} '{v.spec}': {rows} of {X.shape[0]} outer rows at full reduction length "
+                      f"(einsum_ref loop nest, double accumulation), {t:.1f} s"}
+
+
+def ceilings():
+    """Measured ceilings of this machine: register-resident bf16 MFMA loop and a plain copy."""
+    import torch
+    import paper_2410_02682_amd as E
+    s = torch.cuda.current_stream().cuda_stream
+    sink = torch.zeros(16, device="cuda")
+    out = {}
+    for wps in (1, 2):
+        E.eg_ceiling_mfma_bf16(sink.data_ptr(), 256, wps, 2000, s)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fl = E.eg_ceiling_mfma_bf16(sink.data_ptr(), 256, wps, 20000, s)
+        b.record()
+        torch.cuda.synchronize()
+        out[f"mfma_bf16_{wps}_wave_per_simd_tflops"] = fl / a.elapsed_time(b) / 1e9
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    E.eg_ceiling_copy(dst.data_ptr(), src.data_ptr(), n, s)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(5):
+        E.eg_ceiling_copy(dst.data_ptr(), src.data_ptr(), n, s)
+    b.record()
+    torch.cuda.synchronize()
+    out["copy_read_plus_write_gbs"] = 2 * n * 5 / a.elapsed_time(b) / 1e6
+    return out
 
 
 def main():
@@ -47,9 +101,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--partitioning", default="mix")
-    ap.add_argument("--size", type=int, default=8192, help="side of every matrix in the chain")
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5], help="workload (2 = the matrix chain the metric is quoted on)")
+    ap.add_argument("--partitioning", default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -57,21 +112,38 @@ def main():
 
     import torch
     import paper_2410_02682_amd as E
-    from paper_2410_02682_amd.runner import GraphRunner, to_device
-    from synth_inputs import build_config
-    from synth_inputs.prng import make_tensor
+    from paper_2410_02682_amd.runner import GraphRunner
+    from synth_inputs import build_config, prng_torch
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    n = args.size
-    w = build_config(2, dims={"i": n, "j": n, "k": n, "l": n})
-    inp = {v.name: make_tensor(v.recipe, v.bound, v.dtype, w.seed, w.tensor_id(v.name)) for v in w.vertices if v.is_input}
-    r = GraphRunner(w, args.partitioning)
-    r.bind({k: to_device(t) for k, t in inp.items()})
+    w = build_config(args.config)
+    pname = args.partitioning or DEFAULT_PART[args.config]
+    dev = {v.name: prng_torch.make_tensor(v.recipe, v.bound, v.dtype, w.seed, w.tensor_id(v.name)) for v in w.vertices if v.is_input}
+    r = GraphRunner(w, pname)
+    r.bind(dev)
     stream = torch.cuda.current_stream()
     for _ in range(args.warmup):
         r.run(stream)
     torch.cuda.synchronize()
-    launches_per_step = sum(2 if r.plan(v.name)["n_agg"] > 1 else 1 for v in w.einsum_vertices())
+
+    # per-vertex accounting: flops of contractions, algorithmic bytes of every launch
+    esz = {"f32": 4, "bf16": 2}
+    acct = {}
+    launches_per_step = 0
+    for v in w.einsum_vertices():
+        pl = r.plan(v.name)
+        nz = prod(pl["bound_z"])
+        in_bytes = sum(prod(w.vertex(i).bound if w.vertex(i).is_input else r.plan(i)["bound_z"]) * esz[w.vertex(i).dtype] for i in v.inputs)
+        partial = pl["n_agg"] > 1
+        join_out = pl["n_agg"] * nz * 4 if partial else nz * esz[v.dtype]
+        acct[r.vid[v.name]] = {
+            "name": v.name, "kind": pl["kernel"],
+            "flops": 2.0 * prod(pl["bound"]) if pl["kernel"] == "contract_mfma" else 0.0,
+            "join_bytes": in_bytes + join_out,
+            "agg_bytes": (pl["n_agg"] * nz * 4 + nz * esz[v.dtype]) if partial else 0,
+        }
+        launches_per_step += 2 if partial else 1
+
     E.tr_profile_enable(r.g, launches_per_step * args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -81,38 +153,49 @@ def main():
     t1 = time.perf_counter()
     rec = E.tr_profile_read(r.g)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    flops_per_step = 2.0 * 2.0 * n * n * n
+    flops_per_step = sum(a["flops"] for a in acct.values())
     value = flops_per_step / (ms_per_step * 1e-3) / 1e12
 
-    # dominant kernel: the block-contraction join (one launch = all 8 block products of one vertex)
-    join_ms = [x["ms"] for x in rec if x["stage"] == "join"]
-    agg_ms = [x["ms"] for x in rec if x["stage"] == "aggregate"]
-    avg_join = sum(join_ms) / max(1, len(join_ms))
-    achieved = 2.0 * n * n * n / (avg_join * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "k_contract (bf16 MFMA block contraction, 8 tuples per launch)",
-                "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                "avg_launch_ms": avg_join, "traffic": None}
-    extra = {}
-    if agg_ms:
-        # aggregation: n_agg fp32 slabs read + one output written per launch (bf16 for A.B, fp32 for the result)
-        byts = []
-        for v in w.einsum_vertices():
-            pl = r.plan(v.name)
-            if pl["n_agg"] > 1:
-                byts.append(pl["n_agg"] * n * n * 4 + n * n * (2 if v.dtype == "bf16" else 4))
-        per = [b / (m * 1e-3) / 1e9 for b, m in zip(byts * args.steps, agg_ms)]
-        avg = sum(per) / len(per)
-        extra["aggregate"] = {"bound": "hbm", "achieved": avg, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": avg / PEAK_HBM_GBS,
-                              "avg_launch_ms": sum(agg_ms) / len(agg_ms)}
-    out = {"metric": "einsum-graph TFLOP/s (contractions), % of roofline", "value": value, "unit": "TFLOP/s", "n_gpus": 1,
-           "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-           "config": {"workload": f"{w.name}: (A.B).C, all sides {n}, bf16 in / fp32 accumulate, partitioning '{args.partitioning}' "
-                                  f"({json.dumps(r.part)})"},
-           "roofline": roofline, "other_kernels": extra}
+    # aggregate the recorded launches by kernel family
+    fam = {}
+    for x in rec:
+        a = acct[x["vertex"]]
+        key = "aggregate" if x["stage"] == "aggregate" else a["kind"]
+        f = fam.setdefault(key, {"ms": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0})
+        f["ms"] += x["ms"]
+        f["launches"] += 1
+        if x["stage"] == "aggregate":
+            f["bytes"] += a["agg_bytes"]
+        else:
+            f["flops"] += a["flops"]
+            f["bytes"] += a["join_bytes"]
+    kernels = {}
+    for key, f in fam.items():
+        k = {"launches_per_step": f["launches"] // args.steps, "avg_launch_ms": f["ms"] / f["launches"],
+             "share_of_step": f["ms"] / args.steps / ms_per_step}
+        if key == "contract_mfma":
+            k.update({"bound": "mfma", "achieved": f["flops"] / (f["ms"] * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"})
+        else:
+            k.update({"bound": "hbm", "achieved": f["bytes"] / (f["ms"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"})
+        k["frac"] = k["achieved"] / k["peak"]
+        kernels[key] = k
+
+    dom = "contract_mfma" if "contract_mfma" in kernels else max(kernels, key=lambda k: kernels[k]["share_of_step"])
+    roofline = dict(kernels[dom])
+    roofline["kernel"] = {"contract_mfma": "k_contract_dma / k_contract (block contraction on MFMA, all tuples of a vertex per launch)",
+                          "aggregate": "k_aggregate_vec4", "map": "k_map", "reduce_row": "k_reduce_row", "generic": "k_generic"}[dom]
+    roofline["traffic"] = MEASURED_TRAFFIC.get((f"c{args.config}", pname))
+    out = {"metric": "einsum-graph TFLOP/s (contractions) + GB/s (maps/aggregations), % of roofline", "value": value,
+           "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32" if args.config == 1 else "bf16", "data": "synthetic",
+           "config": {"workload": f"{w.name} dims {json.dumps(w.dims)}, partitioning '{pname}': {json.dumps(r.part)}"},
+           "roofline": roofline, "kernels": kernels}
     r.close()
+    if not args.no_ceilings:
+        out["measured_ceilings"] = ceilings()
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, inp)
+        out["cpu_baseline"] = cpu_baseline(w, dev)
     print(json.dumps(out))
 
 
