@@ -9,13 +9,22 @@ namespace eg {
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
-// fp32 -> bf16, round to nearest, ties to even; infinities pass through, NaN stays NaN.
+// fp32 -> bf16, round to nearest, ties to even (the hardware conversion of gfx950).
 __device__ __forceinline__ uint16_t f32_to_bf16(float f)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7f800000u) == 0x7f800000u) return (uint16_t)((u >> 16) | ((u & 0xffffu) ? 0x40u : 0u));
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    __bf16 h = (__bf16)f;
+    return *(uint16_t *)&h;
+}
+
+typedef __bf16 eg_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float eg_f32x2 __attribute__((ext_vector_type(2)));
+
+// two fp32 -> one dword holding two bf16 (a in the low half)
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b)
+{
+    eg_f32x2 v = {a, b};
+    eg_bf16x2 r = __builtin_convertvector(v, eg_bf16x2);
+    return *(uint32_t *)&r;
 }
 
 __device__ __forceinline__ float load_elem(const void *p, int dt, int64_t off)
@@ -49,10 +58,10 @@ __device__ __forceinline__ void store8(void *p, int dt, int64_t off, const float
 {
     if (dt == EG_BF16) {
         uint4 r;
-        r.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-        r.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
-        r.z = (uint32_t)f32_to_bf16(v[4]) | ((uint32_t)f32_to_bf16(v[5]) << 16);
-        r.w = (uint32_t)f32_to_bf16(v[6]) | ((uint32_t)f32_to_bf16(v[7]) << 16);
+        r.x = pack_bf16x2(v[0], v[1]);
+        r.y = pack_bf16x2(v[2], v[3]);
+        r.z = pack_bf16x2(v[4], v[5]);
+        r.w = pack_bf16x2(v[6], v[7]);
         *(uint4 *)((uint16_t *)p + off) = r;
     } else {
         *(float4 *)((float *)p + off) = make_float4(v[0], v[1], v[2], v[3]);
@@ -61,25 +70,39 @@ __device__ __forceinline__ void store8(void *p, int dt, int64_t off, const float
 }
 
 // The scalar function (x) of a vertex (Section 3 of the paper: any scalar function of the joined values).
-__device__ __forceinline__ float otimes_eval(int op, float x, float y, float alpha)
+// OP >= 0 fixes the function at compile time; OP = -1 reads it from `op`.  FAST selects the hardware
+// exponential (relative error about |x| * 6e-8) and reciprocal (1 ulp), used only where the result is
+// stored as bf16.
+template <int OP, bool FAST>
+__device__ __forceinline__ float otimes_t(int op, float x, float y, float alpha)
 {
-    switch (op) {
+    const int o = OP >= 0 ? OP : op;
+    switch (o) {
     case EG_MUL: return alpha * (x * y);
     case EG_ADD: return alpha * x + y;
     case EG_SUB: return alpha * (x - y);
-    case EG_DIV: return x / y;
+    case EG_DIV: return FAST ? x * __frcp_rn(y) : x / y;
     case EG_SQDIFF: return (x - y) * (x - y);
     case EG_ABSDIFF: return fabsf(x - y);
-    case EG_EXP_SUB: return expf(x - y);
+    case EG_EXP_SUB: return FAST ? __expf(x - y) : expf(x - y);
     case EG_RELU_GRAD: return y > 0.f ? x : 0.f;
-    case EG_SILU_MUL: return (x / (1.f + expf(-x))) * y;
+    case EG_SILU_MUL: return (x / (1.f + (FAST ? __expf(-x) : expf(-x)))) * y;
     case EG_IDENT: return x;
     case EG_SCALE: return alpha * x;
     case EG_RELU: return x > 0.f ? x : 0.f;
-    case EG_EXP: return expf(x);
+    case EG_EXP: return FAST ? __expf(x) : expf(x);
     case EG_LOG: return logf(x);
     default: return 0.f;
     }
+}
+
+__device__ __forceinline__ float otimes_eval(int op, float x, float y, float alpha) { return otimes_t<-1, false>(op, x, y, alpha); }
+
+template <int OPLUS>
+__device__ __forceinline__ float oplus_t(int oplus, float a, float b)
+{
+    const int o = OPLUS >= 0 ? OPLUS : oplus;
+    return o == EG_AGG_MAX ? fmaxf(a, b) : a + b;
 }
 
 __device__ __forceinline__ float oplus_identity(int oplus) { return oplus == EG_AGG_MAX ? -INFINITY : 0.f; }

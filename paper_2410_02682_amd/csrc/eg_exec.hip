@@ -62,22 +62,29 @@ static LabelInfo label_info(const Vertex &v, const Operand &X, const Operand *Y,
     return li;
 }
 
+// Only partitioned labels (d > 1) enter the device-side tuple space: the others have key 0 in every tuple,
+// and the kernels pay scalar instructions per entry.  Row-major order over the kept labels is unchanged.
 static TupleSpace tuple_space(const Vertex &v, const LabelInfo &li)
 {
     TupleSpace ts;
     memset(&ts, 0, sizeof ts);
-    ts.n = li.nl;
-    for (int l = 0; l < li.nl; l++) {
-        ts.d[l] = v.d[l];
-        ts.step_x[l] = li.ext[l] * li.sx[l];
-        ts.step_y[l] = li.ext[l] * li.sy[l];
-        ts.step_z[l] = li.ext[l] * li.sz[l];
-    }
+    int32_t aggw[kMaxLabels] = {0};
     int64_t w = 1;
     for (int i = (int)v.agg.size() - 1; i >= 0; i--) {
-        ts.agg_w[v.agg[i]] = (int32_t)w;
+        aggw[v.agg[i]] = (int32_t)w;
         w *= v.d[v.agg[i]];
     }
+    int n = 0;
+    for (int l = 0; l < li.nl; l++) {
+        if (v.d[l] <= 1) continue;
+        ts.d[n] = v.d[l];
+        ts.step_x[n] = li.ext[l] * li.sx[l];
+        ts.step_y[n] = li.ext[l] * li.sy[l];
+        ts.step_z[n] = li.ext[l] * li.sz[l];
+        ts.agg_w[n] = aggw[l];
+        n++;
+    }
+    ts.n = n;
     return ts;
 }
 
@@ -243,8 +250,20 @@ struct Routed {
     GenericParams gp;
 };
 
+// How many pieces the reduction range of every output is cut into when a row reduction has too few
+// outputs to fill the chip: each piece becomes one more partial slab for the aggregation kernel.
+static int reduce_split(int64_t outs_total, int64_t red_elems)
+{
+    if (outs_total >= 1024 || red_elems < 32768) return 1;
+    int64_t s = (1024 + outs_total - 1) / outs_total;
+    if (s > red_elems / 8192) s = red_elems / 8192;
+    if (s > 64) s = 64;
+    return s < 1 ? 1 : (int)s;
+}
+
+// split: 0 = decide here (dry run), otherwise the value fixed when the workspace was laid out
 static int route(const Vertex &v, const Operand &X, const Operand *Y, const std::vector<int64_t> &zstride,
-                 const OutSpec &out, Routed &r)
+                 const OutSpec &out, Routed &r, int split = 0)
 {
     LabelInfo li = label_info(v, X, Y, zstride);
     TupleSpace ts = tuple_space(v, li);
@@ -324,6 +343,7 @@ static int route(const Vertex &v, const Operand &X, const Operand *Y, const std:
                 if (binary && p.zdims.sy[i] % 8) vy = false;
             }
             p.vec = (vx && vy) ? 8 : 1;
+            p.split = split > 0 ? split : reduce_split(p.outs_per_block * n_tuples, p.red_elems);
             r.kind = EG_KERNEL_REDUCE_ROW;
             return EG_OK;
         }
@@ -351,6 +371,7 @@ static int route(const Vertex &v, const Operand &X, const Operand *Y, const std:
 struct Layout {
     std::vector<int64_t> result_off;    // per vertex: byte offset of its tensor in the workspace (-1: not there)
     std::vector<int64_t> partial_off;   // per vertex: byte offset of its partial slabs (-1: none)
+    std::vector<int> split;             // per vertex: extra slabs per aggIdx from a split row reduction (1: none)
     int64_t total = 0;
 };
 
@@ -406,12 +427,15 @@ private:
     int64_t top_ = 0;
 };
 
+static int dry_route(const eg_graph *g, int vertex, Routed &r);
+
 static Layout make_layout(const eg_graph *g)
 {
     const int nv = (int)g->v.size();
     Layout L;
     L.result_off.assign(nv, -1);
     L.partial_off.assign(nv, -1);
+    L.split.assign(nv, 1);
     std::vector<int> last_use(nv, -1);
     for (int i = 0; i < nv; i++)
         for (int k = 0; k < g->v[i].n_in; k++) last_use[g->v[i].in[k]] = i;
@@ -420,8 +444,12 @@ static Layout make_layout(const eg_graph *g)
         const Vertex &v = g->v[i];
         if (v.is_input) continue;
         if (!v.is_output) L.result_off[i] = arena.alloc(numel(v.bound) * dtype_size(v.dtype));
-        if (v.plan.n_agg > 1) {
-            L.partial_off[i] = arena.alloc(v.plan.n_agg * numel(v.bound) * 4);
+        {
+            Routed r;
+            if (dry_route(g, i, r) == EG_OK && r.kind == EG_KERNEL_REDUCE_ROW) L.split[i] = r.rp.split;
+        }
+        if (v.plan.n_agg * L.split[i] > 1) {
+            L.partial_off[i] = arena.alloc(v.plan.n_agg * L.split[i] * numel(v.bound) * 4);
             arena.release(L.partial_off[i]);          // live only while this vertex runs
         }
         for (int k = 0; k < v.n_in; k++) {
@@ -438,8 +466,9 @@ static Layout make_layout(const eg_graph *g)
 
 using namespace eg;
 
-// Kernel family a vertex would use with dense row-major operands (what einsum_graph_plan reports).
-int eg_route_vertex(const eg_graph *g, int vertex)
+// Routing of a vertex with dense row-major operands (what einsum_graph_plan reports and what the workspace
+// layout assumes).
+int eg::dry_route(const eg_graph *g, int vertex, Routed &r)
 {
     const Vertex &v = g->v[vertex];
     static char dummy_buf[64];
@@ -449,8 +478,13 @@ int eg_route_vertex(const eg_graph *g, int vertex)
     if (v.n_in > 1) { Y.ptr = aligned; Y.dtype = g->v[v.in[1]].dtype; Y.stride = dense_strides(g->v[v.in[1]].bound); }
     OutSpec out{aligned, 0, (int32_t)v.dtype};
     if (v.plan.n_agg > 1) { out.slab_elems = numel(v.bound); out.dtype = EG_F32; }
+    return route(v, X, v.n_in > 1 ? &Y : nullptr, dense_strides(v.bound), out, r);
+}
+
+int eg_route_vertex(const eg_graph *g, int vertex)
+{
     Routed r;
-    if (route(v, X, v.n_in > 1 ? &Y : nullptr, dense_strides(v.bound), out, r) != EG_OK) return EG_KERNEL_NONE;
+    if (dry_route(g, vertex, r) != EG_OK) return EG_KERNEL_NONE;
     return r.kind;
 }
 
@@ -591,7 +625,7 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
     char *ws = (char *)workspace;
 
     // route everything first so that a failure launches nothing
-    struct Step { int vertex; Routed r; bool agg; const void *partials; void *dst; std::vector<int64_t> dst_stride; };
+    struct Step { int vertex; Routed r; bool agg; int64_t slabs; const void *partials; void *dst; std::vector<int64_t> dst_stride; };
     std::vector<Step> steps;
     auto operand_of = [&](int u) {
         Operand o;
@@ -612,7 +646,8 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
         Operand Z = operand_of(i);
         s.dst = (void *)Z.ptr;
         s.dst_stride = Z.stride;
-        s.agg = v.plan.n_agg > 1;
+        s.slabs = v.plan.n_agg * L.split[i];
+        s.agg = s.slabs > 1;
         OutSpec out;
         std::vector<int64_t> zstride;
         if (s.agg) {
@@ -628,8 +663,18 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
             out.dtype = v.dtype;
             zstride = Z.stride;
         }
-        int rc = route(v, X, v.n_in > 1 ? &Y : nullptr, zstride, out, s.r);
+        int rc = route(v, X, v.n_in > 1 ? &Y : nullptr, zstride, out, s.r, L.split[i]);
         if (rc) return rc;
+        if (L.split[i] > 1 && s.r.kind != EG_KERNEL_REDUCE_ROW) {
+            // the bound relations' strides sent this vertex to another kernel than the layout assumed:
+            // run it unsplit, writing the tensor directly when nothing else needs aggregating
+            s.slabs = v.plan.n_agg;
+            s.agg = s.slabs > 1;
+            if (!s.agg) { out.ptr = s.dst; out.slab_elems = 0; out.dtype = v.dtype; zstride = Z.stride; }
+            rc = route(v, X, v.n_in > 1 ? &Y : nullptr, zstride, out, s.r, 1);
+            if (rc) return rc;
+        }
+        if (s.r.kind == EG_KERNEL_REDUCE_ROW && s.r.rp.split != L.split[i]) s.r.rp.split = L.split[i];
         steps.push_back(std::move(s));
     }
     hipStream_t st = (hipStream_t)hip_stream;
@@ -651,7 +696,7 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
         if (rc) return rc;
         if (s.agg) {
             rc = timed(s.vertex, 1, EG_KERNEL_NONE, [&] {
-                return aggregate_into(v.oplus, s.partials, v.plan.n_agg, numel(v.bound), s.dst, v.dtype, v.bound, s.dst_stride, hip_stream);
+                return aggregate_into(v.oplus, s.partials, s.slabs, numel(v.bound), s.dst, v.dtype, v.bound, s.dst_stride, hip_stream);
             });
             if (rc) return rc;
         }

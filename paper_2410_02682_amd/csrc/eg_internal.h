@@ -101,6 +101,7 @@ struct ReduceParams {             // Z[z] = oplus over r of otimes(X[z, r], Y[z,
     int64_t n_tuples;
     int64_t outs_per_block;
     int64_t red_elems;            // prod(rdims.ext)
+    int32_t split;                // pieces per output's reduction range (1 = none); piece s lands in slab aggIdx*split+s
 };
 
 struct GenericParams {            // any EinSum: one output element per lane, sequential loop over l_agg

@@ -64,157 +64,233 @@ __global__ __launch_bounds__(kThreads) void k_generic(const GenericParams p)
 }
 
 // ------------------------------------------------------------------------------------------------
-// element-wise map / binary join without aggregated labels; VEC elements per lane along the last dim
+// element-wise map / binary join without aggregated labels; VEC elements per lane along the last dim.
+// grid.x covers one tuple's block (one vector per lane: many small workgroups stream best from HBM),
+// grid.y/z select the tuple, so everything about the tuple is scalar work.
 // ------------------------------------------------------------------------------------------------
-template <int VEC>
+__device__ __forceinline__ int64_t tuple_of_block() { return (int64_t)blockIdx.z * 65535 + blockIdx.y; }
+
+// ROWMODE: the last dim is long, so a workgroup stays inside one row, covers 4 * 256 consecutive vectors of
+// it (four per lane, all loads issued before the first use) and the row's offsets are scalar work computed
+// once; otherwise every lane decodes its own flat index and handles one vector.
+template <int VEC, int OP, bool FAST, bool ROWMODE>
 __global__ __launch_bounds__(kThreads) void k_map(const MapParams p)
 {
-    const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (gid >= p.n_tuples * p.vecs_per_block) return;
-    const int64_t t = gid / p.vecs_per_block;
-    int64_t e = gid - t * p.vecs_per_block;
+    constexpr int U = ROWMODE ? 4 : 1;
+    const int64_t t = tuple_of_block();
+    if (t >= p.n_tuples) return;
     int64_t ox, oy, oz, agg;
     decode_tuple(p.ts, t, ox, oy, oz, agg);
     const int vd = p.dims.n - 1;
-    {   // last dim advances in steps of VEC, the others element by element
-        const int64_t nv = (p.dims.ext[vd] + VEC - 1) / VEC;
-        int64_t q = e / nv, k = (e - q * nv) * VEC;
+    const uint32_t nv = ((uint32_t)p.dims.ext[vd] + VEC - 1) / VEC;
+    uint32_t e, col;
+    if (ROWMODE) {
+        const uint32_t per_row = (nv + U * kThreads - 1) / (U * kThreads);
+        e = blockIdx.x / per_row;                                   // row: uniform
+        col = (blockIdx.x - e * per_row) * (U * kThreads) + threadIdx.x;
+    } else {
+        const uint32_t e0 = blockIdx.x * kThreads + threadIdx.x;
+        if (e0 >= (uint32_t)p.vecs_per_block) return;
+        e = e0 / nv;
+        col = e0 - e * nv;
+    }
+    for (int i = vd - 1; i >= 0; i--) {
+        const uint32_t ext = (uint32_t)p.dims.ext[i], q = e / ext;
+        const int64_t k2 = e - q * ext;
         e = q;
-        ox += k * p.dims.sx[vd]; oy += k * p.dims.sy[vd]; oz += k * p.dims.sz[vd];
-        for (int i = vd - 1; i >= 0; i--) {
-            int64_t q2 = e / p.dims.ext[i], k2 = e - q2 * p.dims.ext[i];
-            e = q2;
-            ox += k2 * p.dims.sx[i]; oy += k2 * p.dims.sy[i]; oz += k2 * p.dims.sz[i];
-        }
+        ox += k2 * p.dims.sx[i]; oy += k2 * p.dims.sy[i]; oz += k2 * p.dims.sz[i];
     }
     char *zb = out_base(p.out, agg);
     if (VEC == 8) {
-        float x[8], y[8], z[8];
-        if (p.dims.sx[vd] == 1) load8(p.x, p.dtx, ox, x);
-        else { float s = load_elem(p.x, p.dtx, ox);
+        float x[U][8], y[U][8];
+        const bool xv = p.dims.sx[vd] == 1, yv = p.dims.sy[vd] == 1;
 #pragma unroll
-            for (int i = 0; i < 8; i++) x[i] = s; }
-        if (p.binary) {
-            if (p.dims.sy[vd] == 1) load8(p.y, p.dty, oy, y);
-            else { float s = load_elem(p.y, p.dty, oy);
+        for (int u = 0; u < U; u++) {
+            const uint32_t c = col + u * kThreads;
+            const int64_t k = (int64_t)(c < nv ? c : nv - 1) * VEC;   // clamped: lanes past the row's end repeat its last vector
+            if (xv) load8(p.x, p.dtx, ox + k, x[u]);
+            else { float s = load_elem(p.x, p.dtx, ox + k * p.dims.sx[vd]);
 #pragma unroll
-                for (int i = 0; i < 8; i++) y[i] = s; }
-        } else {
+                for (int i = 0; i < 8; i++) x[u][i] = s; }
+            if (p.binary) {
+                if (yv) load8(p.y, p.dty, oy + k, y[u]);
+                else { float s = load_elem(p.y, p.dty, oy + k * p.dims.sy[vd]);
 #pragma unroll
-            for (int i = 0; i < 8; i++) y[i] = 0.f;
+                    for (int i = 0; i < 8; i++) y[u][i] = s; }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; i++) y[u][i] = 0.f;
+            }
         }
 #pragma unroll
-        for (int i = 0; i < 8; i++) z[i] = otimes_eval(p.otimes, x[i], y[i], p.alpha);
-        store8(zb, p.out.dtype, oz, z);
+        for (int u = 0; u < U; u++) {
+            const uint32_t c = col + u * kThreads;
+            if (c >= nv) continue;
+            float z[8];
+#pragma unroll
+            for (int i = 0; i < 8; i++) z[i] = otimes_t<OP, FAST>(p.otimes, x[u][i], y[u][i], p.alpha);
+            store8(zb, p.out.dtype, oz + (int64_t)c * VEC * p.dims.sz[vd], z);
+        }
     } else {
-        float x = load_elem(p.x, p.dtx, ox);
-        float y = p.binary ? load_elem(p.y, p.dty, oy) : 0.f;
-        store_elem(zb, p.out.dtype, oz, otimes_eval(p.otimes, x, y, p.alpha));
+        const int64_t k = col;
+        float x = load_elem(p.x, p.dtx, ox + k * p.dims.sx[vd]);
+        float y = p.binary ? load_elem(p.y, p.dty, oy + k * p.dims.sy[vd]) : 0.f;
+        store_elem(zb, p.out.dtype, oz + k * p.dims.sz[vd], otimes_t<OP, FAST>(p.otimes, x, y, p.alpha));
     }
 }
 
 // ------------------------------------------------------------------------------------------------
-// row reduction: LANES lanes cooperate on one output element; the reduced labels are X's trailing dims
+// row reduction: LANES lanes cooperate on one output element; the reduced labels are X's trailing dims.
+// With split > 1 (few outputs, long reductions) each output's reduction range is cut into `split` pieces
+// that land in consecutive partial slabs (slab = aggIdx * split + piece) for the aggregation kernel.
 // ------------------------------------------------------------------------------------------------
+template <int OPLUS>
 __device__ __forceinline__ float wave_reduce(int oplus, float v)
 {
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v = oplus_eval(oplus, v, __shfl_xor(v, off, 64));
+    for (int off = 32; off >= 1; off >>= 1) v = oplus_t<OPLUS>(oplus, v, __shfl_xor(v, off, 64));
     return v;
 }
 
-template <int LANES, int VEC>
+template <int LANES, int VEC, int OP, int OPLUS>
 __global__ __launch_bounds__(kThreads) void k_reduce_row(const ReduceParams p)
 {
     constexpr int PER_WG = kThreads / LANES;
     __shared__ float red[kThreads / 64];
     const int sub = threadIdx.x / LANES, lane = threadIdx.x % LANES;
-    const int64_t o = (int64_t)blockIdx.x * PER_WG + sub;
-    const bool active = o < p.n_tuples * p.outs_per_block;     // whole lane groups are active or not
-    float acc = oplus_identity(p.oplus);
+    const int64_t t = tuple_of_block();
+    const uint32_t slot = blockIdx.x * PER_WG + sub;              // (output, piece) within the tuple's block
+    const uint32_t split = (uint32_t)p.split;
+    const uint32_t o = slot / split, piece = slot - o * split;
+    const bool active = t < p.n_tuples && o < (uint32_t)p.outs_per_block;   // whole lane groups are active or not
+    float acc = oplus_identity(OPLUS >= 0 ? OPLUS : p.oplus);
     int64_t oz = 0, agg = 0;
     if (active) {
-        const int64_t t = o / p.outs_per_block, e = o - t * p.outs_per_block;
         int64_t ox, oy;
         decode_tuple(p.ts, t, ox, oy, oz, agg);
-        decode_dims(p.zdims, e, ox, oy, oz);
-        const int vd = p.rdims.n - 1;
-        const int64_t nv = (p.rdims.ext[vd] + VEC - 1) / VEC;
-        const int64_t total = (p.red_elems / p.rdims.ext[vd]) * nv;
-        for (int64_t j = lane; j < total; j += LANES) {
-            int64_t q = j / nv, k = (j - q * nv) * VEC;
-            int64_t bx = ox + k * p.rdims.sx[vd], by = oy + k * p.rdims.sy[vd];
-            for (int i = vd - 1; i >= 0; i--) {
-                int64_t q2 = q / p.rdims.ext[i], k2 = q - q2 * p.rdims.ext[i];
-                q = q2;
-                bx += k2 * p.rdims.sx[i]; by += k2 * p.rdims.sy[i];
+        {
+            uint32_t e = o;
+            for (int i = p.zdims.n - 1; i >= 0; i--) {
+                const uint32_t ext = (uint32_t)p.zdims.ext[i], q = e / ext;
+                const int64_t k = e - q * ext;
+                e = q;
+                ox += k * p.zdims.sx[i]; oy += k * p.zdims.sy[i]; oz += k * p.zdims.sz[i];
             }
-            if (VEC == 8) {
-                float x[8], y[8];
-                load8(p.x, p.dtx, bx, x);
-                if (p.binary) {
-                    if (p.rdims.sy[vd] == 1) load8(p.y, p.dty, by, y);
-                    else { float s = load_elem(p.y, p.dty, by);
+        }
+        const int vd = p.rdims.n - 1;
+        const uint32_t nv = ((uint32_t)p.rdims.ext[vd] + VEC - 1) / VEC;
+        const uint32_t total = (uint32_t)(p.red_elems / p.rdims.ext[vd]) * nv;
+        const uint32_t chunk = (total + split - 1) / split;
+        const uint32_t lo = piece * chunk, hi = (lo + chunk < total) ? lo + chunk : total;
+        const bool flat = p.rdims.n == 1;
+        for (uint32_t j0 = lo + lane; j0 < hi; j0 += 4 * LANES) {
+            float x[4][VEC], y[4][VEC];
+            bool ok[4];
 #pragma unroll
-                        for (int i = 0; i < 8; i++) y[i] = s; }
+            for (int u = 0; u < 4; u++) {                          // issue the loads of four vectors before using any
+                const uint32_t j = j0 + u * LANES;
+                ok[u] = j < hi;
+                const uint32_t jj = ok[u] ? j : lo;
+                int64_t bx, by;
+                if (flat) {
+                    bx = ox + (int64_t)jj * VEC * p.rdims.sx[vd];
+                    by = oy + (int64_t)jj * VEC * p.rdims.sy[vd];
                 } else {
-#pragma unroll
-                    for (int i = 0; i < 8; i++) y[i] = 0.f;
+                    uint32_t q = jj / nv;
+                    const int64_t k = (int64_t)(jj - q * nv) * VEC;
+                    bx = ox + k * p.rdims.sx[vd];
+                    by = oy + k * p.rdims.sy[vd];
+                    for (int i = vd - 1; i >= 0; i--) {
+                        const uint32_t ext = (uint32_t)p.rdims.ext[i], q2 = q / ext;
+                        const int64_t k2 = q - q2 * ext;
+                        q = q2;
+                        bx += k2 * p.rdims.sx[i]; by += k2 * p.rdims.sy[i];
+                    }
                 }
+                if (VEC == 8) {
+                    load8(p.x, p.dtx, bx, (float (&)[8])x[u]);
+                    if (p.binary) {
+                        if (p.rdims.sy[vd] == 1) load8(p.y, p.dty, by, (float (&)[8])y[u]);
+                        else { float s = load_elem(p.y, p.dty, by);
 #pragma unroll
-                for (int i = 0; i < 8; i++) acc = oplus_eval(p.oplus, acc, otimes_eval(p.otimes, x[i], y[i], p.alpha));
-            } else {
-                float x = load_elem(p.x, p.dtx, bx);
-                float y = p.binary ? load_elem(p.y, p.dty, by) : 0.f;
-                acc = oplus_eval(p.oplus, acc, otimes_eval(p.otimes, x, y, p.alpha));
+                            for (int i = 0; i < VEC; i++) y[u][i] = s; }
+                    }
+                } else {
+                    x[u][0] = load_elem(p.x, p.dtx, bx);
+                    if (p.binary) y[u][0] = load_elem(p.y, p.dty, by);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                if (!ok[u]) continue;
+#pragma unroll
+                for (int i = 0; i < VEC; i++)
+                    acc = oplus_t<OPLUS>(p.oplus, acc, otimes_t<OP, false>(p.otimes, x[u][i], p.binary ? y[u][i] : 0.f, p.alpha));
             }
         }
     }
-    acc = wave_reduce(p.oplus, acc);
+    acc = wave_reduce<OPLUS>(p.oplus, acc);
+    // partial mode: slab (aggIdx * split + piece) of the fp32 workspace; otherwise the destination tensor
+    char *zb = (char *)p.out.ptr + (p.out.slab_elems ? (agg * split + piece) * p.out.slab_elems * 4 : 0);
     if (LANES > 64) {                       // one output per workgroup: combine the four waves through LDS
         if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = acc;
         __syncthreads();
         if (threadIdx.x == 0) {
             float v = red[0];
-            for (int w = 1; w < kThreads / 64; w++) v = oplus_eval(p.oplus, v, red[w]);
-            if (active) store_elem(out_base(p.out, agg), p.out.dtype, oz, v);
+            for (int w = 1; w < kThreads / 64; w++) v = oplus_t<OPLUS>(p.oplus, v, red[w]);
+            if (active) store_elem(zb, p.out.dtype, oz, v);
         }
     } else if (lane == 0 && active) {
-        store_elem(out_base(p.out, agg), p.out.dtype, oz, acc);
+        store_elem(zb, p.out.dtype, oz, acc);
     }
 }
 
 // ------------------------------------------------------------------------------------------------
 // aggregation of partial slabs: out[e] = (+)_{a ascending} partials[a][e], fp32, one final cast
 // ------------------------------------------------------------------------------------------------
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// N > 0: the slab count is known at compile time, so all N loads are in flight before the first add.
+// The adds themselves stay in ascending slab order.  Partial slabs are read once: streaming loads.
+template <int N>
 __global__ __launch_bounds__(kThreads) void k_aggregate_vec4(const AggregateParams p)
 {
     const int64_t i4 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     const int64_t e = i4 * 4;
     if (e >= p.slab_elems) return;
-    const float4 *src = (const float4 *)(p.partials + e);
+    const f32x4 *src = (const f32x4 *)(p.partials + e);
     const int64_t slab4 = p.slab_elems / 4;
-    float4 acc = src[0];
-    if (p.oplus == EG_AGG_MAX) {
-#pragma unroll 4
-        for (int64_t a = 1; a < p.n_agg; a++) {
-            float4 v = src[a * slab4];
-            acc.x = fmaxf(acc.x, v.x); acc.y = fmaxf(acc.y, v.y); acc.z = fmaxf(acc.z, v.z); acc.w = fmaxf(acc.w, v.w);
+    f32x4 acc;
+    if (N > 0) {
+        f32x4 v[N > 0 ? N : 1];
+#pragma unroll
+        for (int a = 0; a < N; a++) v[a] = __builtin_nontemporal_load(src + a * slab4);
+        acc = v[0];
+#pragma unroll
+        for (int a = 1; a < N; a++) {
+            if (p.oplus == EG_AGG_MAX) { acc.x = fmaxf(acc.x, v[a].x); acc.y = fmaxf(acc.y, v[a].y); acc.z = fmaxf(acc.z, v[a].z); acc.w = fmaxf(acc.w, v[a].w); }
+            else acc += v[a];
         }
     } else {
+        acc = __builtin_nontemporal_load(src);
+        if (p.oplus == EG_AGG_MAX) {
 #pragma unroll 4
-        for (int64_t a = 1; a < p.n_agg; a++) {
-            float4 v = src[a * slab4];
-            acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+            for (int64_t a = 1; a < p.n_agg; a++) {
+                f32x4 v = __builtin_nontemporal_load(src + a * slab4);
+                acc.x = fmaxf(acc.x, v.x); acc.y = fmaxf(acc.y, v.y); acc.z = fmaxf(acc.z, v.z); acc.w = fmaxf(acc.w, v.w);
+            }
+        } else {
+#pragma unroll 4
+            for (int64_t a = 1; a < p.n_agg; a++) acc += __builtin_nontemporal_load(src + a * slab4);
         }
     }
     if (p.out_dtype == EG_BF16) {
         uint2 r;
-        r.x = (uint32_t)f32_to_bf16(acc.x) | ((uint32_t)f32_to_bf16(acc.y) << 16);
-        r.y = (uint32_t)f32_to_bf16(acc.z) | ((uint32_t)f32_to_bf16(acc.w) << 16);
+        r.x = pack_bf16x2(acc.x, acc.y);
+        r.y = pack_bf16x2(acc.z, acc.w);
         *(uint2 *)((uint16_t *)p.out + e) = r;
     } else {
-        *(float4 *)((float *)p.out + e) = acc;
+        *(f32x4 *)((float *)p.out + e) = acc;
     }
 }
 
@@ -263,35 +339,94 @@ int launch_generic(const GenericParams &p, void *stream)
     return check_launch("k_generic");
 }
 
+// grid.x = workgroups per tuple, grid.y * grid.z >= tuples (y capped at 65535)
+static int tuple_grid(int64_t per_tuple_items, int64_t per_wg, int64_t n_tuples, dim3 &grid)
+{
+    int64_t gx = (per_tuple_items + per_wg - 1) / per_wg;
+    if (gx < 1) gx = 1;
+    if (gx >= (1ll << 31) || per_tuple_items >= (1ll << 32)) return fail(EG_ERR_LIMIT, "block too large for one launch");
+    const int64_t gy = n_tuples < 65535 ? n_tuples : 65535;
+    const int64_t gz = (n_tuples + 65534) / 65535;
+    if (gz > 65535) return fail(EG_ERR_LIMIT, "too many tuples");
+    grid = dim3((unsigned)gx, (unsigned)gy, (unsigned)gz);
+    return EG_OK;
+}
+
+template <int OP>
+static void launch_map_vec(const MapParams &p, dim3 grid, bool rowmode, hipStream_t st)
+{
+    const bool fast = p.out.dtype == EG_BF16;     // hardware exponential only where the result is rounded to bf16
+    if (rowmode) {
+        if (fast) hipLaunchKernelGGL((k_map<8, OP, true, true>), grid, dim3(kThreads), 0, st, p);
+        else hipLaunchKernelGGL((k_map<8, OP, false, true>), grid, dim3(kThreads), 0, st, p);
+    } else {
+        if (fast) hipLaunchKernelGGL((k_map<8, OP, true, false>), grid, dim3(kThreads), 0, st, p);
+        else hipLaunchKernelGGL((k_map<8, OP, false, false>), grid, dim3(kThreads), 0, st, p);
+    }
+}
+
 int launch_map(const MapParams &p, void *stream)
 {
     if (!p.x || (p.binary && !p.y) || !p.out.ptr) return fail(EG_ERR_NULL, "map kernel: NULL operand");
     if (p.dims.n < 1) return fail(EG_ERR_LIMIT, "map kernel: empty index space");
     if (p.vec != 1 && p.vec != 8) return fail(EG_ERR_LIMIT, "map kernel: vector width %d", p.vec);
-    unsigned grid;
-    int rc = grid_for(p.n_tuples * p.vecs_per_block, kThreads, grid);
+    hipStream_t st = (hipStream_t)stream;
+    dim3 grid;
+    if (p.vec == 1) {
+        int rc = tuple_grid(p.vecs_per_block, kThreads, p.n_tuples, grid);
+        if (rc) return rc;
+        hipLaunchKernelGGL((k_map<1, -1, false, false>), grid, dim3(kThreads), 0, st, p);
+        return check_launch("k_map");
+    }
+    const int64_t nv = p.dims.ext[p.dims.n - 1] / 8;
+    const bool rowmode = nv >= 768;                // a row keeps at least three quarters of a workgroup's 1024 slots busy
+    int rc;
+    if (rowmode) {
+        const int64_t rows = p.vecs_per_block / nv, per_row = (nv + 4 * kThreads - 1) / (4 * kThreads);
+        rc = tuple_grid(rows * per_row, 1, p.n_tuples, grid);
+    } else {
+        rc = tuple_grid(p.vecs_per_block, kThreads, p.n_tuples, grid);
+    }
     if (rc) return rc;
-    if (p.vec == 8) hipLaunchKernelGGL(k_map<8>, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, p);
-    else hipLaunchKernelGGL(k_map<1>, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, p);
+    switch (p.otimes) {
+#define EG_CASE(OP) case OP: launch_map_vec<OP>(p, grid, rowmode, st); break;
+    EG_CASE(EG_MUL) EG_CASE(EG_ADD) EG_CASE(EG_SUB) EG_CASE(EG_DIV) EG_CASE(EG_SQDIFF) EG_CASE(EG_ABSDIFF)
+    EG_CASE(EG_EXP_SUB) EG_CASE(EG_RELU_GRAD) EG_CASE(EG_SILU_MUL) EG_CASE(EG_IDENT) EG_CASE(EG_SCALE)
+    EG_CASE(EG_RELU) EG_CASE(EG_EXP) EG_CASE(EG_LOG)
+#undef EG_CASE
+    default: return fail(EG_ERR_BAD_OP, "map kernel: unknown scalar function %d", p.otimes);
+    }
     return check_launch("k_map");
+}
+
+template <int LANES, int VEC>
+static void launch_reduce_ops(const ReduceParams &p, dim3 grid, hipStream_t st)
+{
+    // the common (x)/(+) pairs are compiled in; anything else reads them at run time
+    if (p.otimes == EG_IDENT && p.oplus == EG_AGG_MAX) hipLaunchKernelGGL((k_reduce_row<LANES, VEC, EG_IDENT, EG_AGG_MAX>), grid, dim3(kThreads), 0, st, p);
+    else if (p.otimes == EG_IDENT && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_row<LANES, VEC, EG_IDENT, EG_AGG_SUM>), grid, dim3(kThreads), 0, st, p);
+    else if (p.otimes == EG_MUL && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_row<LANES, VEC, EG_MUL, EG_AGG_SUM>), grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((k_reduce_row<LANES, VEC, -1, -1>), grid, dim3(kThreads), 0, st, p);
 }
 
 int launch_reduce_row(const ReduceParams &p, void *stream)
 {
     if (!p.x || (p.binary && !p.y) || !p.out.ptr) return fail(EG_ERR_NULL, "reduce kernel: NULL operand");
     if (p.rdims.n < 1) return fail(EG_ERR_LIMIT, "reduce kernel: empty reduction space");
-    const int64_t outs = p.n_tuples * p.outs_per_block;
-    const bool wide = p.red_elems >= 16384 || outs < 1024;     // long rows or few rows: a workgroup per output
-    unsigned grid;
-    int rc = grid_for(outs, wide ? 1 : kThreads / 64, grid);
+    if (p.split < 1 || (p.split > 1 && !p.out.slab_elems)) return fail(EG_ERR_LIMIT, "reduce kernel: split needs partial slabs");
+    if (p.red_elems >= (1ll << 32)) return fail(EG_ERR_LIMIT, "reduce kernel: reduction space above 2^32");
+    const int64_t slots = p.outs_per_block * p.split;
+    const bool wide = p.split > 1 || p.red_elems >= 16384 || slots * p.n_tuples < 1024;   // long or few rows: a workgroup each
+    dim3 grid;
+    int rc = tuple_grid(slots, wide ? 1 : kThreads / 64, p.n_tuples, grid);
     if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
     if (wide) {
-        if (p.vec == 8) hipLaunchKernelGGL((k_reduce_row<256, 8>), dim3(grid), dim3(kThreads), 0, st, p);
-        else hipLaunchKernelGGL((k_reduce_row<256, 1>), dim3(grid), dim3(kThreads), 0, st, p);
+        if (p.vec == 8) launch_reduce_ops<256, 8>(p, grid, st);
+        else launch_reduce_ops<256, 1>(p, grid, st);
     } else {
-        if (p.vec == 8) hipLaunchKernelGGL((k_reduce_row<64, 8>), dim3(grid), dim3(kThreads), 0, st, p);
-        else hipLaunchKernelGGL((k_reduce_row<64, 1>), dim3(grid), dim3(kThreads), 0, st, p);
+        if (p.vec == 8) launch_reduce_ops<64, 8>(p, grid, st);
+        else launch_reduce_ops<64, 1>(p, grid, st);
     }
     return check_launch("k_reduce_row");
 }
@@ -305,8 +440,16 @@ int launch_aggregate(const AggregateParams &p, void *stream)
     unsigned grid;
     int rc = grid_for(vec ? p.slab_elems / 4 : p.slab_elems, kThreads, grid);
     if (rc) return rc;
-    if (vec) hipLaunchKernelGGL(k_aggregate_vec4, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, p);
-    else hipLaunchKernelGGL(k_aggregate_scalar, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, p);
+    if (vec) {
+        hipStream_t st = (hipStream_t)stream;
+        switch (p.n_agg) {
+        case 2: hipLaunchKernelGGL(k_aggregate_vec4<2>, dim3(grid), dim3(kThreads), 0, st, p); break;
+        case 4: hipLaunchKernelGGL(k_aggregate_vec4<4>, dim3(grid), dim3(kThreads), 0, st, p); break;
+        case 8: hipLaunchKernelGGL(k_aggregate_vec4<8>, dim3(grid), dim3(kThreads), 0, st, p); break;
+        case 16: hipLaunchKernelGGL(k_aggregate_vec4<16>, dim3(grid), dim3(kThreads), 0, st, p); break;
+        default: hipLaunchKernelGGL(k_aggregate_vec4<0>, dim3(grid), dim3(kThreads), 0, st, p); break;
+        }
+    } else hipLaunchKernelGGL(k_aggregate_scalar, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, p);
     return check_launch("k_aggregate");
 }
 

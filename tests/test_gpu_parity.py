@@ -198,6 +198,9 @@ def test_every_scalar_function_elementwise(shape, part, dtype):
     ("ij,jk->ik", (40, 72), (72, 24), "absdiff", "max", {"i": 2, "j": 2, "k": 2}),
     ("ij,j->i", (40, 1024), (1024,), "mul", "sum", {"j": 2}),
     ("ij,jk->ik", (37, 53), (53, 29), "mul", "sum", {}),          # nothing divides a vector: scalar paths
+    ("ij->", (256, 1024), None, "exp", "sum", {}),                # one output, long reduction: split into pieces
+    ("ij->", (256, 1024), None, "ident", "max", {"i": 2}),        # split pieces x two partial blocks
+    ("bij,bij->b", (3, 200, 328), (3, 200, 328), "mul", "sum", {"i": 2}),
 ])
 def test_maps_reductions_and_extended_operators(spec, bx, by, otimes, oplus, part):
     print(f"{spec} {otimes}/{oplus} {part}", flush=True)
