@@ -46,7 +46,7 @@ __device__ __forceinline__ void decode_group2(const DimList &g, int64_t idx, int
 // Per-lane source offsets (elements, relative to the operand's block base) of the 8 chunks this lane
 // fetches per stage, without the k advance.
 //   KC: instruction i of wave w deposits rows (4i+w)*8 .. +7, lane -> row +lane/8, physical chunk lane%8,
-//       logical chunk (lane%8) ^ (row&7) = (lane%8) ^ (lane/8).
+//       logical chunk (lane%8) ^ ((row>>1)&7).
 //   MC: instruction i of wave w deposits k-rows (4i+w)*2 .. +1, lane -> k-row +lane/32, physical chunk lane%32,
 //       logical chunk (lane%32) ^ 4*(krow%4), krow%4 = (2w + lane/32)%4.
 template <bool KC>
@@ -56,7 +56,8 @@ struct Src {
     __device__ __forceinline__ void init(const DimList &grp, int64_t first, int64_t extent, int64_t k_inner_stride, int wave, int lane)
     {
         if (KC) {
-            const int lc = (lane & 7) ^ (lane >> 3);
+            // LDS row of this lane's chunk is (4i+wave)*8 + lane/8; its swizzle key (row>>1)&7 does not depend on i
+            const int lc = (lane & 7) ^ ((wave * 4 + (lane >> 4)) & 7);
 #pragma unroll
             for (int i = 0; i < 8; i++) {
                 int64_t r = first + (4 * i + wave) * 8 + (lane >> 3);
@@ -84,7 +85,7 @@ struct Src {
 __device__ __forceinline__ int kc_frag_off(int row, int ks, int lane)
 {
     const int lc = 2 * ks + (lane >> 5);
-    return row * 128 + ((lc ^ (row & 7)) << 4);
+    return row * 128 + ((lc ^ ((row >> 1) & 7)) << 4);      // 16 consecutive rows hit 16 distinct 16-byte bank groups
 }
 
 // MC layout: two transposing 8-byte reads (k = 8*(lane/32) + 0..3 and +4..7 of the k-step).
@@ -194,15 +195,15 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
         ga = xb + ka * 2;
         gb = yb + kb * 2;
     };
-    // issues the 16 direct loads of a stage into the LDS stage at `dst`: uniform base + 32-bit lane offset
+    // direct load i (0..7: X tile, 8..15: Y tile) of a stage into the LDS stage at `dst`: uniform base + 32-bit lane offset
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    auto dma = [&](int i, const char *ga, const char *gb, char *dst) {
+        if (i < 8) __builtin_amdgcn_global_load_lds(EG_GLB(ga + sa.boff[i]), EG_LDS(dst + (4 * i + wave_u) * 1024), 16, 0, 0);
+        else __builtin_amdgcn_global_load_lds(EG_GLB(gb + sb.boff[i - 8]), EG_LDS(dst + TILE_BYTES + (4 * (i - 8) + wave_u) * 1024), 16, 0, 0);
+    };
     auto issue = [&](const char *ga, const char *gb, char *dst) {
 #pragma unroll
-        for (int i = 0; i < 8; i++)
-            __builtin_amdgcn_global_load_lds(EG_GLB(ga + sa.boff[i]), EG_LDS(dst + (4 * i + wave_u) * 1024), 16, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 8; i++)
-            __builtin_amdgcn_global_load_lds(EG_GLB(gb + sb.boff[i]), EG_LDS(dst + TILE_BYTES + (4 * i + wave_u) * 1024), 16, 0, 0);
+        for (int i = 0; i < 16; i++) dma(i, ga, gb, dst);
     };
 
     f32x16 acc[4][4];
@@ -228,7 +229,8 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
 #define EG_STAGE_NEXT(C, O, HAS_NEXT2, K_NEXT2) /* one stage; its successor is already in flight into O */ \
     do {                                                                                          \
         mfma_rows<0, 1>(a0, b0, acc); EG_PIN();                                                   \
-        stage_ptrs((HAS_NEXT2) ? (K_NEXT2) : 0, ga2, gb2);   /* scalar work rides under the MFMAs */ \
+        const bool has2 = (HAS_NEXT2);                                                            \
+        stage_ptrs(has2 ? (K_NEXT2) : 0, ga2, gb2);          /* scalar work rides under the MFMAs */ \
         load_frags<A_KC, B_KC>(C, C + TILE_BYTES, 1, a1, b1, wm, wn, lane); EG_PIN();             \
         mfma_rows<1, 4>(a0, b0, acc); EG_PIN();                                                   \
         EG_KSTEP(a1, b1, a0, b0, C, 2)                                                            \
@@ -236,10 +238,18 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
         __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): this wave's deposits for O landed */     \
         __syncthreads();                    /* everybody's landed; everybody has left C */        \
         EG_PIN();                                                                                 \
-        mfma_rows<0, 1>(a1, b1, acc); EG_PIN();                                                   \
-        if (HAS_NEXT2) issue(ga2, gb2, C);                                                        \
+        /* last k-step: every MFMA is followed by one direct load of the stage after next into C */ \
+        _Pragma("unroll") for (int j = 0; j < 4; j++) {                                           \
+            acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[0], b1[j], acc[0][j], 0, 0, 0); EG_PIN(); \
+            if (has2) dma(j, ga2, gb2, C);                                                        \
+            EG_PIN();                                                                             \
+        }                                                                                         \
         load_frags<A_KC, B_KC>(O, O + TILE_BYTES, 0, a0, b0, wm, wn, lane); EG_PIN();             \
-        mfma_rows<1, 4>(a1, b1, acc); EG_PIN();                                                   \
+        _Pragma("unroll") for (int q = 0; q < 12; q++) {                                          \
+            acc[1 + q / 4][q % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[1 + q / 4], b1[q % 4], acc[1 + q / 4][q % 4], 0, 0, 0); EG_PIN(); \
+            if (has2) dma(4 + q, ga2, gb2, C);                                                    \
+            EG_PIN();                                                                             \
+        }                                                                                         \
     } while (0)
     // Every stage, the last one included, runs the same straight-line code (the last one pays for one idle
     // barrier and twelve unused fragment reads): an MFMA under a branch inside the loop would make the
