@@ -20,6 +20,7 @@ namespace eg {
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short short4v __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 namespace dma {
 
@@ -297,6 +298,48 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
     char *zb = (char *)p.out.ptr + (p.out.slab_elems ? agg * p.out.slab_elems * 4 : 0);
     const bool out_bf16 = p.out.dtype == EG_BF16;
     const int lrow = lane & 31, lhalf = lane >> 5;
+    if (p.out_vec) {
+        // Z is contiguous along the tile's columns: each wave stages 32 rows x 128 columns of its patch in LDS
+        // (row pitch 544 bytes keeps the two half-waves on different banks) and writes them out as whole row
+        // segments, 16 bytes per lane.  LDS operations of one wave execute in order, so no barrier is needed.
+        constexpr int PITCH = 544, WBUF = 32 * PITCH;
+        char *wbuf = wave < 3 ? lds1 + wave * WBUF : lds0 + 4096;
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+#pragma unroll
+            for (int j = 0; j < 4; j++)
+#pragma unroll
+                for (int r = 0; r < 16; r++)
+                    *(float *)(wbuf + (8 * (r >> 2) + 4 * lhalf + (r & 3)) * PITCH + (j * 32 + lrow) * 4) = p.alpha * acc[i][j][r];
+            if (!out_bf16) {
+                const int c = wn * 128 + lrow * 4;                        // 4 consecutive columns
+                const int64_t zc = bz + zcol[c];
+                const bool cok = n0 + c < p.N;
+#pragma unroll
+                for (int it = 0; it < 16; it++) {
+                    const int row = 2 * it + lhalf, rr = wm * 128 + i * 32 + row;
+                    const f32x4 v = *(const f32x4 *)(wbuf + row * PITCH + lrow * 16);
+                    if (cok && m0 + rr < p.M) *(f32x4 *)((float *)zb + zrow[rr] + zc) = v;
+                }
+            } else {
+                const int l16 = lane & 15, lq = lane >> 4;
+                const int c = wn * 128 + l16 * 8;                         // 8 consecutive columns
+                const int64_t zc = bz + zcol[c];
+                const bool cok = n0 + c < p.N;
+#pragma unroll
+                for (int it = 0; it < 8; it++) {
+                    const int row = 4 * it + lq, rr = wm * 128 + i * 32 + row;
+                    const f32x4 v0 = *(const f32x4 *)(wbuf + row * PITCH + l16 * 32);
+                    const f32x4 v1 = *(const f32x4 *)(wbuf + row * PITCH + l16 * 32 + 16);
+                    uint4 o;
+                    o.x = pack_bf16x2(v0.x, v0.y); o.y = pack_bf16x2(v0.z, v0.w);
+                    o.z = pack_bf16x2(v1.x, v1.y); o.w = pack_bf16x2(v1.z, v1.w);
+                    if (cok && m0 + rr < p.M) *(uint4 *)((uint16_t *)zb + zrow[rr] + zc) = o;
+                }
+            }
+        }
+        return;
+    }
     int64_t zn[4];
     bool nok[4];
 #pragma unroll
@@ -365,6 +408,13 @@ int launch_contract_dma(ContractParams &p, void *stream)
     p.tiles_n = (int32_t)((p.N + dma::BN - 1) / dma::BN);
     const int64_t wgs = p.n_tuples * p.n_batch * p.tiles_m * p.tiles_n;
     if (wgs < 1 || wgs >= (1ll << 31)) return fail(EG_ERR_LIMIT, "contraction needs %lld workgroups", (long long)wgs);
+    // wide epilogue stores need Z contiguous along the innermost N label and every other Z offset a multiple of 8 elements
+    bool vec = p.n.s1[p.n.n - 1] == 1 && p.n.ext[p.n.n - 1] % 8 == 0 && ((uintptr_t)p.out.ptr & 15) == 0 && p.out.slab_elems % 8 == 0;
+    for (int i = 0; i < p.m.n; i++) vec = vec && p.m.s1[i] % 8 == 0;
+    for (int i = 0; i + 1 < p.n.n; i++) vec = vec && p.n.s1[i] % 8 == 0;
+    for (int i = 0; i < p.batch.n; i++) vec = vec && p.batch.s2[i] % 8 == 0;
+    for (int l = 0; l < p.ts.n; l++) vec = vec && p.ts.step_z[l] % 8 == 0;
+    p.out_vec = vec ? 1 : 0;
     if (p.a_kcontig) return p.b_kcontig ? dma::launch_parity<true, true>(p, stream) : dma::launch_parity<true, false>(p, stream);
     return p.b_kcontig ? dma::launch_parity<false, true>(p, stream) : dma::launch_parity<false, false>(p, stream);
 }
