@@ -9,8 +9,11 @@
 //     contiguous along M or N sits as [k][256 mn] and is read with the 16-bit transposing LDS read, which
 //     hands every lane four consecutive k for its own column;
 //   * two LDS stages: the loads of stage t+1 are in flight while the MFMAs of stage t run.
-// Requirements (checked on the host): K is a multiple of 64 made of runs of 64 along the innermost K label,
-// in-block offsets fit 31 bits.  Anything else goes to the register-staged kernel.
+//   * the loads are buffer loads with a 2 GiB descriptor: a lane whose chunk lies beyond K in the last,
+//     partial stage is given an offset outside the descriptor, fetches nothing and deposits zeros.
+// Requirements (checked on the host): K is one label of any extent, or several whose innermost extent is a
+// multiple of 64 (a stage never straddles two K labels); in-block offsets fit 31 bits.  Anything else goes
+// to the register-staged kernel.
 #include <hip/hip_runtime.h>
 
 #include "eg_device.h"
@@ -53,12 +56,14 @@ __device__ __forceinline__ void decode_group2(const DimList &g, int64_t idx, int
 template <bool KC>
 struct Src {
     uint32_t boff[8];         // byte offset of the chunk instruction i fetches, relative to the stage's first k
+    int kl;                   // k (within the stage) of chunk 0 of this lane; chunk i sits at kl (KC) or kl + 8 i (MC)
 
     __device__ __forceinline__ void init(const DimList &grp, int64_t first, int64_t extent, int64_t k_inner_stride, int wave, int lane)
     {
         if (KC) {
             // LDS row of this lane's chunk is (4i+wave)*8 + lane/8; its swizzle key (row>>1)&7 does not depend on i
             const int lc = (lane & 7) ^ ((wave * 4 + (lane >> 4)) & 7);
+            kl = lc * 8;
 #pragma unroll
             for (int i = 0; i < 8; i++) {
                 int64_t r = first + (4 * i + wave) * 8 + (lane >> 3);
@@ -74,10 +79,17 @@ struct Src {
             m = m + 8 <= extent ? m : extent - 8;
             int64_t o0, o1;
             decode_group2(grp, m, o0, o1);
+            kl = 2 * wave + (lane >> 5);
 #pragma unroll
             for (int i = 0; i < 8; i++)
                 boff[i] = (uint32_t)((o0 + (8 * i + 2 * wave + (lane >> 5)) * k_inner_stride) * 2);
         }
+    }
+    // offset handed to load i of a stage that has `krem` valid k left: beyond the descriptor when the chunk's k is past the end
+    __device__ __forceinline__ uint32_t voff(int i, int krem) const
+    {
+        const int k = KC ? kl : kl + 8 * i;
+        return k < krem ? boff[i] : 0x80000000u;
     }
 };
 
@@ -180,8 +192,14 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
         }
     }
     const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
-    const char *xb = (const char *)p.x + bx * 2;
-    const char *yb = (const char *)p.y + by * 2;
+    // block bases are the same for the whole workgroup: say so, the buffer descriptors must live in scalar registers
+    auto uniform_ptr = [](const char *q) {
+        const uint64_t v = (uint64_t)q;
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+        return (const char *)(((uint64_t)hi << 32) | lo);
+    };
+    const char *xb = uniform_ptr((const char *)p.x + bx * 2);
+    const char *yb = uniform_ptr((const char *)p.y + by * 2);
     const int kin = p.k.n - 1;                        // innermost K label: every 64-run of k lies inside it
 
     Src<A_KC> sa;
@@ -189,22 +207,30 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
     sa.init(p.m, m0, p.M, p.k.s0[kin], wave, lane);
     sb.init(p.n, n0, p.N, p.k.s1[kin], wave, lane);
 
-    // uniform source pointers of the stage that starts at k0
-    auto stage_ptrs = [&](int64_t k0, const char *&ga, const char *&gb) {
+    // uniform source pointers of the stage that starts at k0, and how many k it still has (64 or more: a full stage)
+    auto stage_ptrs = [&](int64_t k0, const char *&ga, const char *&gb, int &krem) {
         int64_t ka, kb;
         decode_group2(p.k, k0, ka, kb);                // offset of the run's first k in X and in Y
         ga = xb + ka * 2;
         gb = yb + kb * 2;
+        const int64_t left = p.K - k0;
+        krem = left < BK ? (int)left : BK;
     };
-    // direct load i (0..7: X tile, 8..15: Y tile) of a stage into the LDS stage at `dst`: uniform base + 32-bit lane offset
+    // direct load i (0..7: X tile, 8..15: Y tile) of a stage into the LDS stage at `dst`: a 2 GiB buffer descriptor
+    // on the uniform stage base + a 32-bit lane offset (in-block offsets are below 2^31; 2^31 itself means "no fetch, zeros")
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    auto dma = [&](int i, const char *ga, const char *gb, char *dst) {
-        if (i < 8) __builtin_amdgcn_global_load_lds(EG_GLB(ga + sa.boff[i]), EG_LDS(dst + (4 * i + wave_u) * 1024), 16, 0, 0);
-        else __builtin_amdgcn_global_load_lds(EG_GLB(gb + sb.boff[i - 8]), EG_LDS(dst + TILE_BYTES + (4 * (i - 8) + wave_u) * 1024), 16, 0, 0);
+    auto dma = [&](int i, const char *ga, const char *gb, int krem, char *dst) {
+        if (i < 8) {
+            __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)ga, 0, (int)0x80000000u, 0x00020000);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, EG_LDS(dst + (4 * i + wave_u) * 1024), 16, (int)sa.voff(i, krem), 0, 0, 0);
+        } else {
+            __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)gb, 0, (int)0x80000000u, 0x00020000);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, EG_LDS(dst + TILE_BYTES + (4 * (i - 8) + wave_u) * 1024), 16, (int)sb.voff(i - 8, krem), 0, 0, 0);
+        }
     };
-    auto issue = [&](const char *ga, const char *gb, char *dst) {
+    auto issue = [&](const char *ga, const char *gb, int krem, char *dst) {
 #pragma unroll
-        for (int i = 0; i < 16; i++) dma(i, ga, gb, dst);
+        for (int i = 0; i < 16; i++) dma(i, ga, gb, krem, dst);
     };
 
     f32x16 acc[4][4];
@@ -220,7 +246,7 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
     // return while the matrix pipe is busy.  The last k-step of a stage runs after the barrier, together with
     // the direct loads of the stage after next and the first fragment reads of the next stage.
     // sched_barrier pins this order against the compiler's own scheduling.
-    const int64_t nk = p.K / BK;
+    const int64_t nk = (p.K + BK - 1) / BK;
     bf16x8 a0[4], b0[4], a1[4], b1[4];
 #define EG_PIN() __builtin_amdgcn_sched_barrier(0)
 #define EG_KSTEP(FA, FB, NA, NB, BUF, KS_NEXT)                                                    \
@@ -231,7 +257,7 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
     do {                                                                                          \
         mfma_rows<0, 1>(a0, b0, acc); EG_PIN();                                                   \
         const bool has2 = (HAS_NEXT2);                                                            \
-        stage_ptrs(has2 ? (K_NEXT2) : 0, ga2, gb2);          /* scalar work rides under the MFMAs */ \
+        stage_ptrs(has2 ? (K_NEXT2) : 0, ga2, gb2, kr2);          /* scalar work rides under the MFMAs */ \
         load_frags<A_KC, B_KC>(C, C + TILE_BYTES, 1, a1, b1, wm, wn, lane); EG_PIN();             \
         mfma_rows<1, 4>(a0, b0, acc); EG_PIN();                                                   \
         EG_KSTEP(a1, b1, a0, b0, C, 2)                                                            \
@@ -242,13 +268,13 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
         /* last k-step: every MFMA is followed by one direct load of the stage after next into C */ \
         _Pragma("unroll") for (int j = 0; j < 4; j++) {                                           \
             acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[0], b1[j], acc[0][j], 0, 0, 0); EG_PIN(); \
-            if (has2) dma(j, ga2, gb2, C);                                                        \
+            if (has2) dma(j, ga2, gb2, kr2, C);                                                        \
             EG_PIN();                                                                             \
         }                                                                                         \
         load_frags<A_KC, B_KC>(O, O + TILE_BYTES, 0, a0, b0, wm, wn, lane); EG_PIN();             \
         _Pragma("unroll") for (int q = 0; q < 12; q++) {                                          \
             acc[1 + q / 4][q % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[1 + q / 4], b1[q % 4], acc[1 + q / 4][q % 4], 0, 0, 0); EG_PIN(); \
-            if (has2) dma(4 + q, ga2, gb2, C);                                                    \
+            if (has2) dma(4 + q, ga2, gb2, kr2, C);                                                    \
             EG_PIN();                                                                             \
         }                                                                                         \
     } while (0)
@@ -256,13 +282,14 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
     // barrier and twelve unused fragment reads): an MFMA under a branch inside the loop would make the
     // compiler shuffle the 256 accumulator registers.  The stage count's parity is a template parameter.
     const char *ga2, *gb2;
-    stage_ptrs(0, ga2, gb2);
-    issue(ga2, gb2, lds0);
+    int kr2;
+    stage_ptrs(0, ga2, gb2, kr2);
+    issue(ga2, gb2, kr2, lds0);
     __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
     if (nk > 1) {
-        stage_ptrs(BK, ga2, gb2);
-        issue(ga2, gb2, lds1);
+        stage_ptrs(BK, ga2, gb2, kr2);
+        issue(ga2, gb2, kr2, lds1);
     }
     load_frags<A_KC, B_KC>(lds0, lds0 + TILE_BYTES, 0, a0, b0, wm, wn, lane);
     if (ODD) {
@@ -381,7 +408,7 @@ static int launch_one(ContractParams &p, void *stream)
 template <bool A_KC, bool B_KC>
 static int launch_parity(ContractParams &p, void *stream)
 {
-    return ((p.K / BK) & 1) ? launch_one<A_KC, B_KC, true>(p, stream) : launch_one<A_KC, B_KC, false>(p, stream);
+    return (((p.K + BK - 1) / BK) & 1) ? launch_one<A_KC, B_KC, true>(p, stream) : launch_one<A_KC, B_KC, false>(p, stream);
 }
 
 }  // namespace dma
@@ -390,8 +417,9 @@ bool contract_dma_eligible(const ContractParams &p)
 {
     if (p.in_dtype != EG_BF16) return false;
     if (p.m.n < 1 || p.n.n < 1 || p.k.n < 1) return false;
-    if (p.K % dma::BK || p.k.ext[p.k.n - 1] % dma::BK) return false;       // stages never straddle a K label
-    if (p.span_x >= (1ll << 30) || p.span_y >= (1ll << 30)) return false;  // 32-bit lane offsets (in bytes < 2^31)
+    if (p.k.n > 1 && p.k.ext[p.k.n - 1] % dma::BK) return false;           // a stage never straddles two K labels
+    if ((p.a_kcontig || p.b_kcontig) && p.K % 8) return false;             // 16-byte chunks along K are whole or absent
+    if (p.span_x >= (1ll << 30) - 64 || p.span_y >= (1ll << 30) - 64) return false;  // lane byte offsets + 16 stay below 2^31
     if (p.a_kcontig ? p.k.s0[p.k.n - 1] != 1 : (p.m.s0[p.m.n - 1] != 1 || p.m.ext[p.m.n - 1] % 8)) return false;
     if (p.b_kcontig ? p.k.s1[p.k.n - 1] != 1 : (p.n.s0[p.n.n - 1] != 1 || p.n.ext[p.n.n - 1] % 8)) return false;
     if (!p.a_kcontig && p.M < 8) return false;

@@ -82,6 +82,9 @@ LAYOUTS = [
     ("bshd,ahd->bsa", (2, 72, 3, 40), (88, 3, 40)),
     ("ijk,kl->ijl", (3, 40, 264), (264, 72)),
     ("bf,bh->fh", (264, 136), (264, 72)),
+    ("ji,jk->ik", (100, 200), (100, 136)),       # K tail that is no multiple of 8 (both operands strided along K)
+    ("ij,kj->ik", (200, 24), (136, 24)),         # K shorter than one stage
+    ("ij,jk->ik", (264, 1384), (1384, 264)),     # many stages, odd count, tail of 40
 ]
 
 
