@@ -16,6 +16,8 @@
 // to the register-staged kernel.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "eg_device.h"
 
 namespace eg {
@@ -27,7 +29,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 namespace dma {
 
-constexpr int BM = 256, BN = 256, BK = 64, THREADS = 256;
+constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int TILE_BYTES = 256 * 64 * 2;          // one operand tile of one stage: 32 KiB
 constexpr int STAGE_BYTES = 2 * TILE_BYTES;
 
@@ -47,26 +49,27 @@ __device__ __forceinline__ void decode_group2(const DimList &g, int64_t idx, int
     }
 }
 
-// Per-lane source offsets (elements, relative to the operand's block base) of the 8 chunks this lane
-// fetches per stage, without the k advance.
-//   KC: instruction i of wave w deposits rows (4i+w)*8 .. +7, lane -> row +lane/8, physical chunk lane%8,
+// Per-lane source offsets (bytes, relative to the operand's block base) of the 32/NW chunks this lane
+// fetches per stage (NW waves per workgroup), without the k advance.
+//   KC: instruction i of wave w deposits rows (NW i+w)*8 .. +7, lane -> row +lane/8, physical chunk lane%8,
 //       logical chunk (lane%8) ^ ((row>>1)&7).
-//   MC: instruction i of wave w deposits k-rows (4i+w)*2 .. +1, lane -> k-row +lane/32, physical chunk lane%32,
+//   MC: instruction i of wave w deposits k-rows (NW i+w)*2 .. +1, lane -> k-row +lane/32, physical chunk lane%32,
 //       logical chunk (lane%32) ^ 4*(krow%4), krow%4 = (2w + lane/32)%4.
-template <bool KC>
+template <bool KC, int NW>
 struct Src {
-    uint32_t boff[8];         // byte offset of the chunk instruction i fetches, relative to the stage's first k
-    int kl;                   // k (within the stage) of chunk 0 of this lane; chunk i sits at kl (KC) or kl + 8 i (MC)
+    static constexpr int LD = 32 / NW;
+    uint32_t boff[LD];        // byte offset of the chunk instruction i fetches, relative to the stage's first k
+    int kl;                   // k (within the stage) of chunk 0 of this lane; chunk i sits at kl (KC) or kl + 2 NW i (MC)
 
     __device__ __forceinline__ void init(const DimList &grp, int64_t first, int64_t extent, int64_t k_inner_stride, int wave, int lane)
     {
         if (KC) {
-            // LDS row of this lane's chunk is (4i+wave)*8 + lane/8; its swizzle key (row>>1)&7 does not depend on i
+            // LDS row of this lane's chunk is (NW i+wave)*8 + lane/8; its swizzle key (row>>1)&7 does not depend on i
             const int lc = (lane & 7) ^ ((wave * 4 + (lane >> 4)) & 7);
             kl = lc * 8;
 #pragma unroll
-            for (int i = 0; i < 8; i++) {
-                int64_t r = first + (4 * i + wave) * 8 + (lane >> 3);
+            for (int i = 0; i < LD; i++) {
+                int64_t r = first + (NW * i + wave) * 8 + (lane >> 3);
                 r = r < extent ? r : extent - 1;
                 int64_t o0, o1;
                 decode_group2(grp, r, o0, o1);
@@ -81,14 +84,14 @@ struct Src {
             decode_group2(grp, m, o0, o1);
             kl = 2 * wave + (lane >> 5);
 #pragma unroll
-            for (int i = 0; i < 8; i++)
-                boff[i] = (uint32_t)((o0 + (8 * i + 2 * wave + (lane >> 5)) * k_inner_stride) * 2);
+            for (int i = 0; i < LD; i++)
+                boff[i] = (uint32_t)((o0 + (2 * NW * i + 2 * wave + (lane >> 5)) * k_inner_stride) * 2);
         }
     }
     // offset handed to load i of a stage that has `krem` valid k left: beyond the descriptor when the chunk's k is past the end
     __device__ __forceinline__ uint32_t voff(int i, int krem) const
     {
-        const int k = KC ? kl : kl + 8 * i;
+        const int k = KC ? kl : kl + 2 * NW * i;
         return k < krem ? boff[i] : 0x80000000u;
     }
 };
@@ -111,54 +114,60 @@ __device__ __forceinline__ int mc_frag_off(int col0, int ks, int lane, int secon
     return kr * 512 + (pc << 4) + ((n & 7) << 1);
 }
 
-// Fragments of one k-step (16 k): four 32-row A fragments and four 32-column B fragments of this wave.
-template <bool A_KC, bool B_KC>
-__device__ __forceinline__ void load_frags(const char *la, const char *lb, int ks, bf16x8 (&a)[4], bf16x8 (&b)[4], int wm, int wn, int lane)
+// Fragments of one k-step (16 k): four 32-row A fragments and NT 32-column B fragments of this wave
+// (row0, col0: first row / column of the wave's patch inside the tile).
+template <bool A_KC, bool B_KC, int NT>
+__device__ __forceinline__ void load_frags(const char *la, const char *lb, int ks, bf16x8 (&a)[4], bf16x8 (&b)[NT], int row0, int col0, int lane)
 {
 #pragma unroll
     for (int i = 0; i < 4; i++) {
         if (A_KC) {
-            a[i] = *(const bf16x8 *)(la + kc_frag_off(wm * 128 + i * 32 + (lane & 31), ks, lane));
+            a[i] = *(const bf16x8 *)(la + kc_frag_off(row0 + i * 32 + (lane & 31), ks, lane));
         } else {
-            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off(wm * 128 + i * 32, ks, lane, 0)));
-            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off(wm * 128 + i * 32, ks, lane, 1)));
+            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off(row0 + i * 32, ks, lane, 0)));
+            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off(row0 + i * 32, ks, lane, 1)));
             short4v *dst = (short4v *)&a[i];
             dst[0] = lo; dst[1] = hi;
         }
     }
 #pragma unroll
-    for (int j = 0; j < 4; j++) {
+    for (int j = 0; j < NT; j++) {
         if (B_KC) {
-            b[j] = *(const bf16x8 *)(lb + kc_frag_off(wn * 128 + j * 32 + (lane & 31), ks, lane));
+            b[j] = *(const bf16x8 *)(lb + kc_frag_off(col0 + j * 32 + (lane & 31), ks, lane));
         } else {
-            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off(wn * 128 + j * 32, ks, lane, 0)));
-            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off(wn * 128 + j * 32, ks, lane, 1)));
+            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off(col0 + j * 32, ks, lane, 0)));
+            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off(col0 + j * 32, ks, lane, 1)));
             short4v *dst = (short4v *)&b[j];
             dst[0] = lo; dst[1] = hi;
         }
     }
 }
 
-// MFMAs of one k-step for rows [I0, I1) of this wave's 4x4 grid of 32x32 tiles.
-template <int I0, int I1>
-__device__ __forceinline__ void mfma_rows(const bf16x8 (&a)[4], const bf16x8 (&b)[4], f32x16 (&acc)[4][4])
+// MFMAs of one k-step for rows [I0, I1) of this wave's 4 x NT grid of 32x32 tiles.
+template <int I0, int I1, int NT>
+__device__ __forceinline__ void mfma_rows(const bf16x8 (&a)[4], const bf16x8 (&b)[NT], f32x16 (&acc)[4][NT])
 {
 #pragma unroll
     for (int i = I0; i < I1; i++)
 #pragma unroll
-        for (int j = 0; j < 4; j++)
+        for (int j = 0; j < NT; j++)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
 }
 
-template <bool A_KC, bool B_KC, bool ODD>
-__global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p)
+// NW = 4: one wave per SIMD, each owning 128 x 128 of the tile.  NW = 8: two waves per SIMD, each owning
+// 128 x 64; one wave's MFMAs then cover the other's LDS reads and barrier waits, at 1.5x the LDS read traffic.
+template <int NW, bool A_KC, bool B_KC, bool ODD>
+__global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p)
 {
+    constexpr int NT = 16 / NW;                       // 32-column MFMA tiles per wave: the wave's patch is 128 x 32 NT
+    constexpr int LD = 32 / NW;                       // direct loads per operand tile, wave and stage
     // Two separate LDS objects, one per stage: the compiler can then tell that the fragment reads of one
     // stage never alias the direct loads in flight into the other, and does not wait for them.
     __shared__ __attribute__((aligned(1024))) char lds0[STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) char lds1[STAGE_BYTES];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / (NW / 2), wn = wave % (NW / 2);
+    const int row0 = wm * 128, col0 = wn * (32 * NT);
 
     // ---- workgroup -> (tuple, batch, tile); consecutive logical ids stay on one XCD -----------------
     const int64_t total = (int64_t)gridDim.x;
@@ -202,8 +211,8 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
     const char *yb = uniform_ptr((const char *)p.y + by * 2);
     const int kin = p.k.n - 1;                        // innermost K label: every 64-run of k lies inside it
 
-    Src<A_KC> sa;
-    Src<B_KC> sb;
+    Src<A_KC, NW> sa;
+    Src<B_KC, NW> sb;
     sa.init(p.m, m0, p.M, p.k.s0[kin], wave, lane);
     sb.init(p.n, n0, p.N, p.k.s1[kin], wave, lane);
 
@@ -216,65 +225,65 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
         const int64_t left = p.K - k0;
         krem = left < BK ? (int)left : BK;
     };
-    // direct load i (0..7: X tile, 8..15: Y tile) of a stage into the LDS stage at `dst`: a 2 GiB buffer descriptor
+    // direct load i (0..LD-1: X tile, LD..2LD-1: Y tile) of a stage into the LDS stage at `dst`: a 2 GiB buffer descriptor
     // on the uniform stage base + a 32-bit lane offset (in-block offsets are below 2^31; 2^31 itself means "no fetch, zeros")
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     auto dma = [&](int i, const char *ga, const char *gb, int krem, char *dst) {
-        if (i < 8) {
+        if (i < LD) {
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)ga, 0, (int)0x80000000u, 0x00020000);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, EG_LDS(dst + (4 * i + wave_u) * 1024), 16, (int)sa.voff(i, krem), 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, EG_LDS(dst + (NW * i + wave_u) * 1024), 16, (int)sa.voff(i, krem), 0, 0, 0);
         } else {
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)gb, 0, (int)0x80000000u, 0x00020000);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, EG_LDS(dst + TILE_BYTES + (4 * (i - 8) + wave_u) * 1024), 16, (int)sb.voff(i - 8, krem), 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, EG_LDS(dst + TILE_BYTES + (NW * (i - LD) + wave_u) * 1024), 16, (int)sb.voff(i - LD, krem), 0, 0, 0);
         }
     };
     auto issue = [&](const char *ga, const char *gb, int krem, char *dst) {
 #pragma unroll
-        for (int i = 0; i < 16; i++) dma(i, ga, gb, krem, dst);
+        for (int i = 0; i < 2 * LD; i++) dma(i, ga, gb, krem, dst);
     };
 
-    f32x16 acc[4][4];
+    f32x16 acc[4][NT];
 #pragma unroll
     for (int i = 0; i < 4; i++)
 #pragma unroll
-        for (int j = 0; j < 4; j++)
+        for (int j = 0; j < NT; j++)
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
     // Software pipeline.  Fragment registers alternate between two sets (f0 = a0/b0, f1 = a1/b1).  Each k-step
-    // issues its first 4 MFMAs, then the LDS reads of the next k-step, then its other 12 MFMAs, so the reads
+    // issues its first NT MFMAs, then the LDS reads of the next k-step, then its other 3 NT MFMAs, so the reads
     // return while the matrix pipe is busy.  The last k-step of a stage runs after the barrier, together with
     // the direct loads of the stage after next and the first fragment reads of the next stage.
     // sched_barrier pins this order against the compiler's own scheduling.
     const int64_t nk = (p.K + BK - 1) / BK;
-    bf16x8 a0[4], b0[4], a1[4], b1[4];
+    bf16x8 a0[4], b0[NT], a1[4], b1[NT];
 #define EG_PIN() __builtin_amdgcn_sched_barrier(0)
 #define EG_KSTEP(FA, FB, NA, NB, BUF, KS_NEXT)                                                    \
-    mfma_rows<0, 1>(FA, FB, acc); EG_PIN();                                                       \
-    load_frags<A_KC, B_KC>(BUF, BUF + TILE_BYTES, KS_NEXT, NA, NB, wm, wn, lane); EG_PIN();       \
-    mfma_rows<1, 4>(FA, FB, acc); EG_PIN();
+    mfma_rows<0, 1, NT>(FA, FB, acc); EG_PIN();                                                   \
+    load_frags<A_KC, B_KC, NT>(BUF, BUF + TILE_BYTES, KS_NEXT, NA, NB, row0, col0, lane); EG_PIN(); \
+    mfma_rows<1, 4, NT>(FA, FB, acc); EG_PIN();
 #define EG_STAGE_NEXT(C, O, HAS_NEXT2, K_NEXT2) /* one stage; its successor is already in flight into O */ \
     do {                                                                                          \
-        mfma_rows<0, 1>(a0, b0, acc); EG_PIN();                                                   \
+        mfma_rows<0, 1, NT>(a0, b0, acc); EG_PIN();                                               \
         const bool has2 = (HAS_NEXT2);                                                            \
-        stage_ptrs(has2 ? (K_NEXT2) : 0, ga2, gb2, kr2);          /* scalar work rides under the MFMAs */ \
-        load_frags<A_KC, B_KC>(C, C + TILE_BYTES, 1, a1, b1, wm, wn, lane); EG_PIN();             \
-        mfma_rows<1, 4>(a0, b0, acc); EG_PIN();                                                   \
+        stage_ptrs(has2 ? (K_NEXT2) : 0, ga2, gb2, kr2);     /* scalar work rides under the MFMAs */ \
+        load_frags<A_KC, B_KC, NT>(C, C + TILE_BYTES, 1, a1, b1, row0, col0, lane); EG_PIN();     \
+        mfma_rows<1, 4, NT>(a0, b0, acc); EG_PIN();                                               \
         EG_KSTEP(a1, b1, a0, b0, C, 2)                                                            \
         EG_KSTEP(a0, b0, a1, b1, C, 3)                                                            \
         __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): this wave's deposits for O landed */     \
         __syncthreads();                    /* everybody's landed; everybody has left C */        \
         EG_PIN();                                                                                 \
         /* last k-step: every MFMA is followed by one direct load of the stage after next into C */ \
-        _Pragma("unroll") for (int j = 0; j < 4; j++) {                                           \
+        _Pragma("unroll") for (int j = 0; j < NT; j++) {                                          \
             acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[0], b1[j], acc[0][j], 0, 0, 0); EG_PIN(); \
-            if (has2) dma(j, ga2, gb2, kr2, C);                                                        \
+            if (has2) dma(j, ga2, gb2, kr2, C);                                                   \
             EG_PIN();                                                                             \
         }                                                                                         \
-        load_frags<A_KC, B_KC>(O, O + TILE_BYTES, 0, a0, b0, wm, wn, lane); EG_PIN();             \
-        _Pragma("unroll") for (int q = 0; q < 12; q++) {                                          \
-            acc[1 + q / 4][q % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[1 + q / 4], b1[q % 4], acc[1 + q / 4][q % 4], 0, 0, 0); EG_PIN(); \
-            if (has2) dma(4 + q, ga2, gb2, kr2, C);                                                    \
+        load_frags<A_KC, B_KC, NT>(O, O + TILE_BYTES, 0, a0, b0, row0, col0, lane); EG_PIN();     \
+        _Pragma("unroll") for (int q = 0; q < 3 * NT; q++) {                                      \
+            acc[1 + q / NT][q % NT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[1 + q / NT], b1[q % NT], acc[1 + q / NT][q % NT], 0, 0, 0); EG_PIN(); \
+            if (has2) dma(NT + q, ga2, gb2, kr2, C);                                              \
             EG_PIN();                                                                             \
         }                                                                                         \
     } while (0)
@@ -291,7 +300,7 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
         stage_ptrs(BK, ga2, gb2, kr2);
         issue(ga2, gb2, kr2, lds1);
     }
-    load_frags<A_KC, B_KC>(lds0, lds0 + TILE_BYTES, 0, a0, b0, wm, wn, lane);
+    load_frags<A_KC, B_KC, NT>(lds0, lds0 + TILE_BYTES, 0, a0, b0, row0, col0, lane);
     if (ODD) {
         EG_STAGE_NEXT(lds0, lds1, 2 < nk, 2 * BK);
         for (int64_t st = 1; st < nk; st += 2) {
@@ -312,7 +321,7 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
     // ---- epilogue ---------------------------------------------------------------------------------
     // Z offsets of the tile's 256 rows and 256 columns go through LDS (free now): one decode per thread.
     int64_t *zrow = (int64_t *)lds0, *zcol = zrow + 256;
-    {
+    if (tid < 256) {
         int64_t unused, z;
         const int64_t m = m0 + tid, n = n0 + tid;
         decode_group2(p.m, m < p.M ? m : 0, unused, z);
@@ -326,38 +335,43 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
     const bool out_bf16 = p.out.dtype == EG_BF16;
     const int lrow = lane & 31, lhalf = lane >> 5;
     if (p.out_vec) {
-        // Z is contiguous along the tile's columns: each wave stages 32 rows x 128 columns of its patch in LDS
-        // (row pitch 544 bytes keeps the two half-waves on different banks) and writes them out as whole row
-        // segments, 16 bytes per lane.  LDS operations of one wave execute in order, so no barrier is needed.
-        constexpr int PITCH = 544, WBUF = 32 * PITCH;
-        char *wbuf = wave < 3 ? lds1 + wave * WBUF : lds0 + 4096;
+        // Z is contiguous along the tile's columns: each wave stages 32 rows x CW columns of its patch in LDS
+        // (the row pitch leaves 32 bytes of padding, which keeps the two half-waves on different banks) and
+        // writes them out as whole row segments, 16 bytes per lane.  LDS operations of one wave execute in
+        // order, so no barrier is needed.  The last wave's buffer sits behind the offset tables in lds0.
+        constexpr int CW = 32 * NT, PITCH = CW * 4 + 32, WBUF = 32 * PITCH;
+        static_assert((NW - 1) * WBUF <= STAGE_BYTES && 4096 + WBUF <= STAGE_BYTES, "epilogue buffers fit the two stages");
+        char *wbuf = wave < NW - 1 ? lds1 + wave * WBUF : lds0 + 4096;
+        constexpr int LPR_F = CW / 4, RPI_F = 64 / LPR_F;     // fp32 out: lanes per row, rows per store instruction
+        constexpr int LPR_B = CW / 8, RPI_B = 64 / LPR_B;     // bf16 out
 #pragma unroll
         for (int i = 0; i < 4; i++) {
 #pragma unroll
-            for (int j = 0; j < 4; j++)
+            for (int j = 0; j < NT; j++)
 #pragma unroll
                 for (int r = 0; r < 16; r++)
                     *(float *)(wbuf + (8 * (r >> 2) + 4 * lhalf + (r & 3)) * PITCH + (j * 32 + lrow) * 4) = p.alpha * acc[i][j][r];
             if (!out_bf16) {
-                const int c = wn * 128 + lrow * 4;                        // 4 consecutive columns
+                const int lc = lane % LPR_F, lr = lane / LPR_F;
+                const int c = col0 + lc * 4;                              // 4 consecutive columns
                 const int64_t zc = bz + zcol[c];
                 const bool cok = n0 + c < p.N;
 #pragma unroll
-                for (int it = 0; it < 16; it++) {
-                    const int row = 2 * it + lhalf, rr = wm * 128 + i * 32 + row;
-                    const f32x4 v = *(const f32x4 *)(wbuf + row * PITCH + lrow * 16);
+                for (int it = 0; it < 32 / RPI_F; it++) {
+                    const int row = RPI_F * it + lr, rr = row0 + i * 32 + row;
+                    const f32x4 v = *(const f32x4 *)(wbuf + row * PITCH + lc * 16);
                     if (cok && m0 + rr < p.M) *(f32x4 *)((float *)zb + zrow[rr] + zc) = v;
                 }
             } else {
-                const int l16 = lane & 15, lq = lane >> 4;
-                const int c = wn * 128 + l16 * 8;                         // 8 consecutive columns
+                const int lc = lane % LPR_B, lr = lane / LPR_B;
+                const int c = col0 + lc * 8;                              // 8 consecutive columns
                 const int64_t zc = bz + zcol[c];
                 const bool cok = n0 + c < p.N;
 #pragma unroll
-                for (int it = 0; it < 8; it++) {
-                    const int row = 4 * it + lq, rr = wm * 128 + i * 32 + row;
-                    const f32x4 v0 = *(const f32x4 *)(wbuf + row * PITCH + l16 * 32);
-                    const f32x4 v1 = *(const f32x4 *)(wbuf + row * PITCH + l16 * 32 + 16);
+                for (int it = 0; it < 32 / RPI_B; it++) {
+                    const int row = RPI_B * it + lr, rr = row0 + i * 32 + row;
+                    const f32x4 v0 = *(const f32x4 *)(wbuf + row * PITCH + lc * 32);
+                    const f32x4 v1 = *(const f32x4 *)(wbuf + row * PITCH + lc * 32 + 16);
                     uint4 o;
                     o.x = pack_bf16x2(v0.x, v0.y); o.y = pack_bf16x2(v0.z, v0.w);
                     o.z = pack_bf16x2(v1.x, v1.y); o.w = pack_bf16x2(v1.z, v1.w);
@@ -367,11 +381,11 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
         }
         return;
     }
-    int64_t zn[4];
-    bool nok[4];
+    int64_t zn[NT];
+    bool nok[NT];
 #pragma unroll
-    for (int j = 0; j < 4; j++) {
-        const int c = wn * 128 + j * 32 + lrow;
+    for (int j = 0; j < NT; j++) {
+        const int c = col0 + j * 32 + lrow;
         zn[j] = bz + zcol[c];
         nok[j] = n0 + c < p.N;
     }
@@ -379,11 +393,11 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
     for (int i = 0; i < 4; i++) {
 #pragma unroll
         for (int r = 0; r < 16; r++) {
-            const int rr = wm * 128 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+            const int rr = row0 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
             if (m0 + rr >= p.M) continue;
             const int64_t zm = zrow[rr];
 #pragma unroll
-            for (int j = 0; j < 4; j++) {
+            for (int j = 0; j < NT; j++) {
                 if (!nok[j]) continue;
                 const float val = p.alpha * acc[i][j][r];
                 const int64_t off = zm + zn[j];
@@ -395,20 +409,27 @@ __global__ __launch_bounds__(THREADS) void k_contract_dma(const ContractParams p
     }
 }
 
-template <bool A_KC, bool B_KC, bool ODD>
+template <int NW, bool A_KC, bool B_KC, bool ODD>
 static int launch_one(ContractParams &p, void *stream)
 {
     const int64_t wgs = p.n_tuples * p.n_batch * p.tiles_m * p.tiles_n;
-    hipLaunchKernelGGL((k_contract_dma<A_KC, B_KC, ODD>), dim3((unsigned)wgs), dim3(THREADS), 0, (hipStream_t)stream, p);
+    hipLaunchKernelGGL((k_contract_dma<NW, A_KC, B_KC, ODD>), dim3((unsigned)wgs), dim3(NW * 64), 0, (hipStream_t)stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(EG_ERR_HIP, "k_contract_dma launch failed: %s", hipGetErrorString(e));
     return EG_OK;
 }
 
-template <bool A_KC, bool B_KC>
+template <int NW, bool A_KC, bool B_KC>
 static int launch_parity(ContractParams &p, void *stream)
 {
-    return (((p.K + BK - 1) / BK) & 1) ? launch_one<A_KC, B_KC, true>(p, stream) : launch_one<A_KC, B_KC, false>(p, stream);
+    return (((p.K + BK - 1) / BK) & 1) ? launch_one<NW, A_KC, B_KC, true>(p, stream) : launch_one<NW, A_KC, B_KC, false>(p, stream);
+}
+
+template <int NW>
+static int launch_layout(ContractParams &p, void *stream)
+{
+    if (p.a_kcontig) return p.b_kcontig ? launch_parity<NW, true, true>(p, stream) : launch_parity<NW, true, false>(p, stream);
+    return p.b_kcontig ? launch_parity<NW, false, true>(p, stream) : launch_parity<NW, false, false>(p, stream);
 }
 
 }  // namespace dma
@@ -443,8 +464,9 @@ int launch_contract_dma(ContractParams &p, void *stream)
     for (int i = 0; i < p.batch.n; i++) vec = vec && p.batch.s2[i] % 8 == 0;
     for (int l = 0; l < p.ts.n; l++) vec = vec && p.ts.step_z[l] % 8 == 0;
     p.out_vec = vec ? 1 : 0;
-    if (p.a_kcontig) return p.b_kcontig ? dma::launch_parity<true, true>(p, stream) : dma::launch_parity<true, false>(p, stream);
-    return p.b_kcontig ? dma::launch_parity<false, true>(p, stream) : dma::launch_parity<false, false>(p, stream);
+    static const char *waves = getenv("EINDECOMP_DMA_WAVES");         // 4 or 8 waves per workgroup (for comparisons)
+    if (waves && atoi(waves) == 4) return dma::launch_layout<4>(p, stream);
+    return dma::launch_layout<8>(p, stream);
 }
 
 }  // namespace eg
