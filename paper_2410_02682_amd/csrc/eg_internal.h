@@ -66,6 +66,7 @@ struct ContractParams {
     int64_t span_x, span_y;       // largest element offset inside one block of X / Y
     int32_t tiles_m, tiles_n;     // filled by the launcher
     int32_t out_vec;              // filled by the launcher: 1 = Z rows can be written as 16-byte vectors along N
+    int32_t total_tiles, grid;    // filled by the launcher: output tiles over all tuples and batch entries; workgroups that share them
 };
 
 struct StridedDims {              // collapsed index space with per-operand element strides

@@ -26,6 +26,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 namespace dma {
 
@@ -154,44 +155,70 @@ __device__ __forceinline__ void mfma_rows(const bf16x8 (&a)[4], const bf16x8 (&b
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
 }
 
+// What is uniform over a workgroup about one output tile.
+struct TileInfo {
+    int64_t m0, n0;          // first row / column of the tile inside the block
+    const char *xb, *yb;     // X and Y at the tuple's blocks and the batch entry
+    int64_t bz, agg;         // Z element offset of the tuple's block and batch entry; aggIdx of the tuple
+};
+
 // NW = 4: one wave per SIMD, each owning 128 x 128 of the tile.  NW = 8: two waves per SIMD, each owning
 // 128 x 64; one wave's MFMAs then cover the other's LDS reads and barrier waits, at 1.5x the LDS read traffic.
+//
+// The kernel is persistent: one workgroup per compute unit walks over its share of the tiles.  While a tile's
+// epilogue runs, the first two stages of the workgroup's next tile are already on their way into LDS, and the
+// next tile's addressing was worked out while the current tile waited for its own first stage.
 template <int NW, bool A_KC, bool B_KC, bool ODD>
 __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p)
 {
     constexpr int NT = 16 / NW;                       // 32-column MFMA tiles per wave: the wave's patch is 128 x 32 NT
     constexpr int LD = 32 / NW;                       // direct loads per operand tile, wave and stage
-    // Two separate LDS objects, one per stage: the compiler can then tell that the fragment reads of one
-    // stage never alias the direct loads in flight into the other, and does not wait for them.
+    constexpr int CW = 32 * NT, PITCH = CW * 4 + 32, WBUF = 8 * PITCH;   // epilogue staging: 8 rows of a wave's patch
+    // Separate LDS objects for the two stages and for the epilogue: the compiler can then tell that the fragment
+    // reads of one stage, or the epilogue's staging, never alias the direct loads in flight into another object,
+    // and does not wait for them.
     __shared__ __attribute__((aligned(1024))) char lds0[STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) char lds1[STAGE_BYTES];
+    __shared__ __attribute__((aligned(16))) char ldsx[2 * 4096 + NW * WBUF];   // two sets of Z offset tables + staging
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / (NW / 2), wn = wave % (NW / 2);
     const int row0 = wm * 128, col0 = wn * (32 * NT);
 
-    // ---- workgroup -> (tuple, batch, tile); consecutive logical ids stay on one XCD -----------------
-    const int64_t total = (int64_t)gridDim.x;
-    int64_t logical;
-    {
-        const int64_t per = total / 8, rem = total % 8;
-        const int64_t x = blockIdx.x % 8, j = blockIdx.x / 8;
-        logical = x * per + (x < rem ? x : rem) + j;
+    // ---- this workgroup's tiles: logical ids first, first + stride, ...; concurrent ids share an XCD ----
+    const uint32_t total = (uint32_t)p.total_tiles, G = gridDim.x;
+    uint32_t first, stride, count;
+    if ((G & 7) == 0) {
+        const uint32_t per = total / 8, rem = total % 8, x = blockIdx.x % 8, j = blockIdx.x / 8;
+        const uint32_t nx = per + (x < rem ? 1 : 0);
+        stride = G / 8;
+        first = x * per + (x < rem ? x : rem) + j;
+        count = j < nx ? (nx - j + stride - 1) / stride : 0;
+    } else {
+        stride = G;
+        first = blockIdx.x;
+        count = first < total ? (total - first + G - 1) / G : 0;
     }
-    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
-    const int64_t tb = logical / tiles;
-    const int tl = (int)(logical - tb * tiles);
-    constexpr int GM = 8;
-    const int span = GM * p.tiles_n;
-    const int grp = tl / span, first_m = grp * GM;
-    const int gsz = (p.tiles_m - first_m) < GM ? (p.tiles_m - first_m) : GM;
-    const int tile_m = first_m + (tl - grp * span) % gsz;
-    const int tile_n = (tl - grp * span) / gsz;
-    const int64_t tuple = tb / p.n_batch, bidx = tb - tuple * p.n_batch;
+    if (count == 0) return;
 
-    int64_t bx, by, bz, agg;
-    decode_tuple(p.ts, tuple, bx, by, bz, agg);
-    {
-        uint32_t rem = (uint32_t)bidx;
+    auto uniform_ptr = [](const char *q) {            // the buffer descriptors must live in scalar registers
+        const uint64_t v = (uint64_t)q;
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+        return (const char *)(((uint64_t)hi << 32) | lo);
+    };
+    // logical id -> (tuple, batch entry, tile); tiles are walked in groups of 8 tile rows
+    auto tile_info = [&](uint32_t logical, TileInfo &t) {
+        const uint32_t tiles = (uint32_t)p.tiles_m * (uint32_t)p.tiles_n;
+        const uint32_t tb = logical / tiles, tl = logical - tb * tiles;
+        constexpr uint32_t GM = 8;
+        const uint32_t span = GM * (uint32_t)p.tiles_n;
+        const uint32_t grp = tl / span, first_m = grp * GM;
+        const uint32_t gsz = ((uint32_t)p.tiles_m - first_m) < GM ? ((uint32_t)p.tiles_m - first_m) : GM;
+        const uint32_t tile_m = first_m + (tl - grp * span) % gsz;
+        const uint32_t tile_n = (tl - grp * span) / gsz;
+        const uint32_t nb = (uint32_t)p.n_batch, tuple = tb / nb, bidx = tb - tuple * nb;
+        int64_t bx, by, bz, agg;
+        decode_tuple(p.ts, tuple, bx, by, bz, agg);
+        uint32_t rem = bidx;
         for (int i = p.batch.n - 1; i >= 0; i--) {
             uint32_t e = (uint32_t)p.batch.ext[i], q = rem / e, k = rem - q * e;
             rem = q;
@@ -199,22 +226,20 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
             by += (int64_t)k * p.batch.s1[i];
             bz += (int64_t)k * p.batch.s2[i];
         }
-    }
-    const int64_t m0 = (int64_t)tile_m * BM, n0 = (int64_t)tile_n * BN;
-    // block bases are the same for the whole workgroup: say so, the buffer descriptors must live in scalar registers
-    auto uniform_ptr = [](const char *q) {
-        const uint64_t v = (uint64_t)q;
-        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-        return (const char *)(((uint64_t)hi << 32) | lo);
+        t.m0 = (int64_t)tile_m * BM;
+        t.n0 = (int64_t)tile_n * BN;
+        t.xb = uniform_ptr((const char *)p.x + bx * 2);
+        t.yb = uniform_ptr((const char *)p.y + by * 2);
+        t.bz = bz;
+        t.agg = agg;
     };
-    const char *xb = uniform_ptr((const char *)p.x + bx * 2);
-    const char *yb = uniform_ptr((const char *)p.y + by * 2);
     const int kin = p.k.n - 1;                        // innermost K label: every 64-run of k lies inside it
+    const int64_t nk = (p.K + BK - 1) / BK;
 
+    TileInfo cur, nxt;
     Src<A_KC, NW> sa;
     Src<B_KC, NW> sb;
-    sa.init(p.m, m0, p.M, p.k.s0[kin], wave, lane);
-    sb.init(p.n, n0, p.N, p.k.s1[kin], wave, lane);
+    const char *xb, *yb;                              // bases the direct loads currently work from
 
     // uniform source pointers of the stage that starts at k0, and how many k it still has (64 or more: a full stage)
     auto stage_ptrs = [&](int64_t k0, const char *&ga, const char *&gb, int &krem) {
@@ -237,25 +262,50 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, EG_LDS(dst + TILE_BYTES + (NW * (i - LD) + wave_u) * 1024), 16, (int)sb.voff(i - LD, krem), 0, 0, 0);
         }
     };
+    // The same load written out by hand, for the loads that travel during an epilogue: the compiler keeps track of
+    // direct loads it issued itself and would hold the epilogue's first LDS access until they have landed.  These
+    // are waited for by the explicit vmcnt(0) and barrier at the head of the tile loop.  M0 (the LDS base of a
+    // direct load) is put back, so the compiler's own picture of it stays right.
+    auto dma_untracked = [&](int i, const char *ga, const char *gb, int krem, char *dst) {
+        const bool isa = i < LD;
+        const uint64_t base = (uint64_t)(isa ? ga : gb);
+        u32x4 rs;
+        rs.x = (uint32_t)base;
+        rs.y = (uint32_t)(base >> 32) & 0xffffu;       // stride 0
+        rs.z = 0x80000000u;
+        rs.w = 0x00020000u;
+        const uint32_t l = (uint32_t)(uintptr_t)EG_LDS(dst + (isa ? 0 : TILE_BYTES) + (NW * (isa ? i : i - LD) + wave_u) * 1024);
+        const uint32_t off = isa ? sa.voff(i, krem) : sb.voff(i - LD, krem);
+        uint32_t keep;
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
+                     : "=&s"(keep) : "s"(l), "v"(off), "s"(rs) : "memory");
+    };
     auto issue = [&](const char *ga, const char *gb, int krem, char *dst) {
 #pragma unroll
-        for (int i = 0; i < 2 * LD; i++) dma(i, ga, gb, krem, dst);
+        for (int i = 0; i < 2 * LD; i++) dma_untracked(i, ga, gb, krem, dst);
     };
-
-    f32x16 acc[4][NT];
-#pragma unroll
-    for (int i = 0; i < 4; i++)
-#pragma unroll
-        for (int j = 0; j < NT; j++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+    const char *ga2, *gb2;
+    int kr2;
+    // per-lane addressing of tile t, then its first two stages on their way (both LDS stages must be free)
+    auto start_tile = [&](const TileInfo &t) {
+        sa.init(p.m, t.m0, p.M, p.k.s0[kin], wave, lane);
+        sb.init(p.n, t.n0, p.N, p.k.s1[kin], wave, lane);
+        xb = uniform_ptr(t.xb);
+        yb = uniform_ptr(t.yb);
+        stage_ptrs(0, ga2, gb2, kr2);
+        issue(ga2, gb2, kr2, lds0);
+        if (nk > 1) {
+            stage_ptrs(BK, ga2, gb2, kr2);
+            issue(ga2, gb2, kr2, lds1);
+        }
+    };
 
     // Software pipeline.  Fragment registers alternate between two sets (f0 = a0/b0, f1 = a1/b1).  Each k-step
     // issues its first NT MFMAs, then the LDS reads of the next k-step, then its other 3 NT MFMAs, so the reads
     // return while the matrix pipe is busy.  The last k-step of a stage runs after the barrier, together with
     // the direct loads of the stage after next and the first fragment reads of the next stage.
     // sched_barrier pins this order against the compiler's own scheduling.
-    const int64_t nk = (p.K + BK - 1) / BK;
+    f32x16 acc[4][NT];
     bf16x8 a0[4], b0[NT], a1[4], b1[NT];
 #define EG_PIN() __builtin_amdgcn_sched_barrier(0)
 #define EG_KSTEP(FA, FB, NA, NB, BUF, KS_NEXT)                                                    \
@@ -287,133 +337,150 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
             EG_PIN();                                                                             \
         }                                                                                         \
     } while (0)
-    // Every stage, the last one included, runs the same straight-line code (the last one pays for one idle
-    // barrier and twelve unused fragment reads): an MFMA under a branch inside the loop would make the
-    // compiler shuffle the 256 accumulator registers.  The stage count's parity is a template parameter.
-    const char *ga2, *gb2;
-    int kr2;
-    stage_ptrs(0, ga2, gb2, kr2);
-    issue(ga2, gb2, kr2, lds0);
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
-    if (nk > 1) {
-        stage_ptrs(BK, ga2, gb2, kr2);
-        issue(ga2, gb2, kr2, lds1);
-    }
-    load_frags<A_KC, B_KC, NT>(lds0, lds0 + TILE_BYTES, 0, a0, b0, row0, col0, lane);
-    if (ODD) {
-        EG_STAGE_NEXT(lds0, lds1, 2 < nk, 2 * BK);
-        for (int64_t st = 1; st < nk; st += 2) {
-            EG_STAGE_NEXT(lds1, lds0, st + 2 < nk, (st + 2) * BK);
-            EG_STAGE_NEXT(lds0, lds1, st + 3 < nk, (st + 3) * BK);
-        }
-    } else {
-        for (int64_t st = 0; st < nk; st += 2) {
-            EG_STAGE_NEXT(lds0, lds1, st + 2 < nk, (st + 2) * BK);
-            EG_STAGE_NEXT(lds1, lds0, st + 3 < nk, (st + 3) * BK);
-        }
-    }
-    __syncthreads();
-#undef EG_STAGE_NEXT
-#undef EG_KSTEP
-#undef EG_PIN
 
-    // ---- epilogue ---------------------------------------------------------------------------------
-    // Z offsets of the tile's 256 rows and 256 columns go through LDS (free now): one decode per thread.
-    int64_t *zrow = (int64_t *)lds0, *zcol = zrow + 256;
-    if (tid < 256) {
-        int64_t unused, z;
-        const int64_t m = m0 + tid, n = n0 + tid;
-        decode_group2(p.m, m < p.M ? m : 0, unused, z);
-        zrow[tid] = z;
-        decode_group2(p.n, n < p.N ? n : 0, unused, z);
-        zcol[tid] = z;
-    }
-    __syncthreads();
-    // lane holds column (lane % 32) and rows 8*(r/4) + 4*(lane/32) + r%4 of each 32x32 tile
-    char *zb = (char *)p.out.ptr + (p.out.slab_elems ? agg * p.out.slab_elems * 4 : 0);
     const bool out_bf16 = p.out.dtype == EG_BF16;
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    if (p.out_vec) {
-        // Z is contiguous along the tile's columns: each wave stages 32 rows x CW columns of its patch in LDS
-        // (the row pitch leaves 32 bytes of padding, which keeps the two half-waves on different banks) and
-        // writes them out as whole row segments, 16 bytes per lane.  LDS operations of one wave execute in
-        // order, so no barrier is needed.  The last wave's buffer sits behind the offset tables in lds0.
-        constexpr int CW = 32 * NT, PITCH = CW * 4 + 32, WBUF = 32 * PITCH;
-        static_assert((NW - 1) * WBUF <= STAGE_BYTES && 4096 + WBUF <= STAGE_BYTES, "epilogue buffers fit the two stages");
-        char *wbuf = wave < NW - 1 ? lds1 + wave * WBUF : lds0 + 4096;
-        constexpr int LPR_F = CW / 4, RPI_F = 64 / LPR_F;     // fp32 out: lanes per row, rows per store instruction
-        constexpr int LPR_B = CW / 8, RPI_B = 64 / LPR_B;     // bf16 out
+
+    tile_info(first, cur);
+    start_tile(cur);
+    for (uint32_t it = 0;; it++) {
+        const bool more = it + 1 < count;
+        // while the first stages travel: the next tile's uniform addressing and this tile's Z offset tables
+        // (256 rows, 256 columns; two sets in turn, so a wave already in the next tile cannot disturb a slower one)
+        if (more) tile_info(first + (it + 1) * stride, nxt);
+        int64_t *zrow = (int64_t *)(ldsx + (it & 1) * 4096), *zcol = zrow + 256;
+        if (tid < 256) {
+            int64_t unused, z;
+            const int64_t m = cur.m0 + tid, n = cur.n0 + tid;
+            decode_group2(p.m, m < p.M ? m : 0, unused, z);
+            zrow[tid] = z;
+            decode_group2(p.n, n < p.N ? n : 0, unused, z);
+            zcol[tid] = z;
+        }
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
+        for (int i = 0; i < 4; i++)
 #pragma unroll
             for (int j = 0; j < NT; j++)
 #pragma unroll
-                for (int r = 0; r < 16; r++)
-                    *(float *)(wbuf + (8 * (r >> 2) + 4 * lhalf + (r & 3)) * PITCH + (j * 32 + lrow) * 4) = p.alpha * acc[i][j][r];
-            if (!out_bf16) {
-                const int lc = lane % LPR_F, lr = lane / LPR_F;
-                const int c = col0 + lc * 4;                              // 4 consecutive columns
-                const int64_t zc = bz + zcol[c];
-                const bool cok = n0 + c < p.N;
-#pragma unroll
-                for (int it = 0; it < 32 / RPI_F; it++) {
-                    const int row = RPI_F * it + lr, rr = row0 + i * 32 + row;
-                    const f32x4 v = *(const f32x4 *)(wbuf + row * PITCH + lc * 16);
-                    if (cok && m0 + rr < p.M) *(f32x4 *)((float *)zb + zrow[rr] + zc) = v;
-                }
-            } else {
-                const int lc = lane % LPR_B, lr = lane / LPR_B;
-                const int c = col0 + lc * 8;                              // 8 consecutive columns
-                const int64_t zc = bz + zcol[c];
-                const bool cok = n0 + c < p.N;
-#pragma unroll
-                for (int it = 0; it < 32 / RPI_B; it++) {
-                    const int row = RPI_B * it + lr, rr = row0 + i * 32 + row;
-                    const f32x4 v0 = *(const f32x4 *)(wbuf + row * PITCH + lc * 32);
-                    const f32x4 v1 = *(const f32x4 *)(wbuf + row * PITCH + lc * 32 + 16);
-                    uint4 o;
-                    o.x = pack_bf16x2(v0.x, v0.y); o.y = pack_bf16x2(v0.z, v0.w);
-                    o.z = pack_bf16x2(v1.x, v1.y); o.w = pack_bf16x2(v1.z, v1.w);
-                    if (cok && m0 + rr < p.M) *(uint4 *)((uint16_t *)zb + zrow[rr] + zc) = o;
-                }
+                for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+        __builtin_amdgcn_s_waitcnt(0x0F70);           // both stages (and the previous tile's stores) are done
+        __syncthreads();
+        load_frags<A_KC, B_KC, NT>(lds0, lds0 + TILE_BYTES, 0, a0, b0, row0, col0, lane);
+        // Every stage, the last one included, runs the same straight-line code (the last one pays for one idle
+        // barrier and a set of unused fragment reads): an MFMA under a branch inside the loop would make the
+        // compiler shuffle the accumulator registers.  The stage count's parity is a template parameter.
+        if (ODD) {
+            EG_STAGE_NEXT(lds0, lds1, 2 < nk, 2 * BK);
+            for (int64_t st = 1; st < nk; st += 2) {
+                EG_STAGE_NEXT(lds1, lds0, st + 2 < nk, (st + 2) * BK);
+                EG_STAGE_NEXT(lds0, lds1, st + 3 < nk, (st + 3) * BK);
+            }
+        } else {
+            for (int64_t st = 0; st < nk; st += 2) {
+                EG_STAGE_NEXT(lds0, lds1, st + 2 < nk, (st + 2) * BK);
+                EG_STAGE_NEXT(lds1, lds0, st + 3 < nk, (st + 3) * BK);
             }
         }
-        return;
-    }
-    int64_t zn[NT];
-    bool nok[NT];
+        __syncthreads();                              // every wave has left both stages
+        if (more) start_tile(nxt);                    // travels during the epilogue
+
+        // ---- epilogue of the current tile -----------------------------------------------------------
+        // lane holds column (lane % 32) and rows 8*(r/4) + 4*(lane/32) + r%4 of each 32x32 tile
+        char *zb = (char *)p.out.ptr + (p.out.slab_elems ? cur.agg * p.out.slab_elems * 4 : 0);
+        // Everything per-lane below is derived from a lane id the compiler cannot see through, or it would work
+        // out the addressing of all the unrolled stores once, before the tile loop, and keep it in scratch memory.
+        int elane = lane;
+        asm volatile("" : "+v"(elane));
+        const int lrow = elane & 31, lhalf = elane >> 5;
+        char *wbuf = ldsx + 2 * 4096 + wave_u * WBUF;  // this wave's staging rows
+        const int mrem = (int)(p.M - cur.m0 < BM ? p.M - cur.m0 : BM);     // rows / columns of the tile inside the block
+        const int nrem = (int)(p.N - cur.n0 < BN ? p.N - cur.n0 : BN);
+        if (p.out_vec) {
+            // Z is contiguous along the tile's columns: each wave stages 8 rows x CW columns of its patch at a time
+            // in LDS (the row pitch leaves 32 bytes of padding, which keeps the two half-waves on different banks)
+            // and writes them out as whole row segments, 16 bytes per lane.  LDS operations of one wave execute
+            // in order, so no barrier is needed.
+            constexpr int LPR_F = CW / 4, RPI_F = 64 / LPR_F;     // fp32 out: lanes per row, rows per store instruction
+            constexpr int LPR_B = CW / 8, RPI_B = 64 / LPR_B;     // bf16 out
+            static_assert(RPI_F <= 8 && RPI_B <= 8, "a store instruction covers at most the 8 staged rows");
 #pragma unroll
-    for (int j = 0; j < NT; j++) {
-        const int c = col0 + j * 32 + lrow;
-        zn[j] = bz + zcol[c];
-        nok[j] = n0 + c < p.N;
-    }
+            for (int i = 0; i < 4; i++) {
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
+                for (int q = 0; q < 4; q++) {
 #pragma unroll
-        for (int r = 0; r < 16; r++) {
-            const int rr = row0 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
-            if (m0 + rr >= p.M) continue;
-            const int64_t zm = zrow[rr];
+                    for (int j = 0; j < NT; j++)
+#pragma unroll
+                        for (int rr = 0; rr < 4; rr++)
+                            *(float *)(wbuf + (4 * lhalf + rr) * PITCH + (j * 32 + lrow) * 4) = p.alpha * acc[i][j][4 * q + rr];
+                    if (!out_bf16) {
+                        const int lc = elane % LPR_F, lr = elane / LPR_F;
+                        const int c = col0 + lc * 4;                          // 4 consecutive columns
+                        const int64_t zc = cur.bz + zcol[c];
+                        const bool cok = c < nrem;
+#pragma unroll
+                        for (int h = 0; h < 8 / RPI_F; h++) {
+                            const int row = RPI_F * h + lr, rr = row0 + i * 32 + 8 * q + row;
+                            const f32x4 v = *(const f32x4 *)(wbuf + row * PITCH + lc * 16);
+                            if (cok && rr < mrem) *(f32x4 *)((float *)zb + zrow[rr] + zc) = v;
+                        }
+                    } else {
+                        const int lc = elane % LPR_B, lr = elane / LPR_B;
+                        const int c = col0 + lc * 8;                          // 8 consecutive columns
+                        const int64_t zc = cur.bz + zcol[c];
+                        const bool cok = c < nrem;
+#pragma unroll
+                        for (int h = 0; h < 8 / RPI_B; h++) {
+                            const int row = RPI_B * h + lr, rr = row0 + i * 32 + 8 * q + row;
+                            const f32x4 v0 = *(const f32x4 *)(wbuf + row * PITCH + lc * 32);
+                            const f32x4 v1 = *(const f32x4 *)(wbuf + row * PITCH + lc * 32 + 16);
+                            uint4 o;
+                            o.x = pack_bf16x2(v0.x, v0.y); o.y = pack_bf16x2(v0.z, v0.w);
+                            o.z = pack_bf16x2(v1.x, v1.y); o.w = pack_bf16x2(v1.z, v1.w);
+                            if (cok && rr < mrem) *(uint4 *)((uint16_t *)zb + zrow[rr] + zc) = o;
+                        }
+                    }
+                }
+            }
+        } else {
+            int64_t zn[NT];
+            bool nok[NT];
 #pragma unroll
             for (int j = 0; j < NT; j++) {
-                if (!nok[j]) continue;
-                const float val = p.alpha * acc[i][j][r];
-                const int64_t off = zm + zn[j];
-                if (out_bf16) ((uint16_t *)zb)[off] = f32_to_bf16(val);
-                else ((float *)zb)[off] = val;
+                const int c = col0 + j * 32 + lrow;
+                zn[j] = cur.bz + zcol[c];
+                nok[j] = c < nrem;
             }
-            asm volatile("" ::: "memory");             // keep the scheduler from hoisting all 64 row lookups at once
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+#pragma unroll
+                for (int r = 0; r < 16; r++) {
+                    const int rr = row0 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
+                    if (rr < mrem) {
+                        const int64_t zm = zrow[rr];
+#pragma unroll
+                        for (int j = 0; j < NT; j++) {
+                            if (!nok[j]) continue;
+                            const float val = p.alpha * acc[i][j][r];
+                            const int64_t off = zm + zn[j];
+                            if (out_bf16) ((uint16_t *)zb)[off] = f32_to_bf16(val);
+                            else ((float *)zb)[off] = val;
+                        }
+                    }
+                    asm volatile("" ::: "memory");     // keep the scheduler from hoisting all 64 row lookups at once
+                }
+            }
         }
+        if (!more) break;
+        cur = nxt;
     }
+#undef EG_STAGE_NEXT
+#undef EG_KSTEP
+#undef EG_PIN
 }
 
 template <int NW, bool A_KC, bool B_KC, bool ODD>
 static int launch_one(ContractParams &p, void *stream)
 {
-    const int64_t wgs = p.n_tuples * p.n_batch * p.tiles_m * p.tiles_n;
-    hipLaunchKernelGGL((k_contract_dma<NW, A_KC, B_KC, ODD>), dim3((unsigned)wgs), dim3(NW * 64), 0, (hipStream_t)stream, p);
+    hipLaunchKernelGGL((k_contract_dma<NW, A_KC, B_KC, ODD>), dim3((unsigned)p.grid), dim3(NW * 64), 0, (hipStream_t)stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(EG_ERR_HIP, "k_contract_dma launch failed: %s", hipGetErrorString(e));
     return EG_OK;
@@ -456,7 +523,17 @@ int launch_contract_dma(ContractParams &p, void *stream)
     p.tiles_m = (int32_t)((p.M + dma::BM - 1) / dma::BM);
     p.tiles_n = (int32_t)((p.N + dma::BN - 1) / dma::BN);
     const int64_t wgs = p.n_tuples * p.n_batch * p.tiles_m * p.tiles_n;
-    if (wgs < 1 || wgs >= (1ll << 31)) return fail(EG_ERR_LIMIT, "contraction needs %lld workgroups", (long long)wgs);
+    if (wgs < 1 || wgs >= (1ll << 31)) return fail(EG_ERR_LIMIT, "contraction has %lld output tiles", (long long)wgs);
+    // one workgroup per compute unit (its LDS need admits no second one), a multiple of 8 so that every XCD gets the same number
+    static int n_cu = 0;
+    if (!n_cu) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return fail(EG_ERR_HIP, "cannot query the device");
+        n_cu = prop.multiProcessorCount > 8 ? prop.multiProcessorCount / 8 * 8 : 8;
+    }
+    p.total_tiles = (int32_t)wgs;
+    p.grid = (int32_t)(wgs < n_cu ? wgs : n_cu);
     // wide epilogue stores need Z contiguous along the innermost N label and every other Z offset a multiple of 8 elements
     bool vec = p.n.s1[p.n.n - 1] == 1 && p.n.ext[p.n.n - 1] % 8 == 0 && ((uintptr_t)p.out.ptr & 15) == 0 && p.out.slab_elems % 8 == 0;
     for (int i = 0; i < p.m.n; i++) vec = vec && p.m.s1[i] % 8 == 0;
