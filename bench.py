@@ -23,7 +23,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E (datasheet)
 DEFAULT_PART = {1: "d222", 2: "mix", 3: "batch8", 4: "heads8", 5: "k16"}
 # HBM bytes per launch of the dominant kernel of the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # (see profiles/); None until measured for the chosen workload.
-MEASURED_TRAFFIC = {("c2", "mix"): 1539 * 2**20 + 512 * 2**20}   # contraction launch: 1539 MiB fetched + 512 MiB written
+MEASURED_TRAFFIC = {("c2", "mix"): 1670 * 2**20 + 512 * 2**20}   # contraction launch: 1670 MiB fetched + 512 MiB written
 
 
 def prod(xs):
