@@ -365,6 +365,15 @@ static int route(const Vertex &v, const Operand &X, const Operand *Y, const std:
     return EG_OK;
 }
 
+// Element stride between the partial slabs of a vertex in the workspace.  More than two slabs of 1 MiB or more
+// are spaced 4 KiB further apart than their dense size: slab sizes are often powers of two, and then every lane
+// of the aggregation would pull its n_agg vectors from addresses that fall on the same memory channel and bank
+// (measured: 5-8 % slower).
+static int64_t slab_stride_of(int64_t dense_elems, int64_t slabs)
+{
+    return slabs > 2 && dense_elems >= (1 << 18) ? dense_elems + 1024 : dense_elems;
+}
+
 // ------------------------------------------------------------------------------------------------
 // workspace layout: intermediates and partial slabs, first-fit with reuse after the last consumer
 // ------------------------------------------------------------------------------------------------
@@ -449,7 +458,7 @@ static Layout make_layout(const eg_graph *g)
             if (dry_route(g, i, r) == EG_OK && r.kind == EG_KERNEL_REDUCE_ROW) L.split[i] = r.rp.split;
         }
         if (v.plan.n_agg * L.split[i] > 1) {
-            L.partial_off[i] = arena.alloc(v.plan.n_agg * L.split[i] * numel(v.bound) * 4);
+            L.partial_off[i] = arena.alloc(v.plan.n_agg * L.split[i] * slab_stride_of(numel(v.bound), v.plan.n_agg * L.split[i]) * 4);
             arena.release(L.partial_off[i]);          // live only while this vertex runs
         }
         for (int k = 0; k < v.n_in; k++) {
@@ -518,7 +527,7 @@ static int launch_routed(Routed &r, void *stream)
     }
 }
 
-static int aggregate_into(int oplus, const void *partials, int64_t n_agg, int64_t slab_elems, void *out, int out_dtype,
+static int aggregate_into(int oplus, const void *partials, int64_t n_agg, int64_t slab_elems, int64_t slab_stride, void *out, int out_dtype,
                           const std::vector<int64_t> &bound, const std::vector<int64_t> &stride, void *stream)
 {
     AggregateParams ap;
@@ -526,6 +535,7 @@ static int aggregate_into(int oplus, const void *partials, int64_t n_agg, int64_
     ap.partials = (const float *)partials;
     ap.n_agg = n_agg;
     ap.slab_elems = slab_elems;
+    ap.slab_stride = slab_stride;
     ap.oplus = oplus;
     ap.out_dtype = out_dtype;
     ap.out = out;
@@ -625,7 +635,7 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
     char *ws = (char *)workspace;
 
     // route everything first so that a failure launches nothing
-    struct Step { int vertex; Routed r; bool agg; int64_t slabs; const void *partials; void *dst; std::vector<int64_t> dst_stride; };
+    struct Step { int vertex; Routed r; bool agg; int64_t slabs, stride; const void *partials; void *dst; std::vector<int64_t> dst_stride; };
     std::vector<Step> steps;
     auto operand_of = [&](int u) {
         Operand o;
@@ -653,7 +663,7 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
         if (s.agg) {
             s.partials = ws + L.partial_off[i];
             out.ptr = (void *)s.partials;
-            out.slab_elems = numel(v.bound);
+            out.slab_elems = slab_stride_of(numel(v.bound), s.slabs);
             out.dtype = EG_F32;
             zstride = dense_strides(v.bound);
         } else {
@@ -675,6 +685,7 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
             if (rc) return rc;
         }
         if (s.r.kind == EG_KERNEL_REDUCE_ROW && s.r.rp.split != L.split[i]) s.r.rp.split = L.split[i];
+        s.stride = out.slab_elems;                 // what the join kernel was given
         steps.push_back(std::move(s));
     }
     hipStream_t st = (hipStream_t)hip_stream;
@@ -696,7 +707,7 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
         if (rc) return rc;
         if (s.agg) {
             rc = timed(s.vertex, 1, EG_KERNEL_NONE, [&] {
-                return aggregate_into(v.oplus, s.partials, s.slabs, numel(v.bound), s.dst, v.dtype, v.bound, s.dst_stride, hip_stream);
+                return aggregate_into(v.oplus, s.partials, s.slabs, numel(v.bound), s.stride, s.dst, v.dtype, v.bound, s.dst_stride, hip_stream);
             });
             if (rc) return rc;
         }
@@ -712,7 +723,7 @@ int tr_aggregate(eg_agg oplus, const void *partials, int64_t n_agg, int64_t slab
     if (slab_elems != numel(out->bound)) return fail(EG_ERR_BAD_BOUND, "tr_aggregate: slab_elems %lld differs from the output's %lld elements",
                                                       (long long)slab_elems, (long long)numel(out->bound));
     if ((uintptr_t)partials & 15) return fail(EG_ERR_WORKSPACE, "tr_aggregate: partials must be 16-byte aligned");
-    return aggregate_into((int)oplus, partials, n_agg, slab_elems, out->ptr, out->dtype, out->bound, out->stride, hip_stream);
+    return aggregate_into((int)oplus, partials, n_agg, slab_elems, slab_elems, out->ptr, out->dtype, out->bound, out->stride, hip_stream);
 }
 
 }  // extern "C"

@@ -39,7 +39,7 @@ struct TupleSpace {
 // tensor in its own dtype and strides.
 struct OutSpec {
     void *ptr;            // device: slab 0 (partials) or the destination tensor
-    int64_t slab_elems;   // elements per slab (partials only; 0 otherwise)
+    int64_t slab_elems;   // element stride between slabs (partials only; 0 otherwise); at least the dense size of Z
     int32_t dtype;        // eg_dtype of what is stored through ptr
 };
 
@@ -124,7 +124,8 @@ struct GenericParams {            // any EinSum: one output element per lane, se
 struct AggregateParams {          // out[e] = oplus_a partials[a][e], ascending a, fp32, one final cast
     const float *partials;
     int64_t n_agg;
-    int64_t slab_elems;
+    int64_t slab_elems;           // elements of the output (and of every slab)
+    int64_t slab_stride;          // element stride between slabs (>= slab_elems)
     int32_t oplus;
     int32_t out_dtype;
     void *out;

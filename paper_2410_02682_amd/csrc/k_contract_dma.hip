@@ -2,7 +2,8 @@
 //
 // Same operation as k_contract.hip (the per-block kernel K of Section 4.3 of the paper for (x) = multiply,
 // (+) = sum, all tuples of the join in one launch), specialised for the large bf16 blocks:
-//   * 4 waves per workgroup, each owning a 128x128 output patch = 4x4 MFMA 32x32x16 tiles (fp32 accumulators);
+//   * 8 waves per workgroup (two per SIMD), each owning a 128x64 output patch = 4x2 MFMA 32x32x16 tiles (fp32 accumulators);
+//   * persistent workgroups, one per compute unit, each walking over its share of the output tiles;
 //   * every 16-byte chunk of both operand tiles travels global memory -> LDS directly; the chunk a lane
 //     fetches is chosen so that the contiguous 1 KiB an instruction deposits is already the swizzled layout;
 //   * an operand contiguous along K sits in LDS as [row][64 k] and is read with 16-byte reads; an operand

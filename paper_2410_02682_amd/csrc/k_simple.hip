@@ -259,7 +259,7 @@ __global__ __launch_bounds__(kThreads) void k_aggregate_vec4(const AggregatePara
     const int64_t e = i4 * 4;
     if (e >= p.slab_elems) return;
     const f32x4 *src = (const f32x4 *)(p.partials + e);
-    const int64_t slab4 = p.slab_elems / 4;
+    const int64_t slab4 = p.slab_stride / 4;
     f32x4 acc;
     if (N > 0) {
         f32x4 v[N > 0 ? N : 1];
@@ -299,7 +299,7 @@ __global__ __launch_bounds__(kThreads) void k_aggregate_scalar(const AggregatePa
     const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (e >= p.slab_elems) return;
     float acc = p.partials[e];
-    for (int64_t a = 1; a < p.n_agg; a++) acc = oplus_eval(p.oplus, acc, p.partials[a * p.slab_elems + e]);
+    for (int64_t a = 1; a < p.n_agg; a++) acc = oplus_eval(p.oplus, acc, p.partials[a * p.slab_stride + e]);
     int64_t off = e;
     if (!p.contiguous) {
         int64_t ox = 0, oy = 0;
@@ -435,7 +435,8 @@ int launch_aggregate(const AggregateParams &p, void *stream)
 {
     if (!p.partials || !p.out) return fail(EG_ERR_NULL, "aggregate kernel: NULL operand");
     if (p.n_agg < 1 || p.slab_elems < 1) return fail(EG_ERR_LIMIT, "aggregate kernel: empty input");
-    const bool vec = p.contiguous && p.slab_elems % 4 == 0 && ((uintptr_t)p.partials & 15) == 0 &&
+    if (p.slab_stride < p.slab_elems) return fail(EG_ERR_LIMIT, "aggregate kernel: slabs overlap");
+    const bool vec = p.contiguous && p.slab_elems % 4 == 0 && p.slab_stride % 4 == 0 && ((uintptr_t)p.partials & 15) == 0 &&
                      ((uintptr_t)p.out & 15) == 0;
     unsigned grid;
     int rc = grid_for(vec ? p.slab_elems / 4 : p.slab_elems, kThreads, grid);

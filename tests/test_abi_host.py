@@ -182,6 +182,20 @@ def test_workspace_accounts_for_partial_slabs_and_reuse():
     E.einsum_graph_destroy(g)
 
 
+def test_workspace_spaces_many_large_slabs_apart():
+    # more than two partial slabs of at least 1 MiB sit 4 KiB further apart than their dense size
+    g = E.einsum_graph_create()
+    a = E.einsum_graph_add_input(g, [1024, 512], "bf16")
+    b = E.einsum_graph_add_input(g, [512, 1024], "bf16")
+    ab = E.einsum_graph_add_einsum(g, "ij,jk->ik", "mul", "sum", 1.0, [a, b], "f32")
+    E.einsum_graph_mark_output(g, ab)
+    E.einsum_graph_set_partition(g, ab, [1, 2, 1])
+    assert E.tr_workspace_bytes(g) == 2 * 1024 * 1024 * 4
+    E.einsum_graph_set_partition(g, ab, [1, 8, 1])
+    assert E.tr_workspace_bytes(g) == 8 * (1024 * 1024 + 1024) * 4
+    E.einsum_graph_destroy(g)
+
+
 def test_kernel_routing_of_the_workload_vertices():
     want = {
         2: {"AB": "contract_mfma", "ABC": "contract_mfma"},
