@@ -219,6 +219,44 @@ int tr_profile_count(eg_graph *g);
  * synchronised the stream.  Host outputs, any may be NULL. */
 int tr_profile_get(eg_graph *g, int i, int *vertex, int *stage, int *kernel, float *ms);
 
+/* ---- Choosing the partitioning vectors: EinDecomp (Sections 6-8 of the paper) ------------------------------
+ *
+ * Host-only integer code.  A cost is an upper bound on the floating point numbers that would travel between
+ * processors if every join result ran on its own processor (Section 7); on one GPU it is the planner's objective,
+ * not a measured quantity.  All pointers are host pointers. */
+
+/* Section 7, "transferring into the join": p (n_X + n_Y), p = prod d = the number of join results, n_X / n_Y the
+ * elements of one block of X / Y under d (a vertex with one input pays p n_X).  d: one entry per unique label in
+ * schema order, each dividing its label's bound (EG_ERR_BAD_PARTITION / EG_ERR_INDIVISIBLE otherwise). */
+int eg_cost_join(const eg_graph *g, int vertex, const int32_t *d, int n_unique_labels, int64_t *cost);
+
+/* Section 7, "transferring into the aggregation": (p / n_agg)(n_agg - 1) n_Z with n_agg = prod d over the
+ * aggregated labels and n_Z the elements of one output block. */
+int eg_cost_agg(const eg_graph *g, int vertex, const int32_t *d, int n_unique_labels, int64_t *cost);
+
+/* Section 7, "re-partitioning across operations": a tensor with the given bound produced in blocks cut d_producer
+ * ways per dimension and consumed in blocks cut d_consumer ways: (n_c/n_int - 1)(n/n_c)(n_c + n_p), plus n_p n/n_c
+ * when n_p != n_int.  Zero when the cuts agree.  Every cut entry must divide its bound; should the formula's
+ * value not be a whole number the call fails with EG_ERR_BAD_PARTITION. */
+int eg_cost_repart(int rank, const int64_t *bound, const int32_t *d_consumer, const int32_t *d_producer, int64_t *cost);
+
+/* Section 8.1: the partitioning vectors of a vertex with exactly p join results whose entries are powers of two
+ * dividing the bounds.  *count receives how many there are; the first min(count, capacity) are written to d_out
+ * (capacity x n_unique_labels entries, may be NULL), exponents in lexicographic order over the schema.
+ * p must be a power of two. */
+int eindecomp_viable(const eg_graph *g, int vertex, int p, int32_t *d_out, int capacity, int *count);
+
+/* Sections 8.2-8.4: labels every einsum vertex of the graph with a partitioning vector of p join results (fewer
+ * for a vertex whose bounds admit no such vector), as einsum_graph_set_partition would.  When no intermediate
+ * result has two consumers the labelling minimises the total cost (dynamic programme over the table M[v, d_Z];
+ * *exact = 1).  Otherwise the graph is cut into paths, longest first, each optimised on its own with inputs from
+ * outside the path free of charge (*exact = 0).  *total_cost receives the cost of the labelling with every
+ * producer -> consumer edge included.  total_cost and exact may be NULL.  On error no vertex is relabelled. */
+int eindecomp_plan(eg_graph *g, int p, int64_t *total_cost, int *exact);
+
+/* Cost of the graph's current labelling, split into its three parts (any pointer may be NULL). */
+int eindecomp_labelling_cost(const eg_graph *g, int64_t *join, int64_t *agg, int64_t *repart);
+
 /* ---- Measured ceilings of the machine (context for roofline reports; not part of the einsum path) ------- */
 
 /* Enqueues a register-resident loop of bf16 32x32x16 MFMAs (no memory traffic): `waves_per_simd` (1 or 2)

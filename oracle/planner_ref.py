@@ -119,7 +119,22 @@ class PVertex:
 
 
 def from_workload(w) -> List[PVertex]:
-    return [PVertex(v.name, None if v.is_input else v.spec, [] if v.is_input else v.inputs, v.bound) for v in w.vertices]
+    """Vertices of a synthetic workload; an einsum vertex's bound is b_Z = b_XY[l_Z; l_XY] (Section 3)."""
+    out: List[PVertex] = []
+    bound: Dict[str, List[int]] = {}
+    for v in w.vertices:
+        if v.is_input:
+            bound[v.name] = [int(x) for x in v.bound]
+            out.append(PVertex(v.name, None, [], bound[v.name]))
+            continue
+        ins, lz = split_spec(v.spec)
+        lb: Dict[str, int] = {}
+        for s_, name in zip(ins, v.inputs):
+            for l, e in zip(s_, bound[name]):
+                lb[l] = e
+        bound[v.name] = [lb[l] for l in lz]
+        out.append(PVertex(v.name, v.spec, v.inputs, bound[v.name]))
+    return out
 
 
 def label_bounds(g: Dict[str, PVertex], v: PVertex) -> Dict[str, int]:

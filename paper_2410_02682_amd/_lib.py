@@ -56,6 +56,12 @@ EXPORTS = {
     "tr_profile_count": (ctypes.c_int, [ctypes.c_void_p]),
     "tr_profile_get": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int),
                                       ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]),
+    "eg_cost_join": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, c_i32p, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]),
+    "eg_cost_agg": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, c_i32p, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]),
+    "eg_cost_repart": (ctypes.c_int, [ctypes.c_int, c_i64p, c_i32p, c_i32p, ctypes.POINTER(ctypes.c_int64)]),
+    "eindecomp_viable": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, c_i32p, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]),
+    "eindecomp_plan": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int)]),
+    "eindecomp_labelling_cost": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int64)]),
     "eg_ceiling_mfma_bf16": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]),
     "eg_ceiling_copy": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]),
     "eg_last_error": (ctypes.c_char_p, []),

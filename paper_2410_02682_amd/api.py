@@ -8,7 +8,7 @@ turn Python lists into C arrays.  Device memory is handed over as raw pointers
 from __future__ import annotations
 
 import ctypes
-from typing import List, Optional, Sequence
+from typing import List, Optional, Sequence, Tuple
 
 from . import _lib
 from ._lib import PlanView
@@ -128,6 +128,50 @@ def tr_execute(g, inputs: List, outputs: List, workspace_ptr: int, workspace_byt
 
 def tr_aggregate(oplus: str, partials_ptr: int, n_agg: int, slab_elems: int, out_rel, stream: int = 0) -> None:
     _check(_lib.load().tr_aggregate(OPLUS[oplus], ctypes.c_void_p(partials_ptr), n_agg, slab_elems, out_rel, ctypes.c_void_p(stream)))
+
+
+# ---- EinDecomp: cost model and choice of the partitioning vectors (host only) -----------------------------
+def eg_cost_join(g, vertex: int, d: Sequence[int]) -> int:
+    c = ctypes.c_int64()
+    _check(_lib.load().eg_cost_join(g, vertex, _i32(d), len(d), ctypes.byref(c)))
+    return c.value
+
+
+def eg_cost_agg(g, vertex: int, d: Sequence[int]) -> int:
+    c = ctypes.c_int64()
+    _check(_lib.load().eg_cost_agg(g, vertex, _i32(d), len(d), ctypes.byref(c)))
+    return c.value
+
+
+def eg_cost_repart(bound: Sequence[int], d_consumer: Sequence[int], d_producer: Sequence[int]) -> int:
+    if not (len(bound) == len(d_consumer) == len(d_producer)):
+        raise ValueError("bound and the two cuts must have the same length")
+    c = ctypes.c_int64()
+    _check(_lib.load().eg_cost_repart(len(bound), _i64(bound), _i32(d_consumer), _i32(d_producer), ctypes.byref(c)))
+    return c.value
+
+
+def eindecomp_viable(g, vertex: int, p: int) -> List[List[int]]:
+    lib = _lib.load()
+    n = ctypes.c_int()
+    _check(lib.eindecomp_viable(g, vertex, p, None, 0, ctypes.byref(n)))
+    nl = len(einsum_graph_plan(g, vertex)["labels"])
+    buf = (ctypes.c_int32 * max(1, n.value * nl))()
+    _check(lib.eindecomp_viable(g, vertex, p, buf, n.value, ctypes.byref(n)))
+    return [list(buf[i * nl:(i + 1) * nl]) for i in range(n.value)]
+
+
+def eindecomp_plan(g, p: int) -> Tuple[int, bool]:
+    """Labels every einsum vertex; returns (total cost, whether the labelling is the proven optimum)."""
+    c, ex = ctypes.c_int64(), ctypes.c_int()
+    _check(_lib.load().eindecomp_plan(g, p, ctypes.byref(c), ctypes.byref(ex)))
+    return c.value, bool(ex.value)
+
+
+def eindecomp_labelling_cost(g) -> dict:
+    j, a, r = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    _check(_lib.load().eindecomp_labelling_cost(g, ctypes.byref(j), ctypes.byref(a), ctypes.byref(r)))
+    return dict(join=j.value, agg=a.value, repart=r.value, total=j.value + a.value + r.value)
 
 
 def tr_profile_enable(g, max_launches: int) -> None:

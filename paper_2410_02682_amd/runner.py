@@ -37,7 +37,9 @@ class GraphRunner:
         self.device = device
         self.g = api.einsum_graph_create()
         self.vid: Dict[str, int] = {}
-        self.part = w.partitionings[partitioning]
+        # "eindecomp:<p>": let the library choose the partitioning vectors (p join results per vertex)
+        planned = partitioning.startswith("eindecomp:")
+        self.part = {} if planned else w.partitionings[partitioning]
         self.out_names = list(outputs) if outputs is not None else list(w.outputs)
         for v in w.vertices:
             if v.is_input:
@@ -46,6 +48,12 @@ class GraphRunner:
                 self.vid[v.name] = api.einsum_graph_add_einsum(self.g, v.spec, v.otimes, v.oplus, v.alpha,
                                                                [self.vid[n] for n in v.inputs], v.dtype)
                 api.einsum_graph_set_partition(self.g, self.vid[v.name], d_vector(v.spec, self.part.get(v.name, {})))
+        self.plan_cost = None
+        if planned:
+            self.plan_cost, self.plan_exact = api.eindecomp_plan(self.g, int(partitioning.split(":")[1]))
+            for v in w.einsum_vertices():
+                pl = api.einsum_graph_plan(self.g, self.vid[v.name])
+                self.part[v.name] = {l: int(x) for l, x in zip(pl["labels"], pl["d"]) if x > 1}
         for n in self.out_names:
             api.einsum_graph_mark_output(self.g, self.vid[n])
         self.rel_in, self.rel_out = [], []

@@ -69,6 +69,17 @@ def test_config_outputs_through_workspace_match_oracle(n, pname):
         assert bad == 0, f"config {n} {pname} output {name}: {bad} elements out of tolerance (worst {worst:.2f}x)"
 
 
+@pytest.mark.parametrize("n,p", [(n, p) for n in range(1, 6) for p in (4, 16)])
+def test_config_under_the_planners_own_labelling_matches_oracle(n, p):
+    # the partitioning vectors chosen by eindecomp_plan instead of hand-written ones; the result may not depend on them
+    w, inp, ref = _reference(n)
+    print(f"config {n} labelled by the planner for p = {p}", flush=True)
+    got = _run(w, f"eindecomp:{p}", inp)
+    for name in w.outputs:
+        bad, worst = violations(got[name].as_f64(), ref[name].as_f64(), rtol_for(w, name))
+        assert bad == 0, f"config {n} planner p={p} output {name}: {bad} elements out of tolerance (worst {worst:.2f}x)"
+
+
 # ------------------------------------------------------------------ contraction layouts, tails, label groups
 LAYOUTS = [
     # spec, bound X, bound Y: K-contiguous / M-contiguous A x K-contiguous / N-contiguous B, ragged tails
