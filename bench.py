@@ -20,7 +20,12 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA (datasheet)
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E (datasheet)
-DEFAULT_PART = {1: "d222", 2: "mix", 3: "batch8", 4: "heads8", 5: "k16"}
+# vector-ALU bound of the distance contractions: 256 compute units x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 fused
+# multiply-adds per second (packed fp32 instructions are not used); every label combination costs one of them (or
+# one maximum) plus a subtraction, which the hardware issues beside it (measured: the pair runs at the rate of the
+# multiply-add alone), and is counted as three operations (subtract, multiply, add)
+PEAK_ALU_TFLOPS = 256 * 4 * 16 * 2.4e9 * 3 / 1e12
+DEFAULT_PART = {1: "d222", 2: "mix", 3: "batch8", 4: "heads8", 5: "k16", 6: "splitn8", 7: "d222"}
 # HBM bytes per launch of the dominant kernel of the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # (see profiles/); None until measured for the chosen workload.
 MEASURED_TRAFFIC = {("c2", "mix"): 1670 * 2**20 + 512 * 2**20}   # contraction launch: 1670 MiB fetched + 512 MiB written
@@ -39,8 +44,9 @@ def cpu_baseline(w, dev, budget_s=15.0):
     import torch
     from oracle.einsum_ref import einsum_ref
     from synth_inputs.workloads import parse_spec
-    v = next(v for v in w.einsum_vertices() if v.otimes == "mul" and v.oplus == "sum" and len(v.inputs) == 2
+    v = next(v for v in w.einsum_vertices() if v.oplus != "none" and len(v.inputs) == 2
              and all(w.vertex(i).is_input for i in v.inputs))
+    per_pair = 2.0 if v.otimes == "mul" else 3.0
 
     def host(t):
         t = t.detach().contiguous().cpu()
@@ -48,11 +54,12 @@ def cpu_baseline(w, dev, budget_s=15.0):
 
     X, Y = host(dev[v.inputs[0]]), host(dev[v.inputs[1]])
     lX, lY, lZ = parse_spec(v.spec)
-    per_row = 2.0 * prod(X.shape[1:]) * prod(n for l, n in zip(lY, Y.shape) if l not in lX)
+    per_row = per_pair * prod(X.shape[1:]) * prod(n for l, n in zip(lY, Y.shape) if l not in lX)
 
     def run(rows):
         t0 = time.perf_counter()
-        einsum_ref(v.spec, X[:rows], Y, out_dtype=v.dtype)
+        einsum_ref(v.spec, X[:rows], Y, otimes=v.otimes, oplus=v.oplus, alpha=v.alpha, out_dtype=v.dtype,
+                   x_dtype=w.vertex(v.inputs[0]).dtype, y_dtype=w.vertex(v.inputs[1]).dtype)
         return time.perf_counter() - t0
 
     r0 = max(1, min(X.shape[0], 4))
@@ -81,6 +88,14 @@ def ceilings():
         b.record()
         torch.cuda.synchronize()
         out[f"mfma_bf16_{wps}_wave_per_simd_tflops"] = fl / a.elapsed_time(b) / 1e9
+    E.eg_ceiling_valu_f32(sink.data_ptr(), 256, 2, 500, s)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    pairs = E.eg_ceiling_valu_f32(sink.data_ptr(), 256, 2, 10000, s)
+    b.record()
+    torch.cuda.synchronize()
+    out["valu_f32_sub_fma_pairs_as_tflops"] = 3.0 * pairs / a.elapsed_time(b) / 1e9
     n = 1 << 30
     src = torch.empty(n, dtype=torch.uint8, device="cuda")
     dst = torch.empty_like(src)
@@ -101,7 +116,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5], help="workload (2 = the matrix chain the metric is quoted on)")
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5, 6, 7], help="workload (2 = the matrix chain the metric is quoted on)")
     ap.add_argument("--partitioning", default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true")
@@ -138,7 +153,8 @@ def main():
         join_out = pl["n_agg"] * nz * 4 if partial else nz * esz[v.dtype]
         acct[r.vid[v.name]] = {
             "name": v.name, "kind": pl["kernel"],
-            "flops": 2.0 * prod(pl["bound"]) if pl["kernel"] == "contract_mfma" else 0.0,
+            # a multiply-add per label combination on the matrix pipes; subtract, square (or magnitude), add (or max) on the vector ALU
+            "flops": {"contract_mfma": 2.0, "contract_alu": 3.0}.get(pl["kernel"], 0.0) * prod(pl["bound"]),
             "join_bytes": in_bytes + join_out,
             "agg_bytes": (pl["n_agg"] * nz * 4 + nz * esz[v.dtype]) if partial else 0,
         }
@@ -175,15 +191,20 @@ def main():
              "share_of_step": f["ms"] / args.steps / ms_per_step}
         if key == "contract_mfma":
             k.update({"bound": "mfma", "achieved": f["flops"] / (f["ms"] * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"})
+        elif key == "contract_alu":
+            k.update({"bound": "alu", "achieved": f["flops"] / (f["ms"] * 1e-3) / 1e12, "peak": PEAK_ALU_TFLOPS, "unit": "TFLOP/s"})
         else:
             k.update({"bound": "hbm", "achieved": f["bytes"] / (f["ms"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"})
         k["frac"] = k["achieved"] / k["peak"]
         kernels[key] = k
 
     dom = "contract_mfma" if "contract_mfma" in kernels else max(kernels, key=lambda k: kernels[k]["share_of_step"])
+    if args.config == 7:
+        dom = "contract_alu"
     roofline = dict(kernels[dom])
     roofline["kernel"] = {"contract_mfma": "k_contract_dma / k_contract (block contraction on MFMA, all tuples of a vertex per launch)",
-                          "aggregate": "k_aggregate_vec4", "map": "k_map", "reduce_row": "k_reduce_row", "generic": "k_generic"}[dom]
+                          "aggregate": "k_aggregate_vec4", "map": "k_map", "reduce_row": "k_reduce_row", "generic": "k_generic",
+                          "contract_alu": "k_contract_alu (contraction-shaped vertex with another scalar function, vector ALU)"}[dom]
     roofline["traffic"] = MEASURED_TRAFFIC.get((f"c{args.config}", pname))
     out = {"metric": "einsum-graph TFLOP/s (contractions) + GB/s (maps/aggregations), % of roofline", "value": value,
            "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,

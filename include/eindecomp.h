@@ -96,7 +96,8 @@ typedef enum {
     EG_KERNEL_CONTRACT_MFMA = 1,   /* (x)=mul, (+)=sum as a strided batched matrix product on MFMA   */
     EG_KERNEL_MAP = 2,             /* no aggregated label: elementwise map / binary join             */
     EG_KERNEL_REDUCE_ROW = 3,      /* aggregated labels are the contiguous tail of X: wave reductions */
-    EG_KERNEL_GENERIC = 4          /* any EinSum: one output element per lane, loop over l_agg       */
+    EG_KERNEL_GENERIC = 4,         /* any EinSum: one output element per lane, loop over l_agg       */
+    EG_KERNEL_CONTRACT_ALU = 5     /* contraction-shaped EinSum with another (x)/(+) pair (squared L2, L-infinity, ...): LDS tiles, vector ALU */
 } eg_kernel_kind;
 
 /* Read-only view of one vertex's plan.  All pointers are host memory owned by the graph and stay
@@ -263,6 +264,11 @@ int eindecomp_labelling_cost(const eg_graph *g, int64_t *join, int64_t *agg, int
  * waves on each SIMD of `cus` compute units, iters*8 MFMAs per wave.  sink: device, >= 4 bytes, never
  * written.  *flops (host) receives the launch's operation count; the caller times it. */
 int eg_ceiling_mfma_bf16(void *sink, int cus, int waves_per_simd, int iters, double *flops, void *hip_stream);
+
+/* Enqueues a register-resident loop of fp32 subtract + fused-multiply-add pairs (the instruction pair of the
+ * squared-distance kernel): `waves_per_simd` (1, 2 or 4) waves on each SIMD of `cus` compute units, iters*64 pairs
+ * per lane.  sink: device, >= 4 bytes, never written.  *pairs (host) receives the launch's pair count. */
+int eg_ceiling_valu_f32(void *sink, int cus, int waves_per_simd, int iters, double *pairs, void *hip_stream);
 
 /* Enqueues a plain device-to-device copy of `bytes` (multiple of 16; dst/src device, 16-byte aligned). */
 int eg_ceiling_copy(void *dst, const void *src, int64_t bytes, void *hip_stream);

@@ -17,7 +17,7 @@ DTYPE = {"f32": 0, "bf16": 1}
 OPLUS = {"none": 0, "sum": 1, "max": 2}
 OTIMES = {"mul": 0, "add": 1, "sub": 2, "div": 3, "sqdiff": 4, "absdiff": 5, "exp_sub": 6, "relu_grad": 7,
           "silu_mul": 8, "ident": 32, "scale": 33, "relu": 34, "exp": 35, "log": 36}
-KERNEL_NAMES = {0: "none", 1: "contract_mfma", 2: "map", 3: "reduce_row", 4: "generic"}
+KERNEL_NAMES = {0: "none", 1: "contract_mfma", 2: "map", 3: "reduce_row", 4: "generic", 5: "contract_alu"}
 
 
 class EgError(RuntimeError):
@@ -198,6 +198,13 @@ def eg_ceiling_mfma_bf16(sink_ptr: int, cus: int, waves_per_simd: int, iters: in
     fl = ctypes.c_double()
     _check(_lib.load().eg_ceiling_mfma_bf16(ctypes.c_void_p(sink_ptr), cus, waves_per_simd, iters, ctypes.byref(fl), ctypes.c_void_p(stream)))
     return fl.value
+
+
+def eg_ceiling_valu_f32(sink_ptr: int, cus: int, waves_per_simd: int, iters: int, stream: int = 0) -> float:
+    """Enqueues the register-resident subtract + fused-multiply-add loop; returns its pair count."""
+    n = ctypes.c_double()
+    _check(_lib.load().eg_ceiling_valu_f32(ctypes.c_void_p(sink_ptr), cus, waves_per_simd, iters, ctypes.byref(n), ctypes.c_void_p(stream)))
+    return n.value
 
 
 def eg_ceiling_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:

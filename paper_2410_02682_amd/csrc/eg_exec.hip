@@ -139,7 +139,7 @@ static bool vec_ok(const StridedDims &dims, int which, int vd, int vec, const vo
 // ------------------------------------------------------------------------------------------------
 static bool build_contract(const Vertex &v, const LabelInfo &li, const Operand &X, const Operand &Y, ContractParams &cp)
 {
-    if (v.otimes != EG_MUL || v.oplus != EG_AGG_SUM || v.n_in != 2) return false;
+    if (v.n_in != 2 || (v.oplus != EG_AGG_SUM && v.oplus != EG_AGG_MAX)) return false;
     if (X.dtype != Y.dtype) return false;
     const int epc = X.dtype == EG_BF16 ? 8 : 4;
     if (!aligned16(X.ptr) || !aligned16(Y.ptr)) return false;
@@ -233,6 +233,8 @@ static bool build_contract(const Vertex &v, const LabelInfo &li, const Operand &
         cp.span_y += (li.ext[l] - 1) * li.sy[l];
     }
     cp.in_dtype = X.dtype;
+    cp.otimes = v.otimes;
+    cp.oplus = v.oplus;
     cp.alpha = (float)v.alpha;
     cp.x = X.ptr;
     cp.y = Y.ptr;
@@ -300,7 +302,7 @@ static int route(const Vertex &v, const Operand &X, const Operand *Y, const std:
         r.cp.ts = ts;
         r.cp.out = out;
         r.cp.n_tuples = n_tuples;
-        r.kind = EG_KERNEL_CONTRACT_MFMA;
+        r.kind = v.otimes == EG_MUL && v.oplus == EG_AGG_SUM ? EG_KERNEL_CONTRACT_MFMA : EG_KERNEL_CONTRACT_ALU;
         return EG_OK;
     }
 
@@ -519,7 +521,8 @@ static int ensure_events(eg_graph *g, size_t n)
 static int launch_routed(Routed &r, void *stream)
 {
     switch (r.kind) {
-    case EG_KERNEL_CONTRACT_MFMA: return launch_contract(r.cp, stream);
+    case EG_KERNEL_CONTRACT_MFMA:
+    case EG_KERNEL_CONTRACT_ALU: return launch_contract(r.cp, stream);
     case EG_KERNEL_MAP: return launch_map(r.mp, stream);
     case EG_KERNEL_REDUCE_ROW: return launch_reduce_row(r.rp, stream);
     case EG_KERNEL_GENERIC: return launch_generic(r.gp, stream);

@@ -58,6 +58,7 @@ struct ContractParams {
     int32_t a_kcontig;            // 1: X is contiguous along the innermost K label, 0: along innermost M label
     int32_t b_kcontig;            // 1: Y is contiguous along the innermost K label, 0: along innermost N label
     int32_t in_dtype;             // dtype of X and Y
+    int32_t otimes, oplus;        // the vertex's scalar function and reduction; anything but multiply / sum runs on the vector ALU
     float alpha;
     const void *x;
     const void *y;

@@ -26,6 +26,26 @@ __global__ __launch_bounds__(256) void k_mfma_ceiling(float *sink, int iters)
     if (s == -1.f) sink[0] = s;      // never true: keeps the loop alive
 }
 
+// Register-resident chains of the instruction pair the distance kernels live on: subtract, then fused
+// multiply-add of the difference with itself into an accumulator (16 independent accumulators per lane).
+__global__ __launch_bounds__(256) void k_valu_ceiling(float *sink, int iters, float x)
+{
+    float a[16];
+    for (int i = 0; i < 16; i++) a[i] = threadIdx.x * 0.001f + i;
+    for (int it = 0; it < iters; it++) {
+#pragma unroll
+        for (int r = 0; r < 4; r++)
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                const float d = a[i] - x;
+                a[i] = __builtin_fmaf(d, d, a[i]);
+            }
+    }
+    float s = 0.f;
+    for (int i = 0; i < 16; i++) s += a[i];
+    if (s == 12345.678f) sink[0] = s;  // never true for the x the launcher passes: keeps the loop alive
+}
+
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // One 16-byte vector per lane, streaming (non-temporal) load and store: the fastest plain copy found on this part.
@@ -50,6 +70,19 @@ int eg_ceiling_mfma_bf16(void *sink, int cus, int waves_per_simd, int iters, dou
     hipLaunchKernelGGL(eg::k_mfma_ceiling, dim3(wgs), dim3(256), 0, (hipStream_t)hip_stream, (float *)sink, iters);
     if (hipGetLastError() != hipSuccess) return eg::fail(EG_ERR_HIP, "k_mfma_ceiling launch failed");
     *flops = (double)wgs * 4.0 * iters * 8.0 * (2.0 * 32 * 32 * 16);
+    return EG_OK;
+}
+
+// Launches `waves_per_simd` (1, 2 or 4) waves on every SIMD of `cus` compute units, each lane running iters*64
+// subtract + fused-multiply-add pairs from registers.  *pairs receives the number of pairs of the launch.
+int eg_ceiling_valu_f32(void *sink, int cus, int waves_per_simd, int iters, double *pairs, void *hip_stream)
+{
+    if (!sink || !pairs) return eg::fail(EG_ERR_NULL, "eg_ceiling_valu_f32: NULL argument");
+    if (cus < 1 || (waves_per_simd != 1 && waves_per_simd != 2 && waves_per_simd != 4) || iters < 1) return eg::fail(EG_ERR_LIMIT, "eg_ceiling_valu_f32: bad launch shape");
+    const int wgs = cus * waves_per_simd;
+    hipLaunchKernelGGL(eg::k_valu_ceiling, dim3(wgs), dim3(256), 0, (hipStream_t)hip_stream, (float *)sink, iters, 1.0001f);
+    if (hipGetLastError() != hipSuccess) return eg::fail(EG_ERR_HIP, "k_valu_ceiling launch failed");
+    *pairs = (double)wgs * 256.0 * iters * 64.0;
     return EG_OK;
 }
 

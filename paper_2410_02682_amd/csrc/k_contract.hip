@@ -301,6 +301,160 @@ __global__ __launch_bounds__(C::THREADS) void k_contract(const ContractParams p)
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// The same tiling for any other scalar function (x) and reduction (+) of Section 3 of the paper (squared
+// difference with sum, absolute difference with max, ...): no matrix instruction fits, so the tile is worked
+// on the vector ALU.  256 threads as a 16 x 16 grid, each thread an 8 x 8 block of the 128 x 128 tile with
+// rows ty + 16 i and columns tx + 16 j (the 16 lanes that differ in tx read 16 consecutive LDS rows, which the
+// swizzle spreads over all banks, and write consecutive columns).  Operands pass through the same loaders and
+// the same LDS layout as above.  The reduction runs over exactly K values: zero-filled tail slots are skipped,
+// since (x)(0, 0) need not be the identity of (+).
+// ------------------------------------------------------------------------------------------------
+template <typename C, int OT, int OP>
+__global__ __launch_bounds__(C::THREADS, 2) void k_contract_alu(const ContractParams p)
+{
+    static_assert(C::BM == 128 && C::BN == 128 && C::THREADS == 256, "16 x 16 threads of 8 x 8 outputs");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+
+    const int64_t total = (int64_t)gridDim.x;
+    int64_t logical;
+    {
+        const int64_t per = total / 8, rem = total % 8;
+        const int64_t x = blockIdx.x % 8, j = blockIdx.x / 8;
+        logical = x * per + (x < rem ? x : rem) + j;
+    }
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    const int64_t tb = logical / tiles;
+    const int tl = (int)(logical - tb * tiles);
+    const int tile_m = tl % p.tiles_m, tile_n = tl / p.tiles_m;
+    const int64_t tuple = tb / p.n_batch, bidx = tb - tuple * p.n_batch;
+
+    int64_t bx, by, bz, agg;
+    decode_tuple(p.ts, tuple, bx, by, bz, agg);
+    {
+        uint32_t rem = (uint32_t)bidx;
+        for (int i = p.batch.n - 1; i >= 0; i--) {
+            uint32_t e = (uint32_t)p.batch.ext[i], q = rem / e, k = rem - q * e;
+            rem = q;
+            bx += (int64_t)k * p.batch.s0[i];
+            by += (int64_t)k * p.batch.s1[i];
+            bz += (int64_t)k * p.batch.s2[i];
+        }
+    }
+    const int64_t m0 = (int64_t)tile_m * C::BM, n0 = (int64_t)tile_n * C::BN;
+
+    Loader<C::BM, C::NVA, C::THREADS, C::BF16> la;
+    Loader<C::BN, C::NVB, C::THREADS, C::BF16> lb;
+    la.init(p.x, bx, p.m, m0, p.M, p.a_kcontig != 0, tid);
+    lb.init(p.y, by, p.n, n0, p.N, p.b_kcontig != 0, tid);
+
+    float acc[8][8];
+    const float ident = oplus_identity(OP >= 0 ? OP : p.oplus);
+#pragma unroll
+    for (int i = 0; i < 8; i++)
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[i][j] = ident;
+
+    const int64_t nk = (p.K + C::BK - 1) / C::BK;
+
+    // one 16-byte chunk (EPC consecutive k) of the thread's 8 rows and 8 columns; `valid` k of it count
+    auto chunk = [&](const char *sa, const char *sb, int c, int valid) {
+        uint4 a[8], b[8];
+#pragma unroll
+        for (int i = 0; i < 8; i++) a[i] = *(const uint4 *)(sa + lds_off(ty + 16 * i, c));
+#pragma unroll
+        for (int j = 0; j < 8; j++) b[j] = *(const uint4 *)(sb + lds_off(tx + 16 * j, c));
+#pragma unroll
+        for (int e = 0; e < C::EPC; e++) {
+            if (e >= valid) break;
+            float xs[8], ys[8];
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const uint32_t wa = ((const uint32_t *)&a[i])[C::BF16 ? e >> 1 : e], wb = ((const uint32_t *)&b[i])[C::BF16 ? e >> 1 : e];
+                xs[i] = C::BF16 ? __uint_as_float((e & 1) ? (wa & 0xffff0000u) : (wa << 16)) : __uint_as_float(wa);
+                ys[i] = C::BF16 ? __uint_as_float((e & 1) ? (wb & 0xffff0000u) : (wb << 16)) : __uint_as_float(wb);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; i++)
+#pragma unroll
+                for (int j = 0; j < 8; j++) acc[i][j] = oplus_t<OP>(p.oplus, acc[i][j], otimes_t<OT, false>(p.otimes, xs[i], ys[j], p.alpha));
+            __builtin_amdgcn_sched_barrier(0);       // one k at a time: unpacking all of a chunk ahead of its use costs registers
+        }
+    };
+
+    // One LDS stage, no register prefetch: a stage is some ten microseconds of arithmetic per wave, the other
+    // workgroups on the compute unit cover the loads, and the registers are needed for the 8 x 8 block.
+    const char *sa = smem, *sb = smem + C::LDS_A;
+    for (int64_t kt = 0; kt < nk; kt++) {
+        la.fetch(p.k, 0, kt * C::BK, p.K, tid);
+        lb.fetch(p.k, 1, kt * C::BK, p.K, tid);
+        la.commit(smem, tid);
+        lb.commit(smem + C::LDS_A, tid);
+        __syncthreads();
+        const int64_t left = p.K - kt * C::BK;
+        if (left >= C::BK) {
+#pragma unroll 1
+            for (int c = 0; c < 8; c++) chunk(sa, sb, c, C::EPC);
+        } else {
+            for (int c = 0; c * C::EPC < left; c++) chunk(sa, sb, c, (int)(left - c * C::EPC < C::EPC ? left - c * C::EPC : C::EPC));
+        }
+        __syncthreads();
+    }
+
+    char *zb = (char *)p.out.ptr + (p.out.slab_elems ? agg * p.out.slab_elems * 4 : 0);
+    const bool out_bf16 = p.out.dtype == EG_BF16;
+    int64_t zn[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) {
+        const int64_t n = n0 + tx + 16 * j;
+        int64_t unused;
+        decode_group(p.n, n < p.N ? n : 0, unused, zn[j]);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        const int64_t m = m0 + ty + 16 * i;
+        if (m >= p.M) continue;
+        int64_t unused, zm;
+        decode_group(p.m, m, unused, zm);
+#pragma unroll
+        for (int j = 0; j < 8; j++) {
+            if (n0 + tx + 16 * j >= p.N) continue;
+            const int64_t off = bz + zm + zn[j];
+            if (out_bf16) ((uint16_t *)zb)[off] = f32_to_bf16(acc[i][j]);
+            else ((float *)zb)[off] = acc[i][j];
+        }
+    }
+}
+
+template <typename C, int OT, int OP>
+static int launch_alu(ContractParams &p, void *stream)
+{
+    p.tiles_m = (int32_t)((p.M + C::BM - 1) / C::BM);
+    p.tiles_n = (int32_t)((p.N + C::BN - 1) / C::BN);
+    const int64_t wgs = p.n_tuples * p.n_batch * p.tiles_m * p.tiles_n;
+    if (wgs < 1 || wgs >= (1ll << 31)) return fail(EG_ERR_LIMIT, "contraction needs %lld workgroups", (long long)wgs);
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void *)k_contract_alu<C, OT, OP>, hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_A + C::LDS_B) != hipSuccess)
+            return fail(EG_ERR_HIP, "cannot reserve %d bytes of LDS", C::LDS_A + C::LDS_B);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_contract_alu<C, OT, OP>), dim3((unsigned)wgs), dim3(C::THREADS), C::LDS_A + C::LDS_B, (hipStream_t)stream, p);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(EG_ERR_HIP, "k_contract_alu launch failed: %s", hipGetErrorString(e));
+    return EG_OK;
+}
+
+template <typename C>
+static int launch_alu_ops(ContractParams &p, void *stream)
+{
+    // the paper's two examples are compiled in; any other pair reads its operators at run time
+    if (p.otimes == EG_SQDIFF && p.oplus == EG_AGG_SUM) return launch_alu<C, EG_SQDIFF, EG_AGG_SUM>(p, stream);
+    if (p.otimes == EG_ABSDIFF && p.oplus == EG_AGG_MAX) return launch_alu<C, EG_ABSDIFF, EG_AGG_MAX>(p, stream);
+    return launch_alu<C, -1, -1>(p, stream);
+}
+
 template <typename C>
 static int launch_cfg(ContractParams &p, void *stream)
 {
@@ -333,6 +487,11 @@ int launch_contract(ContractParams &p, void *stream)
                                   : (p.n.s0[p.n.n - 1] == 1 && p.n.ext[p.n.n - 1] % epc == 0);
     if (!ok_a || !ok_b) return fail(EG_ERR_LIMIT, "contraction: operand is not vectorisable along its contiguous label");
     if (((uintptr_t)p.x & 15) || ((uintptr_t)p.y & 15)) return fail(EG_ERR_LIMIT, "contraction: operands must be 16-byte aligned");
+    if (p.otimes != EG_MUL || p.oplus != EG_AGG_SUM) {
+        if (p.otimes < EG_MUL || p.otimes > EG_SILU_MUL) return fail(EG_ERR_BAD_OP, "contraction: scalar function %d is not binary", p.otimes);
+        if (p.in_dtype == EG_BF16) return launch_alu_ops<Cfg<128, 128, 64, 64, true>>(p, stream);
+        return launch_alu_ops<Cfg<128, 128, 64, 64, false>>(p, stream);
+    }
     // large bf16 blocks take the direct-to-LDS kernel; EINDECOMP_CONTRACT=staged|dma forces one of the two
     static const char *force = getenv("EINDECOMP_CONTRACT");
     const bool want_dma = force ? (strcmp(force, "dma") == 0) : (p.M >= 128 && p.N >= 128);

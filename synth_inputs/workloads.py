@@ -284,7 +284,63 @@ def config5(dims=None) -> Workload:
     return Workload("c5_split_reduction_bf16", SEED_BASE + 5, vs, ["Z"], parts, dm)
 
 
-CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
+# ----------------------------------------------------------------------------------------------
+# C6: the matrix chain of the paper's first experiment, (A x B) + (C x (D x E)), in its skewed version:
+# for a scale s, A is s x .1s, B .1s x s, C s x .1s, D .1s x 10s, E 10s x s (the square version is config 2's shape)
+# ----------------------------------------------------------------------------------------------
+def config6(dims=None) -> Workload:
+    dm = {"i": 10240, "j": 1024, "k": 10240, "m": 1024, "n": 102400}
+    dm.update(dims or {})
+    sd = lambda k: {"dist": "normal", "std": float(k) ** -0.25}      # a product over k of two such factors has unit variance
+    vs = [
+        Vertex("A", "bf16", bound=(dm["i"], dm["j"]), recipe=sd(dm["j"])),
+        Vertex("B", "bf16", bound=(dm["j"], dm["k"]), recipe=sd(dm["j"])),
+        Vertex("C", "bf16", bound=(dm["i"], dm["m"]), recipe={"dist": "normal", "std": float(dm["m"]) ** -0.5}),
+        Vertex("D", "bf16", bound=(dm["m"], dm["n"]), recipe=sd(dm["n"])),
+        Vertex("E", "bf16", bound=(dm["n"], dm["k"]), recipe=sd(dm["n"])),
+        Vertex("AB", "bf16", spec="ij,jk->ik", inputs=("A", "B")),
+        Vertex("DE", "bf16", spec="mn,nk->mk", inputs=("D", "E")),
+        Vertex("CDE", "bf16", spec="im,mk->ik", inputs=("C", "DE")),
+        Vertex("Z", "f32", spec="ik,ik->ik", inputs=("AB", "CDE"), otimes="add", oplus="none"),
+    ]
+    parts = {
+        # the "3D" cut of every product, the sum cut like the products' outputs
+        "d222": {"AB": {"i": 2, "j": 2, "k": 2}, "DE": {"m": 2, "n": 2, "k": 2}, "CDE": {"i": 2, "m": 2, "k": 2}, "Z": {"i": 2, "k": 4}},
+        # square-root style: outputs cut 2 x 4, nothing aggregated
+        "sqrt": {"AB": {"i": 2, "k": 4}, "DE": {"m": 2, "k": 4}, "CDE": {"i": 2, "k": 4}, "Z": {"i": 2, "k": 4}},
+        # the long contraction of D x E cut 8 ways, the two summands cut differently (a repartition into the sum)
+        "splitn8": {"AB": {"i": 4, "k": 2}, "DE": {"n": 8}, "CDE": {"i": 2, "k": 4}, "Z": {"i": 8}},
+        "whole": {},
+    }
+    return Workload("c6_skewed_chain_bf16", SEED_BASE + 6, vs, ["Z"], parts, dm)
+
+
+# ----------------------------------------------------------------------------------------------
+# C7: the paper's two extended examples: squared L2 and L-infinity distance between the rows of X and the
+# columns of Y (scalar function (x - y)^2 with sum, |x - y| with max)
+# ----------------------------------------------------------------------------------------------
+def config7(dims=None) -> Workload:
+    dm = {"i": 8192, "j": 1024, "k": 8192}
+    dm.update(dims or {})
+    vs = [
+        Vertex("X", "f32", bound=(dm["i"], dm["j"]), recipe={"dist": "uniform"}),
+        Vertex("Y", "f32", bound=(dm["j"], dm["k"]), recipe={"dist": "uniform"}),
+        Vertex("Xh", "bf16", bound=(dm["i"], dm["j"]), recipe={"dist": "uniform"}),
+        Vertex("Yh", "bf16", bound=(dm["k"], dm["j"]), recipe={"dist": "uniform"}),
+        Vertex("L2", "f32", spec="ij,jk->ik", inputs=("X", "Y"), otimes="sqdiff"),
+        Vertex("Linf", "f32", spec="ij,jk->ik", inputs=("X", "Y"), otimes="absdiff", oplus="max"),
+        Vertex("L2h", "f32", spec="ij,kj->ik", inputs=("Xh", "Yh"), otimes="sqdiff"),
+        Vertex("Linfh", "bf16", spec="ij,kj->ik", inputs=("Xh", "Yh"), otimes="absdiff", oplus="max"),
+    ]
+
+    def all4(d):
+        return {n: dict(d) for n in ("L2", "Linf", "L2h", "Linfh")}
+
+    parts = {"d222": all4({"i": 2, "j": 2, "k": 2}), "ik8": all4({"i": 2, "k": 4}), "j8": all4({"j": 8}), "whole": {}}
+    return Workload("c7_distances", SEED_BASE + 7, vs, ["L2", "Linf", "L2h", "Linfh"], parts, dm)
+
+
+CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5, 6: config6, 7: config7}
 
 # Scaled-down shapes that the CPU oracle finishes in seconds while every block still spans
 # several kernel tiles with ragged tails.
@@ -294,6 +350,8 @@ SMALL_DIMS = {
     3: {"b": 256, "f": 384, "h": 320, "c": 128},
     4: {"b": 2, "s": 128, "a": 256, "h": 8, "d": 32, "f": 704},
     5: {"i": 4, "j": 48, "k": 1024, "l": 192},
+    6: {"i": 320, "j": 40, "k": 288, "m": 48, "n": 2560},
+    7: {"i": 200, "j": 152, "k": 136},
 }
 
 

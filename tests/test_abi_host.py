@@ -204,6 +204,8 @@ def test_kernel_routing_of_the_workload_vertices():
         4: {"Q": "contract_mfma", "T1": "contract_mfma", "T2": "map", "Cmax": "reduce_row", "O": "contract_mfma",
             "Yatt": "contract_mfma", "Hh": "map", "Out": "contract_mfma"},
         5: {"Z": "contract_mfma"},
+        6: {"AB": "contract_mfma", "DE": "contract_mfma", "CDE": "contract_mfma", "Z": "map"},
+        7: {"L2": "contract_alu", "Linf": "contract_alu", "L2h": "contract_alu", "Linfh": "contract_alu"},
     }
     for n, kinds in want.items():
         w = build_config(n)

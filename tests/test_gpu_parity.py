@@ -36,7 +36,7 @@ def _run(w, pname, inputs, outputs=None):
 
 
 # ------------------------------------------------------------------ the five configurations, scaled down
-CASES = [(n, p) for n in range(1, 6) for p in build_config(n, small=True).partitionings]
+CASES = [(n, p) for n in range(1, 8) for p in build_config(n, small=True).partitionings]
 _ref_cache = {}
 
 
@@ -69,7 +69,7 @@ def test_config_outputs_through_workspace_match_oracle(n, pname):
         assert bad == 0, f"config {n} {pname} output {name}: {bad} elements out of tolerance (worst {worst:.2f}x)"
 
 
-@pytest.mark.parametrize("n,p", [(n, p) for n in range(1, 6) for p in (4, 16)])
+@pytest.mark.parametrize("n,p", [(n, p) for n in range(1, 8) for p in (4, 16)])
 def test_config_under_the_planners_own_labelling_matches_oracle(n, p):
     # the partitioning vectors chosen by eindecomp_plan instead of hand-written ones; the result may not depend on them
     w, inp, ref = _reference(n)

@@ -45,7 +45,7 @@ def test_subrange_regeneration_and_moments():
 
 
 def test_every_config_builds_at_full_and_small_size():
-    for n in range(1, 6):
+    for n in range(1, 8):
         for small in (False, True):
             w = build_config(n, small=small)
             assert w.outputs and w.partitionings
