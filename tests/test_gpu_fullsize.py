@@ -194,3 +194,64 @@ def test_config4_decoder_block_sampled_heads_and_properties():
         assert frac < 1e-5, f"Out: partitionings disagree on a fraction {frac} of the elements"
     finally:
         r.close()
+
+
+def test_config6_skewed_chain_sampled_rows_under_two_labellings():
+    import torch
+    print("config 6 full size, partitioning splitn8", flush=True)
+    w, dev, r = _setup(6, "splitn8", ["DE", "Z"])
+    try:
+        assert r.plan("DE")["n_agg"] == 8 and r.plan("Z")["repart_x"] == 1
+        # D x E has a reduction over 102400 values: sampled rows at full length
+        E_ = _host(dev["E"])
+        mrows = [0, 511, 512, 1023]
+        de = einsum_ref("mn,nk->mk", _host(dev["D"][mrows]), E_, out_dtype="bf16")
+        bad, worst = violations(_f64(_host(r.output("DE")[mrows])), de, RTOL_BF16)
+        assert bad == 0, f"DE rows: {bad} out of tolerance (worst {worst:.2f}x)"
+        # the sum, on sampled rows, from the GPU's own DE (already checked above on its sampled rows)
+        rows = [0, 1279, 1280, 5119, 5120, 10239]
+        ab = einsum_ref("ij,jk->ik", _host(dev["A"][rows]), _host(dev["B"]), out_dtype="bf16")
+        cde = einsum_ref("im,mk->ik", _host(dev["C"][rows]), _host(r.output("DE")), out_dtype="bf16")
+        z = einsum_ref("ik,ik->ik", to_storage(ab, "bf16").data, to_storage(cde, "bf16").data, otimes="add", oplus="none", out_dtype="f32")
+        bad, worst = violations(_f64(_host(r.output("Z")[rows])), z, RTOL_BF16)
+        assert bad == 0, f"Z rows: {bad} out of tolerance (worst {worst:.2f}x)"
+        z_hand = r.output("Z").clone()
+    finally:
+        r.close()
+    print("config 6 full size, labelled by the planner for p = 8", flush=True)
+    from paper_2410_02682_amd.runner import GraphRunner
+    r = GraphRunner(w, "eindecomp:8")
+    try:
+        assert r.plan_exact                               # a tree: the dynamic programme's optimum
+        r.bind(dev)
+        r.run()
+        torch.cuda.synchronize()
+        got = r.output("Z")
+        rms = float(z_hand.double().pow(2).mean().sqrt())
+        frac = float(((got - z_hand).abs() > RTOL_BF16 * (z_hand.abs() + rms)).float().mean())
+        assert frac < 1e-5, f"labellings disagree on a fraction {frac} of the elements"
+    finally:
+        r.close()
+
+
+def test_config7_distances_sampled_rows():
+    print("config 7 full size, partitioning d222", flush=True)
+    w, dev, r = _setup(7, "d222", None)
+    try:
+        for name in ("L2", "Linf", "L2h", "Linfh"):
+            assert r.plan(name)["kernel"] == "contract_alu" and r.plan(name)["n_agg"] == 2
+        rows = [0, 127, 128, 4095, 4096, 8191]
+        X, Y = _host(dev["X"][rows]), _host(dev["Y"])
+        Xh, Yh = _host(dev["Xh"][rows]), _host(dev["Yh"])
+        for name, spec, a, b, ot, op, dt in (("L2", "ij,jk->ik", X, Y, "sqdiff", "sum", "f32"), ("Linf", "ij,jk->ik", X, Y, "absdiff", "max", "f32"),
+                                             ("L2h", "ij,kj->ik", Xh, Yh, "sqdiff", "sum", "f32"), ("Linfh", "ij,kj->ik", Xh, Yh, "absdiff", "max", "bf16")):
+            ref = einsum_ref(spec, a, b, otimes=ot, oplus=op, out_dtype=dt)
+            got = _f64(_host(r.output(name)[rows]))
+            if op == "max":
+                # a maximum of exactly representable differences: the fp32 result is exact (bf16: one rounding of it)
+                assert np.array_equal(got, ref), f"{name}: {int((got != ref).sum())} elements differ"
+            else:
+                bad, worst = violations(got, ref, RTOL_F32)
+                assert bad == 0, f"{name}: {bad} out of tolerance (worst {worst:.2f}x)"
+    finally:
+        r.close()
