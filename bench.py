@@ -157,6 +157,8 @@ def main():
             "flops": {"contract_mfma": 2.0, "contract_alu": 3.0}.get(pl["kernel"], 0.0) * prod(pl["bound"]),
             "join_bytes": in_bytes + join_out,
             "agg_bytes": (pl["n_agg"] * nz * 4 + nz * esz[v.dtype]) if partial else 0,
+            # a fused softmax pass is credited its own minimal traffic: one tensor of the result's shape in, the result out
+            "fused_bytes": nz * (esz[v.dtype] + esz[w.vertex(v.inputs[0]).dtype]),
         }
         launches_per_step += 2 if partial else 1
 
@@ -176,7 +178,7 @@ def main():
     fam = {}
     for x in rec:
         a = acct[x["vertex"]]
-        key = "aggregate" if x["stage"] == "aggregate" else a["kind"]
+        key = "aggregate" if x["stage"] == "aggregate" else ("softmax_fused" if x["kernel"] == "softmax_fused" else a["kind"])
         f = fam.setdefault(key, {"ms": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0})
         f["ms"] += x["ms"]
         f["launches"] += 1
@@ -184,7 +186,7 @@ def main():
             f["bytes"] += a["agg_bytes"]
         else:
             f["flops"] += a["flops"]
-            f["bytes"] += a["join_bytes"]
+            f["bytes"] += a["fused_bytes"] if key == "softmax_fused" else a["join_bytes"]
     kernels = {}
     for key, f in fam.items():
         k = {"launches_per_step": f["launches"] // args.steps, "avg_launch_ms": f["ms"] / f["launches"],
@@ -204,7 +206,8 @@ def main():
     roofline = dict(kernels[dom])
     roofline["kernel"] = {"contract_mfma": "k_contract_dma / k_contract (block contraction on MFMA, all tuples of a vertex per launch)",
                           "aggregate": "k_aggregate_vec4", "map": "k_map", "reduce_row": "k_reduce_row", "generic": "k_generic",
-                          "contract_alu": "k_contract_alu (contraction-shaped vertex with another scalar function, vector ALU)"}[dom]
+                          "contract_alu": "k_contract_alu (contraction-shaped vertex with another scalar function, vector ALU)",
+                          "softmax_fused": "k_softmax_rows"}[dom]
     roofline["traffic"] = MEASURED_TRAFFIC.get((f"c{args.config}", pname))
     out = {"metric": "einsum-graph TFLOP/s (contractions) + GB/s (maps/aggregations), % of roofline", "value": value,
            "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,

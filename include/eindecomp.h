@@ -97,7 +97,8 @@ typedef enum {
     EG_KERNEL_MAP = 2,             /* no aggregated label: elementwise map / binary join             */
     EG_KERNEL_REDUCE_ROW = 3,      /* aggregated labels are the contiguous tail of X: wave reductions */
     EG_KERNEL_GENERIC = 4,         /* any EinSum: one output element per lane, loop over l_agg       */
-    EG_KERNEL_CONTRACT_ALU = 5     /* contraction-shaped EinSum with another (x)/(+) pair (squared L2, L-infinity, ...): LDS tiles, vector ALU */
+    EG_KERNEL_CONTRACT_ALU = 5,    /* contraction-shaped EinSum with another (x)/(+) pair (squared L2, L-infinity, ...): LDS tiles, vector ALU */
+    EG_KERNEL_SOFTMAX_FUSED = 6    /* the softmax vertices max, exp(x - max), sum, division (and a preceding alpha*x + y) in one pass per row */
 } eg_kernel_kind;
 
 /* Read-only view of one vertex's plan.  All pointers are host memory owned by the graph and stay
@@ -201,6 +202,14 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs,
  * out may be strided.  oplus is SUM or MAX.  Also called inside tr_execute. */
 int tr_aggregate(eg_agg oplus, const void *partials, int64_t n_agg, int64_t slab_elems,
                  eg_relation *out, void *hip_stream);
+
+/* Fusion across vertices.  Section 3 of the paper writes softmax as four EinSums (row maximum, exp(x - maximum),
+ * row sum, division); when such a chain reduces over its last label, that label is not partitioned, all its
+ * vertices carry the same partitioning vector and the intermediate tensors have no other consumer, tr_execute
+ * runs it as one pass over the rows (the preceding alpha * x + y vertex included when it feeds only the chain),
+ * rounding where the separate vertices would have rounded.  Row maxima and sums that other vertices consume are
+ * still written.  Enabled by default; enable = 0 makes every vertex run on its own.  Changes the workspace size. */
+int tr_set_fusion(eg_graph *g, int enable);
 
 /* ---- Timing of the launches inside tr_execute (for roofline reports) ----------------------------------- */
 

@@ -440,6 +440,91 @@ private:
 
 static int dry_route(const eg_graph *g, int vertex, Routed &r);
 
+// ------------------------------------------------------------------------------------------------
+// fusion of softmax chains (Section 3 of the paper writes softmax as four EinSums)
+// ------------------------------------------------------------------------------------------------
+struct FuseGroup {
+    int add = -1;              // the alpha * x + y vertex in front of the chain, or -1
+    int vmax = -1, vexp = -1, vsum = -1, vdiv = -1;
+    int src = -1, addend = -1; // what the chain reads: the source tensor and the added operand (or -1)
+    bool emit_max = false, emit_sum = false;
+};
+
+static bool is_iota(const std::vector<int> &l, size_t n)
+{
+    if (l.size() != n) return false;
+    for (size_t i = 0; i < n; i++)
+        if (l[i] != (int)i) return false;
+    return true;
+}
+
+// Chains max -> exp(x - max) -> sum -> division over the last label that can run as one pass: same partitioning
+// vector on every vertex, the reduced label unpartitioned, rows of at most 8192 elements, and no consumer of the
+// exponentials (or of the sum alpha * x + y in front) outside the chain.  Row maxima and sums may have other
+// consumers as long as those come after the division in vertex order.  A purely structural test: it does not
+// depend on strides, so the workspace layout and the execution agree on it.
+static std::vector<FuseGroup> find_fusions(const eg_graph *g)
+{
+    std::vector<FuseGroup> out;
+    if (!g->fuse) return out;
+    const int nv = (int)g->v.size();
+    std::vector<std::vector<int>> cons(nv);
+    for (int i = 0; i < nv; i++)
+        for (int k = 0; k < g->v[i].n_in; k++)
+            if (k == 0 || g->v[i].in[0] != g->v[i].in[1]) cons[g->v[i].in[k]].push_back(i);
+    std::vector<char> taken(nv, 0);
+    auto only = [&](int u, std::initializer_list<int> allowed) {
+        for (int c : cons[u])
+            if (std::find(allowed.begin(), allowed.end(), c) == allowed.end()) return false;
+        return true;
+    };
+    for (int p = 0; p < nv; p++) {
+        const Vertex &P = g->v[p];
+        if (P.is_input || P.n_in != 2 || P.otimes != EG_DIV || !P.agg.empty()) continue;
+        const int e = P.in[0], s = P.in[1];
+        if (e == s || g->v[e].is_input || g->v[s].is_input) continue;
+        const Vertex &E = g->v[e], &S = g->v[s];
+        if (E.n_in != 2 || E.otimes != EG_EXP_SUB || !E.agg.empty() || E.is_output) continue;
+        if (S.n_in != 1 || S.in[0] != e || S.otimes != EG_IDENT || S.oplus != EG_AGG_SUM) continue;
+        const int t = E.in[0], c = E.in[1];
+        if (t == c || g->v[c].is_input) continue;
+        const Vertex &C = g->v[c];
+        if (C.n_in != 1 || C.in[0] != t || C.otimes != EG_IDENT || C.oplus != EG_AGG_MAX) continue;
+        const size_t r = E.lx.size();
+        if (r < 1) continue;
+        // shapes: full-rank operands are labelled 0..r-1 (first-appearance order), the row statistics lack the last label
+        if (!is_iota(E.lx, r) || !is_iota(E.ly, r - 1) || !is_iota(E.lz, r)) continue;
+        if (!is_iota(P.lx, r) || !is_iota(P.ly, r - 1) || !is_iota(P.lz, r)) continue;
+        if (!is_iota(C.lx, r) || !is_iota(C.lz, r - 1) || !is_iota(S.lx, r) || !is_iota(S.lz, r - 1)) continue;
+        if (E.d != P.d || C.d != P.d || S.d != P.d || P.d[r - 1] != 1) continue;
+        if (E.lbound[r - 1] > 8192) continue;
+        if (!only(e, {s, p})) continue;
+        if (taken[e] || taken[s] || taken[c] || taken[p]) continue;
+        FuseGroup grp;
+        grp.vmax = c; grp.vexp = e; grp.vsum = s; grp.vdiv = p; grp.src = t;
+        grp.emit_max = C.is_output || !only(c, {e});
+        grp.emit_sum = S.is_output || !only(s, {p});
+        bool late = true;                       // whoever else reads the statistics must run after the fused pass
+        for (int u : cons[c]) late = late && (u == e || u > p);
+        for (int u : cons[s]) late = late && (u == p || u > p);
+        if (!late) continue;
+        // alpha * x + y in front, when it feeds nothing but the chain
+        if (!g->v[t].is_input) {
+            const Vertex &T = g->v[t];
+            if (T.n_in == 2 && T.otimes == EG_ADD && T.agg.empty() && !T.is_output && T.in[0] != T.in[1] && !taken[t] &&
+                is_iota(T.lx, r) && is_iota(T.lz, r) && T.d == P.d && only(t, {c, e})) {
+                grp.add = t;
+                grp.src = T.in[0];
+                grp.addend = T.in[1];
+            }
+        }
+        for (int u : {grp.add, c, e, s, p})
+            if (u >= 0) taken[u] = 1;
+        out.push_back(grp);
+    }
+    return out;
+}
+
 static Layout make_layout(const eg_graph *g)
 {
     const int nv = (int)g->v.size();
@@ -447,13 +532,41 @@ static Layout make_layout(const eg_graph *g)
     L.result_off.assign(nv, -1);
     L.partial_off.assign(nv, -1);
     L.split.assign(nv, 1);
+    // a fused chain runs where its last vertex stands: it reads the chain's outside operands there and writes the
+    // result (and the row statistics that are still wanted); the other tensors of the chain never exist
+    const std::vector<FuseGroup> groups = find_fusions(g);
+    std::vector<int> group_of(nv, -1);
+    for (size_t k = 0; k < groups.size(); k++)
+        for (int u : {groups[k].add, groups[k].vmax, groups[k].vexp, groups[k].vsum, groups[k].vdiv})
+            if (u >= 0) group_of[u] = (int)k;
+    auto reads_of = [&](int i) {                      // what executes at position i reads these tensors
+        std::vector<int> in;
+        if (group_of[i] >= 0) {
+            const FuseGroup &f = groups[group_of[i]];
+            if (i == f.vdiv) { in.push_back(f.src); if (f.addend >= 0) in.push_back(f.addend); }
+        } else {
+            for (int k = 0; k < g->v[i].n_in; k++) in.push_back(g->v[i].in[k]);
+        }
+        return in;
+    };
     std::vector<int> last_use(nv, -1);
     for (int i = 0; i < nv; i++)
-        for (int k = 0; k < g->v[i].n_in; k++) last_use[g->v[i].in[k]] = i;
+        for (int u : reads_of(i)) last_use[u] = i;
     Arena arena;
     for (int i = 0; i < nv; i++) {
         const Vertex &v = g->v[i];
         if (v.is_input) continue;
+        if (group_of[i] >= 0) {
+            const FuseGroup &f = groups[group_of[i]];
+            if (i != f.vdiv) continue;
+            for (int u : {f.vdiv, f.emit_max ? f.vmax : -1, f.emit_sum ? f.vsum : -1})
+                if (u >= 0 && !g->v[u].is_output) L.result_off[u] = arena.alloc(numel(g->v[u].bound) * dtype_size(g->v[u].dtype));
+            for (int u : reads_of(i))
+                if (last_use[u] == i && L.result_off[u] >= 0) arena.release(L.result_off[u]);
+            for (int u : {f.vdiv, f.emit_max ? f.vmax : -1, f.emit_sum ? f.vsum : -1})
+                if (u >= 0 && !g->v[u].is_output && last_use[u] < 0) arena.release(L.result_off[u]);
+            continue;
+        }
         if (!v.is_output) L.result_off[i] = arena.alloc(numel(v.bound) * dtype_size(v.dtype));
         {
             Routed r;
@@ -564,6 +677,13 @@ int tr_workspace_bytes(eg_graph *g, size_t *bytes)
     return EG_OK;
 }
 
+int tr_set_fusion(eg_graph *g, int enable)
+{
+    if (!g) return fail(EG_ERR_NULL, "graph is NULL");
+    g->fuse = enable != 0;
+    return EG_OK;
+}
+
 int tr_profile_enable(eg_graph *g, int max_launches)
 {
     if (!g) return fail(EG_ERR_NULL, "graph is NULL");
@@ -638,7 +758,8 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
     char *ws = (char *)workspace;
 
     // route everything first so that a failure launches nothing
-    struct Step { int vertex; Routed r; bool agg; int64_t slabs, stride; const void *partials; void *dst; std::vector<int64_t> dst_stride; };
+    struct Step { int vertex; Routed r; bool agg; int64_t slabs, stride; const void *partials; void *dst; std::vector<int64_t> dst_stride;
+                  bool fused = false; SoftmaxParams sp; };
     std::vector<Step> steps;
     auto operand_of = [&](int u) {
         Operand o;
@@ -648,10 +769,72 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
         else { o.ptr = ws + L.result_off[u]; o.stride = dense_strides(pu.bound); }
         return o;
     };
+    const std::vector<FuseGroup> groups = find_fusions(g);
+    std::vector<int> group_of(nv, -1);
+    for (size_t k = 0; k < groups.size(); k++)
+        for (int u : {groups[k].add, groups[k].vmax, groups[k].vexp, groups[k].vsum, groups[k].vdiv})
+            if (u >= 0) group_of[u] = (int)k;
     for (int i = 0; i < nv; i++) {
         Vertex &v = g->v[i];
         if (v.is_input) continue;
         if (!v.plan.valid) return fail(EG_ERR_BAD_PARTITION, "vertex %d has no plan", i);
+        if (group_of[i] >= 0) {
+            const FuseGroup &f = groups[group_of[i]];
+            if (i != f.vdiv) continue;                 // runs as part of the pass that stands at the division
+            Step s;
+            s.vertex = i;
+            s.fused = true;
+            s.agg = false;
+            SoftmaxParams &sp = s.sp;
+            memset(&sp, 0, sizeof sp);
+            const Vertex &E = g->v[f.vexp];
+            const int r = (int)E.lx.size();
+            const Operand src = operand_of(f.src), res = operand_of(f.vdiv);
+            Operand addend, omax, osum;
+            LabelInfo li, li2;                          // li: source / added operand / result; li2: row maxima / row sums
+            li.nl = li2.nl = r;
+            for (int l = 0; l < r; l++) {
+                li.ext[l] = li2.ext[l] = E.lbound[l] / E.d[l];
+                li.sx[l] = src.stride[l]; li.inx[l] = true;
+                li.sz[l] = res.stride[l]; li.inz[l] = true;
+            }
+            if (f.add >= 0) {
+                const Vertex &T = g->v[f.add];
+                addend = operand_of(f.addend);
+                for (size_t k = 0; k < T.ly.size(); k++) { li.sy[T.ly[k]] = addend.stride[k]; li.iny[T.ly[k]] = true; }
+                sp.has_add = 1; sp.add = addend.ptr; sp.dt_add = addend.dtype; sp.dt_t = T.dtype; sp.alpha = (float)T.alpha;
+            }
+            if (f.emit_max) {
+                omax = operand_of(f.vmax);
+                for (int l = 0; l + 1 < r; l++) li2.sx[l] = omax.stride[l];
+                sp.emit_max = 1; sp.row_max = (void *)omax.ptr; sp.dt_max = omax.dtype;
+            }
+            if (f.emit_sum) {
+                osum = operand_of(f.vsum);
+                for (int l = 0; l + 1 < r; l++) li2.sy[l] = osum.stride[l];
+                sp.emit_sum = 1; sp.row_sum = (void *)osum.ptr; sp.dt_sum = osum.dtype;
+            }
+            sp.ts = tuple_space(E, li);                 // E's partitioning vector is the chain's
+            sp.ts2 = tuple_space(E, li2);
+            sp.rows_per_block = 1;
+            for (int l = 0; l + 1 < r; l++) {
+                if (li.ext[l] <= 1) continue;
+                const int k = sp.rows.n++;
+                sp.rows.ext[k] = sp.stats.ext[k] = (int32_t)li.ext[l];
+                sp.rows.sx[k] = li.sx[l]; sp.rows.sy[k] = li.sy[l]; sp.rows.sz[k] = li.sz[l];
+                sp.stats.sx[k] = li2.sx[l]; sp.stats.sy[k] = li2.sy[l];
+                sp.rows_per_block *= li.ext[l];
+            }
+            sp.stats.n = sp.rows.n;
+            sp.n = (int32_t)li.ext[r - 1];
+            sp.sx_last = li.sx[r - 1]; sp.sy_last = li.sy[r - 1]; sp.sz_last = li.sz[r - 1];
+            sp.dt_src = src.dtype; sp.dt_e = E.dtype; sp.dt_p = res.dtype;
+            if (!sp.has_add) sp.dt_t = src.dtype;
+            sp.src = src.ptr; sp.p = (void *)res.ptr;
+            sp.n_tuples = E.plan.n_tuples;
+            steps.push_back(std::move(s));
+            continue;
+        }
         Step s;
         s.vertex = i;
         Operand X = operand_of(v.in[0]), Y;
@@ -706,7 +889,8 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
     };
     for (Step &s : steps) {
         const Vertex &v = g->v[s.vertex];
-        int rc = timed(s.vertex, 0, s.r.kind, [&] { return launch_routed(s.r, hip_stream); });
+        int rc = s.fused ? timed(s.vertex, 0, EG_KERNEL_SOFTMAX_FUSED, [&] { return launch_softmax_rows(s.sp, hip_stream); })
+                         : timed(s.vertex, 0, s.r.kind, [&] { return launch_routed(s.r, hip_stream); });
         if (rc) return rc;
         if (s.agg) {
             rc = timed(s.vertex, 1, EG_KERNEL_NONE, [&] {

@@ -6,6 +6,7 @@
 // count N = prod d[l_X (.) l_Y] is Section 6 and n_agg = prod d[l_agg] is Section 7.
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 #include "eg_internal.h"
@@ -146,6 +147,8 @@ int einsum_graph_create(eg_graph **g)
 {
     if (!g) return fail(EG_ERR_NULL, "einsum_graph_create: g is NULL");
     *g = new eg_graph();
+    const char *f = getenv("EINDECOMP_FUSE");            // EINDECOMP_FUSE=0: graphs start with fusion off (see tr_set_fusion)
+    (*g)->fuse = !(f && f[0] == '0');
     return EG_OK;
 }
 

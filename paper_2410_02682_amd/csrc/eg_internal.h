@@ -122,6 +122,27 @@ struct GenericParams {            // any EinSum: one output element per lane, se
     int64_t red_elems;
 };
 
+// A softmax over the last label, optionally preceded by alpha * x + y, computed row by row in one pass
+// (the vertices max, exp(x - max), sum and division of Section 3's softmax, fused where the partitioning allows).
+struct SoftmaxParams {
+    TupleSpace ts;                // steps of the source (x), of the added operand (y) and of the result (z)
+    TupleSpace ts2;               // steps of the row maxima (x) and of the row sums (y) when those are written
+    StridedDims rows;             // one entry per row label (extent > 1): sx source, sy added operand, sz result
+    StridedDims stats;            // the same entries: sx row maxima, sy row sums
+    int32_t n;                    // row length
+    int64_t sx_last, sy_last, sz_last;   // element strides of the last label in source, added operand, result
+    int32_t has_add, emit_max, emit_sum;
+    int32_t dt_src, dt_add, dt_t, dt_e, dt_p, dt_max, dt_sum;   // storage dtypes; dt_t / dt_e: where the unfused vertices would round
+    float alpha;
+    const void *src;
+    const void *add;
+    void *p;
+    void *row_max;
+    void *row_sum;
+    int64_t n_tuples, rows_per_block;
+    int32_t vec;                  // filled by the launcher: 8 (16-byte accesses along the rows) or 1
+};
+
 struct AggregateParams {          // out[e] = oplus_a partials[a][e], ascending a, fp32, one final cast
     const float *partials;
     int64_t n_agg;
@@ -142,6 +163,7 @@ int launch_map(const MapParams &p, void *stream);
 int launch_reduce_row(const ReduceParams &p, void *stream);
 int launch_generic(const GenericParams &p, void *stream);
 int launch_aggregate(const AggregateParams &p, void *stream);
+int launch_softmax_rows(SoftmaxParams &p, void *stream);
 
 // ------------------------------------------------------------------------------------------------
 // host-side graph
@@ -179,6 +201,7 @@ struct eg_graph {
     std::vector<int> inputs;      // vertex ids of graph inputs, insertion order
     std::vector<int> outputs;     // marked outputs, marking order
     // executor state
+    bool fuse = true;                               // fuse softmax chains where the partitioning allows (tr_set_fusion)
     bool profile = false;
     std::vector<void *> ev_start, ev_stop;          // hipEvent_t pool
     struct Launch { int vertex, stage, kernel; };

@@ -455,3 +455,172 @@ int launch_aggregate(const AggregateParams &p, void *stream)
 }
 
 }  // namespace eg
+
+// ------------------------------------------------------------------------------------------------
+// Fused softmax over the last label (Section 3 of the paper gives softmax as row maximum, exp(x - maximum),
+// row sum and division; here the four run as one pass per row, with the preceding alpha * x + y when there is
+// one).  Values are rounded where the separate vertices would have rounded (dt_t after the addition, dt_e
+// after the exponential), so the result matches the unfused path up to the order of the row sum.
+// ------------------------------------------------------------------------------------------------
+namespace eg {
+
+__device__ __forceinline__ float round_as(float v, int dt) { return dt == EG_BF16 ? bf16_to_f32(f32_to_bf16(v)) : v; }
+
+__device__ __forceinline__ void softmax_row_offsets(const SoftmaxParams &p, int64_t t, uint32_t row, int64_t &ox, int64_t &oy, int64_t &oz, int64_t &oc, int64_t &os)
+{
+    int64_t unused0, unused1;
+    decode_tuple(p.ts, t, ox, oy, oz, unused0);
+    decode_tuple(p.ts2, t, oc, os, unused0, unused1);
+    uint32_t e = row;
+    for (int i = p.rows.n - 1; i >= 0; i--) {
+        const uint32_t ext = (uint32_t)p.rows.ext[i], q = e / ext;
+        const int64_t k = e - q * ext;
+        e = q;
+        ox += k * p.rows.sx[i]; oy += k * p.rows.sy[i]; oz += k * p.rows.sz[i];
+        oc += k * p.stats.sx[i]; os += k * p.stats.sy[i];
+    }
+}
+
+// One wave per row, VPL vectors of 8 elements per lane held in registers (rows of up to 512 * VPL elements).
+template <int VPL>
+__global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p)
+{
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t t = tuple_of_block();
+    const uint32_t row = blockIdx.x * (kThreads / 64) + wave;
+    if (t >= p.n_tuples || row >= (uint32_t)p.rows_per_block) return;          // whole waves leave
+    int64_t ox, oy, oz, oc, os;
+    softmax_row_offsets(p, t, row, ox, oy, oz, oc, os);
+    float v[VPL][8];
+    float m = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < VPL; u++) {
+        const int c = (u * 64 + lane) * 8;
+        if (c < p.n) {
+            load8(p.src, p.dt_src, ox + c, v[u]);
+            if (p.has_add) {
+                float y[8];
+                if (p.sy_last == 1) load8(p.add, p.dt_add, oy + c, y);
+                else { const float s = load_elem(p.add, p.dt_add, oy);
+#pragma unroll
+                    for (int i = 0; i < 8; i++) y[i] = s; }
+#pragma unroll
+                for (int i = 0; i < 8; i++) v[u][i] = round_as(p.alpha * v[u][i] + y[i], p.dt_t);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; i++) m = fmaxf(m, v[u][i]);
+        }
+    }
+    m = wave_reduce<EG_AGG_MAX>(EG_AGG_MAX, m);
+    const bool fast_e = p.dt_e == EG_BF16, fast_p = p.dt_p == EG_BF16;     // as the separate vertices choose
+    float sum = 0.f;
+#pragma unroll
+    for (int u = 0; u < VPL; u++) {
+        if ((u * 64 + lane) * 8 < p.n) {
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const float e = round_as(fast_e ? __expf(v[u][i] - m) : expf(v[u][i] - m), p.dt_e);
+                v[u][i] = e;
+                sum += e;
+            }
+        }
+    }
+    sum = wave_reduce<EG_AGG_SUM>(EG_AGG_SUM, sum);
+    const float inv = __frcp_rn(sum);
+#pragma unroll
+    for (int u = 0; u < VPL; u++) {
+        const int c = (u * 64 + lane) * 8;
+        if (c < p.n) {
+            float z[8];
+#pragma unroll
+            for (int i = 0; i < 8; i++) z[i] = fast_p ? v[u][i] * inv : v[u][i] / sum;
+            store8(p.p, p.dt_p, oz + c, z);
+        }
+    }
+    if (lane == 0) {
+        if (p.emit_max) store_elem(p.row_max, p.dt_max, oc, m);
+        if (p.emit_sum) store_elem(p.row_sum, p.dt_sum, os, sum);
+    }
+}
+
+// Any strides and alignments: one workgroup per row, the row staged in LDS between the three sweeps.
+constexpr int kSoftmaxMaxRow = 8192;
+
+__device__ __forceinline__ float block_reduce(float v, int oplus, float *red)
+{
+    v = oplus == EG_AGG_MAX ? wave_reduce<EG_AGG_MAX>(oplus, v) : wave_reduce<EG_AGG_SUM>(oplus, v);
+    __syncthreads();                                   // red[] may still be read from the previous reduction
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float r = red[0];
+    for (int w = 1; w < kThreads / 64; w++) r = oplus == EG_AGG_MAX ? fmaxf(r, red[w]) : r + red[w];
+    return r;
+}
+
+__global__ __launch_bounds__(kThreads) void k_softmax_rows_scalar(const SoftmaxParams p)
+{
+    __shared__ float buf[kSoftmaxMaxRow];
+    __shared__ float red[kThreads / 64];
+    const int64_t t = tuple_of_block();
+    const uint32_t row = blockIdx.x;
+    if (t >= p.n_tuples || row >= (uint32_t)p.rows_per_block) return;          // whole workgroups leave
+    int64_t ox, oy, oz, oc, os;
+    softmax_row_offsets(p, t, row, ox, oy, oz, oc, os);
+    float m = -INFINITY;
+    for (int c = threadIdx.x; c < p.n; c += kThreads) {
+        float x = load_elem(p.src, p.dt_src, ox + c * p.sx_last);
+        if (p.has_add) x = round_as(p.alpha * x + load_elem(p.add, p.dt_add, oy + c * p.sy_last), p.dt_t);
+        buf[c] = x;
+        m = fmaxf(m, x);
+    }
+    m = block_reduce(m, EG_AGG_MAX, red);
+    const bool fast_e = p.dt_e == EG_BF16, fast_p = p.dt_p == EG_BF16;
+    float sum = 0.f;
+    for (int c = threadIdx.x; c < p.n; c += kThreads) {
+        const float e = round_as(fast_e ? __expf(buf[c] - m) : expf(buf[c] - m), p.dt_e);
+        buf[c] = e;
+        sum += e;
+    }
+    sum = block_reduce(sum, EG_AGG_SUM, red);
+    const float inv = __frcp_rn(sum);
+    for (int c = threadIdx.x; c < p.n; c += kThreads) store_elem(p.p, p.dt_p, oz + c * p.sz_last, fast_p ? buf[c] * inv : buf[c] / sum);
+    if (threadIdx.x == 0) {
+        if (p.emit_max) store_elem(p.row_max, p.dt_max, oc, m);
+        if (p.emit_sum) store_elem(p.row_sum, p.dt_sum, os, sum);
+    }
+}
+
+int launch_softmax_rows(SoftmaxParams &p, void *stream)
+{
+    if (!p.src || !p.p || (p.has_add && !p.add) || (p.emit_max && !p.row_max) || (p.emit_sum && !p.row_sum))
+        return fail(EG_ERR_NULL, "softmax kernel: NULL operand");
+    if (p.n < 1 || p.n > kSoftmaxMaxRow) return fail(EG_ERR_LIMIT, "softmax kernel: row length %d", p.n);
+    if (p.rows_per_block < 1 || p.n_tuples < 1) return fail(EG_ERR_LIMIT, "softmax kernel: empty index space");
+    // 16-byte accesses along the rows need unit stride, whole vectors, and every other offset a multiple of 8 elements
+    bool vec = p.n % 8 == 0 && p.sx_last == 1 && p.sz_last == 1 && (!p.has_add || p.sy_last == 1 || p.sy_last == 0) &&
+               ((uintptr_t)p.src & 15) == 0 && ((uintptr_t)p.p & 15) == 0 && (!p.has_add || ((uintptr_t)p.add & 15) == 0);
+    for (int i = 0; i < p.rows.n && vec; i++)
+        if (p.rows.sx[i] % 8 || p.rows.sz[i] % 8 || (p.has_add && p.sy_last == 1 && p.rows.sy[i] % 8)) vec = false;
+    for (int l = 0; l < p.ts.n && vec; l++)
+        if (p.ts.step_x[l] % 8 || p.ts.step_z[l] % 8 || (p.has_add && p.sy_last == 1 && p.ts.step_y[l] % 8)) vec = false;
+    p.vec = vec ? 8 : 1;
+    hipStream_t st = (hipStream_t)stream;
+    dim3 grid;
+    if (!vec) {
+        int rc = tuple_grid(p.rows_per_block, 1, p.n_tuples, grid);
+        if (rc) return rc;
+        hipLaunchKernelGGL(k_softmax_rows_scalar, grid, dim3(kThreads), 0, st, p);
+        return check_launch("k_softmax_rows_scalar");
+    }
+    int rc = tuple_grid(p.rows_per_block, kThreads / 64, p.n_tuples, grid);
+    if (rc) return rc;
+    const int vpl = (p.n + 511) / 512;
+    if (vpl <= 1) hipLaunchKernelGGL(k_softmax_rows<1>, grid, dim3(kThreads), 0, st, p);
+    else if (vpl <= 2) hipLaunchKernelGGL(k_softmax_rows<2>, grid, dim3(kThreads), 0, st, p);
+    else if (vpl <= 4) hipLaunchKernelGGL(k_softmax_rows<4>, grid, dim3(kThreads), 0, st, p);
+    else if (vpl <= 8) hipLaunchKernelGGL(k_softmax_rows<8>, grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL(k_softmax_rows<16>, grid, dim3(kThreads), 0, st, p);
+    return check_launch("k_softmax_rows");
+}
+
+}  // namespace eg

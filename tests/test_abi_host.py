@@ -221,3 +221,23 @@ def test_kernel_routing_of_the_workload_vertices():
             for name, kind in kinds.items():
                 assert E.einsum_graph_plan(g, vid[name])["kernel"] == kind, (n, pname, name)
             E.einsum_graph_destroy(g)
+
+
+def test_fusion_of_softmax_chains_shrinks_the_workspace_and_can_be_switched_off():
+    w = build_config(4, small=True)
+    sizes = {}
+    for fuse in (True, False):
+        g = E.einsum_graph_create()
+        vid = {}
+        for v in w.vertices:
+            if v.is_input:
+                vid[v.name] = E.einsum_graph_add_input(g, v.bound, v.dtype)
+            else:
+                vid[v.name] = E.einsum_graph_add_einsum(g, v.spec, v.otimes, v.oplus, v.alpha, [vid[n] for n in v.inputs], v.dtype)
+        for n in w.outputs:
+            E.einsum_graph_mark_output(g, vid[n])
+        E.tr_set_fusion(g, fuse)
+        sizes[fuse] = E.tr_workspace_bytes(g)
+        E.einsum_graph_destroy(g)
+    # unfused, the scaled scores, their exponentials and the probabilities coexist; fused, only the probabilities exist
+    assert sizes[True] < sizes[False]

@@ -325,3 +325,66 @@ def test_profile_records_every_launch():
     assert [(x["stage"], x["kernel"]) for x in rec] == [("join", "contract_mfma"), ("aggregate", "none")] * 2
     assert all(x["ms"] > 0 for x in rec)
     r.close()
+
+
+# ------------------------------------------------------------------ fused softmax chains
+def _softmax_workload(bound, dtype, with_add, stats_consumed):
+    from synth_inputs.workloads import Vertex, Workload
+    labs = "bhst"[4 - len(bound):]
+    row = labs[:-1]
+    vs = [Vertex("T", dtype, bound=tuple(bound), recipe={"dist": "normal", "std": 2.0})]
+    src = "T"
+    if with_add:
+        vs.append(Vertex("M", "f32", bound=tuple(bound[-2:]), recipe={"dist": "causal_mask"}))
+        vs.append(Vertex("T2", dtype, spec=f"{labs},{labs[-2:]}->{labs}", otimes="add", oplus="none", alpha=0.25, inputs=("T", "M")))
+        src = "T2"
+    vs += [
+        Vertex("C", "f32", spec=f"{labs}->{row}", otimes="ident", oplus="max", inputs=(src,)),
+        Vertex("E", dtype, spec=f"{labs},{row}->{labs}", otimes="exp_sub", oplus="none", inputs=(src, "C")),
+        Vertex("S", "f32", spec=f"{labs}->{row}", otimes="ident", oplus="sum", inputs=("E",)),
+        Vertex("P", dtype, spec=f"{labs},{row}->{labs}", otimes="div", oplus="none", inputs=("E", "S")),
+    ]
+    outs = ["P"]
+    if stats_consumed:
+        vs.append(Vertex("logS", "f32", spec=f"{row}->{row}", otimes="log", oplus="none", inputs=("S",)))
+        outs += ["logS", "C"]
+    first = labs[0]
+    parts = {"whole": {}, "rows2": {v.name: {first: 2} for v in vs if v.spec}}
+    return Workload("softmax_chain", 77, vs, outs, parts, {})
+
+
+@pytest.mark.parametrize("bound,dtype,with_add,stats", [((6, 40, 2048), "bf16", True, False), ((2, 3, 24, 1024), "bf16", True, True),
+                                                         ((50, 520), "f32", False, True), ((12, 100), "f32", False, False),
+                                                         ((4, 12, 100), "bf16", True, True), ((4, 8192), "bf16", False, False)])
+def test_fused_softmax_matches_oracle_and_the_separate_vertices(bound, dtype, with_add, stats):
+    torch, GraphRunner, to_device, to_host = _gpu()
+    import paper_2410_02682_amd as E
+    w = _softmax_workload(bound, dtype, with_add, stats)
+    inp = make_inputs(w)
+    ref = run_graph(w, inp)
+    for pname in ("whole", "rows2"):
+        print(f"softmax chain {bound} {dtype} add={with_add} stats={stats} {pname}", flush=True)
+        res = {}
+        for fuse in (True, False):
+            r = GraphRunner(w, pname)
+            try:
+                E.tr_set_fusion(r.g, fuse)
+                r.bind({k: to_device(t) for k, t in inp.items()})
+                E.tr_profile_enable(r.g, 32)
+                r.run()
+                torch.cuda.synchronize()
+                kinds = [x["kernel"] for x in E.tr_profile_read(r.g)]
+                assert ("softmax_fused" in kinds) == fuse
+                if fuse:
+                    assert len(kinds) == (2 if stats else 1)       # the fused pass (+ the consumer of the row sums)
+                res[fuse] = {n: to_host(r.output(n)) for n in r.out_names}
+            finally:
+                r.close()
+        for n in w.outputs:
+            rt = rtol_for(w, n)
+            bad, worst = violations(res[True][n].as_f64(), ref[n].as_f64(), rt)
+            assert bad == 0, f"{n} fused: {bad} elements out of tolerance (worst {worst:.2f}x)"
+            # against the separate vertices: the same roundings, only the order of the row sum differs
+            a, b = res[True][n].as_f64(), res[False][n].as_f64()
+            ulp = np.abs(b) * 2.0 ** -7 + 1e-30 if w.vertex(n).dtype == "bf16" else (np.abs(b) + 1.0) * 2.0 ** -20
+            assert np.all(np.abs(a - b) <= ulp), f"{n}: fused and separate results differ by more than one unit in the last place"
