@@ -817,7 +817,14 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
             sp.ts = tuple_space(E, li);                 // E's partitioning vector is the chain's
             sp.ts2 = tuple_space(E, li2);
             sp.rows_per_block = 1;
-            for (int l = 0; l + 1 < r; l++) {
+            // Row labels that the added operand lacks go last, i.e. vary fastest from one wave to the next: rows that
+            // take the same row of the added operand then run next to each other and find it in the cache (otherwise
+            // a mask as large as the caches is fetched again for every batch entry and head).
+            std::vector<int> order;
+            for (int pass = 0; pass < 2; pass++)
+                for (int l = 0; l + 1 < r; l++)
+                    if ((sp.has_add && li.sy[l] == 0) == (pass == 1)) order.push_back(l);
+            for (int l : order) {
                 if (li.ext[l] <= 1) continue;
                 const int k = sp.rows.n++;
                 sp.rows.ext[k] = sp.stats.ext[k] = (int32_t)li.ext[l];

@@ -482,9 +482,15 @@ __device__ __forceinline__ void softmax_row_offsets(const SoftmaxParams &p, int6
 }
 
 // One wave per row, VPL vectors of 8 elements per lane held in registers (rows of up to 512 * VPL elements).
-template <int VPL>
+// MODE fixes the storage dtypes of the chain at compile time (0: sum, exponentials and result all bf16; 1: all
+// fp32; 2: read from the parameters): with run-time dtypes every element pays for both variants of each step.
+template <int VPL, int MODE>
 __global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p)
 {
+    const int dt_t = MODE == 0 ? EG_BF16 : MODE == 1 ? EG_F32 : p.dt_t;
+    const int dt_e = MODE == 0 ? EG_BF16 : MODE == 1 ? EG_F32 : p.dt_e;
+    const int dt_p = MODE == 0 ? EG_BF16 : MODE == 1 ? EG_F32 : p.dt_p;
+    const int dt_src = MODE == 0 ? EG_BF16 : MODE == 1 ? EG_F32 : p.dt_src;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t t = tuple_of_block();
     const uint32_t row = blockIdx.x * (kThreads / 64) + wave;
@@ -497,7 +503,7 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p
     for (int u = 0; u < VPL; u++) {
         const int c = (u * 64 + lane) * 8;
         if (c < p.n) {
-            load8(p.src, p.dt_src, ox + c, v[u]);
+            load8(p.src, dt_src, ox + c, v[u]);
             if (p.has_add) {
                 float y[8];
                 if (p.sy_last == 1) load8(p.add, p.dt_add, oy + c, y);
@@ -505,21 +511,21 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p
 #pragma unroll
                     for (int i = 0; i < 8; i++) y[i] = s; }
 #pragma unroll
-                for (int i = 0; i < 8; i++) v[u][i] = round_as(p.alpha * v[u][i] + y[i], p.dt_t);
+                for (int i = 0; i < 8; i++) v[u][i] = round_as(p.alpha * v[u][i] + y[i], dt_t);
             }
 #pragma unroll
             for (int i = 0; i < 8; i++) m = fmaxf(m, v[u][i]);
         }
     }
     m = wave_reduce<EG_AGG_MAX>(EG_AGG_MAX, m);
-    const bool fast_e = p.dt_e == EG_BF16, fast_p = p.dt_p == EG_BF16;     // as the separate vertices choose
+    const bool fast_e = dt_e == EG_BF16, fast_p = dt_p == EG_BF16;         // as the separate vertices choose
     float sum = 0.f;
 #pragma unroll
     for (int u = 0; u < VPL; u++) {
         if ((u * 64 + lane) * 8 < p.n) {
 #pragma unroll
             for (int i = 0; i < 8; i++) {
-                const float e = round_as(fast_e ? __expf(v[u][i] - m) : expf(v[u][i] - m), p.dt_e);
+                const float e = round_as(fast_e ? __expf(v[u][i] - m) : expf(v[u][i] - m), dt_e);
                 v[u][i] = e;
                 sum += e;
             }
@@ -534,7 +540,7 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p
             float z[8];
 #pragma unroll
             for (int i = 0; i < 8; i++) z[i] = fast_p ? v[u][i] * inv : v[u][i] / sum;
-            store8(p.p, p.dt_p, oz + c, z);
+            store8(p.p, dt_p, oz + c, z);
         }
     }
     if (lane == 0) {
@@ -615,11 +621,18 @@ int launch_softmax_rows(SoftmaxParams &p, void *stream)
     int rc = tuple_grid(p.rows_per_block, kThreads / 64, p.n_tuples, grid);
     if (rc) return rc;
     const int vpl = (p.n + 511) / 512;
-    if (vpl <= 1) hipLaunchKernelGGL(k_softmax_rows<1>, grid, dim3(kThreads), 0, st, p);
-    else if (vpl <= 2) hipLaunchKernelGGL(k_softmax_rows<2>, grid, dim3(kThreads), 0, st, p);
-    else if (vpl <= 4) hipLaunchKernelGGL(k_softmax_rows<4>, grid, dim3(kThreads), 0, st, p);
-    else if (vpl <= 8) hipLaunchKernelGGL(k_softmax_rows<8>, grid, dim3(kThreads), 0, st, p);
-    else hipLaunchKernelGGL(k_softmax_rows<16>, grid, dim3(kThreads), 0, st, p);
+    const bool all_bf16 = p.dt_src == EG_BF16 && p.dt_t == EG_BF16 && p.dt_e == EG_BF16 && p.dt_p == EG_BF16;
+    const bool all_f32 = p.dt_src == EG_F32 && p.dt_t == EG_F32 && p.dt_e == EG_F32 && p.dt_p == EG_F32;
+    const int mode = all_bf16 ? 0 : all_f32 ? 1 : 2;
+#define EG_SM(V) do { if (mode == 0) hipLaunchKernelGGL((k_softmax_rows<V, 0>), grid, dim3(kThreads), 0, st, p); \
+                      else if (mode == 1) hipLaunchKernelGGL((k_softmax_rows<V, 1>), grid, dim3(kThreads), 0, st, p); \
+                      else hipLaunchKernelGGL((k_softmax_rows<V, 2>), grid, dim3(kThreads), 0, st, p); } while (0)
+    if (vpl <= 1) EG_SM(1);
+    else if (vpl <= 2) EG_SM(2);
+    else if (vpl <= 4) EG_SM(4);
+    else if (vpl <= 8) EG_SM(8);
+    else EG_SM(16);
+#undef EG_SM
     return check_launch("k_softmax_rows");
 }
 
