@@ -400,47 +400,71 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
             // in LDS (the row pitch leaves 32 bytes of padding, which keeps the two half-waves on different banks)
             // and writes them out as whole row segments, 16 bytes per lane.  LDS operations of one wave execute
             // in order, so no barrier is needed.
+            // The 16 passes are software-pipelined: the stores of a pass are issued after the LDS writes and reads of
+            // the next one, so a pass's LDS round trip is hidden behind the next pass's LDS traffic (the wave's LDS
+            // operations stay in order, so the single staging buffer is enough).
             constexpr int LPR_F = CW / 4, RPI_F = 64 / LPR_F;     // fp32 out: lanes per row, rows per store instruction
             constexpr int LPR_B = CW / 8, RPI_B = 64 / LPR_B;     // bf16 out
             static_assert(RPI_F <= 8 && RPI_B <= 8, "a store instruction covers at most the 8 staged rows");
+            constexpr int NV4 = CW / 32;                          // 16-byte LDS reads per lane and pass
+            const int lc = out_bf16 ? elane % LPR_B : elane % LPR_F, lr = out_bf16 ? elane / LPR_B : elane / LPR_F;
+            const int c = col0 + lc * (out_bf16 ? 8 : 4);         // first of this lane's 8 or 4 consecutive columns
+            const int64_t zc = cur.bz + zcol[c];
+            const bool cok = c < nrem;
+            f32x4 rd[2][NV4];
+            int64_t zr[2][NV4];
+            auto write_pass = [&](int i, int q) {
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
+                for (int j = 0; j < NT; j++)
 #pragma unroll
-                for (int q = 0; q < 4; q++) {
+                    for (int rr = 0; rr < 4; rr++)
+                        *(float *)(wbuf + (4 * lhalf + rr) * PITCH + (j * 32 + lrow) * 4) = p.alpha * acc[i][j][4 * q + rr];
+            };
+            auto read_pass = [&](int i, int q, f32x4 (&v)[NV4], int64_t (&z)[NV4]) {
+                if (!out_bf16) {
 #pragma unroll
-                    for (int j = 0; j < NT; j++)
+                    for (int h = 0; h < 8 / RPI_F; h++) {
+                        const int row = RPI_F * h + lr;
+                        v[h] = *(const f32x4 *)(wbuf + row * PITCH + lc * 16);
+                        z[h] = zrow[row0 + i * 32 + 8 * q + row];
+                    }
+                } else {
 #pragma unroll
-                        for (int rr = 0; rr < 4; rr++)
-                            *(float *)(wbuf + (4 * lhalf + rr) * PITCH + (j * 32 + lrow) * 4) = p.alpha * acc[i][j][4 * q + rr];
-                    if (!out_bf16) {
-                        const int lc = elane % LPR_F, lr = elane / LPR_F;
-                        const int c = col0 + lc * 4;                          // 4 consecutive columns
-                        const int64_t zc = cur.bz + zcol[c];
-                        const bool cok = c < nrem;
-#pragma unroll
-                        for (int h = 0; h < 8 / RPI_F; h++) {
-                            const int row = RPI_F * h + lr, rr = row0 + i * 32 + 8 * q + row;
-                            const f32x4 v = *(const f32x4 *)(wbuf + row * PITCH + lc * 16);
-                            if (cok && rr < mrem) *(f32x4 *)((float *)zb + zrow[rr] + zc) = v;
-                        }
-                    } else {
-                        const int lc = elane % LPR_B, lr = elane / LPR_B;
-                        const int c = col0 + lc * 8;                          // 8 consecutive columns
-                        const int64_t zc = cur.bz + zcol[c];
-                        const bool cok = c < nrem;
-#pragma unroll
-                        for (int h = 0; h < 8 / RPI_B; h++) {
-                            const int row = RPI_B * h + lr, rr = row0 + i * 32 + 8 * q + row;
-                            const f32x4 v0 = *(const f32x4 *)(wbuf + row * PITCH + lc * 32);
-                            const f32x4 v1 = *(const f32x4 *)(wbuf + row * PITCH + lc * 32 + 16);
-                            uint4 o;
-                            o.x = pack_bf16x2(v0.x, v0.y); o.y = pack_bf16x2(v0.z, v0.w);
-                            o.z = pack_bf16x2(v1.x, v1.y); o.w = pack_bf16x2(v1.z, v1.w);
-                            if (cok && rr < mrem) *(uint4 *)((uint16_t *)zb + zrow[rr] + zc) = o;
-                        }
+                    for (int h = 0; h < 8 / RPI_B; h++) {
+                        const int row = RPI_B * h + lr;
+                        v[2 * h] = *(const f32x4 *)(wbuf + row * PITCH + lc * 32);
+                        v[2 * h + 1] = *(const f32x4 *)(wbuf + row * PITCH + lc * 32 + 16);
+                        z[2 * h] = zrow[row0 + i * 32 + 8 * q + row];
                     }
                 }
+            };
+            auto store_pass = [&](int i, int q, const f32x4 (&v)[NV4], const int64_t (&z)[NV4]) {
+                if (!out_bf16) {
+#pragma unroll
+                    for (int h = 0; h < 8 / RPI_F; h++) {
+                        const int rr = row0 + i * 32 + 8 * q + RPI_F * h + lr;
+                        if (cok && rr < mrem) *(f32x4 *)((float *)zb + z[h] + zc) = v[h];
+                    }
+                } else {
+#pragma unroll
+                    for (int h = 0; h < 8 / RPI_B; h++) {
+                        const int rr = row0 + i * 32 + 8 * q + RPI_B * h + lr;
+                        uint4 o;
+                        o.x = pack_bf16x2(v[2 * h].x, v[2 * h].y); o.y = pack_bf16x2(v[2 * h].z, v[2 * h].w);
+                        o.z = pack_bf16x2(v[2 * h + 1].x, v[2 * h + 1].y); o.w = pack_bf16x2(v[2 * h + 1].z, v[2 * h + 1].w);
+                        if (cok && rr < mrem) *(uint4 *)((uint16_t *)zb + z[2 * h] + zc) = o;
+                    }
+                }
+            };
+#pragma unroll
+            for (int ps = 0; ps < 16; ps++) {
+                write_pass(ps >> 2, ps & 3);
+                read_pass(ps >> 2, ps & 3, rd[ps & 1], zr[ps & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (ps > 0) store_pass((ps - 1) >> 2, (ps - 1) & 3, rd[(ps - 1) & 1], zr[(ps - 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
             }
+            store_pass(3, 3, rd[1], zr[1]);
         } else {
             int64_t zn[NT];
             bool nok[NT];
