@@ -388,3 +388,37 @@ def test_fused_softmax_matches_oracle_and_the_separate_vertices(bound, dtype, wi
             a, b = res[True][n].as_f64(), res[False][n].as_f64()
             ulp = np.abs(b) * 2.0 ** -7 + 1e-30 if w.vertex(n).dtype == "bf16" else (np.abs(b) + 1.0) * 2.0 ** -20
             assert np.all(np.abs(a - b) <= ulp), f"{n}: fused and separate results differ by more than one unit in the last place"
+
+
+# ------------------------------------------------------------------ the whole step inside a HIP graph
+@pytest.mark.parametrize("n,pname", [(3, "mixed"), (4, "heads8"), (5, "k16")])
+def test_execute_can_be_captured_into_a_hip_graph_and_replayed(n, pname):
+    # tr_execute only enqueues kernels on the caller's stream (no allocation, no synchronisation, no memset), so a
+    # caller may capture it; every replay, with the program's own eager work in between, must give the eager result
+    torch, GraphRunner, to_device, to_host = _gpu()
+    w, inp, ref = _reference(n)
+    print(f"config {n} {pname} captured into a graph", flush=True)
+    r = GraphRunner(w, pname)
+    try:
+        r.bind({k: to_device(t) for k, t in inp.items()})
+        r.run()
+        torch.cuda.synchronize()
+        eager = {name: r.output(name).clone() for name in r.out_names}
+        side = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(g, stream=side):
+                r.run(torch.cuda.current_stream())
+        torch.cuda.synchronize()
+        for rep in range(3):
+            for name in r.out_names:
+                r.output(name).zero_()
+            r.workspace.zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for name in r.out_names:
+                assert torch.equal(r.output(name), eager[name]), f"replay {rep}: {name} differs from the eager result"
+        del g
+    finally:
+        r.close()
