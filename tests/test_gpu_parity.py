@@ -422,3 +422,39 @@ def test_execute_can_be_captured_into_a_hip_graph_and_replayed(n, pname):
         del g
     finally:
         r.close()
+
+
+def test_fused_softmax_with_transposed_input_and_output_relations():
+    # the source arrives as a transposed view and the result goes into one: the pass cannot use 16-byte accesses
+    # along its rows and takes the workgroup-per-row variant
+    torch, GraphRunner, to_device, to_host = _gpu()
+    import paper_2410_02682_amd as E
+    s_, t_ = 48, 200
+    xt = HostTensor.from_f32(normal(31, 0, s_ * t_, 2.0).reshape(t_, s_), "f32")         # stored as [t, s]
+    g = E.einsum_graph_create()
+    x = E.einsum_graph_add_input(g, [s_, t_], "f32")
+    c = E.einsum_graph_add_einsum(g, "st->s", "ident", "max", 1.0, [x], "f32")
+    e = E.einsum_graph_add_einsum(g, "st,s->st", "exp_sub", "none", 1.0, [x, c], "f32")
+    sm = E.einsum_graph_add_einsum(g, "st->s", "ident", "sum", 1.0, [e], "f32")
+    p = E.einsum_graph_add_einsum(g, "st,s->st", "div", "none", 1.0, [e, sm], "f32")
+    for v in (c, e, sm, p):
+        E.einsum_graph_set_partition(g, v, [2, 1])
+    E.einsum_graph_mark_output(g, p)
+    dx = to_device(xt)
+    out = torch.zeros((t_, s_), dtype=torch.float32, device="cuda")                         # P stored as [t, s] too
+    rx = E.tensor_partition(dx.data_ptr(), "f32", [s_, t_], [2, 1], strides=[1, s_])
+    rp = E.tensor_partition(out.data_ptr(), "f32", [s_, t_], [2, 1], strides=[1, s_])
+    assert E.tr_workspace_bytes(g) == 0                                                     # fused: no intermediate exists
+    E.tr_profile_enable(g, 8)
+    E.tr_execute(g, [rx], [rp], 0, 0, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert [k["kernel"] for k in E.tr_profile_read(g)] == ["softmax_fused"]
+    x64 = xt.data.astype(np.float64).T                                                      # [s, t]
+    ex = np.exp(x64 - x64.max(axis=1, keepdims=True))
+    ref = ex / ex.sum(axis=1, keepdims=True)
+    got = to_host(out).as_f64().T
+    assert violations(got, ref, RTOL_F32)[0] == 0
+    assert np.allclose(got.sum(axis=1), 1.0, atol=1e-5)
+    for r in (rx, rp):
+        E.tensor_relation_destroy(r)
+    E.einsum_graph_destroy(g)
