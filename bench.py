@@ -118,6 +118,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5, 6, 7], help="workload (2 = the matrix chain the metric is quoted on)")
     ap.add_argument("--partitioning", default=None)
+    ap.add_argument("--fuse-aggregation", action="store_true",
+                    help="alternative method, reported separately: contractions reduce over partitioned contracted labels inside the kernel (no partial slabs, no aggregation launch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true")
     args = ap.parse_args()
@@ -135,6 +137,8 @@ def main():
     pname = args.partitioning or DEFAULT_PART[args.config]
     dev = {v.name: prng_torch.make_tensor(v.recipe, v.bound, v.dtype, w.seed, w.tensor_id(v.name)) for v in w.vertices if v.is_input}
     r = GraphRunner(w, pname)
+    if args.fuse_aggregation:
+        E.tr_set_fused_aggregation(r.g, True)
     r.bind(dev)
     stream = torch.cuda.current_stream()
     for _ in range(args.warmup):
@@ -149,7 +153,7 @@ def main():
         pl = r.plan(v.name)
         nz = prod(pl["bound_z"])
         in_bytes = sum(prod(w.vertex(i).bound if w.vertex(i).is_input else r.plan(i)["bound_z"]) * esz[w.vertex(i).dtype] for i in v.inputs)
-        partial = pl["n_agg"] > 1
+        partial = pl["n_agg"] > 1 and not (args.fuse_aggregation and pl["kernel"] in ("contract_mfma", "contract_alu"))
         join_out = pl["n_agg"] * nz * 4 if partial else nz * esz[v.dtype]
         acct[r.vid[v.name]] = {
             "name": v.name, "kind": pl["kernel"],
@@ -213,7 +217,8 @@ def main():
            "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32" if args.config == 1 else "bf16", "data": "synthetic",
-           "config": {"workload": f"{w.name} dims {json.dumps(w.dims)}, partitioning '{pname}': {json.dumps(r.part)}"},
+           "config": {"workload": f"{w.name} dims {json.dumps(w.dims)}, partitioning '{pname}': {json.dumps(r.part)}"
+                                  + (" [alternative method: aggregation inside the contraction kernels]" if args.fuse_aggregation else "")},
            "roofline": roofline, "kernels": kernels}
     r.close()
     if not args.no_ceilings:

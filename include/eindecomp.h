@@ -211,6 +211,13 @@ int tr_aggregate(eg_agg oplus, const void *partials, int64_t n_agg, int64_t slab
  * still written.  Enabled by default; enable = 0 makes every vertex run on its own.  Changes the workspace size. */
 int tr_set_fusion(eg_graph *g, int enable);
 
+/* The alternative to the two-stage path, for comparison (off by default: the method of Section 4.3 is join, then
+ * aggregation).  With enable != 0 a contraction whose contracted labels are partitioned runs the join tuples that
+ * share an output block as one kernel call that reduces over all their blocks in registers: no partial blocks are
+ * written, no aggregation launch follows, and the floating-point summation order is that of the unpartitioned
+ * contraction.  Other vertices are not affected.  Changes the workspace size. */
+int tr_set_fused_aggregation(eg_graph *g, int enable);
+
 /* ---- Timing of the launches inside tr_execute (for roofline reports) ----------------------------------- */
 
 /* max_launches > 0: from now on tr_execute brackets every kernel launch with a pair of HIP events recorded

@@ -134,6 +134,10 @@ def tr_set_fusion(g, enable: bool) -> None:
     _check(_lib.load().tr_set_fusion(g, 1 if enable else 0))
 
 
+def tr_set_fused_aggregation(g, enable: bool) -> None:
+    _check(_lib.load().tr_set_fused_aggregation(g, 1 if enable else 0))
+
+
 # ---- EinDecomp: cost model and choice of the partitioning vectors (host only) -----------------------------
 def eg_cost_join(g, vertex: int, d: Sequence[int]) -> int:
     c = ctypes.c_int64()

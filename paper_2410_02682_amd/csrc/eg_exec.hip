@@ -525,6 +525,32 @@ static std::vector<FuseGroup> find_fusions(const eg_graph *g)
     return out;
 }
 
+// The alternative to the two-stage path for contractions: the join tuples that share an output key run as one
+// kernel call whose reduction covers all their blocks, so no partial blocks are written and nothing is left to
+// aggregate.  On one GPU that is the same as executing the vertex with its contracted labels unpartitioned.
+static bool merges_aggregation(const eg_graph *g, int i)
+{
+    const Vertex &v = g->v[i];
+    if (!g->agg_in_kernel || v.is_input || v.n_in != 2 || v.plan.n_agg <= 1) return false;
+    const int kind = eg_route_vertex(g, i);
+    return kind == EG_KERNEL_CONTRACT_MFMA || kind == EG_KERNEL_CONTRACT_ALU;
+}
+
+// the vertex as the merged kernel call sees it: contracted labels in one piece, one tuple per output block
+static Vertex merged_vertex(const Vertex &v)
+{
+    Vertex m;
+    m.dtype = v.dtype; m.bound = v.bound; m.spec = v.spec; m.lx = v.lx; m.ly = v.ly; m.lz = v.lz;
+    m.labels = v.labels; m.lbound = v.lbound; m.d = v.d; m.agg = v.agg;
+    m.otimes = v.otimes; m.oplus = v.oplus; m.alpha = v.alpha; m.in[0] = v.in[0]; m.in[1] = v.in[1]; m.n_in = v.n_in;
+    for (int a : v.agg) m.d[a] = 1;
+    m.plan.n_tuples = v.plan.n_tuples / v.plan.n_agg;
+    m.plan.n_agg = 1;
+    m.plan.n_groups = m.plan.n_tuples;
+    m.plan.valid = true;
+    return m;
+}
+
 static Layout make_layout(const eg_graph *g)
 {
     const int nv = (int)g->v.size();
@@ -572,8 +598,9 @@ static Layout make_layout(const eg_graph *g)
             Routed r;
             if (dry_route(g, i, r) == EG_OK && r.kind == EG_KERNEL_REDUCE_ROW) L.split[i] = r.rp.split;
         }
-        if (v.plan.n_agg * L.split[i] > 1) {
-            L.partial_off[i] = arena.alloc(v.plan.n_agg * L.split[i] * slab_stride_of(numel(v.bound), v.plan.n_agg * L.split[i]) * 4);
+        const int64_t n_agg = merges_aggregation(g, i) ? 1 : v.plan.n_agg;
+        if (n_agg * L.split[i] > 1) {
+            L.partial_off[i] = arena.alloc(n_agg * L.split[i] * slab_stride_of(numel(v.bound), n_agg * L.split[i]) * 4);
             arena.release(L.partial_off[i]);          // live only while this vertex runs
         }
         for (int k = 0; k < v.n_in; k++) {
@@ -681,6 +708,13 @@ int tr_set_fusion(eg_graph *g, int enable)
 {
     if (!g) return fail(EG_ERR_NULL, "graph is NULL");
     g->fuse = enable != 0;
+    return EG_OK;
+}
+
+int tr_set_fused_aggregation(eg_graph *g, int enable)
+{
+    if (!g) return fail(EG_ERR_NULL, "graph is NULL");
+    g->agg_in_kernel = enable != 0;
     return EG_OK;
 }
 
@@ -844,12 +878,15 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
         }
         Step s;
         s.vertex = i;
+        const bool merged = merges_aggregation(g, i);
+        const Vertex vm = merged ? merged_vertex(v) : Vertex();
+        const Vertex &vr = merged ? vm : v;            // what is routed: the vertex, or its merged form
         Operand X = operand_of(v.in[0]), Y;
         if (v.n_in > 1) Y = operand_of(v.in[1]);
         Operand Z = operand_of(i);
         s.dst = (void *)Z.ptr;
         s.dst_stride = Z.stride;
-        s.slabs = v.plan.n_agg * L.split[i];
+        s.slabs = vr.plan.n_agg * L.split[i];
         s.agg = s.slabs > 1;
         OutSpec out;
         std::vector<int64_t> zstride;
@@ -866,8 +903,10 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
             out.dtype = v.dtype;
             zstride = Z.stride;
         }
-        int rc = route(v, X, v.n_in > 1 ? &Y : nullptr, zstride, out, s.r, L.split[i]);
+        int rc = route(vr, X, v.n_in > 1 ? &Y : nullptr, zstride, out, s.r, L.split[i]);
         if (rc) return rc;
+        if (merged && s.r.kind != EG_KERNEL_CONTRACT_MFMA && s.r.kind != EG_KERNEL_CONTRACT_ALU)
+            return fail(EG_ERR_LIMIT, "vertex %d: the bound relations' strides leave no contraction kernel for the merged aggregation; turn tr_set_fused_aggregation off", i);
         if (L.split[i] > 1 && s.r.kind != EG_KERNEL_REDUCE_ROW) {
             // the bound relations' strides sent this vertex to another kernel than the layout assumed:
             // run it unsplit, writing the tensor directly when nothing else needs aggregating

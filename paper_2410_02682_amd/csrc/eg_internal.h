@@ -202,6 +202,7 @@ struct eg_graph {
     std::vector<int> outputs;     // marked outputs, marking order
     // executor state
     bool fuse = true;                               // fuse softmax chains where the partitioning allows (tr_set_fusion)
+    bool agg_in_kernel = false;                     // contractions sum over partitioned contracted labels inside the kernel (tr_set_fused_aggregation)
     bool profile = false;
     std::vector<void *> ev_start, ev_stop;          // hipEvent_t pool
     struct Launch { int vertex, stage, kernel; };

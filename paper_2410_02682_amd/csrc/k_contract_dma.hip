@@ -13,10 +13,12 @@
 //   * the loads are buffer loads with a 2 GiB descriptor: a lane whose chunk lies beyond K in the last,
 //     partial stage is given an offset outside the descriptor, fetches nothing and deposits zeros.
 // Requirements (checked on the host): K is one label of any extent, or several whose innermost extent is a
-// multiple of 64 (a stage never straddles two K labels); in-block offsets fit 31 bits.  Anything else goes
+// multiple of 64 (a stage never straddles two K labels); byte offsets within a tile (256 rows, 64 k-rows) fit 31
+// bits and rows do not lie before their tile's first row.  Anything else goes
 // to the register-staged kernel.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdlib>
 
 #include "eg_device.h"
@@ -51,8 +53,9 @@ __device__ __forceinline__ void decode_group2(const DimList &g, int64_t idx, int
     }
 }
 
-// Per-lane source offsets (bytes, relative to the operand's block base) of the 32/NW chunks this lane
-// fetches per stage (NW waves per workgroup), without the k advance.
+// Per-lane source offsets (bytes, relative to the first row of the operand's tile: `origin` is that row's
+// element offset in the block) of the 32/NW chunks this lane fetches per stage (NW waves per workgroup),
+// without the k advance.
 //   KC: instruction i of wave w deposits rows (NW i+w)*8 .. +7, lane -> row +lane/8, physical chunk lane%8,
 //       logical chunk (lane%8) ^ ((row>>1)&7).
 //   MC: instruction i of wave w deposits k-rows (NW i+w)*2 .. +1, lane -> k-row +lane/32, physical chunk lane%32,
@@ -63,7 +66,7 @@ struct Src {
     uint32_t boff[LD];        // byte offset of the chunk instruction i fetches, relative to the stage's first k
     int kl;                   // k (within the stage) of chunk 0 of this lane; chunk i sits at kl (KC) or kl + 2 NW i (MC)
 
-    __device__ __forceinline__ void init(const DimList &grp, int64_t first, int64_t extent, int64_t k_inner_stride, int wave, int lane)
+    __device__ __forceinline__ void init(const DimList &grp, int64_t first, int64_t extent, int64_t origin, int64_t k_inner_stride, int wave, int lane)
     {
         if (KC) {
             // LDS row of this lane's chunk is (NW i+wave)*8 + lane/8; its swizzle key (row>>1)&7 does not depend on i
@@ -75,7 +78,7 @@ struct Src {
                 r = r < extent ? r : extent - 1;
                 int64_t o0, o1;
                 decode_group2(grp, r, o0, o1);
-                boff[i] = (uint32_t)((o0 + lc * 8) * 2);
+                boff[i] = (uint32_t)((o0 - origin + lc * 8) * 2);
             }
         } else {
             const int kr4 = (2 * wave + (lane >> 5)) & 3;
@@ -87,7 +90,7 @@ struct Src {
             kl = 2 * wave + (lane >> 5);
 #pragma unroll
             for (int i = 0; i < LD; i++)
-                boff[i] = (uint32_t)((o0 + (2 * NW * i + 2 * wave + (lane >> 5)) * k_inner_stride) * 2);
+                boff[i] = (uint32_t)((o0 - origin + (2 * NW * i + 2 * wave + (lane >> 5)) * k_inner_stride) * 2);
         }
     }
     // offset handed to load i of a stage that has `krem` valid k left: beyond the descriptor when the chunk's k is past the end
@@ -159,7 +162,8 @@ __device__ __forceinline__ void mfma_rows(const bf16x8 (&a)[4], const bf16x8 (&b
 // What is uniform over a workgroup about one output tile.
 struct TileInfo {
     int64_t m0, n0;          // first row / column of the tile inside the block
-    const char *xb, *yb;     // X and Y at the tuple's blocks and the batch entry
+    const char *xb, *yb;     // X and Y at the tuple's blocks, the batch entry and the tile's first row / column
+    int64_t ox0, oy0;        // element offsets of that first row / column inside the block (what lane offsets are relative to)
     int64_t bz, agg;         // Z element offset of the tuple's block and batch entry; aggIdx of the tuple
 };
 
@@ -229,8 +233,14 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
         }
         t.m0 = (int64_t)tile_m * BM;
         t.n0 = (int64_t)tile_n * BN;
-        t.xb = uniform_ptr((const char *)p.x + bx * 2);
-        t.yb = uniform_ptr((const char *)p.y + by * 2);
+        // lane offsets are 32 bits and count from the tile's first row (an operand contiguous along M or N reads whole
+        // 8-element chunks, so near the block's edge its first chunk may start up to 7 elements before the tile)
+        int64_t unused;
+        const int64_t fm = A_KC || t.m0 + 8 <= p.M ? t.m0 : p.M - 8, fn = B_KC || t.n0 + 8 <= p.N ? t.n0 : p.N - 8;
+        decode_group2(p.m, fm, t.ox0, unused);
+        decode_group2(p.n, fn, t.oy0, unused);
+        t.xb = uniform_ptr((const char *)p.x + (bx + t.ox0) * 2);
+        t.yb = uniform_ptr((const char *)p.y + (by + t.oy0) * 2);
         t.bz = bz;
         t.agg = agg;
     };
@@ -289,8 +299,8 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
     int kr2;
     // per-lane addressing of tile t, then its first two stages on their way (both LDS stages must be free)
     auto start_tile = [&](const TileInfo &t) {
-        sa.init(p.m, t.m0, p.M, p.k.s0[kin], wave, lane);
-        sb.init(p.n, t.n0, p.N, p.k.s1[kin], wave, lane);
+        sa.init(p.m, t.m0, p.M, t.ox0, p.k.s0[kin], wave, lane);
+        sb.init(p.n, t.n0, p.N, t.oy0, p.k.s1[kin], wave, lane);
         xb = uniform_ptr(t.xb);
         yb = uniform_ptr(t.yb);
         stage_ptrs(0, ga2, gb2, kr2);
@@ -532,7 +542,24 @@ bool contract_dma_eligible(const ContractParams &p)
     if (p.m.n < 1 || p.n.n < 1 || p.k.n < 1) return false;
     if (p.k.n > 1 && p.k.ext[p.k.n - 1] % dma::BK) return false;           // a stage never straddles two K labels
     if ((p.a_kcontig || p.b_kcontig) && p.K % 8) return false;             // 16-byte chunks along K are whole or absent
-    if (p.span_x >= (1ll << 30) - 64 || p.span_y >= (1ll << 30) - 64) return false;  // lane byte offsets + 16 stay below 2^31
+    // Lane offsets count from the tile's first row and must stay below 2^31 bytes: rows of a tile must not lie before
+    // its first row (strides nested, outermost first), and 256 rows plus the 64 k-rows of a stage must span less.
+    auto tile_span = [](const DimList &g) -> int64_t {            // largest offset of a row within 255 rows of another
+        int64_t inner = 1, span = 0;
+        for (int i = g.n - 1; i >= 0; i--) {
+            if (g.s0[i] < 0) return -1;
+            if (i + 1 < g.n && g.s0[i] < g.s0[i + 1] * g.ext[i + 1]) return -1;
+            const int64_t steps = std::min<int64_t>(g.ext[i] - 1, 255 / inner + 1);
+            span += steps * g.s0[i];
+            inner *= g.ext[i];
+        }
+        return span;
+    };
+    const int kin = p.k.n - 1;
+    const int64_t sx = tile_span(p.m), sy = tile_span(p.n);
+    if (sx < 0 || sy < 0) return false;
+    if (sx + (p.a_kcontig ? 64 : 64 * std::max<int64_t>(p.k.s0[kin], 1)) >= (1ll << 30) - 64) return false;
+    if (sy + (p.b_kcontig ? 64 : 64 * std::max<int64_t>(p.k.s1[kin], 1)) >= (1ll << 30) - 64) return false;
     if (p.a_kcontig ? p.k.s0[p.k.n - 1] != 1 : (p.m.s0[p.m.n - 1] != 1 || p.m.ext[p.m.n - 1] % 8)) return false;
     if (p.b_kcontig ? p.k.s1[p.k.n - 1] != 1 : (p.n.s0[p.n.n - 1] != 1 || p.n.ext[p.n.n - 1] % 8)) return false;
     if (!p.a_kcontig && p.M < 8) return false;

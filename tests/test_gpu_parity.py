@@ -458,3 +458,33 @@ def test_fused_softmax_with_transposed_input_and_output_relations():
     for r in (rx, rp):
         E.tensor_relation_destroy(r)
     E.einsum_graph_destroy(g)
+
+
+# ------------------------------------------------------------------ aggregation merged into the contraction kernel
+@pytest.mark.parametrize("n,pname", [(1, "d222"), (2, "mix"), (2, "splitk8"), (3, "batch8"), (4, "heads8"), (5, "k16"), (6, "d222"), (7, "d222"), (7, "j8")])
+def test_contractions_with_the_aggregation_merged_into_the_kernel_match_oracle(n, pname):
+    torch, GraphRunner, to_device, to_host = _gpu()
+    import paper_2410_02682_amd as E
+    w, inp, ref = _reference(n)
+    print(f"config {n} {pname}: aggregation inside the contraction kernels", flush=True)
+    r = GraphRunner(w, pname)
+    try:
+        two_stage = E.tr_workspace_bytes(r.g)
+        E.tr_set_fused_aggregation(r.g, True)
+        merged_ws = E.tr_workspace_bytes(r.g)                   # the partial slabs of the contractions are gone
+        assert merged_ws < two_stage if n in (2, 5) else merged_ws <= two_stage
+        r.bind({k: to_device(t) for k, t in inp.items()})
+        E.tr_profile_enable(r.g, 64)
+        r.run()
+        torch.cuda.synchronize()
+        rec = E.tr_profile_read(r.g)
+        names = {i: name for name, i in r.vid.items()}
+        for x in rec:
+            if x["stage"] == "aggregate":                        # only non-contraction vertices still aggregate
+                assert r.plan(names[x["vertex"]])["kernel"] not in ("contract_mfma", "contract_alu")
+        got = {name: to_host(r.output(name)) for name in r.out_names}
+    finally:
+        r.close()
+    for name in w.outputs:
+        bad, worst = violations(got[name].as_f64(), ref[name].as_f64(), rtol_for(w, name))
+        assert bad == 0, f"config {n} {pname} output {name}: {bad} elements out of tolerance (worst {worst:.2f}x)"
