@@ -293,6 +293,7 @@ def test_strided_input_relation_and_small_workspace_is_rejected():
     z = E.einsum_graph_add_einsum(g, "ij,jk->ik", "mul", "sum", 1.0, [a, b], "f32")
     E.einsum_graph_set_partition(g, z, [2, 2, 1])
     E.einsum_graph_mark_output(g, z)
+    E.tr_set_fused_aggregation(g, False)                     # the two-stage path: partial slabs in the workspace
     dx, dy = to_device(xt), to_device(y)
     out = torch.empty((64, 40), dtype=torch.float32, device="cuda")
     ra = E.tensor_partition(dx.data_ptr(), "f32", [64, 96], [2, 2], strides=[1, 64])   # a transposed view
@@ -440,6 +441,7 @@ def test_fused_softmax_with_transposed_input_and_output_relations():
     for v in (c, e, sm, p):
         E.einsum_graph_set_partition(g, v, [2, 1])
     E.einsum_graph_mark_output(g, p)
+    E.tr_set_fusion(g, True)
     dx = to_device(xt)
     out = torch.zeros((t_, s_), dtype=torch.float32, device="cuda")                         # P stored as [t, s] too
     rx = E.tensor_partition(dx.data_ptr(), "f32", [s_, t_], [2, 1], strides=[1, s_])
