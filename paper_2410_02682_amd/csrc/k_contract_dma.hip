@@ -252,14 +252,32 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
     Src<B_KC, NW> sb;
     const char *xb, *yb;                              // bases the direct loads currently work from
 
-    // uniform source pointers of the stage that starts at k0, and how many k it still has (64 or more: a full stage)
-    auto stage_ptrs = [&](int64_t k0, const char *&ga, const char *&gb, int &krem) {
-        int64_t ka, kb;
-        decode_group2(p.k, k0, ka, kb);                // offset of the run's first k in X and in Y
-        ga = xb + ka * 2;
-        gb = yb + kb * 2;
-        const int64_t left = p.K - k0;
-        krem = left < BK ? (int)left : BK;
+    // Uniform source pointers of consecutive stages, and how many k each still has (64: a full stage; 0: past the end,
+    // every lane of its direct loads then deposits zeros without fetching).  Inside a run of the innermost K label
+    // a stage lies one fixed step after the one before; only where a run ends (several fused K labels) are the
+    // offsets decoded afresh, so the main loop's scalar work per stage is two additions.
+    const int64_t dka = (int64_t)BK * p.k.s0[kin] * 2, dkb = (int64_t)BK * p.k.s1[kin] * 2;
+    const int64_t run = p.k.n == 1 ? p.K : p.k.ext[kin];
+    const char *ga_n, *gb_n;
+    int64_t k_n, run_left;
+    auto first_stage = [&]() { k_n = 0; ga_n = xb; gb_n = yb; run_left = run; };
+    auto next_stage = [&](const char *&ga, const char *&gb, int &krem) {
+        ga = ga_n;
+        gb = gb_n;
+        const int64_t left = p.K - k_n;
+        krem = left < BK ? (left > 0 ? (int)left : 0) : BK;
+        k_n += BK;
+        run_left -= BK;
+        if (run_left > 0 || p.k.n == 1 || k_n >= p.K) {
+            ga_n += dka;
+            gb_n += dkb;
+        } else {
+            int64_t ka, kb;
+            decode_group2(p.k, k_n, ka, kb);           // offset of the next run's first k in X and in Y
+            ga_n = xb + ka * 2;
+            gb_n = yb + kb * 2;
+            run_left = run;
+        }
     };
     // direct load i (0..LD-1: X tile, LD..2LD-1: Y tile) of a stage into the LDS stage at `dst`: a 2 GiB buffer descriptor
     // on the uniform stage base + a 32-bit lane offset (in-block offsets are below 2^31; 2^31 itself means "no fetch, zeros")
@@ -303,12 +321,11 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
         sb.init(p.n, t.n0, p.N, t.oy0, p.k.s1[kin], wave, lane);
         xb = uniform_ptr(t.xb);
         yb = uniform_ptr(t.yb);
-        stage_ptrs(0, ga2, gb2, kr2);
+        first_stage();
+        next_stage(ga2, gb2, kr2);
         issue(ga2, gb2, kr2, lds0);
-        if (nk > 1) {
-            stage_ptrs(BK, ga2, gb2, kr2);
-            issue(ga2, gb2, kr2, lds1);
-        }
+        next_stage(ga2, gb2, kr2);
+        if (nk > 1) issue(ga2, gb2, kr2, lds1);
     };
 
     // Software pipeline.  Fragment registers alternate between two sets (f0 = a0/b0, f1 = a1/b1).  Each k-step
@@ -323,11 +340,11 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
     mfma_rows<0, 1, NT>(FA, FB, acc); EG_PIN();                                                   \
     load_frags<A_KC, B_KC, NT>(BUF, BUF + TILE_BYTES, KS_NEXT, NA, NB, row0, col0, lane); EG_PIN(); \
     mfma_rows<1, 4, NT>(FA, FB, acc); EG_PIN();
-#define EG_STAGE_NEXT(C, O, HAS_NEXT2, K_NEXT2) /* one stage; its successor is already in flight into O */ \
+#define EG_STAGE_NEXT(C, O, HAS_NEXT2) /* one stage; its successor is already in flight into O */     \
     do {                                                                                          \
         mfma_rows<0, 1, NT>(a0, b0, acc); EG_PIN();                                               \
         const bool has2 = (HAS_NEXT2);                                                            \
-        stage_ptrs(has2 ? (K_NEXT2) : 0, ga2, gb2, kr2);     /* scalar work rides under the MFMAs */ \
+        next_stage(ga2, gb2, kr2);          /* scalar work rides under the MFMAs */               \
         load_frags<A_KC, B_KC, NT>(C, C + TILE_BYTES, 1, a1, b1, row0, col0, lane); EG_PIN();     \
         mfma_rows<1, 4, NT>(a0, b0, acc); EG_PIN();                                               \
         EG_KSTEP(a1, b1, a0, b0, C, 2)                                                            \
@@ -380,15 +397,15 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
         // barrier and a set of unused fragment reads): an MFMA under a branch inside the loop would make the
         // compiler shuffle the accumulator registers.  The stage count's parity is a template parameter.
         if (ODD) {
-            EG_STAGE_NEXT(lds0, lds1, 2 < nk, 2 * BK);
+            EG_STAGE_NEXT(lds0, lds1, 2 < nk);
             for (int64_t st = 1; st < nk; st += 2) {
-                EG_STAGE_NEXT(lds1, lds0, st + 2 < nk, (st + 2) * BK);
-                EG_STAGE_NEXT(lds0, lds1, st + 3 < nk, (st + 3) * BK);
+                EG_STAGE_NEXT(lds1, lds0, st + 2 < nk);
+                EG_STAGE_NEXT(lds0, lds1, st + 3 < nk);
             }
         } else {
             for (int64_t st = 0; st < nk; st += 2) {
-                EG_STAGE_NEXT(lds0, lds1, st + 2 < nk, (st + 2) * BK);
-                EG_STAGE_NEXT(lds1, lds0, st + 3 < nk, (st + 3) * BK);
+                EG_STAGE_NEXT(lds0, lds1, st + 2 < nk);
+                EG_STAGE_NEXT(lds1, lds0, st + 3 < nk);
             }
         }
         __syncthreads();                              // every wave has left both stages

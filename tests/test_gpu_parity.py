@@ -96,6 +96,9 @@ LAYOUTS = [
     ("ji,jk->ik", (100, 200), (100, 136)),       # K tail that is no multiple of 8 (both operands strided along K)
     ("ij,kj->ik", (200, 24), (136, 24)),         # K shorter than one stage
     ("ij,jk->ik", (264, 1384), (1384, 264)),     # many stages, odd count, tail of 40
+    ("bshd,ahd->bsa", (2, 72, 3, 64), (88, 3, 64)),      # two contracted labels, every stage starts a new run of the inner one
+    ("bshd,ahd->bsa", (2, 72, 3, 128), (88, 3, 128)),    # ... and runs of two stages
+    ("bshd,ahd->bsa", (2, 72, 2, 192), (88, 2, 192)),    # ... runs of three: the stage pointers wrap at odd and even stages
 ]
 
 
