@@ -20,7 +20,10 @@ __device__ __forceinline__ char *out_base(const OutSpec &o, int64_t agg)
 }
 
 // ------------------------------------------------------------------------------------------------
-// generic EinSum: one output element per lane, sequential fp32 loop over the aggregated labels
+// generic EinSum: one output element per lane, sequential fp32 loop over the aggregated labels.
+// A sum is accumulated with a compensation term (Kahan): one lane may add up tens of thousands of
+// same-signed terms, and plain sequential fp32 addition would then lose more than the 1e-5 the
+// fp32 results are held to; the compensated sum's error does not grow with the number of terms.
 // ------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void k_generic(const GenericParams p)
 {
@@ -43,6 +46,7 @@ __global__ __launch_bounds__(kThreads) void k_generic(const GenericParams p)
         const int64_t lsx = p.rdims.sx[last], lsy = p.rdims.sy[last];
         const int32_t ln = p.rdims.ext[last];
         const int64_t outer = p.red_elems / ln;
+        float comp = 0.f;
         for (int64_t it = 0; it < outer; it++) {
             int64_t bx = ox, by = oy;
             for (int i = 0; i < last; i++) {
@@ -52,7 +56,14 @@ __global__ __launch_bounds__(kThreads) void k_generic(const GenericParams p)
             for (int32_t r = 0; r < ln; r++) {
                 float x = load_elem(p.x, p.dtx, bx + r * lsx);
                 float y = p.binary ? load_elem(p.y, p.dty, by + r * lsy) : 0.f;
-                acc = oplus_eval(p.oplus, acc, otimes_eval(p.otimes, x, y, p.alpha));
+                const float v = otimes_eval(p.otimes, x, y, p.alpha);
+                if (p.oplus == EG_AGG_SUM) {
+                    const float u = v - comp, s = acc + u;
+                    comp = (s - acc) - u;
+                    acc = s;
+                } else {
+                    acc = oplus_eval(p.oplus, acc, v);
+                }
             }
             for (int i = last - 1; i >= 0; i--) {
                 if (++idx[i] < p.rdims.ext[i]) break;
