@@ -33,9 +33,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 namespace dma {
 
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int TILE_BYTES = 256 * 64 * 2;          // one operand tile of one stage: 32 KiB
-constexpr int STAGE_BYTES = 2 * TILE_BYTES;
+constexpr int BK = 64;                            // k per stage; output tiles are TS x TS (TS = 256 or 128)
 
 #define EG_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 #define EG_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
@@ -54,17 +52,19 @@ __device__ __forceinline__ void decode_group2(const DimList &g, int64_t idx, int
 }
 
 // Per-lane source offsets (bytes, relative to the first row of the operand's tile: `origin` is that row's
-// element offset in the block) of the 32/NW chunks this lane fetches per stage (NW waves per workgroup),
-// without the k advance.
+// element offset in the block) of the TS/8/NW chunks this lane fetches per stage (NW waves per workgroup,
+// TS rows or columns per tile), without the k advance.
 //   KC: instruction i of wave w deposits rows (NW i+w)*8 .. +7, lane -> row +lane/8, physical chunk lane%8,
 //       logical chunk (lane%8) ^ ((row>>1)&7).
-//   MC: instruction i of wave w deposits k-rows (NW i+w)*2 .. +1, lane -> k-row +lane/32, physical chunk lane%32,
-//       logical chunk (lane%32) ^ 4*(krow%4), krow%4 = (2w + lane/32)%4.
-template <bool KC, int NW>
+//   MC: a k-row holds CPR = TS/8 chunks, so one instruction deposits KR = 64/CPR k-rows (2 for TS = 256, 4 for
+//       TS = 128): instruction i of wave w deposits k-rows KR (NW i+w) .. +KR-1, lane -> k-row +lane/CPR,
+//       physical chunk lane%CPR, logical chunk (lane%CPR) ^ 4*(krow%4), krow%4 = (KR w + lane/CPR)%4.
+template <bool KC, int NW, int TS>
 struct Src {
-    static constexpr int LD = 32 / NW;
+    static constexpr int LD = TS / 8 / NW;
+    static constexpr int CPR = TS / 8, KR = 64 / CPR;
     uint32_t boff[LD];        // byte offset of the chunk instruction i fetches, relative to the stage's first k
-    int kl;                   // k (within the stage) of chunk 0 of this lane; chunk i sits at kl (KC) or kl + 2 NW i (MC)
+    int kl;                   // k (within the stage) of chunk 0 of this lane; chunk i sits at kl (KC) or kl + KR NW i (MC)
 
     __device__ __forceinline__ void init(const DimList &grp, int64_t first, int64_t extent, int64_t origin, int64_t k_inner_stride, int wave, int lane)
     {
@@ -81,22 +81,22 @@ struct Src {
                 boff[i] = (uint32_t)((o0 - origin + lc * 8) * 2);
             }
         } else {
-            const int kr4 = (2 * wave + (lane >> 5)) & 3;
-            const int lc = (lane & 31) ^ (4 * kr4);
+            const int kr4 = (KR * wave + lane / CPR) & 3;
+            const int lc = (lane % CPR) ^ (4 * kr4);
             int64_t m = first + lc * 8;
             m = m + 8 <= extent ? m : extent - 8;
             int64_t o0, o1;
             decode_group2(grp, m, o0, o1);
-            kl = 2 * wave + (lane >> 5);
+            kl = KR * wave + lane / CPR;
 #pragma unroll
             for (int i = 0; i < LD; i++)
-                boff[i] = (uint32_t)((o0 - origin + (2 * NW * i + 2 * wave + (lane >> 5)) * k_inner_stride) * 2);
+                boff[i] = (uint32_t)((o0 - origin + (KR * NW * i + kl) * k_inner_stride) * 2);
         }
     }
     // offset handed to load i of a stage that has `krem` valid k left: beyond the descriptor when the chunk's k is past the end
     __device__ __forceinline__ uint32_t voff(int i, int krem) const
     {
-        const int k = KC ? kl : kl + 2 * NW * i;
+        const int k = KC ? kl : kl + KR * NW * i;
         return k < krem ? boff[i] : 0x80000000u;
     }
 };
@@ -110,27 +110,28 @@ __device__ __forceinline__ int kc_frag_off(int row, int ks, int lane)
 }
 
 // MC layout: two transposing 8-byte reads (k = 8*(lane/32) + 0..3 and +4..7 of the k-step).
+template <int TS>
 __device__ __forceinline__ int mc_frag_off(int col0, int ks, int lane, int second)
 {
     const int s = lane & 15;
     const int kr = 16 * ks + 8 * (lane >> 5) + (s >> 2) + 4 * second;
     const int n = col0 + 16 * ((lane >> 4) & 1) + 4 * (s & 3);
     const int pc = (n >> 3) ^ (4 * (s >> 2));
-    return kr * 512 + (pc << 4) + ((n & 7) << 1);
+    return kr * (TS * 2) + (pc << 4) + ((n & 7) << 1);
 }
 
-// Fragments of one k-step (16 k): four 32-row A fragments and NT 32-column B fragments of this wave
+// Fragments of one k-step (16 k): RT 32-row A fragments and NT 32-column B fragments of this wave
 // (row0, col0: first row / column of the wave's patch inside the tile).
-template <bool A_KC, bool B_KC, int NT>
-__device__ __forceinline__ void load_frags(const char *la, const char *lb, int ks, bf16x8 (&a)[4], bf16x8 (&b)[NT], int row0, int col0, int lane)
+template <bool A_KC, bool B_KC, int RT, int NT, int TS>
+__device__ __forceinline__ void load_frags(const char *la, const char *lb, int ks, bf16x8 (&a)[RT], bf16x8 (&b)[NT], int row0, int col0, int lane)
 {
 #pragma unroll
-    for (int i = 0; i < 4; i++) {
+    for (int i = 0; i < RT; i++) {
         if (A_KC) {
             a[i] = *(const bf16x8 *)(la + kc_frag_off(row0 + i * 32 + (lane & 31), ks, lane));
         } else {
-            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off(row0 + i * 32, ks, lane, 0)));
-            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off(row0 + i * 32, ks, lane, 1)));
+            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off<TS>(row0 + i * 32, ks, lane, 0)));
+            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off<TS>(row0 + i * 32, ks, lane, 1)));
             short4v *dst = (short4v *)&a[i];
             dst[0] = lo; dst[1] = hi;
         }
@@ -140,17 +141,17 @@ __device__ __forceinline__ void load_frags(const char *la, const char *lb, int k
         if (B_KC) {
             b[j] = *(const bf16x8 *)(lb + kc_frag_off(col0 + j * 32 + (lane & 31), ks, lane));
         } else {
-            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off(col0 + j * 32, ks, lane, 0)));
-            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off(col0 + j * 32, ks, lane, 1)));
+            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off<TS>(col0 + j * 32, ks, lane, 0)));
+            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off<TS>(col0 + j * 32, ks, lane, 1)));
             short4v *dst = (short4v *)&b[j];
             dst[0] = lo; dst[1] = hi;
         }
     }
 }
 
-// MFMAs of one k-step for rows [I0, I1) of this wave's 4 x NT grid of 32x32 tiles.
-template <int I0, int I1, int NT>
-__device__ __forceinline__ void mfma_rows(const bf16x8 (&a)[4], const bf16x8 (&b)[NT], f32x16 (&acc)[4][NT])
+// MFMAs of one k-step for rows [I0, I1) of this wave's RT x NT grid of 32x32 tiles.
+template <int I0, int I1, int RT, int NT>
+__device__ __forceinline__ void mfma_rows(const bf16x8 (&a)[RT], const bf16x8 (&b)[NT], f32x16 (&acc)[RT][NT])
 {
 #pragma unroll
     for (int i = I0; i < I1; i++)
@@ -167,27 +168,39 @@ struct TileInfo {
     int64_t bz, agg;         // Z element offset of the tuple's block and batch entry; aggIdx of the tuple
 };
 
-// NW = 4: one wave per SIMD, each owning 128 x 128 of the tile.  NW = 8: two waves per SIMD, each owning
-// 128 x 64; one wave's MFMAs then cover the other's LDS reads and barrier waits, at 1.5x the LDS read traffic.
+// Output tiles are TS x TS; the NW waves of a workgroup form a 2 x NW/2 grid of patches.
+//   TS = 256, NW = 8: two waves per SIMD, each owning 128 x 64; one wave's MFMAs cover the other's LDS reads and
+//       barrier waits.  The kernel for large blocks: one workgroup per compute unit (154 KiB of LDS).
+//   TS = 256, NW = 4: one wave per SIMD, each owning 128 x 128 (two thirds of the LDS read traffic, nothing to
+//       cover a wave's own waits); kept for comparison.
+//   TS = 128, NW = 4: patches of 64 x 64, 78 KiB of LDS, two workgroups per compute unit: one's epilogue and
+//       first loads run under the other's MFMAs.  For launches with too few 256 x 256 tiles to fill the chip
+//       and for short K, where a tile is mostly loading and storing.
 //
-// The kernel is persistent: one workgroup per compute unit walks over its share of the tiles.  While a tile's
+// The kernel is persistent: the workgroups of a compute unit walk over their share of the tiles.  While a tile's
 // epilogue runs, the first two stages of the workgroup's next tile are already on their way into LDS, and the
 // next tile's addressing was worked out while the current tile waited for its own first stage.
-template <int NW, bool A_KC, bool B_KC, bool ODD>
-__global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p)
+template <int TS, int NW, bool A_KC, bool B_KC, bool ODD>
+__global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(const ContractParams p)
 {
-    constexpr int NT = 16 / NW;                       // 32-column MFMA tiles per wave: the wave's patch is 128 x 32 NT
-    constexpr int LD = 32 / NW;                       // direct loads per operand tile, wave and stage
+    constexpr int WN = NW / 2;                        // waves side by side
+    constexpr int RT = TS / 64, NT = TS / WN / 32;    // 32x32 MFMA tiles per wave: RT down, NT across
+    constexpr int LD = TS / 8 / NW;                   // direct loads per operand tile, wave and stage
+    constexpr int TILE_BYTES = TS * BK * 2;           // one operand tile of one stage
+    constexpr int STAGE_BYTES = 2 * TILE_BYTES;
+    constexpr int TBL = 2 * TS * 8;                   // one set of Z offset tables (TS rows, TS columns)
+    constexpr int DPM = 2 * LD / (RT * NT);           // direct loads issued after each MFMA of a stage's last k-step
+    static_assert(DPM * RT * NT == 2 * LD && DPM >= 1, "the last k-step's MFMAs carry all loads of a stage");
     constexpr int CW = 32 * NT, PITCH = CW * 4 + 32, WBUF = 8 * PITCH;   // epilogue staging: 8 rows of a wave's patch
     // Separate LDS objects for the two stages and for the epilogue: the compiler can then tell that the fragment
     // reads of one stage, or the epilogue's staging, never alias the direct loads in flight into another object,
     // and does not wait for them.
     __shared__ __attribute__((aligned(1024))) char lds0[STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) char lds1[STAGE_BYTES];
-    __shared__ __attribute__((aligned(16))) char ldsx[2 * 4096 + NW * WBUF];   // two sets of Z offset tables + staging
+    __shared__ __attribute__((aligned(16))) char ldsx[2 * TBL + NW * WBUF];    // two sets of Z offset tables + staging
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / (NW / 2), wn = wave % (NW / 2);
-    const int row0 = wm * 128, col0 = wn * (32 * NT);
+    const int wm = wave / WN, wn = wave % WN;
+    const int row0 = wm * (32 * RT), col0 = wn * (32 * NT);
 
     // ---- this workgroup's tiles: logical ids first, first + stride, ...; concurrent ids share an XCD ----
     const uint32_t total = (uint32_t)p.total_tiles, G = gridDim.x;
@@ -231,8 +244,8 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
             by += (int64_t)k * p.batch.s1[i];
             bz += (int64_t)k * p.batch.s2[i];
         }
-        t.m0 = (int64_t)tile_m * BM;
-        t.n0 = (int64_t)tile_n * BN;
+        t.m0 = (int64_t)tile_m * TS;
+        t.n0 = (int64_t)tile_n * TS;
         // lane offsets are 32 bits and count from the tile's first row (an operand contiguous along M or N reads whole
         // 8-element chunks, so near the block's edge its first chunk may start up to 7 elements before the tile)
         int64_t unused;
@@ -248,8 +261,8 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
     const int64_t nk = (p.K + BK - 1) / BK;
 
     TileInfo cur, nxt;
-    Src<A_KC, NW> sa;
-    Src<B_KC, NW> sb;
+    Src<A_KC, NW, TS> sa;
+    Src<B_KC, NW, TS> sb;
     const char *xb, *yb;                              // bases the direct loads currently work from
 
     // Uniform source pointers of consecutive stages, and how many k each still has (64: a full stage; 0: past the end,
@@ -333,35 +346,35 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
     // return while the matrix pipe is busy.  The last k-step of a stage runs after the barrier, together with
     // the direct loads of the stage after next and the first fragment reads of the next stage.
     // sched_barrier pins this order against the compiler's own scheduling.
-    f32x16 acc[4][NT];
-    bf16x8 a0[4], b0[NT], a1[4], b1[NT];
+    f32x16 acc[RT][NT];
+    bf16x8 a0[RT], b0[NT], a1[RT], b1[NT];
 #define EG_PIN() __builtin_amdgcn_sched_barrier(0)
 #define EG_KSTEP(FA, FB, NA, NB, BUF, KS_NEXT)                                                    \
-    mfma_rows<0, 1, NT>(FA, FB, acc); EG_PIN();                                                   \
-    load_frags<A_KC, B_KC, NT>(BUF, BUF + TILE_BYTES, KS_NEXT, NA, NB, row0, col0, lane); EG_PIN(); \
-    mfma_rows<1, 4, NT>(FA, FB, acc); EG_PIN();
+    mfma_rows<0, 1, RT, NT>(FA, FB, acc); EG_PIN();                                                   \
+    load_frags<A_KC, B_KC, RT, NT, TS>(BUF, BUF + TILE_BYTES, KS_NEXT, NA, NB, row0, col0, lane); EG_PIN(); \
+    mfma_rows<1, RT, RT, NT>(FA, FB, acc); EG_PIN();
 #define EG_STAGE_NEXT(C, O, HAS_NEXT2) /* one stage; its successor is already in flight into O */     \
     do {                                                                                          \
-        mfma_rows<0, 1, NT>(a0, b0, acc); EG_PIN();                                               \
+        mfma_rows<0, 1, RT, NT>(a0, b0, acc); EG_PIN();                                               \
         const bool has2 = (HAS_NEXT2);                                                            \
         next_stage(ga2, gb2, kr2);          /* scalar work rides under the MFMAs */               \
-        load_frags<A_KC, B_KC, NT>(C, C + TILE_BYTES, 1, a1, b1, row0, col0, lane); EG_PIN();     \
-        mfma_rows<1, 4, NT>(a0, b0, acc); EG_PIN();                                               \
+        load_frags<A_KC, B_KC, RT, NT, TS>(C, C + TILE_BYTES, 1, a1, b1, row0, col0, lane); EG_PIN();     \
+        mfma_rows<1, RT, RT, NT>(a0, b0, acc); EG_PIN();                                               \
         EG_KSTEP(a1, b1, a0, b0, C, 2)                                                            \
         EG_KSTEP(a0, b0, a1, b1, C, 3)                                                            \
         __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): this wave's deposits for O landed */     \
         __syncthreads();                    /* everybody's landed; everybody has left C */        \
         EG_PIN();                                                                                 \
-        /* last k-step: every MFMA is followed by one direct load of the stage after next into C */ \
+        /* last k-step: every MFMA is followed by DPM direct loads of the stage after next into C */ \
         _Pragma("unroll") for (int j = 0; j < NT; j++) {                                          \
             acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[0], b1[j], acc[0][j], 0, 0, 0); EG_PIN(); \
-            if (has2) dma(j, ga2, gb2, kr2, C);                                                   \
+            if (has2) { _Pragma("unroll") for (int d = 0; d < DPM; d++) dma(DPM * j + d, ga2, gb2, kr2, C); } \
             EG_PIN();                                                                             \
         }                                                                                         \
-        load_frags<A_KC, B_KC, NT>(O, O + TILE_BYTES, 0, a0, b0, row0, col0, lane); EG_PIN();     \
-        _Pragma("unroll") for (int q = 0; q < 3 * NT; q++) {                                      \
+        load_frags<A_KC, B_KC, RT, NT, TS>(O, O + TILE_BYTES, 0, a0, b0, row0, col0, lane); EG_PIN();     \
+        _Pragma("unroll") for (int q = 0; q < (RT - 1) * NT; q++) {                               \
             acc[1 + q / NT][q % NT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[1 + q / NT], b1[q % NT], acc[1 + q / NT][q % NT], 0, 0, 0); EG_PIN(); \
-            if (has2) dma(NT + q, ga2, gb2, kr2, C);                                              \
+            if (has2) { _Pragma("unroll") for (int d = 0; d < DPM; d++) dma(DPM * (NT + q) + d, ga2, gb2, kr2, C); } \
             EG_PIN();                                                                             \
         }                                                                                         \
     } while (0)
@@ -375,8 +388,8 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
         // while the first stages travel: the next tile's uniform addressing and this tile's Z offset tables
         // (256 rows, 256 columns; two sets in turn, so a wave already in the next tile cannot disturb a slower one)
         if (more) tile_info(first + (it + 1) * stride, nxt);
-        int64_t *zrow = (int64_t *)(ldsx + (it & 1) * 4096), *zcol = zrow + 256;
-        if (tid < 256) {
+        int64_t *zrow = (int64_t *)(ldsx + (it & 1) * TBL), *zcol = zrow + TS;
+        if (tid < TS) {
             int64_t unused, z;
             const int64_t m = cur.m0 + tid, n = cur.n0 + tid;
             decode_group2(p.m, m < p.M ? m : 0, unused, z);
@@ -385,14 +398,14 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
             zcol[tid] = z;
         }
 #pragma unroll
-        for (int i = 0; i < 4; i++)
+        for (int i = 0; i < RT; i++)
 #pragma unroll
             for (int j = 0; j < NT; j++)
 #pragma unroll
                 for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
         __builtin_amdgcn_s_waitcnt(0x0F70);           // both stages (and the previous tile's stores) are done
         __syncthreads();
-        load_frags<A_KC, B_KC, NT>(lds0, lds0 + TILE_BYTES, 0, a0, b0, row0, col0, lane);
+        load_frags<A_KC, B_KC, RT, NT, TS>(lds0, lds0 + TILE_BYTES, 0, a0, b0, row0, col0, lane);
         // Every stage, the last one included, runs the same straight-line code (the last one pays for one idle
         // barrier and a set of unused fragment reads): an MFMA under a branch inside the loop would make the
         // compiler shuffle the accumulator registers.  The stage count's parity is a template parameter.
@@ -419,9 +432,9 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
         int elane = lane;
         asm volatile("" : "+v"(elane));
         const int lrow = elane & 31, lhalf = elane >> 5;
-        char *wbuf = ldsx + 2 * 4096 + wave_u * WBUF;  // this wave's staging rows
-        const int mrem = (int)(p.M - cur.m0 < BM ? p.M - cur.m0 : BM);     // rows / columns of the tile inside the block
-        const int nrem = (int)(p.N - cur.n0 < BN ? p.N - cur.n0 : BN);
+        char *wbuf = ldsx + 2 * TBL + wave_u * WBUF;   // this wave's staging rows
+        const int mrem = (int)(p.M - cur.m0 < TS ? p.M - cur.m0 : TS);     // rows / columns of the tile inside the block
+        const int nrem = (int)(p.N - cur.n0 < TS ? p.N - cur.n0 : TS);
         if (p.out_vec) {
             // Z is contiguous along the tile's columns: each wave stages 8 rows x CW columns of its patch at a time
             // in LDS (the row pitch leaves 32 bytes of padding, which keeps the two half-waves on different banks)
@@ -484,14 +497,14 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
                 }
             };
 #pragma unroll
-            for (int ps = 0; ps < 16; ps++) {
+            for (int ps = 0; ps < 4 * RT; ps++) {
                 write_pass(ps >> 2, ps & 3);
                 read_pass(ps >> 2, ps & 3, rd[ps & 1], zr[ps & 1]);
                 __builtin_amdgcn_sched_barrier(0);
                 if (ps > 0) store_pass((ps - 1) >> 2, (ps - 1) & 3, rd[(ps - 1) & 1], zr[(ps - 1) & 1]);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            store_pass(3, 3, rd[1], zr[1]);
+            store_pass(RT - 1, 3, rd[1], zr[1]);
         } else {
             int64_t zn[NT];
             bool nok[NT];
@@ -502,7 +515,7 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
                 nok[j] = c < nrem;
             }
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
+            for (int i = 0; i < RT; i++) {
 #pragma unroll
                 for (int r = 0; r < 16; r++) {
                     const int rr = row0 + i * 32 + 8 * (r >> 2) + 4 * lhalf + (r & 3);
@@ -529,26 +542,26 @@ __global__ __launch_bounds__(NW * 64) void k_contract_dma(const ContractParams p
 #undef EG_PIN
 }
 
-template <int NW, bool A_KC, bool B_KC, bool ODD>
+template <int TS, int NW, bool A_KC, bool B_KC, bool ODD>
 static int launch_one(ContractParams &p, void *stream)
 {
-    hipLaunchKernelGGL((k_contract_dma<NW, A_KC, B_KC, ODD>), dim3((unsigned)p.grid), dim3(NW * 64), 0, (hipStream_t)stream, p);
+    hipLaunchKernelGGL((k_contract_dma<TS, NW, A_KC, B_KC, ODD>), dim3((unsigned)p.grid), dim3(NW * 64), 0, (hipStream_t)stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(EG_ERR_HIP, "k_contract_dma launch failed: %s", hipGetErrorString(e));
     return EG_OK;
 }
 
-template <int NW, bool A_KC, bool B_KC>
+template <int TS, int NW, bool A_KC, bool B_KC>
 static int launch_parity(ContractParams &p, void *stream)
 {
-    return (((p.K + BK - 1) / BK) & 1) ? launch_one<NW, A_KC, B_KC, true>(p, stream) : launch_one<NW, A_KC, B_KC, false>(p, stream);
+    return (((p.K + BK - 1) / BK) & 1) ? launch_one<TS, NW, A_KC, B_KC, true>(p, stream) : launch_one<TS, NW, A_KC, B_KC, false>(p, stream);
 }
 
-template <int NW>
+template <int TS, int NW>
 static int launch_layout(ContractParams &p, void *stream)
 {
-    if (p.a_kcontig) return p.b_kcontig ? launch_parity<NW, true, true>(p, stream) : launch_parity<NW, true, false>(p, stream);
-    return p.b_kcontig ? launch_parity<NW, false, true>(p, stream) : launch_parity<NW, false, false>(p, stream);
+    if (p.a_kcontig) return p.b_kcontig ? launch_parity<TS, NW, true, true>(p, stream) : launch_parity<TS, NW, true, false>(p, stream);
+    return p.b_kcontig ? launch_parity<TS, NW, false, true>(p, stream) : launch_parity<TS, NW, false, false>(p, stream);
 }
 
 }  // namespace dma
@@ -589,11 +602,6 @@ int launch_contract_dma(ContractParams &p, void *stream)
 {
     if (!p.x || !p.y || !p.out.ptr) return fail(EG_ERR_NULL, "contraction: NULL operand");
     if (!contract_dma_eligible(p)) return fail(EG_ERR_LIMIT, "contraction: shape not eligible for the direct-to-LDS kernel");
-    p.tiles_m = (int32_t)((p.M + dma::BM - 1) / dma::BM);
-    p.tiles_n = (int32_t)((p.N + dma::BN - 1) / dma::BN);
-    const int64_t wgs = p.n_tuples * p.n_batch * p.tiles_m * p.tiles_n;
-    if (wgs < 1 || wgs >= (1ll << 31)) return fail(EG_ERR_LIMIT, "contraction has %lld output tiles", (long long)wgs);
-    // one workgroup per compute unit (its LDS need admits no second one), a multiple of 8 so that every XCD gets the same number
     static int n_cu = 0;
     if (!n_cu) {
         int dev = 0;
@@ -601,8 +609,23 @@ int launch_contract_dma(ContractParams &p, void *stream)
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return fail(EG_ERR_HIP, "cannot query the device");
         n_cu = prop.multiProcessorCount > 8 ? prop.multiProcessorCount / 8 * 8 : 8;
     }
+    // Tile size: 256 x 256, one workgroup per compute unit, is the faster kernel per flop (a quarter more, measured on
+    // large products).  128 x 128 tiles, two workgroups per unit, are taken when they are all resident at once, i.e. when
+    // the large tiles would leave at least half of the compute units without work (measured: 64 large tiles 1.5-1.8x
+    // faster as 256 small ones; 160 large tiles 1.4x slower as 640 small ones, which need a second round).
+    const char *tile_env = getenv("EINDECOMP_DMA_TILE");              // 128 or 256: for comparisons and tests, read at every launch
+    const int64_t tuples = p.n_tuples * p.n_batch;
+    const int64_t small = tuples * ((p.M + 127) / 128) * ((p.N + 127) / 128);
+    int ts = small <= 2 * n_cu ? 128 : 256;
+    if (tile_env && (atoi(tile_env) == 128 || atoi(tile_env) == 256)) ts = atoi(tile_env);
+    p.tiles_m = (int32_t)((p.M + ts - 1) / ts);
+    p.tiles_n = (int32_t)((p.N + ts - 1) / ts);
+    const int64_t wgs = tuples * p.tiles_m * p.tiles_n;
+    if (wgs < 1 || wgs >= (1ll << 31)) return fail(EG_ERR_LIMIT, "contraction has %lld output tiles", (long long)wgs);
+    // persistent workgroups: as many as fit the chip at once, a multiple of 8 so that every XCD gets the same number
+    const int64_t resident = (ts == 128 ? 2 : 1) * (int64_t)n_cu;
     p.total_tiles = (int32_t)wgs;
-    p.grid = (int32_t)(wgs < n_cu ? wgs : n_cu);
+    p.grid = (int32_t)(wgs < resident ? wgs : resident);
     // wide epilogue stores need Z contiguous along the innermost N label and every other Z offset a multiple of 8 elements
     bool vec = p.n.s1[p.n.n - 1] == 1 && p.n.ext[p.n.n - 1] % 8 == 0 && ((uintptr_t)p.out.ptr & 15) == 0 && p.out.slab_elems % 8 == 0;
     for (int i = 0; i < p.m.n; i++) vec = vec && p.m.s1[i] % 8 == 0;
@@ -610,9 +633,10 @@ int launch_contract_dma(ContractParams &p, void *stream)
     for (int i = 0; i < p.batch.n; i++) vec = vec && p.batch.s2[i] % 8 == 0;
     for (int l = 0; l < p.ts.n; l++) vec = vec && p.ts.step_z[l] % 8 == 0;
     p.out_vec = vec ? 1 : 0;
-    static const char *waves = getenv("EINDECOMP_DMA_WAVES");         // 4 or 8 waves per workgroup (for comparisons)
-    if (waves && atoi(waves) == 4) return dma::launch_layout<4>(p, stream);
-    return dma::launch_layout<8>(p, stream);
+    const char *waves = getenv("EINDECOMP_DMA_WAVES");                // 4 or 8 waves per workgroup of the 256 x 256 kernel (for comparisons)
+    if (ts == 128) return dma::launch_layout<128, 4>(p, stream);
+    if (waves && atoi(waves) == 4) return dma::launch_layout<256, 4>(p, stream);
+    return dma::launch_layout<256, 8>(p, stream);
 }
 
 }  // namespace eg

@@ -59,10 +59,14 @@ def test_config_every_vertex_matches_oracle(n, pname):
         assert bad == 0, f"config {n} {pname} vertex {name}: {bad} elements out of tolerance (worst {worst:.2f}x)"
 
 
+@pytest.mark.parametrize("tile", ["", "256"])
 @pytest.mark.parametrize("n,pname", CASES)
-def test_config_outputs_through_workspace_match_oracle(n, pname):
+def test_config_outputs_through_workspace_match_oracle(n, pname, tile, monkeypatch):
+    # at these sizes the bf16 contraction kernel would always pick its small tile: the second pass forces the large one
     w, inp, ref = _reference(n)
-    print(f"config {n} partitioning {pname}: intermediates in the workspace", flush=True)
+    print(f"config {n} partitioning {pname}: intermediates in the workspace, tile {tile or 'default'}", flush=True)
+    if tile:
+        monkeypatch.setenv("EINDECOMP_DMA_TILE", tile)
     got = _run(w, pname, inp)
     for name in w.outputs:
         bad, worst = violations(got[name].as_f64(), ref[name].as_f64(), rtol_for(w, name))
@@ -102,10 +106,13 @@ LAYOUTS = [
 ]
 
 
-@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("dtype,tile", [("bf16", "128"), ("bf16", "256"), ("f32", "")])
 @pytest.mark.parametrize("spec,bx,by", LAYOUTS)
-def test_contraction_layouts(spec, bx, by, dtype):
-    print(f"contraction {spec} {bx} {by} {dtype}", flush=True)
+def test_contraction_layouts(spec, bx, by, dtype, tile, monkeypatch):
+    # the direct-to-LDS bf16 kernel has two tile sizes and picks the small one for products this small: both are run
+    print(f"contraction {spec} {bx} {by} {dtype} tile {tile or 'default'}", flush=True)
+    if tile:
+        monkeypatch.setenv("EINDECOMP_DMA_TILE", tile)
     x = HostTensor.from_f32(uniform_pm1(11, 0, int(np.prod(bx))).reshape(bx), dtype)
     y = HostTensor.from_f32(uniform_pm1(11, 1, int(np.prod(by))).reshape(by), dtype)
     w = single_vertex(spec, x, y, "f32")
