@@ -433,6 +433,7 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
         asm volatile("" : "+v"(elane));
         const int lrow = elane & 31, lhalf = elane >> 5;
         char *wbuf = ldsx + 2 * TBL + wave_u * WBUF;   // this wave's staging rows
+        const bool slab = p.out.slab_elems != 0;
         const int mrem = (int)(p.M - cur.m0 < TS ? p.M - cur.m0 : TS);     // rows / columns of the tile inside the block
         const int nrem = (int)(p.N - cur.n0 < TS ? p.N - cur.n0 : TS);
         if (p.out_vec) {
@@ -483,7 +484,12 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
 #pragma unroll
                     for (int h = 0; h < 8 / RPI_F; h++) {
                         const int rr = row0 + i * 32 + 8 * q + RPI_F * h + lr;
-                        if (cok && rr < mrem) *(f32x4 *)((float *)zb + z[h] + zc) = v[h];
+                        if (cok && rr < mrem) {
+                            f32x4 *dst = (f32x4 *)((float *)zb + z[h] + zc);
+                            const f32x4 val = v[h];
+                            if (slab) __builtin_nontemporal_store(val, dst);   // partial slabs are read much later, by another kernel
+                            else *dst = val;
+                        }
                     }
                 } else {
 #pragma unroll
