@@ -496,7 +496,9 @@ static std::vector<FuseGroup> find_fusions(const eg_graph *g)
         if (!is_iota(E.lx, r) || !is_iota(E.ly, r - 1) || !is_iota(E.lz, r)) continue;
         if (!is_iota(P.lx, r) || !is_iota(P.ly, r - 1) || !is_iota(P.lz, r)) continue;
         if (!is_iota(C.lx, r) || !is_iota(C.lz, r - 1) || !is_iota(S.lx, r) || !is_iota(S.lz, r - 1)) continue;
-        if (E.d != P.d || C.d != P.d || S.d != P.d || P.d[r - 1] != 1) continue;
+        // the pass runs under the division's partitioning vector; how the vertices inside the chain were cut does not
+        // matter (their tensors are dense, a cut is only a view), but a row must lie inside one block
+        if (P.d[r - 1] != 1) continue;
         if (E.lbound[r - 1] > 8192) continue;
         if (!only(e, {s, p})) continue;
         if (taken[e] || taken[s] || taken[c] || taken[p]) continue;
@@ -512,7 +514,7 @@ static std::vector<FuseGroup> find_fusions(const eg_graph *g)
         if (!g->v[t].is_input) {
             const Vertex &T = g->v[t];
             if (T.n_in == 2 && T.otimes == EG_ADD && T.agg.empty() && !T.is_output && T.in[0] != T.in[1] && !taken[t] &&
-                is_iota(T.lx, r) && is_iota(T.lz, r) && T.d == P.d && only(t, {c, e})) {
+                is_iota(T.lx, r) && is_iota(T.lz, r) && only(t, {c, e})) {
                 grp.add = t;
                 grp.src = T.in[0];
                 grp.addend = T.in[1];
@@ -821,14 +823,14 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
             s.agg = false;
             SoftmaxParams &sp = s.sp;
             memset(&sp, 0, sizeof sp);
-            const Vertex &E = g->v[f.vexp];
+            const Vertex &E = g->v[f.vexp], &P = g->v[f.vdiv];
             const int r = (int)E.lx.size();
             const Operand src = operand_of(f.src), res = operand_of(f.vdiv);
             Operand addend, omax, osum;
             LabelInfo li, li2;                          // li: source / added operand / result; li2: row maxima / row sums
             li.nl = li2.nl = r;
             for (int l = 0; l < r; l++) {
-                li.ext[l] = li2.ext[l] = E.lbound[l] / E.d[l];
+                li.ext[l] = li2.ext[l] = P.lbound[l] / P.d[l];
                 li.sx[l] = src.stride[l]; li.inx[l] = true;
                 li.sz[l] = res.stride[l]; li.inz[l] = true;
             }
@@ -848,8 +850,8 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
                 for (int l = 0; l + 1 < r; l++) li2.sy[l] = osum.stride[l];
                 sp.emit_sum = 1; sp.row_sum = (void *)osum.ptr; sp.dt_sum = osum.dtype;
             }
-            sp.ts = tuple_space(E, li);                 // E's partitioning vector is the chain's
-            sp.ts2 = tuple_space(E, li2);
+            sp.ts = tuple_space(P, li);                 // the division's partitioning vector is the chain's
+            sp.ts2 = tuple_space(P, li2);
             sp.rows_per_block = 1;
             // Row labels that the added operand lacks go last, i.e. vary fastest from one wave to the next: rows that
             // take the same row of the added operand then run next to each other and find it in the cache (otherwise
@@ -872,7 +874,7 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
             sp.dt_src = src.dtype; sp.dt_e = E.dtype; sp.dt_p = res.dtype;
             if (!sp.has_add) sp.dt_t = src.dtype;
             sp.src = src.ptr; sp.p = (void *)res.ptr;
-            sp.n_tuples = E.plan.n_tuples;
+            sp.n_tuples = P.plan.n_tuples;
             steps.push_back(std::move(s));
             continue;
         }

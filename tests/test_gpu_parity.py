@@ -361,6 +361,11 @@ def _softmax_workload(bound, dtype, with_add, stats_consumed):
         outs += ["logS", "C"]
     first = labs[0]
     parts = {"whole": {}, "rows2": {v.name: {first: 2} for v in vs if v.spec}}
+    # every vertex of the chain cut differently (even along the softmax label, except at the division): the fused
+    # pass runs under the division's vector alone
+    second = labs[-2]
+    mixed = {"C": {labs[-1]: 2}, "E": {second: 2, labs[-1]: 4}, "S": {first: 2, labs[-1]: 2}, "P": {second: 2}, "T2": {first: 2, second: 2}, "logS": {}}
+    parts["mixed"] = {v.name: mixed[v.name] for v in vs if v.spec}
     return Workload("softmax_chain", 77, vs, outs, parts, {})
 
 
@@ -373,7 +378,7 @@ def test_fused_softmax_matches_oracle_and_the_separate_vertices(bound, dtype, wi
     w = _softmax_workload(bound, dtype, with_add, stats)
     inp = make_inputs(w)
     ref = run_graph(w, inp)
-    for pname in ("whole", "rows2"):
+    for pname in ("whole", "rows2", "mixed"):
         print(f"softmax chain {bound} {dtype} add={with_add} stats={stats} {pname}", flush=True)
         res = {}
         for fuse in (True, False):
