@@ -314,8 +314,43 @@ __global__ __launch_bounds__(kThreads) void k_aggregate_scalar(const AggregatePa
 {
     const int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (e >= p.slab_elems) return;
+    // ascending slab order, eight loads in flight at a time (a loss cut into hundreds of pieces is one such chain)
     float acc = p.partials[e];
-    for (int64_t a = 1; a < p.n_agg; a++) acc = oplus_eval(p.oplus, acc, p.partials[a * p.slab_stride + e]);
+    for (int64_t a = 1; a < p.n_agg; a += 8) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] = p.partials[(a + j < p.n_agg ? a + j : a) * p.slab_stride + e];
+#pragma unroll
+        for (int j = 0; j < 8; j++)
+            if (a + j < p.n_agg) acc = oplus_eval(p.oplus, acc, v[j]);
+    }
+    int64_t off = e;
+    if (!p.contiguous) {
+        int64_t ox = 0, oy = 0;
+        off = 0;
+        decode_dims(p.dims, e, ox, oy, off);
+    }
+    store_elem(p.out, p.out_dtype, off, acc);
+}
+
+// Few outputs, many slabs (a loss whose reduction was cut into hundreds of pieces): one wave per output element.
+// The lanes fetch 64 slabs' values at once; the additions still run one after the other in ascending slab order
+// (every lane does all of them on values read from the other lanes), so the result is that of the plain loop.
+__global__ __launch_bounds__(64) void k_aggregate_wave(const AggregateParams p)
+{
+    const int64_t e = blockIdx.x;
+    const int lane = threadIdx.x;
+    float acc = 0.f;
+    for (int64_t a0 = 0; a0 < p.n_agg; a0 += 64) {
+        const int64_t a = a0 + lane;
+        const float v = p.partials[(a < p.n_agg ? a : a0) * p.slab_stride + e];
+        const int cnt = (int)(p.n_agg - a0 < 64 ? p.n_agg - a0 : 64);
+        for (int j = 0; j < cnt; j++) {
+            const float x = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), j));
+            acc = (a0 == 0 && j == 0) ? x : oplus_eval(p.oplus, acc, x);
+        }
+    }
+    if (lane != 0) return;
     int64_t off = e;
     if (!p.contiguous) {
         int64_t ox = 0, oy = 0;
@@ -455,6 +490,10 @@ int launch_aggregate(const AggregateParams &p, void *stream)
     const bool vec = p.contiguous && p.slab_elems % 4 == 0 && p.slab_stride % 4 == 0 && ((uintptr_t)p.partials & 15) == 0 &&
                      ((uintptr_t)p.out & 15) == 0;
     unsigned grid;
+    if (p.n_agg >= 32 && p.slab_elems <= 4096) {                    // too few outputs for one lane per output to hide the loads
+        hipLaunchKernelGGL(k_aggregate_wave, dim3((unsigned)p.slab_elems), dim3(64), 0, (hipStream_t)stream, p);
+        return check_launch("k_aggregate");
+    }
     int rc = grid_for(vec ? p.slab_elems / 4 : p.slab_elems, kThreads, grid);
     if (rc) return rc;
     if (vec) {

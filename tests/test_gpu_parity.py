@@ -292,6 +292,27 @@ def test_tr_aggregate_sum_max_and_strided_output(out_dtype):
             E.tensor_relation_destroy(rel)
 
 
+@pytest.mark.parametrize("n_agg,shape", [(100, (3,)), (512, (1,)), (33, (5, 7)), (300, (64, 64)), (40, (65, 64))])
+def test_tr_aggregate_of_many_slabs_adds_in_ascending_order(n_agg, shape):
+    # the reference is the plain loop in fp32, ((p0 + p1) + p2) + ...: every variant of the kernel (one lane per output,
+    # one wave per output with 64 slabs fetched at a time) must reproduce it bit for bit
+    torch, GraphRunner, to_device, to_host = _gpu()
+    import paper_2410_02682_amd as E
+    n = int(np.prod(shape))
+    rnd = normal(19, n_agg, n_agg * n, 3.0).reshape(n_agg, n)
+    parts = torch.from_numpy(rnd).cuda()
+    for op in ("sum", "max"):
+        out = torch.zeros(shape, dtype=torch.float32, device="cuda")
+        rel = E.tensor_partition(out.data_ptr(), "f32", shape, [1] * len(shape))
+        E.tr_aggregate(op, parts.data_ptr(), n_agg, n, rel, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        E.tensor_relation_destroy(rel)
+        acc = rnd[0].copy()
+        for a in range(1, n_agg):
+            acc = (acc + rnd[a]).astype(np.float32) if op == "sum" else np.maximum(acc, rnd[a])
+        assert np.array_equal(out.cpu().numpy().ravel(), acc), (op, n_agg, shape)
+
+
 def test_strided_input_relation_and_small_workspace_is_rejected():
     torch, GraphRunner, to_device, to_host = _gpu()
     import paper_2410_02682_amd as E
