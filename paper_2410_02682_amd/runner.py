@@ -74,20 +74,28 @@ class GraphRunner:
                     return [int(part.get(l, 1)) for l in labs]
         return [1] * len(self.w.vertex(name).bound)
 
-    def bind(self, inputs: Dict[str, torch.Tensor]):
+    def bind(self, inputs: Dict[str, torch.Tensor], outputs: Optional[Dict[str, torch.Tensor]] = None):
+        """Views the given device tensors as tensor relations.  Any strided view will do (a relation is a base pointer,
+        bounds and element strides); outputs not given are allocated dense."""
         self.release_relations()
         for v in self.w.vertices:
             if v.is_input:
                 t = inputs[v.name]
-                assert t.is_contiguous() and tuple(t.shape) == tuple(v.bound) and t.dtype == TORCH_DTYPE[v.dtype]
+                assert tuple(t.shape) == tuple(v.bound) and t.dtype == TORCH_DTYPE[v.dtype]
                 self.tensors[v.name] = t
-                self.rel_in.append(api.tensor_partition(t.data_ptr(), v.dtype, v.bound, self._input_partition(v.name)))
+                self.rel_in.append(api.tensor_partition(t.data_ptr(), v.dtype, v.bound, self._input_partition(v.name),
+                                                        strides=None if t.is_contiguous() else list(t.stride())))
         for n in self.out_names:
             v = self.w.vertex(n)
             pl = self.plan(n)
-            t = torch.empty(tuple(pl["bound_z"]), dtype=TORCH_DTYPE[v.dtype], device=self.device)
+            if outputs is not None and n in outputs:
+                t = outputs[n]
+                assert tuple(t.shape) == tuple(pl["bound_z"]) and t.dtype == TORCH_DTYPE[v.dtype]
+            else:
+                t = torch.empty(tuple(pl["bound_z"]), dtype=TORCH_DTYPE[v.dtype], device=self.device)
             self.tensors[n] = t
-            self.rel_out.append(api.tensor_partition(t.data_ptr(), v.dtype, pl["bound_z"], pl["d_z"]))
+            self.rel_out.append(api.tensor_partition(t.data_ptr(), v.dtype, pl["bound_z"], pl["d_z"],
+                                                     strides=None if t.is_contiguous() else list(t.stride())))
         nbytes = api.tr_workspace_bytes(self.g)
         self.workspace_bytes = nbytes
         self.workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
