@@ -89,6 +89,15 @@ def ceilings():
         b.record()
         torch.cuda.synchronize()
         out[f"mfma_bf16_{wps}_wave_per_simd_tflops"] = fl / a.elapsed_time(b) / 1e9
+    # the same loop on pseudo-random operands: the chip's clock under the matrix pipes depends on the operand bits
+    E.eg_ceiling_mfma_bf16_random(sink.data_ptr(), 256, 1000, s)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    fl = E.eg_ceiling_mfma_bf16_random(sink.data_ptr(), 256, 10000, s)
+    b.record()
+    torch.cuda.synchronize()
+    out["mfma_bf16_random_operands_tflops"] = fl / a.elapsed_time(b) / 1e9
     E.eg_ceiling_valu_f32(sink.data_ptr(), 256, 2, 500, s)
     torch.cuda.synchronize()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

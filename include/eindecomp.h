@@ -281,6 +281,12 @@ int eindecomp_labelling_cost(const eg_graph *g, int64_t *join, int64_t *agg, int
  * written.  *flops (host) receives the launch's operation count; the caller times it. */
 int eg_ceiling_mfma_bf16(void *sink, int cus, int waves_per_simd, int iters, double *flops, void *hip_stream);
 
+/* The same loop on pseudo-random bf16 operands (sign and mantissa bits from a hash, four A and four B fragments
+ * per lane): one wave on each SIMD of `cus` compute units, iters*16 MFMAs per wave.  The chip's clock under the
+ * matrix pipes' power draw depends on how many operand bits toggle, so this, not the loop on constants, is the rate
+ * a contraction on real data can be held against.  sink, *flops: as above. */
+int eg_ceiling_mfma_bf16_random(void *sink, int cus, int iters, double *flops, void *hip_stream);
+
 /* Enqueues a register-resident loop of fp32 subtract + fused-multiply-add pairs (the instruction pair of the
  * squared-distance kernel): `waves_per_simd` (1, 2 or 4) waves on each SIMD of `cus` compute units, iters*64 pairs
  * per lane.  sink: device, >= 4 bytes, never written.  *pairs (host) receives the launch's pair count. */

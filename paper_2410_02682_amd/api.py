@@ -208,6 +208,13 @@ def eg_ceiling_mfma_bf16(sink_ptr: int, cus: int, waves_per_simd: int, iters: in
     return fl.value
 
 
+def eg_ceiling_mfma_bf16_random(sink_ptr: int, cus: int, iters: int, stream: int = 0) -> float:
+    """Enqueues the MFMA loop on pseudo-random operands; returns its operation count (the caller times it)."""
+    fl = ctypes.c_double()
+    _check(_lib.load().eg_ceiling_mfma_bf16_random(ctypes.c_void_p(sink_ptr), cus, iters, ctypes.byref(fl), ctypes.c_void_p(stream)))
+    return fl.value
+
+
 def eg_ceiling_valu_f32(sink_ptr: int, cus: int, waves_per_simd: int, iters: int, stream: int = 0) -> float:
     """Enqueues the register-resident subtract + fused-multiply-add loop; returns its pair count."""
     n = ctypes.c_double()

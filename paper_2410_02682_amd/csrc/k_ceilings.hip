@@ -26,6 +26,40 @@ __global__ __launch_bounds__(256) void k_mfma_ceiling(float *sink, int iters)
     if (s == -1.f) sink[0] = s;      // never true: keeps the loop alive
 }
 
+// The same loop on operands that look like data: four A and four B fragments of pseudo-random bf16 values per lane
+// (sign and mantissa bits from a hash, magnitudes around one), 16 accumulator tiles.  What the matrix pipes deliver
+// depends on how many operand bits toggle, because the chip lowers its clock under the power they draw; this is the
+// rate to hold a contraction on real operands against.
+__global__ __launch_bounds__(256) void k_mfma_ceiling_random(float *sink, int iters, unsigned seed)
+{
+    bf16x8 a[4], b[4];
+    unsigned h = (threadIdx.x + 1) * 2654435761u ^ seed ^ (blockIdx.x * 40503u);
+    for (int s = 0; s < 4; s++)
+        for (int i = 0; i < 8; i++) {
+            h = h * 1664525u + 1013904223u;
+            const unsigned short ua = (unsigned short)(0x3c00 + ((h >> 16) & 0x83ff));
+            h = h * 1664525u + 1013904223u;
+            const unsigned short ub = (unsigned short)(0x3c00 + ((h >> 16) & 0x83ff));
+            a[s][i] = __builtin_bit_cast(__bf16, ua);
+            b[s][i] = __builtin_bit_cast(__bf16, ub);
+        }
+    f32x16 acc[4][4];
+    for (int i = 0; i < 4; i++)
+        for (int j = 0; j < 4; j++)
+            for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
+    for (int it = 0; it < iters; it++) {
+#pragma unroll
+        for (int i = 0; i < 4; i++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    float s = 0.f;
+    for (int i = 0; i < 4; i++)
+        for (int j = 0; j < 4; j++)
+            for (int r = 0; r < 16; r++) s += acc[i][j][r];
+    if (s == -1.2345f) sink[0] = s;  // never true: keeps the loop alive
+}
+
 // Register-resident chains of the instruction pair the distance kernels live on: subtract, then fused
 // multiply-add of the difference with itself into an accumulator (16 independent accumulators per lane).
 __global__ __launch_bounds__(256) void k_valu_ceiling(float *sink, int iters, float x)
@@ -70,6 +104,18 @@ int eg_ceiling_mfma_bf16(void *sink, int cus, int waves_per_simd, int iters, dou
     hipLaunchKernelGGL(eg::k_mfma_ceiling, dim3(wgs), dim3(256), 0, (hipStream_t)hip_stream, (float *)sink, iters);
     if (hipGetLastError() != hipSuccess) return eg::fail(EG_ERR_HIP, "k_mfma_ceiling launch failed");
     *flops = (double)wgs * 4.0 * iters * 8.0 * (2.0 * 32 * 32 * 16);
+    return EG_OK;
+}
+
+// As eg_ceiling_mfma_bf16, on pseudo-random operands (16 MFMAs per wave and iteration); one wave per SIMD only,
+// the loop holds 256 accumulator registers.
+int eg_ceiling_mfma_bf16_random(void *sink, int cus, int iters, double *flops, void *hip_stream)
+{
+    if (!sink || !flops) return eg::fail(EG_ERR_NULL, "eg_ceiling_mfma_bf16_random: NULL argument");
+    if (cus < 1 || iters < 1) return eg::fail(EG_ERR_LIMIT, "eg_ceiling_mfma_bf16_random: bad launch shape");
+    hipLaunchKernelGGL(eg::k_mfma_ceiling_random, dim3(cus), dim3(256), 0, (hipStream_t)hip_stream, (float *)sink, iters, 7u);
+    if (hipGetLastError() != hipSuccess) return eg::fail(EG_ERR_HIP, "k_mfma_ceiling_random launch failed");
+    *flops = (double)cus * 4.0 * iters * 16.0 * (2.0 * 32 * 32 * 16);
     return EG_OK;
 }
 
