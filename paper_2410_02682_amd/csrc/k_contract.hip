@@ -496,6 +496,12 @@ int launch_contract(ContractParams &p, void *stream)
     static const char *force = getenv("EINDECOMP_CONTRACT");
     const bool want_dma = force ? (strcmp(force, "dma") == 0) : (p.M >= 128 && p.N >= 128);
     if (want_dma && !(force && strcmp(force, "staged") == 0) && contract_dma_eligible(p)) return launch_contract_dma(p, stream);
+    // a launch with few 128 x 128 tiles is a latency chain of MFMAs on a handful of compute units: quarter the tiles
+    const int64_t tiles128 = p.n_tuples * p.n_batch * ((p.M + 127) / 128) * ((p.N + 127) / 128);
+    if (tiles128 <= 64) {
+        if (p.in_dtype == EG_BF16) return launch_cfg<Cfg<64, 64, 32, 32, true>>(p, stream);
+        return launch_cfg<Cfg<64, 64, 32, 32, false>>(p, stream);
+    }
     if (p.in_dtype == EG_BF16) return launch_cfg<Cfg<128, 128, 64, 64, true>>(p, stream);
     return launch_cfg<Cfg<128, 128, 64, 64, false>>(p, stream);
 }
