@@ -123,6 +123,20 @@ def test_contraction_layouts(spec, bx, by, dtype, tile, monkeypatch):
     assert bad == 0, f"{bad} elements out of tolerance (worst {worst:.2f}x)"
 
 
+@pytest.mark.parametrize("spec,bx,by", [("ij,jk->ik", (4000, 72), (72, 2200)), ("ji,kj->ik", (100, 4000), (2200, 100))])
+def test_fp32_contraction_with_many_tiles(spec, bx, by):
+    # 16 x 9 tiles of 256 x 256 with ragged edges: enough of them for the fp32 kernel's eight-wave configuration
+    print(f"fp32 contraction {spec} {bx} {by}", flush=True)
+    x = HostTensor.from_f32(uniform_pm1(21, 0, int(np.prod(bx))).reshape(bx), "f32")
+    y = HostTensor.from_f32(uniform_pm1(21, 1, int(np.prod(by))).reshape(by), "f32")
+    w = single_vertex(spec, x, y, "f32", parts={"whole": {}, "d": {"i": 2, "j": 2}})
+    ref = run_graph(w, {"X": x, "Y": y})["Z"]
+    for pname in ("whole", "d"):
+        got = _run(w, pname, {"X": x, "Y": y})["Z"]
+        bad, worst = violations(got.as_f64(), ref.as_f64(), RTOL_F32)
+        assert bad == 0, f"{pname}: {bad} elements out of tolerance (worst {worst:.2f}x)"
+
+
 def test_contraction_routes_to_mfma_and_bf16_output_rounds_once():
     torch, GraphRunner, to_device, to_host = _gpu()
     x = HostTensor.from_f32(normal(12, 0, 256 * 192, 1.0).reshape(256, 192), "bf16")
