@@ -492,19 +492,22 @@ int launch_contract(ContractParams &p, void *stream)
         if (p.in_dtype == EG_BF16) return launch_alu_ops<Cfg<128, 128, 64, 64, true>>(p, stream);
         return launch_alu_ops<Cfg<128, 128, 64, 64, false>>(p, stream);
     }
-    // large bf16 blocks take the direct-to-LDS kernel; EINDECOMP_CONTRACT=staged|dma forces one of the two
-    static const char *force = getenv("EINDECOMP_CONTRACT");
-    const bool want_dma = force ? (strcmp(force, "dma") == 0) : (p.M >= 128 && p.N >= 128);
-    if (want_dma && !(force && strcmp(force, "staged") == 0) && contract_dma_eligible(p)) return launch_contract_dma(p, stream);
-    // a launch with few 128 x 128 tiles is a latency chain of MFMAs on a handful of compute units: quarter the tiles
+    // Blocks of at least 128 x 128 take the direct-to-LDS kernel when their layout allows; EINDECOMP_CONTRACT=staged|dma
+    // forces one of the two (read at every launch: tests switch it).  A handful of small fp32 blocks (configuration 1:
+    // eight blocks of 128^3) is a latency chain of slow MFMAs on as many compute units, which 64 x 64 tiles of the
+    // register-staged kernel spread over four times as many.
+    const char *force = getenv("EINDECOMP_CONTRACT");
     const int64_t tiles128 = p.n_tuples * p.n_batch * ((p.M + 127) / 128) * ((p.N + 127) / 128);
+    const bool tiny_f32 = p.in_dtype == EG_F32 && tiles128 <= 64;
+    const bool want_dma = force ? (strcmp(force, "dma") == 0) : (p.M >= 128 && p.N >= 128 && !tiny_f32);
+    if (want_dma && !(force && strcmp(force, "staged") == 0) && contract_dma_eligible(p)) return launch_contract_dma(p, stream);
     if (tiles128 <= 64) {
         if (p.in_dtype == EG_BF16) return launch_cfg<Cfg<64, 64, 32, 32, true>>(p, stream);
         return launch_cfg<Cfg<64, 64, 32, 32, false>>(p, stream);
     }
     if (p.in_dtype == EG_BF16) return launch_cfg<Cfg<128, 128, 64, 64, true>>(p, stream);
-    // fp32: 256 x 256 tiles (eight waves of 128 x 64) once there are enough of them to occupy half the chip
-    // (measured 98-113 TFLOP/s on 4096^3 and 8192^3 against 81-101 with 128 x 128 tiles)
+    // fp32 shapes the direct-to-LDS kernel cannot take: 256 x 256 tiles (eight waves of 128 x 64) once there are enough
+    // of them to occupy half the chip (measured 98-113 TFLOP/s on 4096^3 and 8192^3 against 81-101 with 128 x 128 tiles)
     const int64_t tiles256 = p.n_tuples * p.n_batch * ((p.M + 255) / 256) * ((p.N + 255) / 256);
     if (tiles256 >= 128) return launch_cfg<Cfg<256, 256, 128, 64, false>>(p, stream);
     return launch_cfg<Cfg<128, 128, 64, 64, false>>(p, stream);

@@ -1,21 +1,23 @@
-// bf16 block contraction with direct global->LDS staging (no register round trip), 256x256x64 tiles.
+// Block contraction (bf16 or fp32 operands, fp32 accumulation) with direct global->LDS staging, no register round trip.
 //
 // Same operation as k_contract.hip (the per-block kernel K of Section 4.3 of the paper for (x) = multiply,
-// (+) = sum, all tuples of the join in one launch), specialised for the large bf16 blocks:
-//   * 8 waves per workgroup (two per SIMD), each owning a 128x64 output patch = 4x2 MFMA 32x32x16 tiles (fp32 accumulators);
-//   * persistent workgroups, one per compute unit, each walking over its share of the output tiles;
+// (+) = sum, all tuples of the join in one launch), specialised for blocks of at least 128 x 128:
+//   * 256 x 256 output tiles, 8 waves per workgroup (two per SIMD), each owning a 128x64 patch = 4x2 MFMA 32x32 tiles;
+//     or 128 x 128 tiles with 4 waves and two workgroups per compute unit when large tiles would leave the chip idle;
+//   * persistent workgroups, each walking over its share of the output tiles;
 //   * every 16-byte chunk of both operand tiles travels global memory -> LDS directly; the chunk a lane
 //     fetches is chosen so that the contiguous 1 KiB an instruction deposits is already the swizzled layout;
-//   * an operand contiguous along K sits in LDS as [row][64 k] and is read with 16-byte reads; an operand
-//     contiguous along M or N sits as [k][256 mn] and is read with the 16-bit transposing LDS read, which
-//     hands every lane four consecutive k for its own column;
+//   * a stage is 128 bytes of k per tile row (64 k of bf16, 32 k of fp32) and four k-steps: one 32x32x16 bf16
+//     MFMA per 32x32 tile and step, or four 32x32x2 fp32 MFMAs on the four k a 16-byte chunk brings;
+//   * an operand contiguous along K sits in LDS as [row][128 bytes of k] and is read with 16-byte reads; an operand
+//     contiguous along M or N sits as [k][TS mn] and is read with the 16-bit transposing LDS read (bf16), which
+//     hands every lane four consecutive k for its own column, or with four 4-byte reads (fp32);
 //   * two LDS stages: the loads of stage t+1 are in flight while the MFMAs of stage t run.
 //   * the loads are buffer loads with a 2 GiB descriptor: a lane whose chunk lies beyond K in the last,
 //     partial stage is given an offset outside the descriptor, fetches nothing and deposits zeros.
 // Requirements (checked on the host): K is one label of any extent, or several whose innermost extent is a
-// multiple of 64 (a stage never straddles two K labels); byte offsets within a tile (256 rows, 64 k-rows) fit 31
-// bits and rows do not lie before their tile's first row.  Anything else goes
-// to the register-staged kernel.
+// multiple of the stage's k (a stage never straddles two K labels); byte offsets within a tile (256 rows, 64 k-rows)
+// fit 31 bits and rows do not lie before their tile's first row.  Anything else goes to the register-staged kernel.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -33,7 +35,13 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 namespace dma {
 
-constexpr int BK = 64;                            // k per stage; output tiles are TS x TS (TS = 256 or 128)
+// Element type: bf16 (F32 = false) or fp32.  A stage holds 128 bytes of k per row: 64 k of bf16, 32 k of fp32, and is
+// four k-steps either way (one 32x32x16 bf16 MFMA, or four 32x32x2 fp32 MFMAs on the four k a 16-byte chunk brings).
+template <bool F32> struct Elem {
+    static constexpr int ES = F32 ? 4 : 2;         // bytes per element
+    static constexpr int EPC = 16 / ES;            // elements per 16-byte chunk
+    static constexpr int BK = 128 / ES;            // k per stage; output tiles are TS x TS (TS = 256 or 128)
+};
 
 #define EG_LDS(p) ((__attribute__((address_space(3))) void *)(p))
 #define EG_GLB(p) ((const __attribute__((address_space(1))) void *)(p))
@@ -59,10 +67,11 @@ __device__ __forceinline__ void decode_group2(const DimList &g, int64_t idx, int
 //   MC: a k-row holds CPR = TS/8 chunks, so one instruction deposits KR = 64/CPR k-rows (2 for TS = 256, 4 for
 //       TS = 128): instruction i of wave w deposits k-rows KR (NW i+w) .. +KR-1, lane -> k-row +lane/CPR,
 //       physical chunk lane%CPR, logical chunk (lane%CPR) ^ 4*(krow%4), krow%4 = (KR w + lane/CPR)%4.
-template <bool KC, int NW, int TS>
+template <bool KC, int NW, int TS, bool F32>
 struct Src {
+    static constexpr int ES = Elem<F32>::ES, EPC = Elem<F32>::EPC;
     static constexpr int LD = TS / 8 / NW;
-    static constexpr int CPR = TS / 8, KR = 64 / CPR;
+    static constexpr int CPR = TS / EPC, KR = 64 / CPR;   // chunks per k-row of an MC tile, k-rows per 1 KiB instruction
     uint32_t boff[LD];        // byte offset of the chunk instruction i fetches, relative to the stage's first k
     int kl;                   // k (within the stage) of chunk 0 of this lane; chunk i sits at kl (KC) or kl + KR NW i (MC)
 
@@ -71,26 +80,28 @@ struct Src {
         if (KC) {
             // LDS row of this lane's chunk is (NW i+wave)*8 + lane/8; its swizzle key (row>>1)&7 does not depend on i
             const int lc = (lane & 7) ^ ((wave * 4 + (lane >> 4)) & 7);
-            kl = lc * 8;
+            kl = lc * EPC;
 #pragma unroll
             for (int i = 0; i < LD; i++) {
                 int64_t r = first + (NW * i + wave) * 8 + (lane >> 3);
                 r = r < extent ? r : extent - 1;
                 int64_t o0, o1;
                 decode_group2(grp, r, o0, o1);
-                boff[i] = (uint32_t)((o0 - origin + lc * 8) * 2);
+                boff[i] = (uint32_t)((o0 - origin + lc * EPC) * ES);
             }
         } else {
+            // bf16: chunks of four consecutive k-rows are XOR-ed apart for the transposing reads; fp32 fragments are read
+            // with 4-byte reads of 32 consecutive columns, which need no swizzle
             const int kr4 = (KR * wave + lane / CPR) & 3;
-            const int lc = (lane % CPR) ^ (4 * kr4);
-            int64_t m = first + lc * 8;
-            m = m + 8 <= extent ? m : extent - 8;
+            const int lc = F32 ? lane % CPR : (lane % CPR) ^ (4 * kr4);
+            int64_t m = first + lc * EPC;
+            m = m + EPC <= extent ? m : extent - EPC;
             int64_t o0, o1;
             decode_group2(grp, m, o0, o1);
             kl = KR * wave + lane / CPR;
 #pragma unroll
             for (int i = 0; i < LD; i++)
-                boff[i] = (uint32_t)((o0 - origin + (KR * NW * i + kl) * k_inner_stride) * 2);
+                boff[i] = (uint32_t)((o0 - origin + (KR * NW * i + kl) * k_inner_stride) * ES);
         }
     }
     // offset handed to load i of a stage that has `krem` valid k left: beyond the descriptor when the chunk's k is past the end
@@ -120,44 +131,60 @@ __device__ __forceinline__ int mc_frag_off(int col0, int ks, int lane, int secon
     return kr * (TS * 2) + (pc << 4) + ((n & 7) << 1);
 }
 
-// Fragments of one k-step (16 k): RT 32-row A fragments and NT 32-column B fragments of this wave
-// (row0, col0: first row / column of the wave's patch inside the tile).
-template <bool A_KC, bool B_KC, int RT, int NT, int TS>
-__device__ __forceinline__ void load_frags(const char *la, const char *lb, int ks, bf16x8 (&a)[RT], bf16x8 (&b)[NT], int row0, int col0, int lane)
+// Fragments of one k-step (16 k of bf16, 8 k of fp32): RT 32-row A fragments and NT 32-column B fragments of this wave
+// (row0, col0: first row / column of the wave's patch inside the tile).  A fragment is 16 bytes per lane: eight bf16
+// (k = 8 * (lane / 32) + 0..7 of the step) or four fp32 (k = 4 * (lane / 32) + 0..3).
+template <bool KC, int TS, bool F32>
+__device__ __forceinline__ u32x4 load_frag(const char *l, int first, int ks, int lane)
+{
+    if (KC) return *(const u32x4 *)(l + kc_frag_off(first + (lane & 31), ks, lane));
+    if (F32) {
+        const char *q = l + (8 * ks + 4 * (lane >> 5)) * (TS * 4) + (first + (lane & 31)) * 4;
+        u32x4 v;
+        v.x = *(const uint32_t *)q; v.y = *(const uint32_t *)(q + TS * 4); v.z = *(const uint32_t *)(q + 2 * TS * 4); v.w = *(const uint32_t *)(q + 3 * TS * 4);
+        return v;
+    }
+    short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(l + mc_frag_off<TS>(first, ks, lane, 0)));
+    short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(l + mc_frag_off<TS>(first, ks, lane, 1)));
+    u32x4 v;
+    short4v *dst = (short4v *)&v;
+    dst[0] = lo; dst[1] = hi;
+    return v;
+}
+
+template <bool A_KC, bool B_KC, int RT, int NT, int TS, bool F32>
+__device__ __forceinline__ void load_frags(const char *la, const char *lb, int ks, u32x4 (&a)[RT], u32x4 (&b)[NT], int row0, int col0, int lane)
 {
 #pragma unroll
-    for (int i = 0; i < RT; i++) {
-        if (A_KC) {
-            a[i] = *(const bf16x8 *)(la + kc_frag_off(row0 + i * 32 + (lane & 31), ks, lane));
-        } else {
-            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off<TS>(row0 + i * 32, ks, lane, 0)));
-            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(la + mc_frag_off<TS>(row0 + i * 32, ks, lane, 1)));
-            short4v *dst = (short4v *)&a[i];
-            dst[0] = lo; dst[1] = hi;
-        }
-    }
+    for (int i = 0; i < RT; i++) a[i] = load_frag<A_KC, TS, F32>(la, row0 + i * 32, ks, lane);
 #pragma unroll
-    for (int j = 0; j < NT; j++) {
-        if (B_KC) {
-            b[j] = *(const bf16x8 *)(lb + kc_frag_off(col0 + j * 32 + (lane & 31), ks, lane));
-        } else {
-            short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off<TS>(col0 + j * 32, ks, lane, 0)));
-            short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)EG_LDS(lb + mc_frag_off<TS>(col0 + j * 32, ks, lane, 1)));
-            short4v *dst = (short4v *)&b[j];
-            dst[0] = lo; dst[1] = hi;
-        }
+    for (int j = 0; j < NT; j++) b[j] = load_frag<B_KC, TS, F32>(lb, col0 + j * 32, ks, lane);
+}
+
+// One 32x32 tile's share of a k-step.
+template <bool F32>
+__device__ __forceinline__ void mma(const u32x4 &a, const u32x4 &b, f32x16 &acc)
+{
+    if (F32) {
+        // the elements are copied out first: a bit cast applied directly to an element of a vector reference read element 0 every time
+        const uint32_t a0 = a.x, a1 = a.y, a2 = a.z, a3 = a.w, b0 = b.x, b1 = b.y, b2 = b.z, b3 = b.w;
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a0), __uint_as_float(b0), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a1), __uint_as_float(b1), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a2), __uint_as_float(b2), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a3), __uint_as_float(b3), acc, 0, 0, 0);
+    } else {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
     }
 }
 
 // MFMAs of one k-step for rows [I0, I1) of this wave's RT x NT grid of 32x32 tiles.
-template <int I0, int I1, int RT, int NT>
-__device__ __forceinline__ void mfma_rows(const bf16x8 (&a)[RT], const bf16x8 (&b)[NT], f32x16 (&acc)[RT][NT])
+template <int I0, int I1, int RT, int NT, bool F32>
+__device__ __forceinline__ void mfma_rows(const u32x4 (&a)[RT], const u32x4 (&b)[NT], f32x16 (&acc)[RT][NT])
 {
 #pragma unroll
     for (int i = I0; i < I1; i++)
 #pragma unroll
-        for (int j = 0; j < NT; j++)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NT; j++) mma<F32>(a[i], b[j], acc[i][j]);
 }
 
 // What is uniform over a workgroup about one output tile.
@@ -180,13 +207,14 @@ struct TileInfo {
 // The kernel is persistent: the workgroups of a compute unit walk over their share of the tiles.  While a tile's
 // epilogue runs, the first two stages of the workgroup's next tile are already on their way into LDS, and the
 // next tile's addressing was worked out while the current tile waited for its own first stage.
-template <int TS, int NW, bool A_KC, bool B_KC, bool ODD>
+template <int TS, int NW, bool A_KC, bool B_KC, bool ODD, bool F32>
 __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(const ContractParams p)
 {
+    constexpr int ES = Elem<F32>::ES, EPC = Elem<F32>::EPC, BK = Elem<F32>::BK;
     constexpr int WN = NW / 2;                        // waves side by side
     constexpr int RT = TS / 64, NT = TS / WN / 32;    // 32x32 MFMA tiles per wave: RT down, NT across
     constexpr int LD = TS / 8 / NW;                   // direct loads per operand tile, wave and stage
-    constexpr int TILE_BYTES = TS * BK * 2;           // one operand tile of one stage
+    constexpr int TILE_BYTES = TS * 128;              // one operand tile of one stage: 128 bytes of k per row
     constexpr int STAGE_BYTES = 2 * TILE_BYTES;
     constexpr int TBL = 2 * TS * 8;                   // one set of Z offset tables (TS rows, TS columns)
     constexpr int DPM = 2 * LD / (RT * NT);           // direct loads issued after each MFMA of a stage's last k-step
@@ -249,11 +277,11 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
         // lane offsets are 32 bits and count from the tile's first row (an operand contiguous along M or N reads whole
         // 8-element chunks, so near the block's edge its first chunk may start up to 7 elements before the tile)
         int64_t unused;
-        const int64_t fm = A_KC || t.m0 + 8 <= p.M ? t.m0 : p.M - 8, fn = B_KC || t.n0 + 8 <= p.N ? t.n0 : p.N - 8;
+        const int64_t fm = A_KC || t.m0 + EPC <= p.M ? t.m0 : p.M - EPC, fn = B_KC || t.n0 + EPC <= p.N ? t.n0 : p.N - EPC;
         decode_group2(p.m, fm, t.ox0, unused);
         decode_group2(p.n, fn, t.oy0, unused);
-        t.xb = uniform_ptr((const char *)p.x + (bx + t.ox0) * 2);
-        t.yb = uniform_ptr((const char *)p.y + (by + t.oy0) * 2);
+        t.xb = uniform_ptr((const char *)p.x + (bx + t.ox0) * ES);
+        t.yb = uniform_ptr((const char *)p.y + (by + t.oy0) * ES);
         t.bz = bz;
         t.agg = agg;
     };
@@ -261,15 +289,15 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
     const int64_t nk = (p.K + BK - 1) / BK;
 
     TileInfo cur, nxt;
-    Src<A_KC, NW, TS> sa;
-    Src<B_KC, NW, TS> sb;
+    Src<A_KC, NW, TS, F32> sa;
+    Src<B_KC, NW, TS, F32> sb;
     const char *xb, *yb;                              // bases the direct loads currently work from
 
     // Uniform source pointers of consecutive stages, and how many k each still has (64: a full stage; 0: past the end,
     // every lane of its direct loads then deposits zeros without fetching).  Inside a run of the innermost K label
     // a stage lies one fixed step after the one before; only where a run ends (several fused K labels) are the
     // offsets decoded afresh, so the main loop's scalar work per stage is two additions.
-    const int64_t dka = (int64_t)BK * p.k.s0[kin] * 2, dkb = (int64_t)BK * p.k.s1[kin] * 2;
+    const int64_t dka = (int64_t)BK * p.k.s0[kin] * ES, dkb = (int64_t)BK * p.k.s1[kin] * ES;
     const int64_t run = p.k.n == 1 ? p.K : p.k.ext[kin];
     const char *ga_n, *gb_n;
     int64_t k_n, run_left;
@@ -287,8 +315,8 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
         } else {
             int64_t ka, kb;
             decode_group2(p.k, k_n, ka, kb);           // offset of the next run's first k in X and in Y
-            ga_n = xb + ka * 2;
-            gb_n = yb + kb * 2;
+            ga_n = xb + ka * ES;
+            gb_n = yb + kb * ES;
             run_left = run;
         }
     };
@@ -347,19 +375,19 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
     // the direct loads of the stage after next and the first fragment reads of the next stage.
     // sched_barrier pins this order against the compiler's own scheduling.
     f32x16 acc[RT][NT];
-    bf16x8 a0[RT], b0[NT], a1[RT], b1[NT];
+    u32x4 a0[RT], b0[NT], a1[RT], b1[NT];
 #define EG_PIN() __builtin_amdgcn_sched_barrier(0)
 #define EG_KSTEP(FA, FB, NA, NB, BUF, KS_NEXT)                                                    \
-    mfma_rows<0, 1, RT, NT>(FA, FB, acc); EG_PIN();                                                   \
-    load_frags<A_KC, B_KC, RT, NT, TS>(BUF, BUF + TILE_BYTES, KS_NEXT, NA, NB, row0, col0, lane); EG_PIN(); \
-    mfma_rows<1, RT, RT, NT>(FA, FB, acc); EG_PIN();
+    mfma_rows<0, 1, RT, NT, F32>(FA, FB, acc); EG_PIN();                                                   \
+    load_frags<A_KC, B_KC, RT, NT, TS, F32>(BUF, BUF + TILE_BYTES, KS_NEXT, NA, NB, row0, col0, lane); EG_PIN(); \
+    mfma_rows<1, RT, RT, NT, F32>(FA, FB, acc); EG_PIN();
 #define EG_STAGE_NEXT(C, O, HAS_NEXT2) /* one stage; its successor is already in flight into O */     \
     do {                                                                                          \
-        mfma_rows<0, 1, RT, NT>(a0, b0, acc); EG_PIN();                                               \
+        mfma_rows<0, 1, RT, NT, F32>(a0, b0, acc); EG_PIN();                                               \
         const bool has2 = (HAS_NEXT2);                                                            \
         next_stage(ga2, gb2, kr2);          /* scalar work rides under the MFMAs */               \
-        load_frags<A_KC, B_KC, RT, NT, TS>(C, C + TILE_BYTES, 1, a1, b1, row0, col0, lane); EG_PIN();     \
-        mfma_rows<1, RT, RT, NT>(a0, b0, acc); EG_PIN();                                               \
+        load_frags<A_KC, B_KC, RT, NT, TS, F32>(C, C + TILE_BYTES, 1, a1, b1, row0, col0, lane); EG_PIN();     \
+        mfma_rows<1, RT, RT, NT, F32>(a0, b0, acc); EG_PIN();                                               \
         EG_KSTEP(a1, b1, a0, b0, C, 2)                                                            \
         EG_KSTEP(a0, b0, a1, b1, C, 3)                                                            \
         __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): this wave's deposits for O landed */     \
@@ -367,13 +395,13 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
         EG_PIN();                                                                                 \
         /* last k-step: every MFMA is followed by DPM direct loads of the stage after next into C */ \
         _Pragma("unroll") for (int j = 0; j < NT; j++) {                                          \
-            acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[0], b1[j], acc[0][j], 0, 0, 0); EG_PIN(); \
+            mma<F32>(a1[0], b1[j], acc[0][j]); EG_PIN();                                          \
             if (has2) { _Pragma("unroll") for (int d = 0; d < DPM; d++) dma(DPM * j + d, ga2, gb2, kr2, C); } \
             EG_PIN();                                                                             \
         }                                                                                         \
-        load_frags<A_KC, B_KC, RT, NT, TS>(O, O + TILE_BYTES, 0, a0, b0, row0, col0, lane); EG_PIN();     \
+        load_frags<A_KC, B_KC, RT, NT, TS, F32>(O, O + TILE_BYTES, 0, a0, b0, row0, col0, lane); EG_PIN();     \
         _Pragma("unroll") for (int q = 0; q < (RT - 1) * NT; q++) {                               \
-            acc[1 + q / NT][q % NT] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1[1 + q / NT], b1[q % NT], acc[1 + q / NT][q % NT], 0, 0, 0); EG_PIN(); \
+            mma<F32>(a1[1 + q / NT], b1[q % NT], acc[1 + q / NT][q % NT]); EG_PIN();              \
             if (has2) { _Pragma("unroll") for (int d = 0; d < DPM; d++) dma(DPM * (NT + q) + d, ga2, gb2, kr2, C); } \
             EG_PIN();                                                                             \
         }                                                                                         \
@@ -405,7 +433,7 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
                 for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
         __builtin_amdgcn_s_waitcnt(0x0F70);           // both stages (and the previous tile's stores) are done
         __syncthreads();
-        load_frags<A_KC, B_KC, RT, NT, TS>(lds0, lds0 + TILE_BYTES, 0, a0, b0, row0, col0, lane);
+        load_frags<A_KC, B_KC, RT, NT, TS, F32>(lds0, lds0 + TILE_BYTES, 0, a0, b0, row0, col0, lane);
         // Every stage, the last one included, runs the same straight-line code (the last one pays for one idle
         // barrier and a set of unused fragment reads): an MFMA under a branch inside the loop would make the
         // compiler shuffle the accumulator registers.  The stage count's parity is a template parameter.
@@ -548,38 +576,41 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
 #undef EG_PIN
 }
 
-template <int TS, int NW, bool A_KC, bool B_KC, bool ODD>
+template <int TS, int NW, bool A_KC, bool B_KC, bool ODD, bool F32>
 static int launch_one(ContractParams &p, void *stream)
 {
-    hipLaunchKernelGGL((k_contract_dma<TS, NW, A_KC, B_KC, ODD>), dim3((unsigned)p.grid), dim3(NW * 64), 0, (hipStream_t)stream, p);
+    hipLaunchKernelGGL((k_contract_dma<TS, NW, A_KC, B_KC, ODD, F32>), dim3((unsigned)p.grid), dim3(NW * 64), 0, (hipStream_t)stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(EG_ERR_HIP, "k_contract_dma launch failed: %s", hipGetErrorString(e));
     return EG_OK;
 }
 
-template <int TS, int NW, bool A_KC, bool B_KC>
+template <int TS, int NW, bool A_KC, bool B_KC, bool F32>
 static int launch_parity(ContractParams &p, void *stream)
 {
-    return (((p.K + BK - 1) / BK) & 1) ? launch_one<TS, NW, A_KC, B_KC, true>(p, stream) : launch_one<TS, NW, A_KC, B_KC, false>(p, stream);
+    constexpr int BK = Elem<F32>::BK;
+    return (((p.K + BK - 1) / BK) & 1) ? launch_one<TS, NW, A_KC, B_KC, true, F32>(p, stream) : launch_one<TS, NW, A_KC, B_KC, false, F32>(p, stream);
 }
 
-template <int TS, int NW>
+template <int TS, int NW, bool F32>
 static int launch_layout(ContractParams &p, void *stream)
 {
-    if (p.a_kcontig) return p.b_kcontig ? launch_parity<TS, NW, true, true>(p, stream) : launch_parity<TS, NW, true, false>(p, stream);
-    return p.b_kcontig ? launch_parity<TS, NW, false, true>(p, stream) : launch_parity<TS, NW, false, false>(p, stream);
+    if (p.a_kcontig) return p.b_kcontig ? launch_parity<TS, NW, true, true, F32>(p, stream) : launch_parity<TS, NW, true, false, F32>(p, stream);
+    return p.b_kcontig ? launch_parity<TS, NW, false, true, F32>(p, stream) : launch_parity<TS, NW, false, false, F32>(p, stream);
 }
 
 }  // namespace dma
 
 bool contract_dma_eligible(const ContractParams &p)
 {
-    if (p.in_dtype != EG_BF16) return false;
+    if (p.in_dtype != EG_BF16 && p.in_dtype != EG_F32) return false;
+    const bool f32 = p.in_dtype == EG_F32;
+    const int64_t es = f32 ? 4 : 2, epc = 16 / es, bk = 128 / es;
     if (p.m.n < 1 || p.n.n < 1 || p.k.n < 1) return false;
-    if (p.k.n > 1 && p.k.ext[p.k.n - 1] % dma::BK) return false;           // a stage never straddles two K labels
-    if ((p.a_kcontig || p.b_kcontig) && p.K % 8) return false;             // 16-byte chunks along K are whole or absent
+    if (p.k.n > 1 && p.k.ext[p.k.n - 1] % bk) return false;                // a stage never straddles two K labels
+    if ((p.a_kcontig || p.b_kcontig) && p.K % epc) return false;           // 16-byte chunks along K are whole or absent
     // Lane offsets count from the tile's first row and must stay below 2^31 bytes: rows of a tile must not lie before
-    // its first row (strides nested, outermost first), and 256 rows plus the 64 k-rows of a stage must span less.
+    // its first row (strides nested, outermost first), and 256 rows plus the k-rows of a stage must span less.
     auto tile_span = [](const DimList &g) -> int64_t {            // largest offset of a row within 255 rows of another
         int64_t inner = 1, span = 0;
         for (int i = g.n - 1; i >= 0; i--) {
@@ -594,12 +625,13 @@ bool contract_dma_eligible(const ContractParams &p)
     const int kin = p.k.n - 1;
     const int64_t sx = tile_span(p.m), sy = tile_span(p.n);
     if (sx < 0 || sy < 0) return false;
-    if (sx + (p.a_kcontig ? 64 : 64 * std::max<int64_t>(p.k.s0[kin], 1)) >= (1ll << 30) - 64) return false;
-    if (sy + (p.b_kcontig ? 64 : 64 * std::max<int64_t>(p.k.s1[kin], 1)) >= (1ll << 30) - 64) return false;
-    if (p.a_kcontig ? p.k.s0[p.k.n - 1] != 1 : (p.m.s0[p.m.n - 1] != 1 || p.m.ext[p.m.n - 1] % 8)) return false;
-    if (p.b_kcontig ? p.k.s1[p.k.n - 1] != 1 : (p.n.s0[p.n.n - 1] != 1 || p.n.ext[p.n.n - 1] % 8)) return false;
-    if (!p.a_kcontig && p.M < 8) return false;
-    if (!p.b_kcontig && p.N < 8) return false;
+    const int64_t lim = ((1ll << 31) - 256) / es;                           // elements
+    if (sx + (p.a_kcontig ? 64 : 64 * std::max<int64_t>(p.k.s0[kin], 1)) >= lim) return false;
+    if (sy + (p.b_kcontig ? 64 : 64 * std::max<int64_t>(p.k.s1[kin], 1)) >= lim) return false;
+    if (p.a_kcontig ? p.k.s0[p.k.n - 1] != 1 : (p.m.s0[p.m.n - 1] != 1 || p.m.ext[p.m.n - 1] % epc)) return false;
+    if (p.b_kcontig ? p.k.s1[p.k.n - 1] != 1 : (p.n.s0[p.n.n - 1] != 1 || p.n.ext[p.n.n - 1] % epc)) return false;
+    if (!p.a_kcontig && p.M < epc) return false;
+    if (!p.b_kcontig && p.N < epc) return false;
     if (((uintptr_t)p.x & 15) || ((uintptr_t)p.y & 15)) return false;
     return true;
 }
@@ -640,9 +672,10 @@ int launch_contract_dma(ContractParams &p, void *stream)
     for (int l = 0; l < p.ts.n; l++) vec = vec && p.ts.step_z[l] % 8 == 0;
     p.out_vec = vec ? 1 : 0;
     const char *waves = getenv("EINDECOMP_DMA_WAVES");                // 4 or 8 waves per workgroup of the 256 x 256 kernel (for comparisons)
-    if (ts == 128) return dma::launch_layout<128, 4>(p, stream);
-    if (waves && atoi(waves) == 4) return dma::launch_layout<256, 4>(p, stream);
-    return dma::launch_layout<256, 8>(p, stream);
+    if (p.in_dtype == EG_F32) return ts == 128 ? dma::launch_layout<128, 4, true>(p, stream) : dma::launch_layout<256, 8, true>(p, stream);
+    if (ts == 128) return dma::launch_layout<128, 4, false>(p, stream);
+    if (waves && atoi(waves) == 4) return dma::launch_layout<256, 4, false>(p, stream);
+    return dma::launch_layout<256, 8, false>(p, stream);
 }
 
 }  // namespace eg

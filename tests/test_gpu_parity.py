@@ -106,13 +106,15 @@ LAYOUTS = [
 ]
 
 
-@pytest.mark.parametrize("dtype,tile", [("bf16", "128"), ("bf16", "256"), ("f32", "")])
+@pytest.mark.parametrize("dtype,tile", [("bf16", "128"), ("bf16", "256"), ("f32", "128"), ("f32", "256"), ("f32", "")])
 @pytest.mark.parametrize("spec,bx,by", LAYOUTS)
 def test_contraction_layouts(spec, bx, by, dtype, tile, monkeypatch):
-    # the direct-to-LDS bf16 kernel has two tile sizes and picks the small one for products this small: both are run
+    # the direct-to-LDS kernel has two tile sizes and would pick the small one (or, for fp32, the register-staged kernel)
+    # for products this small: each is run; ("f32", "") is the library's own choice
     print(f"contraction {spec} {bx} {by} {dtype} tile {tile or 'default'}", flush=True)
     if tile:
         monkeypatch.setenv("EINDECOMP_DMA_TILE", tile)
+        monkeypatch.setenv("EINDECOMP_CONTRACT", "dma")      # wherever the layout is eligible for it
     x = HostTensor.from_f32(uniform_pm1(11, 0, int(np.prod(bx))).reshape(bx), dtype)
     y = HostTensor.from_f32(uniform_pm1(11, 1, int(np.prod(by))).reshape(by), dtype)
     w = single_vertex(spec, x, y, "f32")
