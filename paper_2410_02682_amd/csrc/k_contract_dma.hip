@@ -15,9 +15,11 @@
 //   * two LDS stages: the loads of stage t+1 are in flight while the MFMAs of stage t run.
 //   * the loads are buffer loads with a 2 GiB descriptor: a lane whose chunk lies beyond K in the last,
 //     partial stage is given an offset outside the descriptor, fetches nothing and deposits zeros.
-// Requirements (checked on the host): K is one label of any extent, or several whose innermost extent is a
-// multiple of the stage's k (a stage never straddles two K labels); byte offsets within a tile (256 rows, 64 k-rows)
-// fit 31 bits and rows do not lie before their tile's first row.  Anything else goes to the register-staged kernel.
+// Several K labels: every run of the innermost one starts a stage of its own (a run of 96 k is a full stage and
+// a half-filled one), so a stage never straddles two runs.
+// Requirements (checked on the host): along a K-contiguous operand runs are whole 16-byte chunks on chunk boundaries;
+// byte offsets within a tile (256 rows, 64 k-rows) fit 31 bits and rows do not lie before their tile's first row.
+// Anything else goes to the register-staged kernel.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -285,39 +287,42 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
         t.bz = bz;
         t.agg = agg;
     };
-    const int kin = p.k.n - 1;                        // innermost K label: every 64-run of k lies inside it
-    const int64_t nk = (p.K + BK - 1) / BK;
+    const int kin = p.k.n - 1;                        // innermost K label: every stage lies inside one run of it
+    const int64_t run = p.k.n == 1 ? p.K : p.k.ext[kin];            // k of one run of the innermost K label
+    const int64_t nk = (p.K / run) * ((run + BK - 1) / BK);          // stages: every run starts a stage of its own
 
     TileInfo cur, nxt;
     Src<A_KC, NW, TS, F32> sa;
     Src<B_KC, NW, TS, F32> sb;
     const char *xb, *yb;                              // bases the direct loads currently work from
 
-    // Uniform source pointers of consecutive stages, and how many k each still has (64: a full stage; 0: past the end,
-    // every lane of its direct loads then deposits zeros without fetching).  Inside a run of the innermost K label
-    // a stage lies one fixed step after the one before; only where a run ends (several fused K labels) are the
-    // offsets decoded afresh, so the main loop's scalar work per stage is two additions.
+    // Uniform source pointers of consecutive stages, and how many k each has (a full stage, less at the end of a run of
+    // the innermost K label, 0 past the end: every lane of its direct loads then deposits zeros without fetching).
+    // Inside a run a stage lies one fixed step after the one before; where a run ends (several fused K labels) the
+    // next stage starts the next run and its offsets are decoded afresh, so a stage never straddles two runs and the
+    // main loop's scalar work per stage is two additions almost always.
     const int64_t dka = (int64_t)BK * p.k.s0[kin] * ES, dkb = (int64_t)BK * p.k.s1[kin] * ES;
-    const int64_t run = p.k.n == 1 ? p.K : p.k.ext[kin];
     const char *ga_n, *gb_n;
     int64_t k_n, run_left;
     auto first_stage = [&]() { k_n = 0; ga_n = xb; gb_n = yb; run_left = run; };
     auto next_stage = [&](const char *&ga, const char *&gb, int &krem) {
         ga = ga_n;
         gb = gb_n;
-        const int64_t left = p.K - k_n;
-        krem = left < BK ? (left > 0 ? (int)left : 0) : BK;
-        k_n += BK;
-        run_left -= BK;
-        if (run_left > 0 || p.k.n == 1 || k_n >= p.K) {
+        krem = k_n >= p.K ? 0 : (run_left < BK ? (int)run_left : BK);
+        if (run_left > BK) {
+            k_n += BK;
+            run_left -= BK;
             ga_n += dka;
             gb_n += dkb;
         } else {
-            int64_t ka, kb;
-            decode_group2(p.k, k_n, ka, kb);           // offset of the next run's first k in X and in Y
-            ga_n = xb + ka * ES;
-            gb_n = yb + kb * ES;
+            k_n += run_left;
             run_left = run;
+            if (k_n < p.K) {
+                int64_t ka, kb;
+                decode_group2(p.k, k_n, ka, kb);       // offset of the next run's first k in X and in Y
+                ga_n = xb + ka * ES;
+                gb_n = yb + kb * ES;
+            }
         }
     };
     // direct load i (0..LD-1: X tile, LD..2LD-1: Y tile) of a stage into the LDS stage at `dst`: a 2 GiB buffer descriptor
@@ -589,7 +594,8 @@ template <int TS, int NW, bool A_KC, bool B_KC, bool F32>
 static int launch_parity(ContractParams &p, void *stream)
 {
     constexpr int BK = Elem<F32>::BK;
-    return (((p.K + BK - 1) / BK) & 1) ? launch_one<TS, NW, A_KC, B_KC, true, F32>(p, stream) : launch_one<TS, NW, A_KC, B_KC, false, F32>(p, stream);
+    const int64_t run = p.k.n == 1 ? p.K : p.k.ext[p.k.n - 1];
+    return (((p.K / run) * ((run + BK - 1) / BK)) & 1) ? launch_one<TS, NW, A_KC, B_KC, true, F32>(p, stream) : launch_one<TS, NW, A_KC, B_KC, false, F32>(p, stream);
 }
 
 template <int TS, int NW, bool F32>
@@ -607,8 +613,15 @@ bool contract_dma_eligible(const ContractParams &p)
     const bool f32 = p.in_dtype == EG_F32;
     const int64_t es = f32 ? 4 : 2, epc = 16 / es, bk = 128 / es;
     if (p.m.n < 1 || p.n.n < 1 || p.k.n < 1) return false;
-    if (p.k.n > 1 && p.k.ext[p.k.n - 1] % bk) return false;                // a stage never straddles two K labels
-    if ((p.a_kcontig || p.b_kcontig) && p.K % epc) return false;           // 16-byte chunks along K are whole or absent
+    // every run of the innermost K label starts a stage; along a K-contiguous operand 16-byte chunks must be whole and
+    // aligned, so runs are whole chunks and start on chunk boundaries
+    const int64_t run = p.k.n == 1 ? p.K : p.k.ext[p.k.n - 1];
+    (void)bk;
+    if (p.a_kcontig || p.b_kcontig) {
+        if (run % epc) return false;
+        for (int i = 0; i + 1 < p.k.n; i++)
+            if ((p.a_kcontig && p.k.s0[i] % epc) || (p.b_kcontig && p.k.s1[i] % epc)) return false;
+    }
     // Lane offsets count from the tile's first row and must stay below 2^31 bytes: rows of a tile must not lie before
     // its first row (strides nested, outermost first), and 256 rows plus the k-rows of a stage must span less.
     auto tile_span = [](const DimList &g) -> int64_t {            // largest offset of a row within 255 rows of another

@@ -103,6 +103,9 @@ LAYOUTS = [
     ("bshd,ahd->bsa", (2, 72, 3, 64), (88, 3, 64)),      # two contracted labels, every stage starts a new run of the inner one
     ("bshd,ahd->bsa", (2, 72, 3, 128), (88, 3, 128)),    # ... and runs of two stages
     ("bshd,ahd->bsa", (2, 72, 2, 192), (88, 2, 192)),    # ... runs of three: the stage pointers wrap at odd and even stages
+    ("bshd,ahd->bsa", (2, 72, 3, 96), (88, 3, 96)),      # runs that are no whole number of stages: a full and a half-filled stage per run
+    ("bshd,bthd->bhst", (2, 72, 3, 80), (2, 56, 3, 80)),  # ... as the single contracted label of a batched product
+    ("bsha,had->bsd", (2, 72, 3, 40), (3, 40, 136)),     # ... with the second operand contiguous along its columns
 ]
 
 
