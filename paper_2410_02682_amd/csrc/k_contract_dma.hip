@@ -667,7 +667,9 @@ int launch_contract_dma(ContractParams &p, void *stream)
     const char *tile_env = getenv("EINDECOMP_DMA_TILE");              // 128 or 256: for comparisons and tests, read at every launch
     const int64_t tuples = p.n_tuples * p.n_batch;
     const int64_t small = tuples * ((p.M + 127) / 128) * ((p.N + 127) / 128);
-    int ts = small <= 2 * n_cu ? 128 : 256;
+    const int64_t large = tuples * ((p.M + 255) / 256) * ((p.N + 255) / 256);
+    // ... and when the large tiles would be mostly padding (128 columns in a 256-wide tile: config 4's P x V, 0.31 -> 0.29 ms)
+    int ts = (small <= 2 * n_cu || 4 * large * 10 > small * 14) ? 128 : 256;
     if (tile_env && (atoi(tile_env) == 128 || atoi(tile_env) == 256)) ts = atoi(tile_env);
     p.tiles_m = (int32_t)((p.M + ts - 1) / ts);
     p.tiles_n = (int32_t)((p.N + ts - 1) / ts);
