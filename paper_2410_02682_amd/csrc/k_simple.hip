@@ -85,31 +85,22 @@ __global__ __launch_bounds__(kThreads) void k_generic(const GenericParams p)
 __device__ __forceinline__ int64_t tuple_of_block() { return (int64_t)blockIdx.x; }
 __device__ __forceinline__ uint32_t pos_of_block() { return blockIdx.z * 65535u + blockIdx.y; }
 
-// ROWMODE: the last dim is long, so a workgroup stays inside one row, covers 4 * 256 consecutive vectors of
-// it (four per lane, all loads issued before the first use) and the row's offsets are scalar work computed
-// once; otherwise every lane decodes its own flat index and handles one vector.
-template <int VEC, int OP, bool FAST, bool ROWMODE>
+// Every lane decodes its own flat index in the block and handles one vector.  (A variant that kept a workgroup inside
+// one long row, four vectors per lane and the row's offsets as scalar work, was 8 % slower once the workgroups ran
+// tuple-interleaved: 5.2 against 5.6-5.7 TB/s on 180 MB operands.)
+template <int VEC, int OP, bool FAST>
 __global__ __launch_bounds__(kThreads) void k_map(const MapParams p)
 {
-    constexpr int U = ROWMODE ? 4 : 1;
     const int64_t t = tuple_of_block();
     const uint32_t pos = pos_of_block();
     int64_t ox, oy, oz, agg;
     decode_tuple(p.ts, t, ox, oy, oz, agg);
     const int vd = p.dims.n - 1;
     const uint32_t nv = ((uint32_t)p.dims.ext[vd] + VEC - 1) / VEC;
-    uint32_t e, col;
-    if (ROWMODE) {
-        const uint32_t per_row = (nv + U * kThreads - 1) / (U * kThreads);
-        e = pos / per_row;                                          // row: uniform
-        if (e >= (uint32_t)(p.vecs_per_block / nv)) return;
-        col = (pos - e * per_row) * (U * kThreads) + threadIdx.x;
-    } else {
-        const uint32_t e0 = pos * kThreads + threadIdx.x;
-        if (pos >= ((uint32_t)p.vecs_per_block + kThreads - 1) / kThreads || e0 >= (uint32_t)p.vecs_per_block) return;
-        e = e0 / nv;
-        col = e0 - e * nv;
-    }
+    const uint32_t e0 = pos * kThreads + threadIdx.x;
+    if (pos >= ((uint32_t)p.vecs_per_block + kThreads - 1) / kThreads || e0 >= (uint32_t)p.vecs_per_block) return;
+    uint32_t e = e0 / nv;
+    const uint32_t col = e0 - e * nv;
     for (int i = vd - 1; i >= 0; i--) {
         const uint32_t ext = (uint32_t)p.dims.ext[i], q = e / ext;
         const int64_t k2 = e - q * ext;
@@ -118,35 +109,24 @@ __global__ __launch_bounds__(kThreads) void k_map(const MapParams p)
     }
     char *zb = out_base(p.out, agg);
     if (VEC == 8) {
-        float x[U][8], y[U][8];
-        const bool xv = p.dims.sx[vd] == 1, yv = p.dims.sy[vd] == 1;
+        float x[8], y[8], z[8];
+        const int64_t k = (int64_t)col * VEC;
+        if (p.dims.sx[vd] == 1) load8(p.x, p.dtx, ox + k, x);
+        else { float s = load_elem(p.x, p.dtx, ox + k * p.dims.sx[vd]);
 #pragma unroll
-        for (int u = 0; u < U; u++) {
-            const uint32_t c = col + u * kThreads;
-            const int64_t k = (int64_t)(c < nv ? c : nv - 1) * VEC;   // clamped: lanes past the row's end repeat its last vector
-            if (xv) load8(p.x, p.dtx, ox + k, x[u]);
-            else { float s = load_elem(p.x, p.dtx, ox + k * p.dims.sx[vd]);
+            for (int i = 0; i < 8; i++) x[i] = s; }
+        if (p.binary) {
+            if (p.dims.sy[vd] == 1) load8(p.y, p.dty, oy + k, y);
+            else { float s = load_elem(p.y, p.dty, oy + k * p.dims.sy[vd]);
 #pragma unroll
-                for (int i = 0; i < 8; i++) x[u][i] = s; }
-            if (p.binary) {
-                if (yv) load8(p.y, p.dty, oy + k, y[u]);
-                else { float s = load_elem(p.y, p.dty, oy + k * p.dims.sy[vd]);
+                for (int i = 0; i < 8; i++) y[i] = s; }
+        } else {
 #pragma unroll
-                    for (int i = 0; i < 8; i++) y[u][i] = s; }
-            } else {
-#pragma unroll
-                for (int i = 0; i < 8; i++) y[u][i] = 0.f;
-            }
+            for (int i = 0; i < 8; i++) y[i] = 0.f;
         }
 #pragma unroll
-        for (int u = 0; u < U; u++) {
-            const uint32_t c = col + u * kThreads;
-            if (c >= nv) continue;
-            float z[8];
-#pragma unroll
-            for (int i = 0; i < 8; i++) z[i] = otimes_t<OP, FAST>(p.otimes, x[u][i], y[u][i], p.alpha);
-            store8(zb, p.out.dtype, oz + (int64_t)c * VEC * p.dims.sz[vd], z);
-        }
+        for (int i = 0; i < 8; i++) z[i] = otimes_t<OP, FAST>(p.otimes, x[i], y[i], p.alpha);
+        store8(zb, p.out.dtype, oz + k * p.dims.sz[vd], z);
     } else {
         const int64_t k = col;
         float x = load_elem(p.x, p.dtx, ox + k * p.dims.sx[vd]);
@@ -404,16 +384,11 @@ static int tuple_grid(int64_t per_tuple_items, int64_t per_wg, int64_t n_tuples,
 }
 
 template <int OP>
-static void launch_map_vec(const MapParams &p, dim3 grid, bool rowmode, hipStream_t st)
+static void launch_map_vec(const MapParams &p, dim3 grid, hipStream_t st)
 {
     const bool fast = p.out.dtype == EG_BF16;     // hardware exponential only where the result is rounded to bf16
-    if (rowmode) {
-        if (fast) hipLaunchKernelGGL((k_map<8, OP, true, true>), grid, dim3(kThreads), 0, st, p);
-        else hipLaunchKernelGGL((k_map<8, OP, false, true>), grid, dim3(kThreads), 0, st, p);
-    } else {
-        if (fast) hipLaunchKernelGGL((k_map<8, OP, true, false>), grid, dim3(kThreads), 0, st, p);
-        else hipLaunchKernelGGL((k_map<8, OP, false, false>), grid, dim3(kThreads), 0, st, p);
-    }
+    if (fast) hipLaunchKernelGGL((k_map<8, OP, true>), grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((k_map<8, OP, false>), grid, dim3(kThreads), 0, st, p);
 }
 
 int launch_map(const MapParams &p, void *stream)
@@ -423,24 +398,14 @@ int launch_map(const MapParams &p, void *stream)
     if (p.vec != 1 && p.vec != 8) return fail(EG_ERR_LIMIT, "map kernel: vector width %d", p.vec);
     hipStream_t st = (hipStream_t)stream;
     dim3 grid;
+    int rc = tuple_grid(p.vecs_per_block, kThreads, p.n_tuples, grid);
+    if (rc) return rc;
     if (p.vec == 1) {
-        int rc = tuple_grid(p.vecs_per_block, kThreads, p.n_tuples, grid);
-        if (rc) return rc;
-        hipLaunchKernelGGL((k_map<1, -1, false, false>), grid, dim3(kThreads), 0, st, p);
+        hipLaunchKernelGGL((k_map<1, -1, false>), grid, dim3(kThreads), 0, st, p);
         return check_launch("k_map");
     }
-    const int64_t nv = p.dims.ext[p.dims.n - 1] / 8;
-    const bool rowmode = nv >= 768;                // a row keeps at least three quarters of a workgroup's 1024 slots busy
-    int rc;
-    if (rowmode) {
-        const int64_t rows = p.vecs_per_block / nv, per_row = (nv + 4 * kThreads - 1) / (4 * kThreads);
-        rc = tuple_grid(rows * per_row, 1, p.n_tuples, grid);
-    } else {
-        rc = tuple_grid(p.vecs_per_block, kThreads, p.n_tuples, grid);
-    }
-    if (rc) return rc;
     switch (p.otimes) {
-#define EG_CASE(OP) case OP: launch_map_vec<OP>(p, grid, rowmode, st); break;
+#define EG_CASE(OP) case OP: launch_map_vec<OP>(p, grid, st); break;
     EG_CASE(EG_MUL) EG_CASE(EG_ADD) EG_CASE(EG_SUB) EG_CASE(EG_DIV) EG_CASE(EG_SQDIFF) EG_CASE(EG_ABSDIFF)
     EG_CASE(EG_EXP_SUB) EG_CASE(EG_RELU_GRAD) EG_CASE(EG_SILU_MUL) EG_CASE(EG_IDENT) EG_CASE(EG_SCALE)
     EG_CASE(EG_RELU) EG_CASE(EG_EXP) EG_CASE(EG_LOG)
