@@ -163,11 +163,14 @@ def draw_matrix_graph(seed):
     return Workload(f"matrices{seed}", 78_000 + seed, vertices, outputs, parts)
 
 
-def _run(w, pname, inputs):
+def _run(w, pname, inputs, merged=False):
     import torch
+    import paper_2410_02682_amd as E
     from paper_2410_02682_amd.runner import GraphRunner, to_device, to_host
     r = GraphRunner(w, pname)
     try:
+        if merged:
+            E.tr_set_fused_aggregation(r.g, True)     # the alternative method: no partial slabs, no aggregation stage
         r.bind({k: to_device(t) for k, t in inputs.items()})
         r.run()
         torch.cuda.synchronize()
@@ -183,10 +186,10 @@ def test_random_graph_matches_oracle_under_every_labelling(family, seed):
     print(f"graph {seed}: {desc}; outputs {w.outputs}", flush=True)
     inputs = make_inputs(w)
     ref = run_graph(w, inputs)
-    for pname in ("a", "b", "whole", "eindecomp:4"):
-        got = _run(w, pname, inputs)
+    for pname, merged in (("a", False), ("b", False), ("whole", False), ("eindecomp:4", False), ("a", True), ("b", True)):
+        got = _run(w, pname, inputs, merged)
         for name in w.outputs:
             r = ref[name].as_f64()
             assert got[name].shape == ref[name].shape
             bad, worst = violations(got[name].as_f64(), r, rtol_for(w, name))
-            assert bad == 0, f"labelling {pname} output {name}: {bad} elements out of tolerance (worst {worst:.2f}x)"
+            assert bad == 0, f"labelling {pname}{' (aggregation merged)' if merged else ''} output {name}: {bad} elements out of tolerance (worst {worst:.2f}x)"
