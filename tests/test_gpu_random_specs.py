@@ -153,3 +153,61 @@ def test_random_contraction_on_small_integers_is_bit_identical_to_the_oracle(see
     for pname in ("d", "whole"):
         got, kernel = _run(w, pname, {"X": x, "Y": y})
         assert np.array_equal(got.as_f64(), ref), f"{pname} ({kernel}) differs from the exact result"
+
+
+def draw_large_contraction(seed):
+    """A contraction large enough for several tiles of the matrix-core kernels in both directions: one or two labels per
+    role (rows, columns, contracted, sometimes batch), extents that leave ragged tiles and stage tails, any label
+    order in the operands, so both operands can come out contiguous along the contracted label or along rows /
+    columns.  About 1e8..3e8 multiply-adds each (a second or so of the oracle)."""
+    rng = np.random.default_rng(4_2410_02682 + seed)
+    pool = list("abcdefg")
+    rng.shuffle(pool)
+    roles = ["m"] * int(rng.integers(1, 3)) + ["n"] * int(rng.integers(1, 3)) + ["k"] * int(rng.integers(1, 3)) + ["b"] * int(rng.integers(0, 2))
+    role = dict(zip(pool, roles))
+    union = pool[:len(roles)]
+    lx = [l for l in union if role[l] in "mkb"]
+    ly = [l for l in union if role[l] in "nkb"]
+    lz = [l for l in union if role[l] in "mnb"]
+    rng.shuffle(lx); rng.shuffle(ly); rng.shuffle(lz)
+    target = {"m": int(rng.choice([136, 264, 392, 520, 776])), "n": int(rng.choice([136, 264, 392, 520])),
+              "k": int(rng.choice([72, 136, 264, 520, 1032])), "b": int(rng.choice([2, 3]))}
+    bound = {}
+    for r in "mnkb":
+        ls = [l for l in union if role[l] == r]
+        if len(ls) == 1:
+            bound[ls[0]] = target[r]
+        elif len(ls) == 2:                                   # outer x inner = about the target, inner a multiple of 8
+            inner = int(rng.choice([8, 24, 40, 64, 96]))
+            where = lx if ls[0] in lx else ly                # the label that comes later in its operand is the inner one
+            ls.sort(key=where.index)
+            bound[ls[0]], bound[ls[1]] = max(2, target[r] // inner), inner
+    part, p = {}, 1
+    for l in union:
+        divs = [d for d in (1, 2, 3, 4) if bound[l] % d == 0 and (bound[l] // d) % 8 == 0]
+        d = int(rng.choice(divs or [1]))
+        if p * d <= 16:
+            part[l] = d
+            p *= d
+    spec = "".join(lx) + "," + "".join(ly) + "->" + "".join(lz)
+    dt_in = "bf16" if rng.random() < 0.7 else "f32"
+    dt_out = "bf16" if (dt_in == "bf16" and rng.random() < 0.4) else "f32"
+    return spec, tuple(bound[l] for l in lx), tuple(bound[l] for l in ly), part, dt_in, dt_out
+
+
+@pytest.mark.parametrize("tile", ["", "256"])
+@pytest.mark.parametrize("seed", range(max(24, N_CASES // 20)))
+def test_random_large_contraction_matches_oracle(seed, tile, monkeypatch):
+    if tile:
+        monkeypatch.setenv("EINDECOMP_DMA_TILE", tile)       # the large-tile variant too, mostly padding at these sizes
+    spec, bx, by, part, dt_in, dt_out = draw_large_contraction(seed)
+    x = HostTensor.from_f32(uniform_pm1(1300 + seed, 0, int(np.prod(bx))).reshape(bx), dt_in)
+    y = HostTensor.from_f32(uniform_pm1(1300 + seed, 1, int(np.prod(by))).reshape(by), dt_in)
+    w = single_vertex(spec, x, y, dt_out, parts={"d": part, "whole": {}})
+    ref = run_graph(w, {"X": x, "Y": y})["Z"]
+    rtol = RTOL_BF16 if dt_out == "bf16" else RTOL_F32
+    for pname in ("d", "whole"):
+        got, kernel = _run(w, pname, {"X": x, "Y": y})
+        print(f"seed {seed}: {spec} X{bx} Y{by} d {part if pname == 'd' else {}} {dt_in}->{dt_out}: {kernel}", flush=True)
+        bad, worst = violations(got.as_f64(), ref.as_f64(), rtol)
+        assert bad == 0, f"{pname} ({kernel}): {bad} elements out of tolerance (worst {worst:.2f}x)"
