@@ -69,6 +69,22 @@ __device__ __forceinline__ void store8(void *p, int dt, int64_t off, const float
     }
 }
 
+// exp(x - y) where the result is stored as bf16: one multiply-add into the hardware's base-2 exponential.
+// y * log2(e) is rounded once, which puts an absolute error of about |y| * 2^-24 into the exponent, far below
+// the 2^-9 half-ulp of the stored value.  The fused softmax pass uses the same expression, so it agrees bit
+// for bit with the separate vertex.
+constexpr float kLog2e = 1.4426950408889634f;
+__device__ __forceinline__ float exp_sub_scaled(float x, float neg_y_log2e) { return __builtin_amdgcn_exp2f(fmaf(x, kLog2e, neg_y_log2e)); }
+__device__ __forceinline__ float exp_sub_fast(float x, float y) { return exp_sub_scaled(x, -(y * kLog2e)); }
+
+// Rounds two fp32 values to bf16 and back with one conversion instruction.
+__device__ __forceinline__ void round_pair_bf16(float &a, float &b)
+{
+    const uint32_t pk = pack_bf16x2(a, b);
+    a = __uint_as_float(pk << 16);
+    b = __uint_as_float(pk & 0xffff0000u);
+}
+
 // The scalar function (x) of a vertex (Section 3 of the paper: any scalar function of the joined values).
 // OP >= 0 fixes the function at compile time; OP = -1 reads it from `op`.  FAST selects the hardware
 // exponential (relative error about |x| * 6e-8) and reciprocal (1 ulp), used only where the result is
@@ -84,7 +100,7 @@ __device__ __forceinline__ float otimes_t(int op, float x, float y, float alpha)
     case EG_DIV: return FAST ? x * __frcp_rn(y) : x / y;
     case EG_SQDIFF: return (x - y) * (x - y);
     case EG_ABSDIFF: return fabsf(x - y);
-    case EG_EXP_SUB: return FAST ? __expf(x - y) : expf(x - y);
+    case EG_EXP_SUB: return FAST ? exp_sub_fast(x, y) : expf(x - y);
     case EG_RELU_GRAD: return y > 0.f ? x : 0.f;
     case EG_SILU_MUL: return (x / (1.f + (FAST ? __expf(-x) : expf(-x)))) * y;
     case EG_IDENT: return x;

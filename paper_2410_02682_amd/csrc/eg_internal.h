@@ -141,6 +141,7 @@ struct SoftmaxParams {
     void *row_sum;
     int64_t n_tuples, rows_per_block;
     int32_t vec;                  // filled by the launcher: 8 (16-byte accesses along the rows) or 1
+    int32_t share_add;            // filled by the launcher: the rows of a workgroup take the same row of the added operand
 };
 
 struct AggregateParams {          // out[e] = oplus_a partials[a][e], ascending a, fp32, one final cast

@@ -83,7 +83,7 @@ __global__ __launch_bounds__(kThreads) void k_generic(const GenericParams p)
 // the same position of neighbouring blocks: where the blocks cut the innermost label, that is one contiguous stretch
 // of every operand instead of short row pieces a whole row apart (+34 % on a map over rows cut eight ways).
 __device__ __forceinline__ int64_t tuple_of_block() { return (int64_t)blockIdx.x; }
-__device__ __forceinline__ uint32_t pos_of_block() { return blockIdx.z * 65535u + blockIdx.y; }
+__device__ __forceinline__ uint32_t pos_of_block() { return blockIdx.z * gridDim.y + blockIdx.y; }
 
 // Every lane decodes its own flat index in the block and handles one vector.  (A variant that kept a workgroup inside
 // one long row, four vectors per lane and the row's offsets as scalar work, was 8 % slower once the workgroups ran
@@ -370,15 +370,15 @@ int launch_generic(const GenericParams &p, void *stream)
     return check_launch("k_generic");
 }
 
-// grid.x = tuples, grid.y * grid.z >= workgroups per tuple (y capped at 65535)
+// grid.x = tuples, grid.y * grid.z >= workgroups per tuple (y at most 65535, z as small as that allows)
 static int tuple_grid(int64_t per_tuple_items, int64_t per_wg, int64_t n_tuples, dim3 &grid)
 {
     int64_t g = (per_tuple_items + per_wg - 1) / per_wg;
     if (g < 1) g = 1;
     if (g >= (1ll << 31) || per_tuple_items >= (1ll << 32)) return fail(EG_ERR_LIMIT, "block too large for one launch");
     if (n_tuples >= (1ll << 31)) return fail(EG_ERR_LIMIT, "too many tuples");
-    const int64_t gy = g < 65535 ? g : 65535;
     const int64_t gz = (g + 65534) / 65535;
+    const int64_t gy = (g + gz - 1) / gz;              // at most gz - 1 workgroups beyond g
     grid = dim3((unsigned)n_tuples, (unsigned)gy, (unsigned)gz);
     return EG_OK;
 }
@@ -517,6 +517,19 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p
     if (t >= p.n_tuples || row >= (uint32_t)p.rows_per_block) return;          // whole waves leave
     int64_t ox, oy, oz, oc, os;
     softmax_row_offsets(p, t, row, ox, oy, oz, oc, os);
+    // When the workgroup's rows all take the same row of the added operand (a mask shared by batch entries and
+    // heads), the workgroup fetches it once into LDS instead of once per wave.
+    __shared__ uint4 addrow[VPL * 128];                 // 512 * VPL elements of up to 4 bytes
+    if (p.share_add) {
+        const int es = p.dt_add == EG_BF16 ? 2 : 4, chunks = p.n * es / 16;
+        const uint4 *g = (const uint4 *)((const char *)p.add + oy * es);
+        uint4 r[(VPL + 1) / 2];
+#pragma unroll
+        for (int j = 0; j < (VPL + 1) / 2; j++) { const int c = j * kThreads + threadIdx.x; if (c < chunks) r[j] = g[c]; }
+#pragma unroll
+        for (int j = 0; j < (VPL + 1) / 2; j++) { const int c = j * kThreads + threadIdx.x; if (c < chunks) addrow[c] = r[j]; }
+        __syncthreads();
+    }
     float v[VPL][8];
     float m = -INFINITY;
 #pragma unroll
@@ -526,12 +539,17 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p
             load8(p.src, dt_src, ox + c, v[u]);
             if (p.has_add) {
                 float y[8];
-                if (p.sy_last == 1) load8(p.add, p.dt_add, oy + c, y);
+                if (p.share_add) load8(addrow, p.dt_add, c, y);
+                else if (p.sy_last == 1) load8(p.add, p.dt_add, oy + c, y);
                 else { const float s = load_elem(p.add, p.dt_add, oy);
 #pragma unroll
                     for (int i = 0; i < 8; i++) y[i] = s; }
 #pragma unroll
-                for (int i = 0; i < 8; i++) v[u][i] = round_as(p.alpha * v[u][i] + y[i], dt_t);
+                for (int i = 0; i < 8; i++) v[u][i] = p.alpha * v[u][i] + y[i];
+                if (dt_t == EG_BF16) {
+#pragma unroll
+                    for (int i = 0; i < 8; i += 2) round_pair_bf16(v[u][i], v[u][i + 1]);
+                }
             }
 #pragma unroll
             for (int i = 0; i < 8; i++) m = fmaxf(m, v[u][i]);
@@ -539,16 +557,19 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p
     }
     m = wave_reduce<EG_AGG_MAX>(EG_AGG_MAX, m);
     const bool fast_e = dt_e == EG_BF16, fast_p = dt_p == EG_BF16;         // as the separate vertices choose
+    const float neg_m_log2e = -(m * kLog2e);
     float sum = 0.f;
 #pragma unroll
     for (int u = 0; u < VPL; u++) {
         if ((u * 64 + lane) * 8 < p.n) {
 #pragma unroll
-            for (int i = 0; i < 8; i++) {
-                const float e = round_as(fast_e ? __expf(v[u][i] - m) : expf(v[u][i] - m), dt_e);
-                v[u][i] = e;
-                sum += e;
+            for (int i = 0; i < 8; i++) v[u][i] = fast_e ? exp_sub_scaled(v[u][i], neg_m_log2e) : expf(v[u][i] - m);
+            if (dt_e == EG_BF16) {
+#pragma unroll
+                for (int i = 0; i < 8; i += 2) round_pair_bf16(v[u][i], v[u][i + 1]);
             }
+#pragma unroll
+            for (int i = 0; i < 8; i++) sum += v[u][i];
         }
     }
     sum = wave_reduce<EG_AGG_SUM>(EG_AGG_SUM, sum);
@@ -603,7 +624,7 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows_scalar(const SoftmaxP
     const bool fast_e = p.dt_e == EG_BF16, fast_p = p.dt_p == EG_BF16;
     float sum = 0.f;
     for (int c = threadIdx.x; c < p.n; c += kThreads) {
-        const float e = round_as(fast_e ? __expf(buf[c] - m) : expf(buf[c] - m), p.dt_e);
+        const float e = round_as(fast_e ? exp_sub_fast(buf[c], m) : expf(buf[c] - m), p.dt_e);
         buf[c] = e;
         sum += e;
     }
@@ -630,6 +651,11 @@ int launch_softmax_rows(SoftmaxParams &p, void *stream)
     for (int l = 0; l < p.ts.n && vec; l++)
         if (p.ts.step_x[l] % 8 || p.ts.step_z[l] % 8 || (p.has_add && p.sy_last == 1 && p.ts.step_y[l] % 8)) vec = false;
     p.vec = vec ? 8 : 1;
+    // rows of a workgroup (kThreads / 64 consecutive ones) differ only in the innermost row label; if the added
+    // operand lacks that label and its extent is a multiple of the rows per workgroup, they share its row
+    constexpr int rpw = kThreads / 64;
+    p.share_add = vec && p.has_add && p.sy_last == 1 && p.rows.n >= 1 && p.rows.sy[p.rows.n - 1] == 0 &&
+                  p.rows.ext[p.rows.n - 1] % rpw == 0;
     hipStream_t st = (hipStream_t)stream;
     dim3 grid;
     if (!vec) {

@@ -255,3 +255,60 @@ def test_config7_distances_sampled_rows():
                 assert bad == 0, f"{name}: {bad} out of tolerance (worst {worst:.2f}x)"
     finally:
         r.close()
+
+
+def test_blocks_with_more_than_65535_workgroups():
+    """One tuple whose block needs more workgroups than one grid dimension holds (the launch then folds the
+    position over two grid dimensions): an element-wise vertex, a row reduction and a fused softmax chain, each
+    unpartitioned, compared with the oracle on rows at the start, around the fold and at the end."""
+    import torch
+    import paper_2410_02682_amd as E
+    from paper_2410_02682_amd.runner import GraphRunner
+    from oracle.graph_ref import run_graph
+    from synth_inputs.workloads import Vertex, Workload
+
+    def sm(src, lab):                                      # the softmax chain of Section 3 over the last label
+        rows = lab[:-1]
+        return [Vertex("Cmax", "f32", spec=f"{lab}->{rows}", otimes="ident", oplus="max", inputs=(src,)),
+                Vertex("E", "bf16", spec=f"{lab},{rows}->{lab}", otimes="exp_sub", oplus="none", inputs=(src, "Cmax")),
+                Vertex("S", "f32", spec=f"{lab}->{rows}", otimes="ident", oplus="sum", inputs=("E",)),
+                Vertex("Z", "bf16", spec=f"{lab},{rows}->{lab}", otimes="div", oplus="none", inputs=("E", "S"))]
+
+    cases = [
+        ("map", (17408, 8192), [Vertex("Z", "bf16", spec="ij->ij", otimes="scale", oplus="none", alpha=-1.5, inputs=("X",))],
+         "map", 65535 * 256 * 8 // 8192),
+        ("row sums", (2228224, 64), [Vertex("Z", "f32", spec="ij->i", otimes="ident", oplus="sum", inputs=("X",))],
+         "reduce_row", 65535 * 32),
+        ("softmax", (270336, 64), sm("X", "ij"), "softmax_fused", 65535 * 4),
+    ]
+    for name, shape, vs, kernel, fold in cases:
+        print(f"{name} over {shape}, unpartitioned", flush=True)
+        w = Workload("large_" + name.replace(" ", "_"), 0, [Vertex("X", "bf16", bound=shape)] + vs, ["Z"], {"whole": {}})
+        x = (torch.rand(shape, device="cuda", generator=torch.Generator("cuda").manual_seed(11)) * 2 - 1).to(torch.bfloat16)
+        r = GraphRunner(w, "whole")
+        try:
+            r.bind({"X": x})
+            assert r.plan("Z")["n_tuples"] == 1
+            E.tr_profile_enable(r.g, 8)
+            r.run()
+            torch.cuda.synchronize()
+            assert [rec["kernel"] for rec in E.tr_profile_read(r.g)] == [kernel]
+            assert fold < shape[0]
+            rows = sorted(set(list(range(8)) + list(range(fold - 40, min(fold + 40, shape[0]))) + list(range(shape[0] - 8, shape[0]))))
+            sub = Workload("rows", 0, [Vertex("X", "bf16", bound=(len(rows),) + shape[1:])] + vs, ["Z"], {"whole": {}})
+            ref = run_graph(sub, {"X": HostTensor(_host(x[rows]), "bf16")})["Z"].as_f64()
+            got = _f64(_host(r.output("Z")[rows]))
+            bad, worst = violations(got, ref, RTOL_BF16 if w.vertex("Z").dtype == "bf16" else RTOL_F32)
+            assert bad == 0, f"{name}: {bad} out of tolerance (worst {worst:.2f}x)"
+            # every row was written: a pass over all of them that the device can check itself
+            z = r.output("Z").float()
+            if name == "map":
+                assert torch.equal(z, (x.float() * -1.5).to(torch.bfloat16).float())
+            elif name == "softmax":
+                assert float((z.sum(dim=1) - 1).abs().max()) < 2e-2
+            else:
+                assert float((z - x.float().sum(dim=1)).abs().max()) < 1e-3
+        finally:
+            r.close()
+        del x, r
+        torch.cuda.empty_cache()
