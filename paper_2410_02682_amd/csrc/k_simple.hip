@@ -523,11 +523,8 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p
     if (p.share_add) {
         const int es = p.dt_add == EG_BF16 ? 2 : 4, chunks = p.n * es / 16;
         const uint4 *g = (const uint4 *)((const char *)p.add + oy * es);
-        uint4 r[(VPL + 1) / 2];
 #pragma unroll
-        for (int j = 0; j < (VPL + 1) / 2; j++) { const int c = j * kThreads + threadIdx.x; if (c < chunks) r[j] = g[c]; }
-#pragma unroll
-        for (int j = 0; j < (VPL + 1) / 2; j++) { const int c = j * kThreads + threadIdx.x; if (c < chunks) addrow[c] = r[j]; }
+        for (int j = 0; j < (VPL + 1) / 2; j++) { const int c = j * kThreads + threadIdx.x; if (c < chunks) addrow[c] = g[c]; }
         __syncthreads();
     }
     float v[VPL][8];
@@ -651,11 +648,12 @@ int launch_softmax_rows(SoftmaxParams &p, void *stream)
     for (int l = 0; l < p.ts.n && vec; l++)
         if (p.ts.step_x[l] % 8 || p.ts.step_z[l] % 8 || (p.has_add && p.sy_last == 1 && p.ts.step_y[l] % 8)) vec = false;
     p.vec = vec ? 8 : 1;
-    // rows of a workgroup (kThreads / 64 consecutive ones) differ only in the innermost row label; if the added
-    // operand lacks that label and its extent is a multiple of the rows per workgroup, they share its row
+    // rows of a workgroup are kThreads / 64 consecutive ones; if the innermost row labels that the added operand
+    // lacks span a multiple of that many rows, the workgroup's rows share one row of the added operand
     constexpr int rpw = kThreads / 64;
-    p.share_add = vec && p.has_add && p.sy_last == 1 && p.rows.n >= 1 && p.rows.sy[p.rows.n - 1] == 0 &&
-                  p.rows.ext[p.rows.n - 1] % rpw == 0;
+    int64_t lacking = 1;
+    for (int i = p.rows.n - 1; i >= 0 && p.rows.sy[i] == 0; i--) lacking *= p.rows.ext[i];
+    p.share_add = vec && p.has_add && p.sy_last == 1 && p.rows.n >= 1 && lacking % rpw == 0;
     hipStream_t st = (hipStream_t)stream;
     dim3 grid;
     if (!vec) {
