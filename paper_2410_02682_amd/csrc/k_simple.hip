@@ -140,15 +140,17 @@ __global__ __launch_bounds__(kThreads) void k_map(const MapParams p)
 // With split > 1 (few outputs, long reductions) each output's reduction range is cut into `split` pieces
 // that land in consecutive partial slabs (slab = aggIdx * split + piece) for the aggregation kernel.
 // ------------------------------------------------------------------------------------------------
-template <int OPLUS>
+template <int OPLUS, int GROUP = 64>                     // over aligned groups of GROUP lanes (a power of two)
 __device__ __forceinline__ float wave_reduce(int oplus, float v)
 {
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v = oplus_t<OPLUS>(oplus, v, __shfl_xor(v, off, 64));
+    for (int off = GROUP / 2; off >= 1; off >>= 1) v = oplus_t<OPLUS>(oplus, v, __shfl_xor(v, off, 64));
     return v;
 }
 
-template <int LANES, int VEC, int OP, int OPLUS>
+// LANES lanes share one output (8 .. 64: several outputs per wave, short rows; 256: one per workgroup); U vectors
+// per lane are loaded before any is used (1 where a lane has a single vector anyway).
+template <int LANES, int VEC, int OP, int OPLUS, int U>
 __global__ __launch_bounds__(kThreads) void k_reduce_row(const ReduceParams p)
 {
     constexpr int PER_WG = kThreads / LANES;
@@ -179,11 +181,11 @@ __global__ __launch_bounds__(kThreads) void k_reduce_row(const ReduceParams p)
         const uint32_t chunk = (total + split - 1) / split;
         const uint32_t lo = piece * chunk, hi = (lo + chunk < total) ? lo + chunk : total;
         const bool flat = p.rdims.n == 1;
-        for (uint32_t j0 = lo + lane; j0 < hi; j0 += 4 * LANES) {
-            float x[4][VEC], y[4][VEC];
-            bool ok[4];
+        for (uint32_t j0 = lo + lane; j0 < hi; j0 += U * LANES) {
+            float x[U][VEC], y[U][VEC];
+            bool ok[U];
 #pragma unroll
-            for (int u = 0; u < 4; u++) {                          // issue the loads of four vectors before using any
+            for (int u = 0; u < U; u++) {                          // issue the loads of U vectors before using any
                 const uint32_t j = j0 + u * LANES;
                 ok[u] = j < hi;
                 const uint32_t jj = ok[u] ? j : lo;
@@ -217,7 +219,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_row(const ReduceParams p)
                 }
             }
 #pragma unroll
-            for (int u = 0; u < 4; u++) {
+            for (int u = 0; u < U; u++) {
                 if (!ok[u]) continue;
 #pragma unroll
                 for (int i = 0; i < VEC; i++)
@@ -225,7 +227,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_row(const ReduceParams p)
             }
         }
     }
-    acc = wave_reduce<OPLUS>(p.oplus, acc);
+    acc = wave_reduce<OPLUS, (LANES < 64 ? LANES : 64)>(p.oplus, acc);
     // partial mode: slab (aggIdx * split + piece) of the fp32 workspace; otherwise the destination tensor
     char *zb = (char *)p.out.ptr + (p.out.slab_elems ? (agg * split + piece) * p.out.slab_elems * 4 : 0);
     if (LANES > 64) {                       // one output per workgroup: combine the four waves through LDS
@@ -238,6 +240,90 @@ __global__ __launch_bounds__(kThreads) void k_reduce_row(const ReduceParams p)
         }
     } else if (lane == 0 && active) {
         store_elem(zb, p.out.dtype, oz, acc);
+    }
+}
+
+// Short rows: an (output, piece) has at most LANES vectors, one per lane, and a group of LANES lanes takes R
+// consecutive ones, loading all R vectors before it reduces any.  A wave that held a single kilobyte in flight and
+// then walked through its cross-lane reduction left the memory system idle most of the time (0.6 TB/s on rows of 128
+// elements, 2.4 on rows of 512; with this 4-5 TB/s).
+template <int LANES, int OP, int OPLUS, int R>
+__global__ __launch_bounds__(kThreads) void k_reduce_short(const ReduceParams p)
+{
+    constexpr int PER_WG = kThreads / LANES, VEC = 8;
+    const int sub = threadIdx.x / LANES, lane = threadIdx.x % LANES;
+    const int64_t t = tuple_of_block();
+    const uint32_t slot0 = (pos_of_block() * PER_WG + sub) * R;
+    const uint32_t split = (uint32_t)p.split;
+    int64_t tx, ty, tz, agg;
+    decode_tuple(p.ts, t, tx, ty, tz, agg);
+    const int vd = p.rdims.n - 1;
+    const uint32_t nv = ((uint32_t)p.rdims.ext[vd] + VEC - 1) / VEC;
+    const uint32_t total = (uint32_t)(p.red_elems / p.rdims.ext[vd]) * nv;
+    const uint32_t chunk = (total + split - 1) / split;
+    float x[R][VEC], y[R][VEC];
+    bool act[R], ok[R];
+    int64_t oz[R];
+    uint32_t piece[R];
+#pragma unroll
+    for (int r = 0; r < R; r++) {
+        const uint32_t slot = slot0 + r;
+        uint32_t o = slot / split;
+        piece[r] = slot - o * split;
+        act[r] = o < (uint32_t)p.outs_per_block;
+        int64_t ox = tx, oy = ty;
+        oz[r] = tz;
+        uint32_t e = act[r] ? o : 0;
+        for (int i = p.zdims.n - 1; i >= 0; i--) {
+            const uint32_t ext = (uint32_t)p.zdims.ext[i], q = e / ext;
+            const int64_t k = e - q * ext;
+            e = q;
+            ox += k * p.zdims.sx[i]; oy += k * p.zdims.sy[i]; oz[r] += k * p.zdims.sz[i];
+        }
+        const uint32_t lo = piece[r] * chunk, hi = (lo + chunk < total) ? lo + chunk : total;
+        const uint32_t j = lo + lane;
+        ok[r] = act[r] && j < hi;
+        if (ok[r]) {
+            uint32_t q = j / nv;
+            const int64_t k = (int64_t)(j - q * nv) * VEC;
+            int64_t bx = ox + k * p.rdims.sx[vd], by = oy + k * p.rdims.sy[vd];
+            for (int i = vd - 1; i >= 0; i--) {
+                const uint32_t ext = (uint32_t)p.rdims.ext[i], q2 = q / ext;
+                const int64_t k2 = q - q2 * ext;
+                q = q2;
+                bx += k2 * p.rdims.sx[i]; by += k2 * p.rdims.sy[i];
+            }
+            load8(p.x, p.dtx, bx, x[r]);
+            if (p.binary) {
+                if (p.rdims.sy[vd] == 1) load8(p.y, p.dty, by, y[r]);
+                else { const float sv = load_elem(p.y, p.dty, by);
+#pragma unroll
+                    for (int i = 0; i < VEC; i++) y[r][i] = sv; }
+            }
+        }
+    }
+    float acc[R];
+#pragma unroll
+    for (int r = 0; r < R; r++) {
+        acc[r] = oplus_identity(OPLUS >= 0 ? OPLUS : p.oplus);
+        if (ok[r]) {
+#pragma unroll
+            for (int i = 0; i < VEC; i++)
+                acc[r] = oplus_t<OPLUS>(p.oplus, acc[r], otimes_t<OP, false>(p.otimes, x[r][i], p.binary ? y[r][i] : 0.f, p.alpha));
+        }
+    }
+#pragma unroll
+    for (int off = LANES / 2; off >= 1; off >>= 1) {
+#pragma unroll
+        for (int r = 0; r < R; r++) acc[r] = oplus_t<OPLUS>(p.oplus, acc[r], __shfl_xor(acc[r], off, 64));
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int r = 0; r < R; r++) {
+            if (!act[r]) continue;
+            char *zb = (char *)p.out.ptr + (p.out.slab_elems ? (agg * split + piece[r]) * p.out.slab_elems * 4 : 0);
+            store_elem(zb, p.out.dtype, oz[r], acc[r]);
+        }
     }
 }
 
@@ -415,14 +501,23 @@ int launch_map(const MapParams &p, void *stream)
     return check_launch("k_map");
 }
 
-template <int LANES, int VEC>
+template <int LANES, int R>
+static void launch_reduce_short(const ReduceParams &p, dim3 grid, hipStream_t st)
+{
+    if (p.otimes == EG_IDENT && p.oplus == EG_AGG_MAX) hipLaunchKernelGGL((k_reduce_short<LANES, EG_IDENT, EG_AGG_MAX, R>), grid, dim3(kThreads), 0, st, p);
+    else if (p.otimes == EG_IDENT && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_short<LANES, EG_IDENT, EG_AGG_SUM, R>), grid, dim3(kThreads), 0, st, p);
+    else if (p.otimes == EG_MUL && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_short<LANES, EG_MUL, EG_AGG_SUM, R>), grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((k_reduce_short<LANES, -1, -1, R>), grid, dim3(kThreads), 0, st, p);
+}
+
+template <int LANES, int VEC, int U>
 static void launch_reduce_ops(const ReduceParams &p, dim3 grid, hipStream_t st)
 {
     // the common (x)/(+) pairs are compiled in; anything else reads them at run time
-    if (p.otimes == EG_IDENT && p.oplus == EG_AGG_MAX) hipLaunchKernelGGL((k_reduce_row<LANES, VEC, EG_IDENT, EG_AGG_MAX>), grid, dim3(kThreads), 0, st, p);
-    else if (p.otimes == EG_IDENT && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_row<LANES, VEC, EG_IDENT, EG_AGG_SUM>), grid, dim3(kThreads), 0, st, p);
-    else if (p.otimes == EG_MUL && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_row<LANES, VEC, EG_MUL, EG_AGG_SUM>), grid, dim3(kThreads), 0, st, p);
-    else hipLaunchKernelGGL((k_reduce_row<LANES, VEC, -1, -1>), grid, dim3(kThreads), 0, st, p);
+    if (p.otimes == EG_IDENT && p.oplus == EG_AGG_MAX) hipLaunchKernelGGL((k_reduce_row<LANES, VEC, EG_IDENT, EG_AGG_MAX, U>), grid, dim3(kThreads), 0, st, p);
+    else if (p.otimes == EG_IDENT && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_row<LANES, VEC, EG_IDENT, EG_AGG_SUM, U>), grid, dim3(kThreads), 0, st, p);
+    else if (p.otimes == EG_MUL && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_row<LANES, VEC, EG_MUL, EG_AGG_SUM, U>), grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((k_reduce_row<LANES, VEC, -1, -1, U>), grid, dim3(kThreads), 0, st, p);
 }
 
 int launch_reduce_row(const ReduceParams &p, void *stream)
@@ -432,17 +527,36 @@ int launch_reduce_row(const ReduceParams &p, void *stream)
     if (p.split < 1 || (p.split > 1 && !p.out.slab_elems)) return fail(EG_ERR_LIMIT, "reduce kernel: split needs partial slabs");
     if (p.red_elems >= (1ll << 32)) return fail(EG_ERR_LIMIT, "reduce kernel: reduction space above 2^32");
     const int64_t slots = p.outs_per_block * p.split;
-    const bool wide = p.split > 1 || p.red_elems >= 16384 || slots * p.n_tuples < 1024;   // long or few rows: a workgroup each
+    // vectors one (output, piece) reduces over, as the kernel counts them
+    const int vd = p.rdims.n - 1;
+    const int64_t total = (p.red_elems / p.rdims.ext[vd]) * ((p.rdims.ext[vd] + p.vec - 1) / p.vec);
+    const int64_t chunk = (total + p.split - 1) / p.split;
+    const bool wide = chunk * p.vec >= 16384 || slots * p.n_tuples < 1024;   // long or few rows: a workgroup each
+    int lanes = 256;
+    if (!wide) {
+        lanes = 64;
+        if (p.vec == 8) while (lanes > 8 && lanes / 2 >= chunk) lanes /= 2;   // short rows: several outputs per wave
+    }
     dim3 grid;
-    int rc = tuple_grid(slots, wide ? 1 : kThreads / 64, p.n_tuples, grid);
-    if (rc) return rc;
     hipStream_t st = (hipStream_t)stream;
-    if (wide) {
-        if (p.vec == 8) launch_reduce_ops<256, 8>(p, grid, st);
-        else launch_reduce_ops<256, 1>(p, grid, st);
+    if (p.vec == 8 && lanes <= 64 && chunk <= lanes) {        // one vector per lane: four (output, piece) per lane group
+        constexpr int R = 4;
+        int rc = tuple_grid(slots, kThreads / lanes * R, p.n_tuples, grid);
+        if (rc) return rc;
+        if (lanes == 64) launch_reduce_short<64, R>(p, grid, st);
+        else if (lanes == 32) launch_reduce_short<32, R>(p, grid, st);
+        else if (lanes == 16) launch_reduce_short<16, R>(p, grid, st);
+        else launch_reduce_short<8, R>(p, grid, st);
+        return check_launch("k_reduce_short");
+    }
+    int rc = tuple_grid(slots, kThreads / lanes, p.n_tuples, grid);
+    if (rc) return rc;
+    if (p.vec == 8) {
+        if (lanes == 256) launch_reduce_ops<256, 8, 4>(p, grid, st);
+        else launch_reduce_ops<64, 8, 4>(p, grid, st);
     } else {
-        if (p.vec == 8) launch_reduce_ops<64, 8>(p, grid, st);
-        else launch_reduce_ops<64, 1>(p, grid, st);
+        if (lanes == 256) launch_reduce_ops<256, 1, 4>(p, grid, st);
+        else launch_reduce_ops<64, 1, 4>(p, grid, st);
     }
     return check_launch("k_reduce_row");
 }

@@ -257,6 +257,35 @@ def test_maps_reductions_and_extended_operators(spec, bx, by, otimes, oplus, par
     assert bad == 0, f"{bad} elements out of tolerance (worst {worst:.2f}x)"
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,n,otimes,oplus,part", [
+    (1000, 8, "ident", "sum", {}), (1000, 24, "ident", "max", {}), (4099, 64, "ident", "sum", {}),          # 8 lanes per output
+    (1237, 120, "ident", "sum", {}), (1237, 128, "relu", "sum", {"i": 1}),                                  # 16
+    (2050, 136, "ident", "max", {}), (2048, 256, "ident", "sum", {"i": 4}),                                 # 32
+    (1500, 264, "ident", "sum", {}), (1100, 512, "exp", "sum", {}), (1025, 504, "ident", "max", {"i": 5}),   # 64
+    (1100, 520, "ident", "sum", {}),                                                                        # more than one vector per lane
+    (1200, 512, "ident", "sum", {"j": 4}), (1200, 384, "ident", "max", {"j": 3, "i": 2}),                   # pieces of rows into partial slabs
+    (4096, 96, "mul", "sum", {}), (4096, 96, "mul_bcast", "sum", {"i": 2}), (2052, 40, "sqdiff", "sum", {}),   # two operands
+])
+def test_row_reductions_over_short_rows(rows, n, otimes, oplus, part, dtype):
+    """Rows short enough that several outputs share a wave (8 to 64 lanes per output, four outputs per lane group):
+    every group size, output counts that fill neither the last group nor the last workgroup, rows that leave lanes
+    idle, rows cut into partial slabs, a second operand of the same shape or one value per row."""
+    print(f"{rows} x {n} {otimes}/{oplus} {part} {dtype}", flush=True)
+    x = HostTensor.from_f32(uniform_pm1(31, 0, rows * n).reshape(rows, n), dtype)
+    spec, y = "ij->i", None
+    if otimes in ("mul", "sqdiff"):
+        spec, y = "ij,ij->i", HostTensor.from_f32(uniform_pm1(31, 1, rows * n).reshape(rows, n), dtype)
+    elif otimes == "mul_bcast":
+        spec, otimes, y = "ij,i->i", "mul", HostTensor.from_f32(uniform_pm1(31, 1, rows).reshape(rows), dtype)
+    w = single_vertex(spec, x, y, "f32", otimes=otimes, oplus=oplus, parts={"p": part})
+    inputs = {"X": x} if y is None else {"X": x, "Y": y}
+    ref = run_graph(w, inputs)["Z"]
+    got = _run(w, "p", inputs)["Z"]
+    bad, worst = violations(got.as_f64(), ref.as_f64(), RTOL_F32)
+    assert bad == 0, f"{bad} elements out of tolerance (worst {worst:.2f}x)"
+
+
 def test_softmax_pins_on_the_gpu():
     # constant rows of power-of-two length give exactly 1/n; rows sum to one; a row of 1000s needs the max subtraction
     from synth_inputs.workloads import Vertex, Workload
