@@ -263,6 +263,19 @@ static int reduce_split(int64_t outs_total, int64_t red_elems)
     return s < 1 ? 1 : (int)s;
 }
 
+// The same for a column reduction.  There a lane owns a vector of 8 outputs and keeps four 16-byte loads in flight,
+// and 8 lane groups of a workgroup share a piece: enough pieces for some 512 K lanes (64 bytes each, which is what
+// the memory system needs in flight: 128 K lanes reached 3.0 TB/s, 512 K 5.3), each lane with at least 16 steps.
+static int column_split(int64_t vectors_total, int64_t red_elems)
+{
+    const int64_t lanes = vectors_total * 8;
+    if (lanes >= 524288 || red_elems < 256) return 1;
+    int64_t s = (524288 + lanes - 1) / lanes;
+    if (s > red_elems / 128) s = red_elems / 128;
+    if (s > 64) s = 64;
+    return s < 1 ? 1 : (int)s;
+}
+
 // split: 0 = decide here (dry run), otherwise the value fixed when the workspace was laid out
 static int route(const Vertex &v, const Operand &X, const Operand *Y, const std::vector<int64_t> &zstride,
                  const OutSpec &out, Routed &r, int split = 0)
@@ -348,6 +361,44 @@ static int route(const Vertex &v, const Operand &X, const Operand *Y, const std:
             p.split = split > 0 ? split : reduce_split(p.outs_per_block * n_tuples, p.red_elems);
             r.kind = EG_KERNEL_REDUCE_ROW;
             return EG_OK;
+        }
+    }
+
+    // column reduction: the outputs' innermost dimension is contiguous in X and in Z, so lanes can own vectors of
+    // outputs; the aggregated labels lie anywhere else in X
+    {
+        ReduceParams &p = r.rp;
+        memset(&p, 0, sizeof p);
+        std::vector<int> al(v.agg.begin(), v.agg.end());
+        bool ok = true;
+        for (int a : v.agg)
+            if (!li.inx[a]) ok = false;
+        if (ok && collapse(li, zl, p.zdims) && collapse(li, al, p.rdims) && p.zdims.n >= 1 && p.rdims.n >= 1) {
+            const int zd = p.zdims.n - 1;
+            p.outs_per_block = 1;
+            for (int i = 0; i < p.zdims.n; i++) p.outs_per_block *= p.zdims.ext[i];
+            p.red_elems = 1;
+            for (int i = 0; i < p.rdims.n; i++) p.red_elems *= p.rdims.ext[i];
+            const bool yvec = binary && p.zdims.sy[zd] == 1;
+            ok = p.zdims.ext[zd] % 8 == 0 && p.zdims.sx[zd] == 1 && p.zdims.sz[zd] == 1 && aligned16(X.ptr) && aligned16(out.ptr) &&
+                 out.slab_elems % 8 == 0 && p.red_elems >= 16 && p.red_elems < (1ll << 32) &&
+                 (!binary || p.zdims.sy[zd] == 0 || (yvec && aligned16(Y->ptr)));
+            for (int i = 0; i < p.zdims.n && ok; i++)
+                if (i != zd && (p.zdims.sx[i] % 8 || p.zdims.sz[i] % 8 || (yvec && p.zdims.sy[i] % 8))) ok = false;
+            for (int i = 0; i < p.rdims.n && ok; i++)
+                if (p.rdims.sx[i] % 8 || (yvec && p.rdims.sy[i] % 8)) ok = false;
+            for (int l = 0; l < ts.n && ok; l++)
+                if (ts.step_x[l] % 8 || ts.step_z[l] % 8 || (yvec && ts.step_y[l] % 8)) ok = false;
+            if (ok) {
+                p.ts = ts; p.binary = binary; p.otimes = v.otimes; p.oplus = v.oplus; p.alpha = (float)v.alpha;
+                p.dtx = X.dtype; p.dty = Y ? Y->dtype : EG_F32;
+                p.x = X.ptr; p.y = Y ? Y->ptr : nullptr; p.out = out; p.n_tuples = n_tuples;
+                p.vec = 8;
+                p.col = 1;
+                p.split = split > 0 ? split : column_split(p.outs_per_block / 8 * n_tuples, p.red_elems);
+                r.kind = EG_KERNEL_REDUCE_ROW;
+                return EG_OK;
+            }
         }
     }
 

@@ -105,6 +105,8 @@ struct ReduceParams {             // Z[z] = oplus over r of otimes(X[z, r], Y[z,
     int64_t outs_per_block;
     int64_t red_elems;            // prod(rdims.ext)
     int32_t split;                // pieces per output's reduction range (1 = none); piece s lands in slab aggIdx*split+s
+    int32_t col;                  // 1: the outputs' innermost dimension has stride 1 in X and Z; a lane holds 8 consecutive
+                                  //    outputs and walks the reduced index space (rdims then has any strides)
 };
 
 struct GenericParams {            // any EinSum: one output element per lane, sequential loop over l_agg

@@ -327,6 +327,103 @@ __global__ __launch_bounds__(kThreads) void k_reduce_short(const ReduceParams p)
     }
 }
 
+// Reduction over labels that lie outside the outputs' innermost dimension (column sums, `ij->j`, `bij->bj`,
+// `ij,ij->j`): that dimension has stride 1 in X and Z, so a lane owns 8 consecutive outputs and walks a part of the
+// reduced index space, four 16-byte loads in flight.  A workgroup covers a strip of 32 output vectors (512 contiguous
+// bytes of bf16 per step) with 8 lane groups that split the piece's range [lo, hi) into 8 consecutive parts and are
+// combined through LDS in ascending order; the pieces (one per workgroup and strip) become partial slabs like those
+// of a split row reduction.  Sums carry a compensation term, as in the one-output-per-lane kernel: a lane may add
+// tens of thousands of same-signed terms.
+constexpr int kColStrip = 32, kColGroups = kThreads / kColStrip;
+
+template <int OP, int OPLUS>
+__global__ __launch_bounds__(kThreads) void k_reduce_col(const ReduceParams p)
+{
+    constexpr int VEC = 8, U = 4;
+    __shared__ float part[kColGroups][kColStrip][VEC + 1];
+    const int64_t t = tuple_of_block();
+    const int zd = p.zdims.n - 1;
+    const uint32_t nvz = (uint32_t)p.zdims.ext[zd] / VEC;
+    const uint32_t vecs = (uint32_t)(p.outs_per_block / VEC), split = (uint32_t)p.split;
+    const uint32_t strips = (vecs + kColStrip - 1) / kColStrip;
+    const uint32_t wg = pos_of_block();
+    if (wg >= strips * split) return;                               // whole workgroups leave
+    const uint32_t piece = wg / strips, strip = wg - piece * strips;
+    const int lv = threadIdx.x % kColStrip, grp = threadIdx.x / kColStrip;
+    const uint32_t ov = strip * kColStrip + lv;
+    const bool active = ov < vecs;
+    int64_t ox, oy, oz, agg;
+    decode_tuple(p.ts, t, ox, oy, oz, agg);
+    {
+        uint32_t e = (active ? ov : 0) / nvz;
+        const int64_t c = (int64_t)((active ? ov : 0) - e * nvz) * VEC;
+        ox += c; oz += c; oy += c * p.zdims.sy[zd];
+        for (int i = zd - 1; i >= 0; i--) {
+            const uint32_t ext = (uint32_t)p.zdims.ext[i], q = e / ext;
+            const int64_t k = e - q * ext;
+            e = q;
+            ox += k * p.zdims.sx[i]; oy += k * p.zdims.sy[i]; oz += k * p.zdims.sz[i];
+        }
+    }
+    const uint32_t total = (uint32_t)p.red_elems, chunk = (total + split - 1) / split;
+    const uint32_t plo = piece * chunk, phi = (plo + chunk < total) ? plo + chunk : total;
+    const uint32_t sub = (phi - plo + kColGroups - 1) / kColGroups;
+    const uint32_t lo = plo + grp * sub < phi ? plo + grp * sub : phi, hi = (lo + sub < phi) ? lo + sub : phi;
+    const bool sum = (OPLUS >= 0 ? OPLUS : p.oplus) == EG_AGG_SUM;
+    const bool yvec = p.binary && p.zdims.sy[zd] == 1;
+    const int rl = p.rdims.n - 1;
+    float acc[VEC], comp[VEC];
+#pragma unroll
+    for (int i = 0; i < VEC; i++) { acc[i] = oplus_identity(OPLUS >= 0 ? OPLUS : p.oplus); comp[i] = 0.f; }
+    for (uint32_t j0 = lo; active && j0 < hi; j0 += U) {
+        float x[U][VEC], y[U][VEC];
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const uint32_t j = j0 + u < hi ? j0 + u : lo;           // a valid position; its values are not used
+            uint32_t q = j / (uint32_t)p.rdims.ext[rl];
+            const int64_t k = j - q * (uint32_t)p.rdims.ext[rl];
+            int64_t bx = ox + k * p.rdims.sx[rl], by = oy + k * p.rdims.sy[rl];
+            for (int i = rl - 1; i >= 0; i--) {
+                const uint32_t ext = (uint32_t)p.rdims.ext[i], q2 = q / ext;
+                const int64_t k2 = q - q2 * ext;
+                q = q2;
+                bx += k2 * p.rdims.sx[i]; by += k2 * p.rdims.sy[i];
+            }
+            load8(p.x, p.dtx, bx, x[u]);
+            if (yvec) load8(p.y, p.dty, by, y[u]);
+            else if (p.binary) { const float sv = load_elem(p.y, p.dty, by);
+#pragma unroll
+                for (int i = 0; i < VEC; i++) y[u][i] = sv; }
+        }
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            if (j0 + u >= hi) continue;
+#pragma unroll
+            for (int i = 0; i < VEC; i++) {
+                const float v = otimes_t<OP, false>(p.otimes, x[u][i], p.binary ? y[u][i] : 0.f, p.alpha);
+                if (sum) {
+                    const float d = v - comp[i], s2 = acc[i] + d;
+                    comp[i] = (s2 - acc[i]) - d;
+                    acc[i] = s2;
+                } else {
+                    acc[i] = oplus_t<OPLUS>(p.oplus, acc[i], v);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < VEC; i++) part[grp][lv][i] = acc[i];
+    __syncthreads();
+    if (grp != 0 || !active) return;
+#pragma unroll
+    for (int g = 1; g < kColGroups; g++) {                         // ascending parts; an empty part holds the identity
+#pragma unroll
+        for (int i = 0; i < VEC; i++) acc[i] = oplus_t<OPLUS>(p.oplus, acc[i], part[g][lv][i]);
+    }
+    char *zb = (char *)p.out.ptr + (p.out.slab_elems ? (agg * split + piece) * p.out.slab_elems * 4 : 0);
+    store8(zb, p.out.dtype, oz, acc);
+}
+
 // ------------------------------------------------------------------------------------------------
 // aggregation of partial slabs: out[e] = (+)_{a ascending} partials[a][e], fp32, one final cast
 // ------------------------------------------------------------------------------------------------
@@ -526,6 +623,20 @@ int launch_reduce_row(const ReduceParams &p, void *stream)
     if (p.rdims.n < 1) return fail(EG_ERR_LIMIT, "reduce kernel: empty reduction space");
     if (p.split < 1 || (p.split > 1 && !p.out.slab_elems)) return fail(EG_ERR_LIMIT, "reduce kernel: split needs partial slabs");
     if (p.red_elems >= (1ll << 32)) return fail(EG_ERR_LIMIT, "reduce kernel: reduction space above 2^32");
+    hipStream_t st = (hipStream_t)stream;
+    if (p.col) {
+        const int zd = p.zdims.n - 1;
+        if (p.zdims.n < 1 || p.zdims.ext[zd] % 8 || p.zdims.sx[zd] != 1 || p.zdims.sz[zd] != 1 || p.outs_per_block % 8)
+            return fail(EG_ERR_LIMIT, "reduce kernel: outputs are not whole 16-byte vectors");
+        dim3 grid;
+        int rc = tuple_grid((p.outs_per_block / 8 + kColStrip - 1) / kColStrip * p.split, 1, p.n_tuples, grid);
+        if (rc) return rc;
+        if (p.otimes == EG_IDENT && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_col<EG_IDENT, EG_AGG_SUM>), grid, dim3(kThreads), 0, st, p);
+        else if (p.otimes == EG_IDENT && p.oplus == EG_AGG_MAX) hipLaunchKernelGGL((k_reduce_col<EG_IDENT, EG_AGG_MAX>), grid, dim3(kThreads), 0, st, p);
+        else if (p.otimes == EG_MUL && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_col<EG_MUL, EG_AGG_SUM>), grid, dim3(kThreads), 0, st, p);
+        else hipLaunchKernelGGL((k_reduce_col<-1, -1>), grid, dim3(kThreads), 0, st, p);
+        return check_launch("k_reduce_col");
+    }
     const int64_t slots = p.outs_per_block * p.split;
     // vectors one (output, piece) reduces over, as the kernel counts them
     const int vd = p.rdims.n - 1;
@@ -538,7 +649,6 @@ int launch_reduce_row(const ReduceParams &p, void *stream)
         if (p.vec == 8) while (lanes > 8 && lanes / 2 >= chunk) lanes /= 2;   // short rows: several outputs per wave
     }
     dim3 grid;
-    hipStream_t st = (hipStream_t)stream;
     if (p.vec == 8 && lanes <= 64 && chunk <= lanes) {        // one vector per lane: four (output, piece) per lane group
         constexpr int R = 4;
         int rc = tuple_grid(slots, kThreads / lanes * R, p.n_tuples, grid);

@@ -286,6 +286,41 @@ def test_row_reductions_over_short_rows(rows, n, otimes, oplus, part, dtype):
     assert bad == 0, f"{bad} elements out of tolerance (worst {worst:.2f}x)"
 
 
+@pytest.mark.parametrize("dtype,out_dtype", [("f32", "f32"), ("bf16", "f32"), ("bf16", "bf16")])
+@pytest.mark.parametrize("spec,bx,by,otimes,oplus,part", [
+    ("ij->j", (1000, 264), None, "ident", "sum", {}),                     # column sums: few outputs, pieces into slabs
+    ("ij->j", (1000, 264), None, "ident", "max", {"i": 4}),               # the reduced label cut as well
+    ("ij->j", (333, 4096), None, "relu", "sum", {"j": 4}),
+    ("bij->bj", (5, 200, 136), None, "ident", "sum", {"b": 5}),           # the middle label goes
+    ("bij->j", (5, 200, 136), None, "ident", "sum", {"i": 2}),            # two reduced labels that do not fuse with a cut between
+    ("ibj->bj", (70, 3, 72), None, "exp", "sum", {}),
+    ("ij,ij->j", (700, 200), (700, 200), "mul", "sum", {"i": 7}),
+    ("ij,j->j", (700, 200), (200,), "sqdiff", "sum", {}),
+    ("ij,i->j", (700, 200), (700,), "mul", "sum", {"j": 5}),              # one value of Y per reduction step
+    ("ij->j", (70000, 8), None, "ident", "sum", {}),                      # one vector of outputs, a long walk: 64 pieces
+    ("ij->j", (20, 64), None, "ident", "sum", {}),
+])
+def test_reductions_over_leading_labels(spec, bx, by, otimes, oplus, part, dtype, out_dtype):
+    """The outputs' innermost label is contiguous in X, the reduced labels lie in front of it: lanes own vectors of
+    outputs and walk the reduction, which is cut into pieces when there are few outputs."""
+    print(f"{spec} {bx} {otimes}/{oplus} {part} {dtype}->{out_dtype}", flush=True)
+    x = HostTensor.from_f32(uniform_pm1(41, 0, int(np.prod(bx))).reshape(bx), dtype)
+    y = None if by is None else HostTensor.from_f32(uniform_pm1(41, 1, int(np.prod(by))).reshape(by), dtype)
+    w = single_vertex(spec, x, y, out_dtype, otimes=otimes, oplus=oplus, parts={"p": part, "whole": {}})
+    inputs = {"X": x} if y is None else {"X": x, "Y": y}
+    ref = run_graph(w, inputs)["Z"]
+    for pname in ("p", "whole"):
+        import paper_2410_02682_amd as E
+        from paper_2410_02682_amd.runner import GraphRunner
+        r = GraphRunner(w, pname)
+        kernel = r.plan("Z")["kernel"]
+        r.close()
+        assert kernel == "reduce_row", kernel
+        got = _run(w, pname, inputs)["Z"]
+        bad, worst = violations(got.as_f64(), ref.as_f64(), RTOL_BF16 if out_dtype == "bf16" else RTOL_F32)
+        assert bad == 0, f"{pname}: {bad} elements out of tolerance (worst {worst:.2f}x)"
+
+
 def test_softmax_pins_on_the_gpu():
     # constant rows of power-of-two length give exactly 1/n; rows sum to one; a row of 1000s needs the max subtraction
     from synth_inputs.workloads import Vertex, Workload
