@@ -259,8 +259,7 @@ static int reduce_split(int64_t outs_total, int64_t red_elems)
     if (outs_total >= 1024 || red_elems < 32768) return 1;
     int64_t s = (1024 + outs_total - 1) / outs_total;
     if (s > red_elems / 8192) s = red_elems / 8192;
-    if (s > 64) s = 64;
-    return s < 1 ? 1 : (int)s;
+    return s < 1 ? 1 : (int)s;                      // at most 1024 pieces of at least 8192 elements
 }
 
 // The same for a column reduction.  There a lane owns a vector of 8 outputs and keeps four 16-byte loads in flight,
@@ -337,6 +336,8 @@ static int route(const Vertex &v, const Operand &X, const Operand *Y, const std:
         for (int a : v.agg) red *= li.ext[a];
         if (red < 64) tail = false;
     }
+    bool have_row = false;
+    ReduceParams row;
     if (tail) {
         ReduceParams &p = r.rp;
         memset(&p, 0, sizeof p);
@@ -360,7 +361,9 @@ static int route(const Vertex &v, const Operand &X, const Operand *Y, const std:
             p.vec = (vx && vy) ? 8 : 1;
             p.split = split > 0 ? split : reduce_split(p.outs_per_block * n_tuples, p.red_elems);
             r.kind = EG_KERNEL_REDUCE_ROW;
-            return EG_OK;
+            if (p.vec == 8) return EG_OK;
+            have_row = true;                    // element by element: only if the column form below does not apply
+            row = p;
         }
     }
 
@@ -379,16 +382,17 @@ static int route(const Vertex &v, const Operand &X, const Operand *Y, const std:
             for (int i = 0; i < p.zdims.n; i++) p.outs_per_block *= p.zdims.ext[i];
             p.red_elems = 1;
             for (int i = 0; i < p.rdims.n; i++) p.red_elems *= p.rdims.ext[i];
-            const bool yvec = binary && p.zdims.sy[zd] == 1;
-            ok = p.zdims.ext[zd] % 8 == 0 && p.zdims.sx[zd] == 1 && p.zdims.sz[zd] == 1 && aligned16(X.ptr) && aligned16(out.ptr) &&
-                 out.slab_elems % 8 == 0 && p.red_elems >= 16 && p.red_elems < (1ll << 32) &&
-                 (!binary || p.zdims.sy[zd] == 0 || (yvec && aligned16(Y->ptr)));
+            // along that dimension an operand is read in 16-byte vectors (stride 1) or as one value (stride 0, or absent)
+            const bool xvec = p.zdims.sx[zd] == 1, yvec = binary && p.zdims.sy[zd] == 1;
+            ok = p.zdims.ext[zd] % 8 == 0 && p.zdims.sz[zd] == 1 && aligned16(out.ptr) && out.slab_elems % 8 == 0 &&
+                 p.red_elems >= 16 && p.red_elems < (1ll << 32) && (xvec || yvec) &&
+                 (xvec ? aligned16(X.ptr) : p.zdims.sx[zd] == 0) && (!binary || (yvec ? aligned16(Y->ptr) : p.zdims.sy[zd] == 0));
             for (int i = 0; i < p.zdims.n && ok; i++)
-                if (i != zd && (p.zdims.sx[i] % 8 || p.zdims.sz[i] % 8 || (yvec && p.zdims.sy[i] % 8))) ok = false;
+                if (i != zd && ((xvec && p.zdims.sx[i] % 8) || p.zdims.sz[i] % 8 || (yvec && p.zdims.sy[i] % 8))) ok = false;
             for (int i = 0; i < p.rdims.n && ok; i++)
-                if (p.rdims.sx[i] % 8 || (yvec && p.rdims.sy[i] % 8)) ok = false;
+                if ((xvec && p.rdims.sx[i] % 8) || (yvec && p.rdims.sy[i] % 8)) ok = false;
             for (int l = 0; l < ts.n && ok; l++)
-                if (ts.step_x[l] % 8 || ts.step_z[l] % 8 || (yvec && ts.step_y[l] % 8)) ok = false;
+                if ((xvec && ts.step_x[l] % 8) || ts.step_z[l] % 8 || (yvec && ts.step_y[l] % 8)) ok = false;
             if (ok) {
                 p.ts = ts; p.binary = binary; p.otimes = v.otimes; p.oplus = v.oplus; p.alpha = (float)v.alpha;
                 p.dtx = X.dtype; p.dty = Y ? Y->dtype : EG_F32;
@@ -400,6 +404,12 @@ static int route(const Vertex &v, const Operand &X, const Operand *Y, const std:
                 return EG_OK;
             }
         }
+    }
+
+    if (have_row) {
+        r.rp = row;
+        r.kind = EG_KERNEL_REDUCE_ROW;
+        return EG_OK;
     }
 
     GenericParams &p = r.gp;

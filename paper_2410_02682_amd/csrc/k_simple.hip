@@ -357,7 +357,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_col(const ReduceParams p)
     {
         uint32_t e = (active ? ov : 0) / nvz;
         const int64_t c = (int64_t)((active ? ov : 0) - e * nvz) * VEC;
-        ox += c; oz += c; oy += c * p.zdims.sy[zd];
+        ox += c * p.zdims.sx[zd]; oz += c; oy += c * p.zdims.sy[zd];
         for (int i = zd - 1; i >= 0; i--) {
             const uint32_t ext = (uint32_t)p.zdims.ext[i], q = e / ext;
             const int64_t k = e - q * ext;
@@ -370,7 +370,7 @@ __global__ __launch_bounds__(kThreads) void k_reduce_col(const ReduceParams p)
     const uint32_t sub = (phi - plo + kColGroups - 1) / kColGroups;
     const uint32_t lo = plo + grp * sub < phi ? plo + grp * sub : phi, hi = (lo + sub < phi) ? lo + sub : phi;
     const bool sum = (OPLUS >= 0 ? OPLUS : p.oplus) == EG_AGG_SUM;
-    const bool yvec = p.binary && p.zdims.sy[zd] == 1;
+    const bool xvec = p.zdims.sx[zd] == 1, yvec = p.binary && p.zdims.sy[zd] == 1;   // else one value for the 8 outputs
     const int rl = p.rdims.n - 1;
     float acc[VEC], comp[VEC];
 #pragma unroll
@@ -389,7 +389,10 @@ __global__ __launch_bounds__(kThreads) void k_reduce_col(const ReduceParams p)
                 q = q2;
                 bx += k2 * p.rdims.sx[i]; by += k2 * p.rdims.sy[i];
             }
-            load8(p.x, p.dtx, bx, x[u]);
+            if (xvec) load8(p.x, p.dtx, bx, x[u]);
+            else { const float sv = load_elem(p.x, p.dtx, bx);
+#pragma unroll
+                for (int i = 0; i < VEC; i++) x[u][i] = sv; }
             if (yvec) load8(p.y, p.dty, by, y[u]);
             else if (p.binary) { const float sv = load_elem(p.y, p.dty, by);
 #pragma unroll
@@ -497,20 +500,37 @@ __global__ __launch_bounds__(kThreads) void k_aggregate_scalar(const AggregatePa
 }
 
 // Few outputs, many slabs (a loss whose reduction was cut into hundreds of pieces): one wave per output element.
-// The lanes fetch 64 slabs' values at once; the additions still run one after the other in ascending slab order
-// (every lane does all of them on values read from the other lanes), so the result is that of the plain loop.
+// The lanes fetch 512 slabs' values at once into LDS; one lane then adds them one after the other in ascending slab
+// order, so the result is that of the plain loop (reading a value from another lane's register for every addition
+// instead cost 35 ns per slab).
 __global__ __launch_bounds__(64) void k_aggregate_wave(const AggregateParams p)
 {
+    constexpr int B = 8;
+    __shared__ float4 sh[64 * B / 4];
     const int64_t e = blockIdx.x;
     const int lane = threadIdx.x;
-    float acc = 0.f;
-    for (int64_t a0 = 0; a0 < p.n_agg; a0 += 64) {
-        const int64_t a = a0 + lane;
-        const float v = p.partials[(a < p.n_agg ? a : a0) * p.slab_stride + e];
-        const int cnt = (int)(p.n_agg - a0 < 64 ? p.n_agg - a0 : 64);
-        for (int j = 0; j < cnt; j++) {
-            const float x = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), j));
-            acc = (a0 == 0 && j == 0) ? x : oplus_eval(p.oplus, acc, x);
+    const float ident = oplus_identity(p.oplus);           // x (+) identity = x exactly, so the chain may start from it
+    float acc = ident;
+    for (int64_t a0 = 0; a0 < p.n_agg; a0 += 64 * B) {
+        float v[B];
+#pragma unroll
+        for (int b = 0; b < B; b++) {
+            const int64_t a = a0 + b * 64 + lane;
+            v[b] = a < p.n_agg ? p.partials[a * p.slab_stride + e] : ident;
+        }
+        __syncthreads();                                   // the previous round's values have been read
+#pragma unroll
+        for (int b = 0; b < B; b++) ((float *)sh)[b * 64 + lane] = v[b];
+        __syncthreads();
+        if (lane == 0) {
+            const int64_t left = p.n_agg - a0;
+            const int cnt = (int)(left < 64 * B ? left : 64 * B);
+            // slots past cnt hold the identity (see the fill above), so whole vectors are added
+            if (p.oplus == EG_AGG_MAX) {
+                for (int j = 0; j < cnt; j += 4) { const float4 q = sh[j / 4]; acc = fmaxf(fmaxf(fmaxf(fmaxf(acc, q.x), q.y), q.z), q.w); }
+            } else {
+                for (int j = 0; j < cnt; j += 4) { const float4 q = sh[j / 4]; acc = (((acc + q.x) + q.y) + q.z) + q.w; }
+            }
         }
     }
     if (lane != 0) return;
@@ -626,7 +646,7 @@ int launch_reduce_row(const ReduceParams &p, void *stream)
     hipStream_t st = (hipStream_t)stream;
     if (p.col) {
         const int zd = p.zdims.n - 1;
-        if (p.zdims.n < 1 || p.zdims.ext[zd] % 8 || p.zdims.sx[zd] != 1 || p.zdims.sz[zd] != 1 || p.outs_per_block % 8)
+        if (p.zdims.n < 1 || p.zdims.ext[zd] % 8 || (p.zdims.sx[zd] != 1 && p.zdims.sx[zd] != 0) || p.zdims.sz[zd] != 1 || p.outs_per_block % 8)
             return fail(EG_ERR_LIMIT, "reduce kernel: outputs are not whole 16-byte vectors");
         dim3 grid;
         int rc = tuple_grid((p.outs_per_block / 8 + kColStrip - 1) / kColStrip * p.split, 1, p.n_tuples, grid);

@@ -242,6 +242,7 @@ def test_every_scalar_function_elementwise(shape, part, dtype):
     ("ij,j->i", (40, 1024), (1024,), "mul", "sum", {"j": 2}),
     ("ij,jk->ik", (37, 53), (53, 29), "mul", "sum", {}),          # nothing divides a vector: scalar paths
     ("ij->", (256, 1024), None, "exp", "sum", {}),                # one output, long reduction: split into pieces
+    ("ij->", (3000, 4096), None, "ident", "sum", {}),             # ... into a thousand of them
     ("ij->", (256, 1024), None, "ident", "max", {"i": 2}),        # split pieces x two partial blocks
     ("bij,bij->b", (3, 200, 328), (3, 200, 328), "mul", "sum", {"i": 2}),
 ])
@@ -297,6 +298,8 @@ def test_row_reductions_over_short_rows(rows, n, otimes, oplus, part, dtype):
     ("ij,ij->j", (700, 200), (700, 200), "mul", "sum", {"i": 7}),
     ("ij,j->j", (700, 200), (200,), "sqdiff", "sum", {}),
     ("ij,i->j", (700, 200), (700,), "mul", "sum", {"j": 5}),              # one value of Y per reduction step
+    ("i,ij->j", (700,), (700, 200), "mul", "sum", {"i": 2}),              # the matrix is the second operand
+    ("bi,ij->bj", (3, 90), (90, 136), "absdiff", "max", {}),
     ("ij->j", (70000, 8), None, "ident", "sum", {}),                      # one vector of outputs, a long walk: 64 pieces
     ("ij->j", (20, 64), None, "ident", "sum", {}),
 ])
