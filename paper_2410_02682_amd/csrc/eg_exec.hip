@@ -303,6 +303,21 @@ static int route(const Vertex &v, const Operand &X, const Operand *Y, const std:
         bool vx = vec_ok(p.dims, 0, vd, 8, X.ptr, ts, true);
         bool vy = !binary || vec_ok(p.dims, 1, vd, 8, Y->ptr, ts, true);
         p.vec = (vz && vx && vy) ? 8 : 1;
+        // one operand contiguous along another dimension than Z's last (a transpose): tiles through LDS
+        if (p.vec == 1 && vz && p.dims.n >= 2 && (!binary || vx != vy) && (binary || !vx)) {
+            const bool xt = !vx;
+            const int64_t *s = xt ? p.dims.sx : p.dims.sy;
+            const int64_t *step = xt ? ts.step_x : ts.step_y;
+            int td = -1;
+            for (int i = 0; i < vd; i++)
+                if (s[i] == 1 && p.dims.ext[i] % 8 == 0) td = i;
+            bool ok = td >= 0 && aligned16(xt ? X.ptr : Y->ptr);
+            for (int i = 0; i < p.dims.n && ok; i++)
+                if (i != td && s[i] % 8) ok = false;
+            for (int l = 0; l < ts.n && ok; l++)
+                if (step[l] % 8) ok = false;
+            if (ok) { p.tr = xt ? 1 : 2; p.td = td; p.vec = 8; }
+        }
         int64_t rows = 1;
         for (int i = 0; i < vd; i++) rows *= p.dims.ext[i];
         p.vecs_per_block = rows * ((p.dims.ext[vd] + p.vec - 1) / p.vec);

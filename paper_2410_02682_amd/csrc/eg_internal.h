@@ -88,6 +88,8 @@ struct MapParams {                // Z[z] = otimes(X[..], Y[..]) over one block 
     OutSpec out;
     int64_t n_tuples;
     int64_t vecs_per_block;       // prod(ext[0..n-2]) * ceil(ext[n-1] / vec)
+    int32_t tr;                   // 0: none.  1 / 2: X / Y has its stride-1 dimension at dims[td] instead of the last one
+    int32_t td;                   //    (a transposed operand); it goes through LDS in 64 x 64 tiles, the other one is read along Z
 };
 
 struct ReduceParams {             // Z[z] = oplus over r of otimes(X[z, r], Y[z, r]); one wave-group per z

@@ -135,6 +135,77 @@ __global__ __launch_bounds__(kThreads) void k_map(const MapParams p)
     }
 }
 
+// Element-wise vertex with one transposed operand (`ij->ji`, `bhst->bhts`, `ij,ji->ij`): Z is contiguous along its
+// last dimension a = dims[n-1], the transposed operand T along another one, b = dims[td].  A workgroup moves a tile of
+// 64 (a) x 64 (b): T is read in 16-byte vectors along b into LDS (as fp32, rows padded to 65 words), then every
+// lane gathers 8 consecutive a for one b from LDS, reads the other operand (if any) along Z, and writes a 16-byte
+// vector of Z.  Element by element these vertices ran at 1.0-1.6 TB/s.
+constexpr int kTrTile = 64;
+
+template <int OP, bool FAST>
+__global__ __launch_bounds__(kThreads) void k_map_tr(const MapParams p)
+{
+    __shared__ float tile[kTrTile][kTrTile + 1];
+    const int64_t t = tuple_of_block();
+    uint32_t pos = pos_of_block();
+    const int vd = p.dims.n - 1, td = p.td;
+    const uint32_t ea = (uint32_t)p.dims.ext[vd], eb = (uint32_t)p.dims.ext[td];
+    const uint32_t ta = (ea + kTrTile - 1) / kTrTile, tb = (eb + kTrTile - 1) / kTrTile;
+    const bool xt = p.tr == 1;                                      // which operand is the transposed one
+    const int64_t *st = xt ? p.dims.sx : p.dims.sy, *so = xt ? p.dims.sy : p.dims.sx;
+    int64_t ox, oy, oz, agg;
+    decode_tuple(p.ts, t, ox, oy, oz, agg);
+    int64_t ot = xt ? ox : oy, oo = xt ? oy : ox;
+    const uint32_t b0 = (pos % tb) * kTrTile;
+    pos /= tb;
+    const uint32_t a0 = (pos % ta) * kTrTile;
+    pos /= ta;
+    for (int i = vd - 1; i >= 0; i--) {
+        if (i == td) continue;
+        const uint32_t ext = (uint32_t)p.dims.ext[i], q = pos / ext;
+        const int64_t k = pos - q * ext;
+        pos = q;
+        ot += k * st[i]; oo += k * so[i]; oz += k * p.dims.sz[i];
+    }
+    if (pos != 0) return;                                           // beyond the block (whole workgroups leave)
+    const void *tp = xt ? p.x : p.y, *op = xt ? p.y : p.x;
+    const int dtt = xt ? p.dtx : p.dty, dto = xt ? p.dty : p.dtx;
+#pragma unroll
+    for (int h = 0; h < kTrTile * kTrTile / 8 / kThreads; h++) {    // T: rows along a, vectors along b
+        const int v = h * kThreads + threadIdx.x, ra = v / (kTrTile / 8), vb = v % (kTrTile / 8);
+        if (a0 + ra < ea && b0 + vb * 8 < eb) {
+            float x[8];
+            load8(tp, dtt, ot + (int64_t)(a0 + ra) * st[vd] + (b0 + vb * 8), x);
+#pragma unroll
+            for (int i = 0; i < 8; i++) tile[ra][vb * 8 + i] = x[i];
+        }
+    }
+    __syncthreads();
+    char *zb = out_base(p.out, agg);
+#pragma unroll
+    for (int h = 0; h < kTrTile * kTrTile / 8 / kThreads; h++) {    // Z: rows along b, vectors along a
+        const int v = h * kThreads + threadIdx.x, rb = v / (kTrTile / 8), va = v % (kTrTile / 8);
+        if (b0 + rb < eb && a0 + va * 8 < ea) {
+            float tv[8], ov[8], z[8];
+#pragma unroll
+            for (int i = 0; i < 8; i++) tv[i] = tile[va * 8 + i][rb];
+            if (p.binary) {
+                const int64_t o = oo + (int64_t)(b0 + rb) * so[td] + (int64_t)(a0 + va * 8) * so[vd];
+                if (so[vd] == 1) load8(op, dto, o, ov);
+                else { const float sv = load_elem(op, dto, o);
+#pragma unroll
+                    for (int i = 0; i < 8; i++) ov[i] = sv; }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; i++) ov[i] = 0.f;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; i++) z[i] = otimes_t<OP, FAST>(p.otimes, xt ? tv[i] : ov[i], xt ? ov[i] : tv[i], p.alpha);
+            store8(zb, p.out.dtype, oz + (int64_t)(b0 + rb) * p.dims.sz[td] + (a0 + va * 8), z);
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------------
 // row reduction: LANES lanes cooperate on one output element; the reduced labels are X's trailing dims.
 // With split > 1 (few outputs, long reductions) each output's reduction range is cut into `split` pieces
@@ -594,6 +665,13 @@ static void launch_map_vec(const MapParams &p, dim3 grid, hipStream_t st)
     else hipLaunchKernelGGL((k_map<8, OP, false>), grid, dim3(kThreads), 0, st, p);
 }
 
+template <int OP>
+static void launch_map_tr(const MapParams &p, dim3 grid, hipStream_t st)
+{
+    if (p.out.dtype == EG_BF16) hipLaunchKernelGGL((k_map_tr<OP, true>), grid, dim3(kThreads), 0, st, p);
+    else hipLaunchKernelGGL((k_map_tr<OP, false>), grid, dim3(kThreads), 0, st, p);
+}
+
 int launch_map(const MapParams &p, void *stream)
 {
     if (!p.x || (p.binary && !p.y) || !p.out.ptr) return fail(EG_ERR_NULL, "map kernel: NULL operand");
@@ -601,6 +679,25 @@ int launch_map(const MapParams &p, void *stream)
     if (p.vec != 1 && p.vec != 8) return fail(EG_ERR_LIMIT, "map kernel: vector width %d", p.vec);
     hipStream_t st = (hipStream_t)stream;
     dim3 grid;
+    if (p.tr) {
+        const int vd = p.dims.n - 1;
+        const int64_t *s = p.tr == 1 ? p.dims.sx : p.dims.sy;
+        if ((p.tr != 1 && !(p.tr == 2 && p.binary)) || p.dims.n < 2 || p.td < 0 || p.td >= vd || s[p.td] != 1 || p.dims.sz[vd] != 1 ||
+            p.dims.ext[vd] % 8 || p.dims.ext[p.td] % 8)
+            return fail(EG_ERR_LIMIT, "map kernel: not a transposed operand");
+        int64_t tiles = ((p.dims.ext[vd] + kTrTile - 1) / kTrTile) * ((p.dims.ext[p.td] + kTrTile - 1) / kTrTile);
+        for (int i = 0; i < vd; i++)
+            if (i != p.td) tiles *= p.dims.ext[i];
+        int rc = tuple_grid(tiles, 1, p.n_tuples, grid);
+        if (rc) return rc;
+        switch (p.otimes) {
+#define EG_CASE(OP) case OP: launch_map_tr<OP>(p, grid, st); break;
+        EG_CASE(EG_MUL) EG_CASE(EG_ADD) EG_CASE(EG_SUB) EG_CASE(EG_IDENT) EG_CASE(EG_SCALE)
+#undef EG_CASE
+        default: launch_map_tr<-1>(p, grid, st); break;
+        }
+        return check_launch("k_map_tr");
+    }
     int rc = tuple_grid(p.vecs_per_block, kThreads, p.n_tuples, grid);
     if (rc) return rc;
     if (p.vec == 1) {

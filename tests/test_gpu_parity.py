@@ -324,6 +324,34 @@ def test_reductions_over_leading_labels(spec, bx, by, otimes, oplus, part, dtype
         assert bad == 0, f"{pname}: {bad} elements out of tolerance (worst {worst:.2f}x)"
 
 
+@pytest.mark.parametrize("dtype,out_dtype", [("f32", "f32"), ("bf16", "bf16"), ("bf16", "f32")])
+@pytest.mark.parametrize("spec,bx,by,otimes,part", [
+    ("ij->ji", (200, 136), None, "ident", {}),                            # ragged 64 x 64 tiles in both directions
+    ("ij->ji", (64, 64), None, "scale", {"i": 2, "j": 4}),
+    ("ij->ji", (8, 1000), None, "relu", {"j": 5}),
+    ("bij->bji", (3, 72, 264), None, "ident", {"b": 3}),
+    ("bhst->bhts", (2, 3, 80, 136), None, "exp", {"h": 3, "s": 2}),
+    ("ibj->jbi", (72, 5, 40), None, "ident", {}),                         # a label between the two that swap
+    ("ij,ji->ij", (136, 200), (200, 136), "add", {"i": 2}),               # the second operand is the transposed one
+    ("ij,ji->ji", (136, 200), (200, 136), "sub", {"j": 5}),               # the first one is
+    ("ij,i->ji", (136, 200), (136,), "mul", {}),                          # transposed operand and one value per column
+    ("bij,j->bji", (2, 72, 64), (64,), "sqdiff", {}),
+])
+def test_elementwise_vertices_with_a_transposed_operand(spec, bx, by, otimes, part, dtype, out_dtype):
+    print(f"{spec} {bx} {otimes} {part} {dtype}->{out_dtype}", flush=True)
+    x = HostTensor.from_f32(uniform_pm1(51, 0, int(np.prod(bx))).reshape(bx), dtype)
+    y = None if by is None else HostTensor.from_f32(uniform_pm1(51, 1, int(np.prod(by))).reshape(by), dtype)
+    w = single_vertex(spec, x, y, out_dtype, otimes=otimes, oplus="none", alpha=-0.75, parts={"p": part, "whole": {}})
+    inputs = {"X": x} if y is None else {"X": x, "Y": y}
+    ref = run_graph(w, inputs)["Z"]
+    for pname in ("p", "whole"):
+        got = _run(w, pname, inputs)["Z"]
+        bad, worst = violations(got.as_f64(), ref.as_f64(), RTOL_BF16 if out_dtype == "bf16" else RTOL_F32)
+        assert bad == 0, f"{pname}: {bad} elements out of tolerance (worst {worst:.2f}x)"
+        if otimes == "ident" and dtype == out_dtype:                    # a pure permutation moves bits
+            assert np.array_equal(got.data, ref.data)
+
+
 def test_softmax_pins_on_the_gpu():
     # constant rows of power-of-two length give exactly 1/n; rows sum to one; a row of 1000s needs the max subtraction
     from synth_inputs.workloads import Vertex, Workload
