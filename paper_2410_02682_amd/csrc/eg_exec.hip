@@ -325,8 +325,21 @@ static int route(const Vertex &v, const Operand &X, const Operand *Y, const std:
         return EG_OK;
     }
 
-    if (binary && build_contract(v, li, X, *Y, r.cp)) {
-        r.cp.ts = ts;
+    // Z contiguous along a label that only X carries: with a symmetric scalar function the operands change places,
+    // so that label becomes a column label and result tiles are written along their rows in 16-byte vectors
+    // (same products, same order of summation; `ij,jk->ki` ran 30 % slower than `ij,jk->ik` before).
+    bool swap = false;
+    if (binary && (v.otimes == EG_MUL || v.otimes == EG_ADD || v.otimes == EG_SQDIFF || v.otimes == EG_ABSDIFF))
+        for (int l = 0; l < li.nl; l++)
+            if (li.inz[l] && li.ext[l] > 1 && li.sz[l] == 1 && li.inx[l] && !li.iny[l]) swap = true;
+    LabelInfo lc = li;
+    TupleSpace tc = ts;
+    if (swap) {
+        for (int l = 0; l < li.nl; l++) { std::swap(lc.inx[l], lc.iny[l]); std::swap(lc.sx[l], lc.sy[l]); }
+        for (int l = 0; l < ts.n; l++) std::swap(tc.step_x[l], tc.step_y[l]);
+    }
+    if (binary && build_contract(v, lc, swap ? *Y : X, swap ? X : *Y, r.cp)) {
+        r.cp.ts = tc;
         r.cp.out = out;
         r.cp.n_tuples = n_tuples;
         r.kind = v.otimes == EG_MUL && v.oplus == EG_AGG_SUM ? EG_KERNEL_CONTRACT_MFMA : EG_KERNEL_CONTRACT_ALU;
