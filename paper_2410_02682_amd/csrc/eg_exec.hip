@@ -471,7 +471,8 @@ static int64_t slab_stride_of(int64_t dense_elems, int64_t slabs)
 struct Layout {
     std::vector<int64_t> result_off;    // per vertex: byte offset of its tensor in the workspace (-1: not there)
     std::vector<int64_t> partial_off;   // per vertex: byte offset of its partial slabs (-1: none)
-    std::vector<int> split;             // per vertex: extra slabs per aggIdx from a split row reduction (1: none)
+    std::vector<int> split;             // per vertex: extra slabs per aggIdx from a split row reduction or contraction (1: none)
+    std::vector<int> split_label;       // contraction: the contracted label that is cut `split` times finer
     int64_t total = 0;
 };
 
@@ -642,6 +643,42 @@ static Vertex merged_vertex(const Vertex &v)
     return m;
 }
 
+// An under-filled contraction with a long reduction (a matrix times a few vectors, a small product of long rows):
+// the executor cuts one contracted label further than the vertex's own vector says, as many ways as it takes to
+// give the chip's compute units a tile each.  The pieces are ordinary join tuples that write partial slabs, which
+// the aggregation adds in ascending order like any others.  Returns the extra factor (a power of two, 1: none).
+static int contraction_split(const Vertex &v, const ContractParams &cp, int *label)
+{
+    const int64_t tiles = ((cp.M + 127) / 128) * ((cp.N + 127) / 128) * cp.n_batch * v.plan.n_tuples;
+    if (tiles > 128 || cp.K < 4096) return 1;
+    int64_t want = std::min<int64_t>(std::min<int64_t>(512 / tiles, cp.K / 1024), 64);
+    int best = -1;
+    int64_t be = 0;
+    for (int a : v.agg) {
+        const int64_t e = v.lbound[a] / v.d[a];
+        if (e > be) { be = e; best = a; }
+    }
+    int c = 1;
+    while (best >= 0 && c * 2 <= want && be % (c * 2) == 0 && (be / (c * 2)) % 64 == 0) c *= 2;
+    *label = best;
+    return c;
+}
+
+// the vertex with one contracted label cut c times finer
+static Vertex refined_vertex(const Vertex &v, int label, int c)
+{
+    Vertex m;
+    m.dtype = v.dtype; m.bound = v.bound; m.spec = v.spec; m.lx = v.lx; m.ly = v.ly; m.lz = v.lz;
+    m.labels = v.labels; m.lbound = v.lbound; m.d = v.d; m.agg = v.agg;
+    m.otimes = v.otimes; m.oplus = v.oplus; m.alpha = v.alpha; m.in[0] = v.in[0]; m.in[1] = v.in[1]; m.n_in = v.n_in;
+    m.d[label] *= c;
+    m.plan.n_tuples = v.plan.n_tuples * c;
+    m.plan.n_agg = v.plan.n_agg * c;
+    m.plan.n_groups = v.plan.n_groups;
+    m.plan.valid = true;
+    return m;
+}
+
 static Layout make_layout(const eg_graph *g)
 {
     const int nv = (int)g->v.size();
@@ -649,6 +686,7 @@ static Layout make_layout(const eg_graph *g)
     L.result_off.assign(nv, -1);
     L.partial_off.assign(nv, -1);
     L.split.assign(nv, 1);
+    L.split_label.assign(nv, -1);
     // a fused chain runs where its last vertex stands: it reads the chain's outside operands there and writes the
     // result (and the row statistics that are still wanted); the other tensors of the chain never exist
     const std::vector<FuseGroup> groups = find_fusions(g);
@@ -687,7 +725,11 @@ static Layout make_layout(const eg_graph *g)
         if (!v.is_output) L.result_off[i] = arena.alloc(numel(v.bound) * dtype_size(v.dtype));
         {
             Routed r;
-            if (dry_route(g, i, r) == EG_OK && r.kind == EG_KERNEL_REDUCE_ROW) L.split[i] = r.rp.split;
+            if (dry_route(g, i, r) == EG_OK) {
+                if (r.kind == EG_KERNEL_REDUCE_ROW) L.split[i] = r.rp.split;
+                else if ((r.kind == EG_KERNEL_CONTRACT_MFMA || r.kind == EG_KERNEL_CONTRACT_ALU) && !merges_aggregation(g, i))
+                    L.split[i] = contraction_split(v, r.cp, &L.split_label[i]);
+            }
         }
         const int64_t n_agg = merges_aggregation(g, i) ? 1 : v.plan.n_agg;
         if (n_agg * L.split[i] > 1) {
@@ -970,14 +1012,15 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
         Step s;
         s.vertex = i;
         const bool merged = merges_aggregation(g, i);
-        const Vertex vm = merged ? merged_vertex(v) : Vertex();
-        const Vertex &vr = merged ? vm : v;            // what is routed: the vertex, or its merged form
+        const bool refined = !merged && L.split_label[i] >= 0 && L.split[i] > 1;
+        const Vertex vm = merged ? merged_vertex(v) : refined ? refined_vertex(v, L.split_label[i], L.split[i]) : Vertex();
+        const Vertex &vr = merged || refined ? vm : v;   // what is routed: the vertex, its merged form, or its finer cut
         Operand X = operand_of(v.in[0]), Y;
         if (v.n_in > 1) Y = operand_of(v.in[1]);
         Operand Z = operand_of(i);
         s.dst = (void *)Z.ptr;
         s.dst_stride = Z.stride;
-        s.slabs = vr.plan.n_agg * L.split[i];
+        s.slabs = refined ? vr.plan.n_agg : vr.plan.n_agg * L.split[i];
         s.agg = s.slabs > 1;
         OutSpec out;
         std::vector<int64_t> zstride;
@@ -994,11 +1037,12 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
             out.dtype = v.dtype;
             zstride = Z.stride;
         }
-        int rc = route(vr, X, v.n_in > 1 ? &Y : nullptr, zstride, out, s.r, L.split[i]);
+        int rc = route(vr, X, v.n_in > 1 ? &Y : nullptr, zstride, out, s.r, refined ? 1 : L.split[i]);
         if (rc) return rc;
         if (merged && s.r.kind != EG_KERNEL_CONTRACT_MFMA && s.r.kind != EG_KERNEL_CONTRACT_ALU)
             return fail(EG_ERR_LIMIT, "vertex %d: the bound relations' strides leave no contraction kernel for the merged aggregation; turn tr_set_fused_aggregation off", i);
-        if (L.split[i] > 1 && s.r.kind != EG_KERNEL_REDUCE_ROW) {
+        if (L.split[i] > 1 && s.r.kind != EG_KERNEL_REDUCE_ROW &&
+            !(refined && (s.r.kind == EG_KERNEL_CONTRACT_MFMA || s.r.kind == EG_KERNEL_CONTRACT_ALU))) {
             // the bound relations' strides sent this vertex to another kernel than the layout assumed:
             // run it unsplit, writing the tensor directly when nothing else needs aggregating
             s.slabs = v.plan.n_agg;
@@ -1007,7 +1051,7 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
             rc = route(v, X, v.n_in > 1 ? &Y : nullptr, zstride, out, s.r, 1);
             if (rc) return rc;
         }
-        if (s.r.kind == EG_KERNEL_REDUCE_ROW && s.r.rp.split != L.split[i]) s.r.rp.split = L.split[i];
+        if (s.r.kind == EG_KERNEL_REDUCE_ROW && !refined && s.r.rp.split != L.split[i]) s.r.rp.split = L.split[i];
         s.stride = out.slab_elems;                 // what the join kernel was given
         steps.push_back(std::move(s));
     }

@@ -355,6 +355,41 @@ def test_elementwise_vertices_with_a_transposed_operand(spec, bx, by, otimes, pa
             assert np.array_equal(got.data, ref.data)
 
 
+@pytest.mark.parametrize("dtype,out_dtype", [("bf16", "bf16"), ("f32", "f32")])
+@pytest.mark.parametrize("spec,bx,by,otimes,oplus,part", [
+    ("ij,jk->ik", (256, 8192), (8192, 128), "mul", "sum", {}),                # 2 tiles, long K: cut 8 ways by the executor
+    ("ij,kj->ik", (136, 4096), (72, 4096), "mul", "sum", {"j": 2}),           # on top of the vertex's own cut
+    ("ij,jk->ki", (64, 8192), (8192, 264), "mul", "sum", {"k": 3}),
+    ("bij,bjk->bik", (3, 64, 4096), (3, 4096, 64), "mul", "sum", {"b": 3}),
+    ("ij,jk->ik", (64, 4096), (4096, 64), "sqdiff", "sum", {}),
+    ("ij,jk->ik", (64, 4096), (4096, 64), "absdiff", "max", {"i": 2}),
+])
+def test_underfilled_contractions_with_a_long_reduction(spec, bx, by, otimes, oplus, part, dtype, out_dtype):
+    """Few output tiles and thousands of contracted elements: the executor cuts the contracted label further than the
+    vertex's vector says and aggregates the extra partial slabs; the result is that of the vertex as given."""
+    print(f"{spec} {bx} {by} {otimes}/{oplus} {part} {dtype}->{out_dtype}", flush=True)
+    x = HostTensor.from_f32(uniform_pm1(61, 0, int(np.prod(bx))).reshape(bx), dtype)
+    y = HostTensor.from_f32(uniform_pm1(61, 1, int(np.prod(by))).reshape(by), dtype)
+    w = single_vertex(spec, x, y, out_dtype, otimes=otimes, oplus=oplus, parts={"p": part})
+    ref = run_graph(w, {"X": x, "Y": y})["Z"]
+    import paper_2410_02682_amd as E
+    from paper_2410_02682_amd.runner import GraphRunner, to_device, to_host
+    import torch
+    r = GraphRunner(w, "p")
+    try:
+        r.bind({"X": to_device(x), "Y": to_device(y)})
+        E.tr_profile_enable(r.g, 8)
+        r.run()
+        torch.cuda.synchronize()
+        stages = [rec["stage"] for rec in E.tr_profile_read(r.g)]
+        assert stages == ["join", "aggregate"], stages               # partial slabs even where the vertex's vector cuts no contracted label
+        got = to_host(r.output("Z"))
+    finally:
+        r.close()
+    bad, worst = violations(got.as_f64(), ref.as_f64(), RTOL_BF16 if out_dtype == "bf16" else RTOL_F32)
+    assert bad == 0, f"{bad} elements out of tolerance (worst {worst:.2f}x)"
+
+
 def test_softmax_pins_on_the_gpu():
     # constant rows of power-of-two length give exactly 1/n; rows sum to one; a row of 1000s needs the max subtraction
     from synth_inputs.workloads import Vertex, Workload
