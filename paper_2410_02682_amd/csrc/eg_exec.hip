@@ -329,7 +329,7 @@ static int route(const Vertex &v, const Operand &X, const Operand *Y, const std:
     // so that label becomes a column label and result tiles are written along their rows in 16-byte vectors
     // (same products, same order of summation; `ij,jk->ki` ran 30 % slower than `ij,jk->ik` before).
     bool swap = false;
-    if (binary && (v.otimes == EG_MUL || v.otimes == EG_ADD || v.otimes == EG_SQDIFF || v.otimes == EG_ABSDIFF))
+    if (binary && (v.otimes == EG_MUL || v.otimes == EG_SQDIFF || v.otimes == EG_ABSDIFF))   // not ADD: that is alpha * x + y
         for (int l = 0; l < li.nl; l++)
             if (li.inz[l] && li.ext[l] > 1 && li.sz[l] == 1 && li.inx[l] && !li.iny[l]) swap = true;
     LabelInfo lc = li;

@@ -242,6 +242,7 @@ def test_every_scalar_function_elementwise(shape, part, dtype):
     ("ij,jk->ki", (40, 72), (72, 24), "sqdiff", "sum", {"i": 2, "j": 2}),      # result along an X-only label: operands change places
     ("ij,jk->ki", (264, 136), (136, 200), "absdiff", "max", {"k": 5}),
     ("ij,jk->ki", (264, 136), (136, 200), "sub", "sum", {}),                    # not symmetric: they stay
+    ("ij,jk->ki", (264, 136), (136, 200), "add", "max", {"j": 2}),              # alpha * x + y is not symmetric either
     ("ij,j->i", (40, 1024), (1024,), "mul", "sum", {"j": 2}),
     ("ij,jk->ik", (37, 53), (53, 29), "mul", "sum", {}),          # nothing divides a vector: scalar paths
     ("ij->", (256, 1024), None, "exp", "sum", {}),                # one output, long reduction: split into pieces
