@@ -29,7 +29,7 @@ PEAK_ALU_TFLOPS = 256 * 4 * 16 * 2.4e9 * 3 / 1e12
 DEFAULT_PART = {1: "d222", 2: "mix", 3: "batch8", 4: "heads8", 5: "k16", 6: "splitn8", 7: "d222"}
 # HBM bytes per launch of the dominant kernel of the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # (see profiles/); None until measured for the chosen workload.
-MEASURED_TRAFFIC = {("c2", "mix"): 1617 * 2**20 + 512 * 2**20}   # contraction launch: 1617 MiB fetched + 512 MiB written
+MEASURED_TRAFFIC = {("c2", "mix"): 1690 * 2**20 + 512 * 2**20}   # contraction launch: 1690 MiB fetched (1617 on another box) + 512 MiB written
 
 
 def prod(xs):
