@@ -196,6 +196,35 @@ def test_workspace_spaces_many_large_slabs_apart():
     E.einsum_graph_destroy(g)
 
 
+def test_workspace_holds_the_executors_own_pieces():
+    """Few outputs under a long reduction: the executor cuts the reduction into pieces of its own, each one more
+    partial slab in the workspace (nothing of this shows in the vertex's plan)."""
+    def ws(spec, bx, by, d=None, otimes="mul", oplus="sum"):
+        g = E.einsum_graph_create()
+        ins = [E.einsum_graph_add_input(g, list(bx), "bf16")]
+        if by is not None:
+            ins.append(E.einsum_graph_add_input(g, list(by), "bf16"))
+        z = E.einsum_graph_add_einsum(g, spec, otimes, oplus, 1.0, ins, "f32")
+        E.einsum_graph_mark_output(g, z)
+        if d:
+            E.einsum_graph_set_partition(g, z, d)
+        n, plan = E.tr_workspace_bytes(g), E.einsum_graph_plan(g, z)
+        E.einsum_graph_destroy(g)
+        return n, plan
+    # 2 tiles of 128 x 128 under 8192 contracted elements: cut 8 ways (pieces of 1024)
+    n, plan = ws("ij,jk->ik", (256, 8192), (8192, 128))
+    assert n == 8 * 256 * 128 * 4 and plan["n_agg"] == 1 and plan["n_tuples"] == 1
+    # on top of the vertex's own two-way cut: 2 x 4 pieces of 1024
+    n, plan = ws("ij,jk->ik", (256, 8192), (8192, 128), [1, 2, 1])
+    assert n == 8 * 256 * 128 * 4 and plan["n_agg"] == 2
+    # a launch that fills the chip, or a short reduction, is left alone
+    assert ws("ij,jk->ik", (4096, 4096), (4096, 4096))[0] == 0
+    assert ws("ij,jk->ik", (256, 2048), (2048, 128))[0] == 0
+    # one output over 12 M elements: 1024 pieces (the most); 64 columns over 8192 rows: 8 vectors x 8 lane groups x 64 pieces
+    assert ws("ij->", (3000, 4096), None, otimes="ident")[0] == 1024 * 4
+    assert ws("ij->j", (8192, 64), None, otimes="ident")[0] == 64 * 64 * 4
+
+
 def test_kernel_routing_of_the_workload_vertices():
     want = {
         2: {"AB": "contract_mfma", "ABC": "contract_mfma"},
