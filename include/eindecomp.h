@@ -183,7 +183,9 @@ void tensor_relation_destroy(eg_relation *rel);
 
 /* Bytes of device workspace tr_execute needs for the graph as currently annotated: fp32 partial slabs
  * ([n_agg][dense Z] per vertex with a partitioned aggregated label) plus every intermediate vertex that
- * is not a marked output, with buffers reused once their last consumer has run. */
+ * is not a marked output, with buffers reused once their last consumer has run.  Where a vertex has few
+ * outputs under a long reduction, the execution cuts that reduction into further pieces of its own (more
+ * partial slabs, added in ascending order like the others); their space is counted here. */
 int tr_workspace_bytes(eg_graph *g, size_t *bytes);
 
 /* Runs every vertex in topological order on `hip_stream` (a hipStream_t, may be NULL for the default
