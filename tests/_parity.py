@@ -12,8 +12,17 @@ RTOL_F32 = 1e-5      # fp32 storage, fp32 accumulation, exact inputs
 RTOL_BF16 = 2e-2     # bf16 outputs with fp32 accumulation, or anything downstream of a bf16-rounded intermediate
 
 
-def violations(got: np.ndarray, ref: np.ndarray, rtol: float):
+EPS_F32 = 2.0 ** -24
+
+
+def violations(got: np.ndarray, ref: np.ndarray, rtol: float, magnitude: Optional[np.ndarray] = None):
     """Element-wise |g - r| <= rtol*|r| + rtol*rms(r); non-finite reference entries must match exactly.
+
+    magnitude (optional, same shape): the sum of the absolute values of the terms behind every element, as
+    `magnitudes` computes it.  fp32 summation, compensated or not, errs by a few 2^-24 of THAT sum, whatever
+    is left after cancellation (compensated summation: 2 * 2^-24, plus one rounding of each stored operand and
+    of each partial block); 4 * 2^-24 * magnitude is added to the allowance.  For K products of random sign the sum
+    of absolute values is about 0.6 * sqrt(K) times the result, so at K = 1000 this adds half of rtol = 1e-5.
 
     Returns (number of violating elements, worst ratio of error to allowance)."""
     got = np.asarray(got, dtype=np.float64).ravel()
@@ -25,6 +34,9 @@ def violations(got: np.ndarray, ref: np.ndarray, rtol: float):
         r, g = ref[fin], got[fin]
         rms = float(np.sqrt(np.mean(r * r)))
         allow = rtol * np.abs(r) + rtol * rms + 1e-300
+        if magnitude is not None:
+            m = np.asarray(magnitude, dtype=np.float64).ravel()[fin]
+            allow = allow + 4 * EPS_F32 * np.where(np.isfinite(m), np.abs(m), 0.0)
         err = np.abs(g - r)
         err = np.where(np.isfinite(err), err, np.inf)
         ratio = err / allow
@@ -59,3 +71,28 @@ def single_vertex(spec: str, x: HostTensor, y: Optional[HostTensor], out_dtype: 
         ins.append("Y")
     vs.append(Vertex("Z", out_dtype, spec=spec, otimes=otimes, oplus=oplus, alpha=alpha, inputs=tuple(ins)))
     return Workload("adhoc", 0, vs, ["Z"], {k: {"Z": v} for k, v in (parts or {"whole": {}}).items()})
+
+
+
+def magnitudes(w: Workload, inputs: Dict[str, HostTensor]) -> Dict[str, HostTensor]:
+    """Every vertex of the graph evaluated by the oracle on the absolute values of the inputs, with differences
+    turned into sums and scale factors into their absolute values: for sums of products (and of anything built
+    from them) that is the sum of the absolute values of the terms, the quantity rounding errors of a
+    floating-point sum are proportional to.  Scalar functions that cannot cancel are evaluated as they are."""
+    from dataclasses import replace
+    from oracle.graph_ref import run_graph
+
+    def plain(v: Vertex) -> Vertex:
+        if v.is_input:
+            return v
+        otimes, alpha = v.otimes, abs(v.alpha)
+        if otimes == "sub":
+            otimes, alpha = "add", 1.0
+        return replace(v, otimes=otimes, alpha=alpha)
+
+    wm = Workload(w.name + "_magnitude", w.seed, [plain(v) for v in w.vertices], [v.name for v in w.einsum_vertices()])
+
+    def absolute(t: HostTensor) -> HostTensor:
+        return HostTensor(t.data & np.uint16(0x7FFF), "bf16") if t.dtype == "bf16" else HostTensor(np.abs(t.data), "f32")
+
+    return run_graph(wm, {k: absolute(t) for k, t in inputs.items()})
