@@ -545,7 +545,11 @@ def _softmax_workload(bound, dtype, with_add, stats_consumed):
 
 @pytest.mark.parametrize("bound,dtype,with_add,stats", [((6, 40, 2048), "bf16", True, False), ((2, 3, 24, 1024), "bf16", True, True),
                                                          ((50, 520), "f32", False, True), ((12, 100), "f32", False, False),
-                                                         ((4, 12, 100), "bf16", True, True), ((4, 8192), "bf16", False, False)])
+                                                         ((4, 12, 100), "bf16", True, True), ((4, 8192), "bf16", False, False),
+                                                         # rows of a workgroup share the added row (4, 8 or 16 rows lack its labels)
+                                                         ((4, 2, 16, 512), "bf16", True, False), ((8, 24, 2048), "bf16", True, True),
+                                                         ((4, 8, 4096), "bf16", True, False), ((4, 16, 1024), "f32", True, True),
+                                                         ((16, 8, 8192), "bf16", True, False)])
 def test_fused_softmax_matches_oracle_and_the_separate_vertices(bound, dtype, with_add, stats):
     torch, GraphRunner, to_device, to_host = _gpu()
     import paper_2410_02682_amd as E
