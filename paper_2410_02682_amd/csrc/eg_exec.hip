@@ -294,7 +294,9 @@ static int route(const Vertex &v, const Operand &X, const Operand *Y, const std:
         p.dtx = X.dtype; p.dty = Y ? Y->dtype : EG_F32;
         p.x = X.ptr; p.y = Y ? Y->ptr : nullptr; p.out = out; p.n_tuples = n_tuples;
         const int vd = p.dims.n - 1;
-        bool vz = p.dims.sz[vd] == 1 && aligned16(out.ptr) && p.dims.ext[vd] % 8 == 0;
+        // whole 16-byte vectors, except in a dense one-dimensional space that is not cut: there the last vector may be partial
+        const bool flat = p.dims.n == 1 && ts.n == 0;
+        bool vz = p.dims.sz[vd] == 1 && aligned16(out.ptr) && (p.dims.ext[vd] % 8 == 0 || flat);
         for (int i = 0; i < p.dims.n && vz; i++)
             if (i != vd && p.dims.sz[i] % 8) vz = false;
         for (int l = 0; l < ts.n && vz; l++)

@@ -108,7 +108,14 @@ __global__ __launch_bounds__(kThreads) void k_map(const MapParams p)
         ox += k2 * p.dims.sx[i]; oy += k2 * p.dims.sy[i]; oz += k2 * p.dims.sz[i];
     }
     char *zb = out_base(p.out, agg);
-    if (VEC == 8) {
+    if (VEC == 8 && (int64_t)col * VEC + VEC > p.dims.ext[vd]) {
+        // the last, partial vector of a dense one-dimensional index space (any other space has whole vectors only)
+        for (int64_t k = (int64_t)col * VEC; k < p.dims.ext[vd]; k++) {
+            const float x = load_elem(p.x, p.dtx, ox + k * p.dims.sx[vd]);
+            const float y = p.binary ? load_elem(p.y, p.dty, oy + k * p.dims.sy[vd]) : 0.f;
+            store_elem(zb, p.out.dtype, oz + k * p.dims.sz[vd], otimes_t<OP, FAST>(p.otimes, x, y, p.alpha));
+        }
+    } else if (VEC == 8) {
         float x[8], y[8], z[8];
         const int64_t k = (int64_t)col * VEC;
         if (p.dims.sx[vd] == 1) load8(p.x, p.dtx, ox + k, x);

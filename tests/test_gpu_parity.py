@@ -202,7 +202,8 @@ BINARY = ["mul", "add", "sub", "div", "sqdiff", "absdiff", "exp_sub", "relu_grad
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("shape,part", [((96, 200), {"i": 2, "j": 4}), ((7, 13), {}), ((4, 6, 40), {"k": 5})])
+@pytest.mark.parametrize("shape,part", [((96, 200), {"i": 2, "j": 4}), ((7, 13), {}), ((4, 6, 40), {"k": 5}),
+                                        ((4099, 37), {}), ((3, 5), {})])      # dense, not cut, no multiple of 8: vectors and a partial last one
 def test_every_scalar_function_elementwise(shape, part, dtype):
     labs = "ijk"[:len(shape)]
     n = int(np.prod(shape))
