@@ -220,6 +220,14 @@ int tr_set_fusion(eg_graph *g, int enable);
  * contraction.  Other vertices are not affected.  Changes the workspace size. */
 int tr_set_fused_aggregation(eg_graph *g, int enable);
 
+/* Which variant of the block-contraction kernel the (x) = multiply, (+) = sum vertices of this graph run on, for
+ * comparisons and for tests that must reach every variant at sizes the library would route elsewhere; results are
+ * the same up to summation order.  kernel: 0 = the library chooses per vertex, 1 = the register-staged kernel,
+ * 2 = the direct-to-LDS kernel wherever the operand layout allows it.  tile: 0 = the library chooses, 128 or 256 =
+ * output tile size of the direct-to-LDS kernel.  waves: 0 = the library chooses, 4 or 8 = waves per workgroup of its
+ * 256 x 256 variant.  Other values: EG_ERR_LIMIT.  Takes effect at the next tr_execute; changes no workspace size. */
+int tr_set_contract_variant(eg_graph *g, int kernel, int tile, int waves);
+
 /* ---- Timing of the launches inside tr_execute (for roofline reports) ----------------------------------- */
 
 /* max_launches > 0: from now on tr_execute brackets every kernel launch with a pair of HIP events recorded

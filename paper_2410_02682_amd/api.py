@@ -138,6 +138,13 @@ def tr_set_fused_aggregation(g, enable: bool) -> None:
     _check(_lib.load().tr_set_fused_aggregation(g, 1 if enable else 0))
 
 
+CONTRACT_KERNELS = {"auto": 0, "staged": 1, "dma": 2}
+
+
+def tr_set_contract_variant(g, kernel: str = "auto", tile: int = 0, waves: int = 0) -> None:
+    _check(_lib.load().tr_set_contract_variant(g, CONTRACT_KERNELS[kernel], int(tile), int(waves)))
+
+
 # ---- EinDecomp: cost model and choice of the partitioning vectors (host only) -----------------------------
 def eg_cost_join(g, vertex: int, d: Sequence[int]) -> int:
     c = ctypes.c_int64()

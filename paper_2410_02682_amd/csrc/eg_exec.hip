@@ -853,6 +853,18 @@ int tr_set_fused_aggregation(eg_graph *g, int enable)
     return EG_OK;
 }
 
+int tr_set_contract_variant(eg_graph *g, int kernel, int tile, int waves)
+{
+    if (!g) return fail(EG_ERR_NULL, "graph is NULL");
+    if (kernel < 0 || kernel > 2) return fail(EG_ERR_LIMIT, "tr_set_contract_variant: kernel must be 0 (library's choice), 1 (register-staged) or 2 (direct-to-LDS)");
+    if (tile != 0 && tile != 128 && tile != 256) return fail(EG_ERR_LIMIT, "tr_set_contract_variant: tile must be 0, 128 or 256");
+    if (waves != 0 && waves != 4 && waves != 8) return fail(EG_ERR_LIMIT, "tr_set_contract_variant: waves must be 0, 4 or 8");
+    g->contract_kernel = kernel;
+    g->contract_tile = tile;
+    g->contract_waves = waves;
+    return EG_OK;
+}
+
 int tr_profile_enable(eg_graph *g, int max_launches)
 {
     if (!g) return fail(EG_ERR_NULL, "graph is NULL");
@@ -1055,6 +1067,11 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
         }
         if (s.r.kind == EG_KERNEL_REDUCE_ROW && !refined && s.r.rp.split != L.split[i]) s.r.rp.split = L.split[i];
         s.stride = out.slab_elems;                 // what the join kernel was given
+        if (s.r.kind == EG_KERNEL_CONTRACT_MFMA || s.r.kind == EG_KERNEL_CONTRACT_ALU) {
+            s.r.cp.force_kernel = g->contract_kernel;
+            s.r.cp.force_tile = g->contract_tile;
+            s.r.cp.force_waves = g->contract_waves;
+        }
         steps.push_back(std::move(s));
     }
     hipStream_t st = (hipStream_t)hip_stream;

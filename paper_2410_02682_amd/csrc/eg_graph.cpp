@@ -147,10 +147,6 @@ int einsum_graph_create(eg_graph **g)
 {
     if (!g) return fail(EG_ERR_NULL, "einsum_graph_create: g is NULL");
     *g = new eg_graph();
-    const char *f = getenv("EINDECOMP_FUSE");            // EINDECOMP_FUSE=0: graphs start with fusion off (see tr_set_fusion)
-    (*g)->fuse = !(f && f[0] == '0');
-    const char *a = getenv("EINDECOMP_FUSE_AGG");        // EINDECOMP_FUSE_AGG=1: graphs start with tr_set_fused_aggregation on
-    (*g)->agg_in_kernel = a && a[0] == '1';
     return EG_OK;
 }
 

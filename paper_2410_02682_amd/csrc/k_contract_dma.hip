@@ -664,13 +664,12 @@ int launch_contract_dma(ContractParams &p, void *stream)
     // large products).  128 x 128 tiles, two workgroups per unit, are taken when they are all resident at once, i.e. when
     // the large tiles would leave at least half of the compute units without work (measured: 64 large tiles 1.5-1.8x
     // faster as 256 small ones; 160 large tiles 1.4x slower as 640 small ones, which need a second round).
-    const char *tile_env = getenv("EINDECOMP_DMA_TILE");              // 128 or 256: for comparisons and tests, read at every launch
     const int64_t tuples = p.n_tuples * p.n_batch;
     const int64_t small = tuples * ((p.M + 127) / 128) * ((p.N + 127) / 128);
     const int64_t large = tuples * ((p.M + 255) / 256) * ((p.N + 255) / 256);
     // ... and when the large tiles would be mostly padding (128 columns in a 256-wide tile: config 4's P x V, 0.31 -> 0.29 ms)
     int ts = (small <= 2 * n_cu || 4 * large * 10 > small * 14) ? 128 : 256;
-    if (tile_env && (atoi(tile_env) == 128 || atoi(tile_env) == 256)) ts = atoi(tile_env);
+    if (p.force_tile == 128 || p.force_tile == 256) ts = p.force_tile;   // tr_set_contract_variant: comparisons and tests
     p.tiles_m = (int32_t)((p.M + ts - 1) / ts);
     p.tiles_n = (int32_t)((p.N + ts - 1) / ts);
     const int64_t wgs = tuples * p.tiles_m * p.tiles_n;
@@ -686,10 +685,9 @@ int launch_contract_dma(ContractParams &p, void *stream)
     for (int i = 0; i < p.batch.n; i++) vec = vec && p.batch.s2[i] % 8 == 0;
     for (int l = 0; l < p.ts.n; l++) vec = vec && p.ts.step_z[l] % 8 == 0;
     p.out_vec = vec ? 1 : 0;
-    const char *waves = getenv("EINDECOMP_DMA_WAVES");                // 4 or 8 waves per workgroup of the 256 x 256 kernel (for comparisons)
     if (p.in_dtype == EG_F32) return ts == 128 ? dma::launch_layout<128, 4, true>(p, stream) : dma::launch_layout<256, 8, true>(p, stream);
     if (ts == 128) return dma::launch_layout<128, 4, false>(p, stream);
-    if (waves && atoi(waves) == 4) return dma::launch_layout<256, 4, false>(p, stream);
+    if (p.force_waves == 4) return dma::launch_layout<256, 4, false>(p, stream);
     return dma::launch_layout<256, 8, false>(p, stream);
 }
 

@@ -32,10 +32,19 @@ def to_host(x: torch.Tensor) -> HostTensor:
 
 
 class GraphRunner:
-    def __init__(self, w: Workload, partitioning: str, outputs: Optional[Iterable[str]] = None, device="cuda"):
+    def __init__(self, w: Workload, partitioning: str, outputs: Optional[Iterable[str]] = None, device="cuda",
+                 contract: Optional[dict] = None, fuse: Optional[bool] = None, fuse_aggregation: Optional[bool] = None):
+        """contract: arguments of tr_set_contract_variant (kernel / tile / waves); fuse, fuse_aggregation: arguments of
+        tr_set_fusion and tr_set_fused_aggregation.  None leaves the library's defaults."""
         self.w = w
         self.device = device
         self.g = api.einsum_graph_create()
+        if contract:
+            api.tr_set_contract_variant(self.g, **contract)
+        if fuse is not None:
+            api.tr_set_fusion(self.g, fuse)
+        if fuse_aggregation is not None:
+            api.tr_set_fused_aggregation(self.g, fuse_aggregation)
         self.vid: Dict[str, int] = {}
         # "eindecomp:<p>": let the library choose the partitioning vectors (p join results per vertex)
         planned = partitioning.startswith("eindecomp:")

@@ -18,8 +18,3 @@ def has_gpu() -> bool:
         return torch.cuda.is_available()
     except Exception:
         return False
-
-# the library's development switches must not leak into the tests: every test states the mode it checks
-for _name in ("EINDECOMP_FUSE", "EINDECOMP_FUSE_AGG", "EINDECOMP_CONTRACT", "EINDECOMP_DMA_WAVES", "EINDECOMP_DMA_TILE"):
-    if _name in os.environ and os.environ.get("EINDECOMP_TEST_KEEP_ENV") != "1":
-        del os.environ[_name]

@@ -23,9 +23,9 @@ def _gpu():
     return torch, GraphRunner, to_device, to_host
 
 
-def _run(w, pname, inputs, outputs=None):
+def _run(w, pname, inputs, outputs=None, contract=None):
     torch, GraphRunner, to_device, to_host = _gpu()
-    r = GraphRunner(w, pname, outputs=outputs)
+    r = GraphRunner(w, pname, outputs=outputs, contract=contract)
     try:
         r.bind({k: to_device(t) for k, t in inputs.items()})
         r.run()
@@ -61,13 +61,11 @@ def test_config_every_vertex_matches_oracle(n, pname):
 
 @pytest.mark.parametrize("tile", ["", "256"])
 @pytest.mark.parametrize("n,pname", CASES)
-def test_config_outputs_through_workspace_match_oracle(n, pname, tile, monkeypatch):
+def test_config_outputs_through_workspace_match_oracle(n, pname, tile):
     # at these sizes the bf16 contraction kernel would always pick its small tile: the second pass forces the large one
     w, inp, ref = _reference(n)
     print(f"config {n} partitioning {pname}: intermediates in the workspace, tile {tile or 'default'}", flush=True)
-    if tile:
-        monkeypatch.setenv("EINDECOMP_DMA_TILE", tile)
-    got = _run(w, pname, inp)
+    got = _run(w, pname, inp, contract=dict(tile=int(tile)) if tile else None)
     for name in w.outputs:
         bad, worst = violations(got[name].as_f64(), ref[name].as_f64(), rtol_for(w, name))
         assert bad == 0, f"config {n} {pname} output {name}: {bad} elements out of tolerance (worst {worst:.2f}x)"
@@ -111,19 +109,16 @@ LAYOUTS = [
 
 @pytest.mark.parametrize("dtype,tile", [("bf16", "128"), ("bf16", "256"), ("f32", "128"), ("f32", "256"), ("f32", "")])
 @pytest.mark.parametrize("spec,bx,by", LAYOUTS)
-def test_contraction_layouts(spec, bx, by, dtype, tile, monkeypatch):
+def test_contraction_layouts(spec, bx, by, dtype, tile):
     # the direct-to-LDS kernel has two tile sizes and would pick the small one (or, for fp32, the register-staged kernel)
     # for products this small: each is run; ("f32", "") is the library's own choice
     print(f"contraction {spec} {bx} {by} {dtype} tile {tile or 'default'}", flush=True)
-    if tile:
-        monkeypatch.setenv("EINDECOMP_DMA_TILE", tile)
-        monkeypatch.setenv("EINDECOMP_CONTRACT", "dma")      # wherever the layout is eligible for it
+    contract = dict(kernel="dma", tile=int(tile)) if tile else None      # the direct-to-LDS kernel wherever the layout is eligible for it
     x = HostTensor.from_f32(uniform_pm1(11, 0, int(np.prod(bx))).reshape(bx), dtype)
     y = HostTensor.from_f32(uniform_pm1(11, 1, int(np.prod(by))).reshape(by), dtype)
     w = single_vertex(spec, x, y, "f32")
     ref = run_graph(w, {"X": x, "Y": y})["Z"]
-    import paper_2410_02682_amd as E
-    got = _run(w, "whole", {"X": x, "Y": y})["Z"]
+    got = _run(w, "whole", {"X": x, "Y": y}, contract=contract)["Z"]
     bad, worst = violations(got.as_f64(), ref.as_f64(), RTOL_F32)
     assert bad == 0, f"{bad} elements out of tolerance (worst {worst:.2f}x)"
 

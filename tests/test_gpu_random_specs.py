@@ -109,10 +109,10 @@ def draw_case(seed):
     return spec, bx, by, otimes, oplus, alpha, part, dt_in, dt_out
 
 
-def _run(w, pname, inputs):
+def _run(w, pname, inputs, contract=None):
     import torch
     from paper_2410_02682_amd.runner import GraphRunner, to_device, to_host
-    r = GraphRunner(w, pname)
+    r = GraphRunner(w, pname, contract=contract)
     try:
         r.bind({k: to_device(t) for k, t in inputs.items()})
         r.run()
@@ -200,9 +200,8 @@ def draw_large_contraction(seed):
 
 @pytest.mark.parametrize("tile", ["", "256"])
 @pytest.mark.parametrize("seed", range(max(24, N_CASES // 20)))
-def test_random_large_contraction_matches_oracle(seed, tile, monkeypatch):
-    if tile:
-        monkeypatch.setenv("EINDECOMP_DMA_TILE", tile)       # the large-tile variant too, mostly padding at these sizes
+def test_random_large_contraction_matches_oracle(seed, tile):
+    contract = dict(tile=int(tile)) if tile else None        # the large-tile variant too, mostly padding at these sizes
     spec, bx, by, part, dt_in, dt_out = draw_large_contraction(seed)
     x = HostTensor.from_f32(uniform_pm1(1300 + seed, 0, int(np.prod(bx))).reshape(bx), dt_in)
     y = HostTensor.from_f32(uniform_pm1(1300 + seed, 1, int(np.prod(by))).reshape(by), dt_in)
@@ -210,7 +209,7 @@ def test_random_large_contraction_matches_oracle(seed, tile, monkeypatch):
     ref = run_graph(w, {"X": x, "Y": y})["Z"]
     rtol = RTOL_BF16 if dt_out == "bf16" else RTOL_F32
     for pname in ("d", "whole"):
-        got, kernel = _run(w, pname, {"X": x, "Y": y})
+        got, kernel = _run(w, pname, {"X": x, "Y": y}, contract)
         print(f"seed {seed}: {spec} X{bx} Y{by} d {part if pname == 'd' else {}} {dt_in}->{dt_out}: {kernel}", flush=True)
         bad, worst = violations(got.as_f64(), ref.as_f64(), rtol)
         assert bad == 0, f"{pname} ({kernel}): {bad} elements out of tolerance (worst {worst:.2f}x)"
