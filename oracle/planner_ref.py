@@ -26,8 +26,10 @@ Readings taken where the text leaves a choice or contradicts itself:
   * paths: among the vertices not yet labelled, the longest chain of producer -> consumer edges (ties: the
     one whose vertex ids, in creation order, are lexicographically smallest).
 
-Parity unpinned: the path heuristic of Section 8.4 (no printed example); it is checked for validity and against
-the exhaustive optimum only as an upper bound.
+Pins (tests/test_planner_oracle.py): the printed values of Sections 7 and 8.1, closed forms of the re-partition cost,
+exhaustive search for the dynamic programme, and for the path heuristic of Section 8.4 (the paper prints no example)
+a graph with a shared result whose paths, per-path tables M and final vectors were worked out by hand from the
+formulas of Section 7 and are written into the test as literals.  Nothing in this file is unpinned.
 """
 from __future__ import annotations
 

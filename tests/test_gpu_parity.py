@@ -54,9 +54,16 @@ def test_config_every_vertex_matches_oracle(n, pname):
     names = [v.name for v in w.einsum_vertices()]
     print(f"config {n} partitioning {pname}: all vertices as outputs", flush=True)
     got = _run(w, pname, inp, outputs=names)
+    strict = {}
     for name in names:
-        bad, worst = violations(got[name].as_f64(), ref[name].as_f64(), rtol_for(w, name))
+        rep = {}
+        bad, worst = violations(got[name].as_f64(), ref[name].as_f64(), rtol_for(w, name), report=rep)
         assert bad == 0, f"config {n} {pname} vertex {name}: {bad} elements out of tolerance (worst {worst:.2f}x)"
+        strict[name] = rep["strict_worst"] / rtol_for(w, name)
+        # on elements that are not small against the tensor the stated relative bound holds without the rms term
+        assert rep["strict_worst"] <= rtol_for(w, name), f"config {n} {pname} vertex {name}: plain relative error {rep['strict_worst']:.2e}"
+    worst_name = max(strict, key=strict.get)
+    print(f"config {n} {pname}: worst plain relative error on elements above the rms: {strict[worst_name]:.3f} of the bound ({worst_name})", flush=True)
 
 
 @pytest.mark.parametrize("tile", ["", "256"])

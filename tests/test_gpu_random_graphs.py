@@ -187,10 +187,17 @@ def test_random_graph_matches_oracle_under_every_labelling(family, seed):
     inputs = make_inputs(w)
     ref = run_graph(w, inputs)
     mag = magnitudes(w, inputs)                       # what cancelling sums are held against (graph 1028 of the first family)
+    rep = {}
     for pname, merged in (("a", False), ("b", False), ("whole", False), ("eindecomp:4", False), ("a", True), ("b", True)):
         got = _run(w, pname, inputs, merged)
         for name in w.outputs:
             r = ref[name].as_f64()
             assert got[name].shape == ref[name].shape
-            bad, worst = violations(got[name].as_f64(), r, rtol_for(w, name), mag[name].as_f64())
+            bad, worst = violations(got[name].as_f64(), r, rtol_for(w, name), mag[name].as_f64(), report=rep)
             assert bad == 0, f"labelling {pname}{' (aggregation merged)' if merged else ''} output {name}: {bad} elements out of tolerance (worst {worst:.2f}x)"
+    # The allowance for cancelling sums is there for sums that cancel to a millionth of their terms; a graph whose
+    # outputs lean on it in more than a handful of elements has another problem.
+    print(f"graph {seed}: {rep['leaned_on_magnitude']} elements needed the allowance for cancelling sums; "
+          f"worst plain relative error on elements above the rms {rep['strict_worst']:.2e}", flush=True)
+    n_out = sum(int(np.prod(ref[name].shape)) for name in w.outputs) * 6
+    assert rep["leaned_on_magnitude"] <= max(8, n_out // 100), rep

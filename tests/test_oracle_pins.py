@@ -266,6 +266,35 @@ def test_scalar_functions_against_closed_forms():
     np.testing.assert_allclose(un("log", v=np.abs(x) + 1), np.log(np.abs(x) + 1), rtol=1e-15)
 
 
+def test_scalar_functions_at_values_the_mathematics_fixes():
+    """Each scalar function at arguments whose result is known without evaluating the same expression again:
+    sigmoid(ln 3) = 3/4, exp(ln 6 - ln 2) = 3, log(e^2) = 2, and small integers that show where alpha sits."""
+    one = lambda v: np.array([[float(v)]])
+    ev = lambda op, x, y, a=1.0: float(einsum_ref("ij,ij->ij", one(x), one(y), otimes=op, oplus="none", alpha=a)[0, 0])
+    un = lambda op, x, a=1.0: float(einsum_ref("ij->ij", one(x), otimes=op, oplus="none", alpha=a)[0, 0])
+    assert ev("mul", 3, 5, 2.0) == 30.0                       # alpha * x * y
+    assert ev("add", 3, 5, 2.0) == 11.0                       # alpha * x + y: alpha scales x only
+    assert ev("add", 5, 3, 2.0) == 13.0                       # ... and the operands do not commute
+    assert ev("sub", 3, 5, 2.0) == -4.0                       # alpha * (x - y): alpha scales the difference
+    assert ev("sub", 5, 3, 2.0) == 4.0
+    assert ev("div", 1, 4) == 0.25 and ev("div", 4, 1) == 4.0
+    assert ev("sqdiff", 1.5, -2.5) == 16.0 and ev("absdiff", 1.5, -2.5) == 4.0 and ev("absdiff", -2.5, 1.5) == 4.0
+    assert abs(ev("exp_sub", np.log(6.0), np.log(2.0)) - 3.0) < 1e-14
+    assert abs(ev("exp_sub", np.log(2.0), np.log(6.0)) - 1.0 / 3.0) < 1e-15
+    # x * sigmoid(x) * y at x = ln 3: sigmoid = 1 / (1 + 1/3) = 3/4; at x = -ln 3: 1/4; at 0: 0 whatever y
+    assert abs(ev("silu_mul", np.log(3.0), 2.0) - np.log(3.0) * 1.5) < 1e-15
+    assert abs(ev("silu_mul", -np.log(3.0), 2.0) + np.log(3.0) * 0.5) < 1e-15
+    assert ev("silu_mul", 0.0, 7.0) == 0.0
+    assert abs(ev("silu_mul", 2.0, np.log(3.0)) - 2.0 * np.log(3.0) / (1.0 + np.exp(-2.0))) < 1e-15   # sigmoid acts on x, not on y
+    # the derivative of ReLU passes x where y is positive; zero of either sign, and negatives, give zero (ReLU'(0) = 0)
+    assert ev("relu_grad", 7.0, 1e-30) == 7.0 and ev("relu_grad", 7.0, 0.0) == 0.0
+    assert ev("relu_grad", 7.0, -0.0) == 0.0 and ev("relu_grad", 7.0, -2.0) == 0.0 and ev("relu_grad", -7.0, 3.0) == -7.0
+    assert un("ident", -1.25) == -1.25 and un("scale", 4.0, -1.5) == -6.0
+    assert un("relu", -2.0) == 0.0 and un("relu", 3.0) == 3.0 and un("relu", -0.0) == 0.0
+    assert abs(un("exp", np.log(5.0)) - 5.0) < 1e-14 and un("exp", 0.0) == 1.0
+    assert abs(un("log", np.e ** 2) - 2.0) < 1e-15 and un("log", 1.0) == 0.0 and un("log", 0.125) == np.log2(0.125) * np.log(2.0)
+
+
 def test_selected_outputs_match_dense():
     rng = np.random.default_rng(6)
     X, Y = rng.standard_normal((7, 5, 3)), rng.standard_normal((3, 4))

@@ -7,7 +7,7 @@ import pytest
 import paper_2410_02682_amd as E
 from oracle import planner_ref as P
 from synth_inputs import build_config
-from tests.test_planner_oracle import chain, tree, diamond
+from tests.test_planner_oracle import chain, tree, diamond, shared_result_graph
 
 
 def build(vs):
@@ -90,6 +90,22 @@ def test_plan_on_a_graph_with_a_shared_result_follows_the_path_decomposition():
     got = labels_of(g, vid, vs)
     assert got == P.eindecomp_paths(vs, 4)
     assert cost == P.labelling_cost(vs, got) >= P.brute_force(vs, 4)[0]
+    E.einsum_graph_destroy(g)
+
+
+def test_plan_reproduces_the_path_decomposition_worked_by_hand():
+    # the literals derived by hand in tests/test_planner_oracle.py (Section 8.4 with the costs of Section 7, p = 2)
+    vs = shared_result_graph()
+    g, vid = build(vs)
+    cost, exact = E.eindecomp_plan(g, 2)
+    assert not exact and cost == 880
+    assert labels_of(g, vid, vs) == {"T": {"i": 2, "j": 1, "k": 1}, "U": {"i": 2, "k": 1}, "S": {"i": 2, "k": 1, "l": 1},
+                                     "V": {"i": 1, "k": 1, "l": 2}}
+    parts = E.eindecomp_labelling_cost(g)
+    assert parts == dict(join=64 + 32 + 128 + 160, agg=64, repart=48 + 384, total=880)
+    for name, d in (("T", [2, 1, 1]), ("U", [2, 1]), ("S", [2, 1, 1]), ("V", [2, 1, 1])):
+        E.einsum_graph_set_partition(g, vid[name], d)
+    assert E.eindecomp_labelling_cost(g)["total"] == 480
     E.einsum_graph_destroy(g)
 
 

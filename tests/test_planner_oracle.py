@@ -145,3 +145,66 @@ def test_path_decomposition_labels_everything_validly_and_is_no_better_than_the_
     # on a graph that is one path the heuristic is the dynamic programme
     c = chain(4, [8, 16, 4, 8, 8])
     assert P.labelling_cost(c, P.eindecomp_paths(c, 4)) == P.eindecomp_tree(c, 4)[0]
+
+
+# ------------------------------------------------------------------ Section 8.4 worked by hand
+def shared_result_graph():
+    """T = X W feeds both U = relu(T) and V = T W2; S contracts U with V over the rows.  X is 8 x 4, W 4 x 4, W2 4 x 16."""
+    return [P.PVertex("X", None, [], [8, 4]), P.PVertex("W", None, [], [4, 4]), P.PVertex("W2", None, [], [4, 16]),
+            P.PVertex("T", "ij,jk->ik", ["X", "W"], [8, 4]),
+            P.PVertex("U", "ik->ik", ["T"], [8, 4]),
+            P.PVertex("V", "ik,kl->il", ["T", "W2"], [8, 16]),
+            P.PVertex("S", "ik,il->kl", ["U", "V"], [4, 16])]
+
+
+# Worked with pencil from the formulas of Section 7 for p = 2 (every vector has one entry equal to 2).
+#   T (i=8, j=4, k=4), both inputs are graph inputs:
+#     k cut: n_X = 8*4 = 32, n_Y = 4*2 = 8, join 2*(32+8) = 80, nothing aggregated          -> d_Z [1,2]: 80
+#     j cut: n_X = 8*2 = 16, n_Y = 2*4 = 8, join 2*24 = 48, n_agg = 2, n_Z = 32, agg 32     -> d_Z [1,1]: 80
+#     i cut: n_X = 4*4 = 16, n_Y = 16, join 64                                              -> d_Z [2,1]: 64
+#   re-partitions of the 8 x 4 tensor T (n = 32):
+#     [1,2] or [2,1] -> [1,1]: n_p = 16, n_c = 32, n_int = 16: (2-1)*1*(32+16) = 48
+#     [1,1] -> [1,2] or [2,1]: n_p = 32, n_c = 16, n_int = 16: first term 0, n_p != n_int: + 32*2 = 64
+#     [1,2] <-> [2,1]:         n_p = n_c = 16, n_int = 8: (2-1)*2*32 = 64, + 16*2 = 32: 96
+#   U (one input, pays p n_X = 2*16 = 32 under either cut):
+#     k cut, wants T as [1,2]: min(80+0, 80+64, 64+96) = 80   -> d_Z [1,2]: 112, T arrives as [1,2]
+#     i cut, wants T as [2,1]: min(80+96, 80+64, 64+0) = 64   -> d_Z [2,1]:  96, T arrives as [2,1]
+#   S (i=8, k=4, l=16; V lies off the path and costs nothing):
+#     l cut: join 2*(32+64) = 192, U wanted as [1,1]: min(112+48, 96+48) = 144              -> d_Z [1,2]: 336
+#     k cut: join 2*(16+128) = 288, U wanted as [1,2]: min(112, 96+96) = 112                -> d_Z [2,1]: 400
+#     i cut: join 2*(16+64) = 160, n_agg = 2, n_Z = 64, agg 64, U wanted as [2,1]: 96       -> d_Z [1,1]: 320
+#   so the first path T, U, S ends at 320 and is labelled i, i, i.  V alone (T off the path, free):
+#     l cut: 2*(32+32) = 128;  k cut: 2*(16+32) = 96 + agg 128 = 224;  i cut: 2*(16+64) = 160  -> l cut.
+#   With every edge counted: T 64, U 32, V 128 + 48 (T from [2,1] to [1,1]), S 160 + 64 + 384 (V from [1,2] to
+#   [2,1] on its 8 x 16 tensor: n_p = n_c = 64, n_int = 32, n = 128: (2-1)*2*128 = 256, + 64*2 = 128) = 880.
+#   Cutting all four vertices along i costs 64 + 32 + 160 + 224 = 480: the edges between paths are what the
+#   heuristic does not see.
+def test_path_decomposition_of_a_graph_worked_by_hand():
+    vs = shared_result_graph()
+    g = {v.name: v for v in vs}
+    # two chains of three vertices tie; the one through the vertex created first wins, V is left for a path of its own
+    assert P.longest_path(vs, ["T", "U", "V", "S"]) == ["T", "U", "S"]
+    assert P.longest_path(vs, ["V"]) == ["V"]
+    path = ["T", "U", "S"]
+    M = P.dp_chain(g, [g[n] for n in path], set(zip(path[:-1], path[1:])), 2)
+    costs = lambda name: {k: int(c) for k, (c, _, _) in M[name].items()}
+    assert costs("T") == {(1, 2): 80, (1, 1): 80, (2, 1): 64}
+    assert costs("U") == {(1, 2): 112, (2, 1): 96}
+    assert costs("S") == {(1, 2): 336, (2, 1): 400, (1, 1): 320}
+    assert M["U"][(1, 2)][2] == {"T": (1, 2)} and M["U"][(2, 1)][2] == {"T": (2, 1)}
+    assert M["S"][(1, 2)][2] == {"U": (2, 1)} and M["S"][(2, 1)][2] == {"U": (1, 2)} and M["S"][(1, 1)][2] == {"U": (2, 1)}
+    MV = P.dp_chain(g, [g["V"]], set(), 2)
+    assert {k: int(c) for k, (c, _, _) in MV["V"].items()} == {(1, 2): 128, (1, 1): 224, (2, 1): 160}
+    labels = P.eindecomp_paths(vs, 2)
+    assert labels == {"T": {"i": 2, "j": 1, "k": 1}, "U": {"i": 2, "k": 1}, "S": {"i": 2, "k": 1, "l": 1}, "V": {"i": 1, "k": 1, "l": 2}}
+    assert P.labelling_cost(vs, labels) == 880
+    all_i = {"T": {"i": 2, "j": 1, "k": 1}, "U": {"i": 2, "k": 1}, "S": {"i": 2, "k": 1, "l": 1}, "V": {"i": 2, "k": 1, "l": 1}}
+    assert P.labelling_cost(vs, all_i) == 480
+    assert P.brute_force(vs, 2)[0] <= 480
+
+
+def test_repartition_costs_used_in_the_worked_example():
+    assert P.cost_repart([1, 1], [1, 2], [8, 4]) == 48 and P.cost_repart([1, 1], [2, 1], [8, 4]) == 48
+    assert P.cost_repart([1, 2], [1, 1], [8, 4]) == 64 and P.cost_repart([2, 1], [1, 1], [8, 4]) == 64
+    assert P.cost_repart([1, 2], [2, 1], [8, 4]) == 96 and P.cost_repart([2, 1], [1, 2], [8, 4]) == 96
+    assert P.cost_repart([2, 1], [1, 2], [8, 16]) == 384
