@@ -22,8 +22,8 @@ CASES = [
     ("ji,jk->ik", (136, 4360), (136, 4360), {}, "f32"),
     # the contracted label cut in two: every tile is written twice, into two partial slabs, and aggregated
     ("ij,jk->ik", (4360, 144), (144, 4360), {"j": 2}, "f32"),
-    # rows and columns cut as well: 8 tuples, blocks of 2180 x 2180 (9 x 9 large tiles each, ragged), two slabs
-    ("ij,jk->ik", (4360, 144), (144, 4360), {"i": 2, "j": 2, "k": 2}, "bf16"),
+    # rows and columns cut as well: 8 tuples, blocks of 2184 x 2184 (9 x 9 large tiles each, ragged), two slabs
+    ("ij,jk->ik", (4368, 144), (144, 4368), {"i": 2, "j": 2, "k": 2}, "bf16"),
     # batched: 4 x 9 x 9 = 324 large tiles
     ("bij,bjk->bik", (4, 2200, 72), (4, 72, 2200), {}, "f32"),
     ("bij,bkj->bik", (4, 2200, 72), (4, 2200, 72), {"b": 2}, "bf16"),
