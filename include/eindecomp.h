@@ -198,6 +198,23 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs,
                eg_relation *const *outputs, int n_outputs,
                void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* tr_execute for callers that cannot allocate device memory or hand over a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same graph, same relations, same kernels and results as
+ * tr_execute; the partial slabs and intermediates live in a workspace that belongs to the library: a file-scope
+ * device array of tr_static_workspace_bytes() = 32 MiB, of which every GPU the library runs on holds its own copy
+ * until the process ends.  The call allocates nothing on the device and calls no allocating routine; the array's
+ * address on the current device is looked up at the first call on that device.  A graph that needs more
+ * (tr_workspace_bytes) is rejected with EG_ERR_WORKSPACE before anything is launched: use tr_execute then.
+ * All calls on one GPU share that GPU's array.  Nothing in it has to start at zero (every partial slab and
+ * intermediate is written in full before it is read), so nothing is cleared, and what the last call left there
+ * is overwritten.  Two calls that overlap in time on one GPU (different streams, or different threads) race on it:
+ * serialise them on one stream. */
+int tr_execute_static(eg_graph *g, eg_relation *const *inputs, int n_inputs,
+                      eg_relation *const *outputs, int n_outputs, void *hip_stream);
+
+/* Size in bytes of the library's static workspace (the limit of tr_execute_static). */
+size_t tr_static_workspace_bytes(void);
+
 /* The aggregation operator of Section 4.2 on its own: out[e] = (+)_{a = 0 .. n_agg-1} partials[a][e],
  * reduced sequentially in ascending a in fp32, then cast once to out's dtype.  partials: device,
  * fp32, slab-major [n_agg][slab_elems] where a slab is the dense row-major tensor of out's bound.

@@ -50,6 +50,9 @@ EXPORTS = {
     "tr_workspace_bytes": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_size_t)]),
     "tr_execute": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
                                   ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]),
+    "tr_execute_static": (ctypes.c_int, [ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
+                                         ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_void_p]),
+    "tr_static_workspace_bytes": (ctypes.c_size_t, []),
     "tr_aggregate": (ctypes.c_int, [ctypes.c_int, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]),
     "tr_set_fusion": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int]),
     "tr_set_fused_aggregation": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int]),

@@ -126,6 +126,16 @@ def tr_execute(g, inputs: List, outputs: List, workspace_ptr: int, workspace_byt
                                   ctypes.c_void_p(stream)))
 
 
+def tr_execute_static(g, inputs: List, outputs: List, stream: int = 0) -> None:
+    ia = (ctypes.c_void_p * max(1, len(inputs)))(*[r.value if hasattr(r, "value") else r for r in inputs])
+    oa = (ctypes.c_void_p * max(1, len(outputs)))(*[r.value if hasattr(r, "value") else r for r in outputs])
+    _check(_lib.load().tr_execute_static(g, ia, len(inputs), oa, len(outputs), ctypes.c_void_p(stream)))
+
+
+def tr_static_workspace_bytes() -> int:
+    return int(_lib.load().tr_static_workspace_bytes())
+
+
 def tr_aggregate(oplus: str, partials_ptr: int, n_agg: int, slab_elems: int, out_rel, stream: int = 0) -> None:
     _check(_lib.load().tr_aggregate(OPLUS[oplus], ctypes.c_void_p(partials_ptr), n_agg, slab_elems, out_rel, ctypes.c_void_p(stream)))
 

@@ -10,6 +10,7 @@
 #include <algorithm>
 #include <cstring>
 #include <map>
+#include <mutex>
 
 #include "eg_internal.h"
 
@@ -903,8 +904,39 @@ int tr_profile_get(eg_graph *g, int i, int *vertex, int *stage, int *kernel, flo
     return EG_OK;
 }
 
-int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relation *const *outputs, int n_outputs,
-               void *workspace, size_t workspace_bytes, void *hip_stream)
+}  // extern "C"
+
+// The workspace of tr_execute_static: device memory that belongs to the library, one copy per GPU, held until the
+// process ends.  In host code the array's name only stands for the symbol; its device address is looked up once per
+// device (scratch_of_current_device) and everything on the host works with that address.
+#define EG_STATIC_WORKSPACE_BYTES (32u << 20)
+static __device__ __align__(256) unsigned char scratch[EG_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+int scratch_of_current_device(void **ptr)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return fail(EG_ERR_HIP, "cannot tell the current device");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(EG_ERR_HIP, "hipGetSymbolAddress on the static workspace failed: %s", hipGetErrorString(e));
+        if ((uintptr_t)p & 255) return fail(EG_ERR_WORKSPACE, "the static workspace is not 256-byte aligned");
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return EG_OK;
+}
+}  // namespace
+
+// what tr_execute and tr_execute_static share; max_bytes > 0: the workspace is the library's own and holds that much
+static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relation *const *outputs, int n_outputs,
+                         void *workspace, size_t workspace_bytes, void *hip_stream, size_t max_bytes)
 {
     if (!g) return fail(EG_ERR_NULL, "graph is NULL");
     if (n_inputs != (int)g->inputs.size() || n_outputs != (int)g->outputs.size())
@@ -930,6 +962,9 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
         bound_rel[g->outputs[i]] = outputs[i];
     }
     Layout L = make_layout(g);
+    if (max_bytes && (size_t)L.total > max_bytes)
+        return fail(EG_ERR_WORKSPACE, "graph needs %lld workspace bytes, the library's static workspace holds %zu: use tr_execute with a workspace of the caller's",
+                    (long long)L.total, max_bytes);
     if (L.total > 0) {
         if (!workspace) return fail(EG_ERR_WORKSPACE, "graph needs %lld workspace bytes but workspace is NULL", (long long)L.total);
         if ((uintptr_t)workspace & 255) return fail(EG_ERR_WORKSPACE, "workspace must be 256-byte aligned");
@@ -1101,6 +1136,25 @@ int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relatio
     }
     return EG_OK;
 }
+
+extern "C" {
+
+int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relation *const *outputs, int n_outputs,
+               void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return execute_graph(g, inputs, n_inputs, outputs, n_outputs, workspace, workspace_bytes, hip_stream, 0);
+}
+
+int tr_execute_static(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relation *const *outputs, int n_outputs, void *hip_stream)
+{
+    if (!g) return fail(EG_ERR_NULL, "graph is NULL");
+    void *ws = nullptr;
+    int rc = scratch_of_current_device(&ws);
+    if (rc) return rc;
+    return execute_graph(g, inputs, n_inputs, outputs, n_outputs, ws, EG_STATIC_WORKSPACE_BYTES, hip_stream, EG_STATIC_WORKSPACE_BYTES);
+}
+
+size_t tr_static_workspace_bytes(void) { return EG_STATIC_WORKSPACE_BYTES; }
 
 int tr_aggregate(eg_agg oplus, const void *partials, int64_t n_agg, int64_t slab_elems, eg_relation *out, void *hip_stream)
 {

@@ -83,9 +83,10 @@ class GraphRunner:
                     return [int(part.get(l, 1)) for l in labs]
         return [1] * len(self.w.vertex(name).bound)
 
-    def bind(self, inputs: Dict[str, torch.Tensor], outputs: Optional[Dict[str, torch.Tensor]] = None):
+    def bind(self, inputs: Dict[str, torch.Tensor], outputs: Optional[Dict[str, torch.Tensor]] = None, workspace: bool = True):
         """Views the given device tensors as tensor relations.  Any strided view will do (a relation is a base pointer,
-        bounds and element strides); outputs not given are allocated dense."""
+        bounds and element strides); outputs not given are allocated dense.  workspace=False: no workspace is
+        allocated (for run_static, which uses the library's own)."""
         self.release_relations()
         for v in self.w.vertices:
             if v.is_input:
@@ -107,13 +108,19 @@ class GraphRunner:
                                                      strides=None if t.is_contiguous() else list(t.stride())))
         nbytes = api.tr_workspace_bytes(self.g)
         self.workspace_bytes = nbytes
-        self.workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
-        assert self.workspace.data_ptr() % 256 == 0
+        if workspace:
+            self.workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
+            assert self.workspace.data_ptr() % 256 == 0
         return self
 
     def run(self, stream: Optional[torch.cuda.Stream] = None):
         s = stream if stream is not None else torch.cuda.current_stream()
         api.tr_execute(self.g, self.rel_in, self.rel_out, self.workspace.data_ptr(), self.workspace.numel(), s.cuda_stream)
+
+    def run_static(self, stream: Optional[torch.cuda.Stream] = None):
+        """tr_execute_static: the same pass with the library's static workspace (nothing is allocated)."""
+        s = stream if stream is not None else torch.cuda.current_stream()
+        api.tr_execute_static(self.g, self.rel_in, self.rel_out, s.cuda_stream)
 
     def output(self, name: str) -> torch.Tensor:
         return self.tensors[name]
