@@ -9,6 +9,7 @@ arrays in their stored dtype (float64, float32, or uint16 holding bf16 bits).
 from __future__ import annotations
 
 import ctypes
+import os
 from typing import Optional, Sequence
 
 import numpy as np
@@ -27,7 +28,7 @@ _DT = {"f64": 0, "f32": 1, "bf16": 2}
 def _load():
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(_build.build())
+        _lib = ctypes.CDLL(os.environ.get("EINSUM_REF_LIB") or _build.build())   # override: another build of the same source (sanitizers)
         _lib.einsum_ref.restype = ctypes.c_int
         _lib.er_round_bf16.restype = ctypes.c_double
         _lib.er_round_bf16.argtypes = [ctypes.c_double]

@@ -50,5 +50,49 @@ def build(force: bool = False) -> str:
     return LIB
 
 
+SAN_LIB = os.path.join(OBJDIR, "san", "libeindecomp_san.so")
+HOST_SOURCES = ["eg_graph.cpp", "eg_planner.cpp", "eg_exec.hip"]      # everything that runs on the host besides the launchers
+SAN_HOST = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=undefined",
+            "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
+def build_sanitized() -> str:
+    """The library with its host code (graph, planner, executor) under the address and undefined-behaviour sanitizers;
+    device code and the kernel files are the ordinary build's.  For tests/test_host_sanitizers.py: a process that loads
+    it must have clang's shared ASan runtime loaded first (LD_PRELOAD), see sanitizer_runtime()."""
+    build()
+    d = os.path.dirname(SAN_LIB)
+    os.makedirs(d, exist_ok=True)
+
+    def one(src):
+        obj = os.path.join(d, src + ".o")
+        cmd = ["hipcc", "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj] + [f for f in FLAGS if f != "-O3"] + ["-O1"] + SAN_HOST
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError("hipcc (sanitized) failed for %s:\n%s\n%s" % (src, r.stdout, r.stderr))
+        return obj
+
+    with ThreadPoolExecutor(max_workers=3) as ex:
+        objs = list(ex.map(one, HOST_SOURCES))
+    objs += [os.path.join(OBJDIR, s + ".o") for s in SOURCES if s not in HOST_SOURCES]
+    cmd = ["hipcc", "-shared", "-fPIC", "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-shared-libsan", "-o", SAN_LIB] + objs
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError("link (sanitized) failed:\n%s\n%s" % (r.stdout, r.stderr))
+    return SAN_LIB
+
+
+def sanitizer_runtime() -> str:
+    r = subprocess.run(["hipcc", "-print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True)
+    path = r.stdout.strip()
+    if not os.path.isabs(path) or not os.path.exists(path):
+        import glob
+        found = sorted(glob.glob("/opt/rocm/llvm/lib/clang/*/lib/linux/libclang_rt.asan-x86_64.so"))
+        if not found:
+            raise RuntimeError("clang's shared ASan runtime was not found")
+        path = found[-1]
+    return path
+
+
 if __name__ == "__main__":
-    print(build(force="--force" in sys.argv))
+    print(build_sanitized() if "--sanitize" in sys.argv else build(force="--force" in sys.argv))
