@@ -240,10 +240,11 @@ int tr_set_fused_aggregation(eg_graph *g, int enable);
 /* Which variant of the block-contraction kernel the (x) = multiply, (+) = sum vertices of this graph run on, for
  * comparisons and for tests that must reach every variant at sizes the library would route elsewhere; results are
  * the same up to summation order.  kernel: 0 = the library chooses per vertex, 1 = the register-staged kernel,
- * 2 = the direct-to-LDS kernel wherever the operand layout allows it.  tile: 0 = the library chooses, 128 or 256 =
- * output tile size of the direct-to-LDS kernel.  waves: 0 = the library chooses, 4 or 8 = waves per workgroup of its
- * 256 x 256 variant.  Other values: EG_ERR_LIMIT.  Takes effect at the next tr_execute; changes no workspace size. */
-int tr_set_contract_variant(eg_graph *g, int kernel, int tile, int waves);
+ * 2 = the direct-to-LDS kernel wherever the operand layout allows it.  tile_m x tile_n: 0 x 0 = the library chooses;
+ * 128 x 128, 256 x 128 or 256 x 256 = output tile of the direct-to-LDS kernel (fp32 operands have no 256 x 128 variant
+ * and take 256 x 256 instead).  waves: 0 = the library chooses, 4 or 8 = waves per workgroup of the 256 x 256 variant.
+ * Other values: EG_ERR_LIMIT.  Takes effect at the next tr_execute; changes no workspace size. */
+int tr_set_contract_variant(eg_graph *g, int kernel, int tile_m, int tile_n, int waves);
 
 /* ---- Timing of the launches inside tr_execute (for roofline reports) ----------------------------------- */
 

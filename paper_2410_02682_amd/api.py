@@ -151,8 +151,10 @@ def tr_set_fused_aggregation(g, enable: bool) -> None:
 CONTRACT_KERNELS = {"auto": 0, "staged": 1, "dma": 2}
 
 
-def tr_set_contract_variant(g, kernel: str = "auto", tile: int = 0, waves: int = 0) -> None:
-    _check(_lib.load().tr_set_contract_variant(g, CONTRACT_KERNELS[kernel], int(tile), int(waves)))
+def tr_set_contract_variant(g, kernel: str = "auto", tile=0, waves: int = 0) -> None:
+    """tile: 0 (the library chooses), an int t for t x t, or a pair (tile_m, tile_n)."""
+    tm, tn = (tile, tile) if isinstance(tile, int) else tile
+    _check(_lib.load().tr_set_contract_variant(g, CONTRACT_KERNELS[kernel], int(tm), int(tn), int(waves)))
 
 
 # ---- EinDecomp: cost model and choice of the partitioning vectors (host only) -----------------------------

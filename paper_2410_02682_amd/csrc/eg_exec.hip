@@ -854,14 +854,16 @@ int tr_set_fused_aggregation(eg_graph *g, int enable)
     return EG_OK;
 }
 
-int tr_set_contract_variant(eg_graph *g, int kernel, int tile, int waves)
+int tr_set_contract_variant(eg_graph *g, int kernel, int tile_m, int tile_n, int waves)
 {
     if (!g) return fail(EG_ERR_NULL, "graph is NULL");
     if (kernel < 0 || kernel > 2) return fail(EG_ERR_LIMIT, "tr_set_contract_variant: kernel must be 0 (library's choice), 1 (register-staged) or 2 (direct-to-LDS)");
-    if (tile != 0 && tile != 128 && tile != 256) return fail(EG_ERR_LIMIT, "tr_set_contract_variant: tile must be 0, 128 or 256");
+    const bool ok = (tile_m == 0 && tile_n == 0) || (tile_m == 128 && tile_n == 128) || (tile_m == 256 && tile_n == 128) || (tile_m == 256 && tile_n == 256);
+    if (!ok) return fail(EG_ERR_LIMIT, "tr_set_contract_variant: tile must be 0 x 0, 128 x 128, 256 x 128 or 256 x 256");
     if (waves != 0 && waves != 4 && waves != 8) return fail(EG_ERR_LIMIT, "tr_set_contract_variant: waves must be 0, 4 or 8");
     g->contract_kernel = kernel;
-    g->contract_tile = tile;
+    g->contract_tile_m = tile_m;
+    g->contract_tile_n = tile_n;
     g->contract_waves = waves;
     return EG_OK;
 }
@@ -1104,7 +1106,8 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
         s.stride = out.slab_elems;                 // what the join kernel was given
         if (s.r.kind == EG_KERNEL_CONTRACT_MFMA || s.r.kind == EG_KERNEL_CONTRACT_ALU) {
             s.r.cp.force_kernel = g->contract_kernel;
-            s.r.cp.force_tile = g->contract_tile;
+            s.r.cp.force_tile_m = g->contract_tile_m;
+            s.r.cp.force_tile_n = g->contract_tile_n;
             s.r.cp.force_waves = g->contract_waves;
         }
         steps.push_back(std::move(s));

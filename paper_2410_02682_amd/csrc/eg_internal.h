@@ -69,7 +69,7 @@ struct ContractParams {
     int32_t out_vec;              // filled by the launcher: 1 = Z rows can be written as 16-byte vectors along N
     int32_t total_tiles, grid;    // filled by the launcher: output tiles over all tuples and batch entries; workgroups that share them
     int32_t force_kernel;         // 0: the launcher chooses; 1: register-staged kernel; 2: direct-to-LDS kernel wherever the layout allows (tr_set_contract_variant)
-    int32_t force_tile;           // 0: the launcher chooses; 128 / 256: tile size of the direct-to-LDS kernel
+    int32_t force_tile_m, force_tile_n;   // 0: the launcher chooses; 128 x 128, 256 x 128 or 256 x 256: tile of the direct-to-LDS kernel
     int32_t force_waves;          // 0: the launcher chooses; 4 / 8: waves per workgroup of the 256 x 256 direct-to-LDS kernel
 };
 
@@ -211,7 +211,7 @@ struct eg_graph {
     // executor state
     bool fuse = true;                               // fuse softmax chains where the partitioning allows (tr_set_fusion)
     bool agg_in_kernel = false;                     // contractions sum over partitioned contracted labels inside the kernel (tr_set_fused_aggregation)
-    int contract_kernel = 0, contract_tile = 0, contract_waves = 0;   // tr_set_contract_variant (0: the launchers choose)
+    int contract_kernel = 0, contract_tile_m = 0, contract_tile_n = 0, contract_waves = 0;   // tr_set_contract_variant (0: the launchers choose)
     bool profile = false;
     std::vector<void *> ev_start, ev_stop;          // hipEvent_t pool
     struct Launch { int vertex, stage, kernel; };

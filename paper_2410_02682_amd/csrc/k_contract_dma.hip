@@ -3,12 +3,14 @@
 // Same operation as k_contract.hip (the per-block kernel K of Section 4.3 of the paper for (x) = multiply,
 // (+) = sum, all tuples of the join in one launch), specialised for blocks of at least 128 x 128:
 //   * 256 x 256 output tiles, 8 waves per workgroup (two per SIMD), each owning a 128x64 patch = 4x2 MFMA 32x32 tiles;
+//     or 256 x 128 tiles with 4 waves of the same 128x64 patch, stages half as deep and two workgroups per compute unit,
+//     so that one workgroup's epilogue, addressing and first loads run under the other's MFMAs;
 //     or 128 x 128 tiles with 4 waves and two workgroups per compute unit when large tiles would leave the chip idle;
 //   * persistent workgroups, each walking over its share of the output tiles;
 //   * every 16-byte chunk of both operand tiles travels global memory -> LDS directly; the chunk a lane
 //     fetches is chosen so that the contiguous 1 KiB an instruction deposits is already the swizzled layout;
-//   * a stage is 128 bytes of k per tile row (64 k of bf16, 32 k of fp32) and four k-steps: one 32x32x16 bf16
-//     MFMA per 32x32 tile and step, or four 32x32x2 fp32 MFMAs on the four k a 16-byte chunk brings;
+//   * a stage is 128 (or 64) bytes of k per tile row (64 or 32 k of bf16, 32 k of fp32) and four (two) k-steps: one
+//     32x32x16 bf16 MFMA per 32x32 tile and step, or four 32x32x2 fp32 MFMAs on the four k a 16-byte chunk brings;
 //   * an operand contiguous along K sits in LDS as [row][128 bytes of k] and is read with 16-byte reads; an operand
 //     contiguous along M or N sits as [k][TS mn] and is read with the 16-bit transposing LDS read (bf16), which
 //     hands every lane four consecutive k for its own column, or with four 4-byte reads (fp32);
@@ -42,7 +44,6 @@ namespace dma {
 template <bool F32> struct Elem {
     static constexpr int ES = F32 ? 4 : 2;         // bytes per element
     static constexpr int EPC = 16 / ES;            // elements per 16-byte chunk
-    static constexpr int BK = 128 / ES;            // k per stage; output tiles are TS x TS (TS = 256 or 128)
 };
 
 #define EG_LDS(p) ((__attribute__((address_space(3))) void *)(p))
@@ -62,30 +63,37 @@ __device__ __forceinline__ void decode_group2(const DimList &g, int64_t idx, int
 }
 
 // Per-lane source offsets (bytes, relative to the first row of the operand's tile: `origin` is that row's
-// element offset in the block) of the TS/8/NW chunks this lane fetches per stage (NW waves per workgroup,
-// TS rows or columns per tile), without the k advance.
-//   KC: instruction i of wave w deposits rows (NW i+w)*8 .. +7, lane -> row +lane/8, physical chunk lane%8,
-//       logical chunk (lane%8) ^ ((row>>1)&7).
-//   MC: a k-row holds CPR = TS/8 chunks, so one instruction deposits KR = 64/CPR k-rows (2 for TS = 256, 4 for
-//       TS = 128): instruction i of wave w deposits k-rows KR (NW i+w) .. +KR-1, lane -> k-row +lane/CPR,
+// element offset in the block) of the chunks this lane fetches per stage (NW waves per workgroup, T rows or columns
+// of this operand per tile, KB bytes of k per row and stage), without the k advance.
+//   KC: a row holds CR = KB/16 chunks, so one 1 KiB instruction deposits RPI = 64/CR rows (8 for KB = 128, 16 for 64):
+//       instruction i of wave w deposits rows (NW i+w)*RPI .. +RPI-1, lane -> row +lane/CR, physical chunk lane%CR,
+//       logical chunk (lane%CR) ^ key(row), key = (row>>1)&7 for 128-byte rows, (row>>2)&3 for 64-byte rows: the 16 rows a
+//       16-byte LDS read instruction touches in one pass then fall into 16 different 16-byte bank groups.
+//   MC: a k-row holds CPR = T/8 chunks, so one instruction deposits KR = 64/CPR k-rows (2 for T = 256, 4 for
+//       T = 128): instruction i of wave w deposits k-rows KR (NW i+w) .. +KR-1, lane -> k-row +lane/CPR,
 //       physical chunk lane%CPR, logical chunk (lane%CPR) ^ 4*(krow%4), krow%4 = (KR w + lane/CPR)%4.
-template <bool KC, int NW, int TS, bool F32>
+template <bool KC, int NW, int T, int KB, bool F32>
 struct Src {
     static constexpr int ES = Elem<F32>::ES, EPC = Elem<F32>::EPC;
-    static constexpr int LD = TS / 8 / NW;
-    static constexpr int CPR = TS / EPC, KR = 64 / CPR;   // chunks per k-row of an MC tile, k-rows per 1 KiB instruction
+    static constexpr int LD = T * KB / 1024 / NW;         // direct loads of this operand per wave and stage
+    static constexpr int CR = KB / 16, RPI = 64 / CR;     // chunks per row of a KC tile, rows per 1 KiB instruction
+    static constexpr int CPR = T / EPC, KR = 64 / CPR;    // chunks per k-row of an MC tile, k-rows per 1 KiB instruction
+    static_assert(LD >= 1 && LD * NW * 1024 == T * KB, "a stage of this operand is a whole number of 1 KiB instructions per wave");
+    static_assert(KB == 128 || KB == 64, "rows of 128 or 64 bytes of k");
+    static_assert((NW * KR) % 4 == 0, "the swizzle key of an MC chunk must not depend on the instruction index");
     uint32_t boff[LD];        // byte offset of the chunk instruction i fetches, relative to the stage's first k
     int kl;                   // k (within the stage) of chunk 0 of this lane; chunk i sits at kl (KC) or kl + KR NW i (MC)
 
     __device__ __forceinline__ void init(const DimList &grp, int64_t first, int64_t extent, int64_t origin, int64_t k_inner_stride, int wave, int lane)
     {
         if (KC) {
-            // LDS row of this lane's chunk is (NW i+wave)*8 + lane/8; its swizzle key (row>>1)&7 does not depend on i
-            const int lc = (lane & 7) ^ ((wave * 4 + (lane >> 4)) & 7);
+            // LDS row of this lane's chunk is (NW i+wave)*RPI + lane/CR; its swizzle key does not depend on i
+            const int key = KB == 128 ? ((wave * 4 + (lane >> 4)) & 7) : ((lane >> 4) & 3);
+            const int lc = (lane % CR) ^ key;
             kl = lc * EPC;
 #pragma unroll
             for (int i = 0; i < LD; i++) {
-                int64_t r = first + (NW * i + wave) * 8 + (lane >> 3);
+                int64_t r = first + (NW * i + wave) * RPI + lane / CR;
                 r = r < extent ? r : extent - 1;
                 int64_t o0, o1;
                 decode_group2(grp, r, o0, o1);
@@ -116,13 +124,15 @@ struct Src {
 
 // LDS byte address of the fragment chunk lane `lane` feeds to the MFMA for 32-row tile `t32` (rows t32*32..+31
 // of the wave's 128) at k-step ks (16 k per step).  KC layout: one 16-byte read.
+template <int KB>
 __device__ __forceinline__ int kc_frag_off(int row, int ks, int lane)
 {
     const int lc = 2 * ks + (lane >> 5);
-    return row * 128 + ((lc ^ ((row >> 1) & 7)) << 4);      // 16 consecutive rows hit 16 distinct 16-byte bank groups
+    const int key = KB == 128 ? (row >> 1) & 7 : (row >> 2) & 3;
+    return row * KB + ((lc ^ key) << 4);                    // 16 consecutive rows hit 16 distinct 16-byte bank groups
 }
 
-// MC layout: two transposing 8-byte reads (k = 8*(lane/32) + 0..3 and +4..7 of the k-step).
+// MC layout: two transposing 8-byte reads (k = 8*(lane/32) + 0..3 and +4..7 of the k-step); TS: columns of the operand's tile.
 template <int TS>
 __device__ __forceinline__ int mc_frag_off(int col0, int ks, int lane, int second)
 {
@@ -136,10 +146,10 @@ __device__ __forceinline__ int mc_frag_off(int col0, int ks, int lane, int secon
 // Fragments of one k-step (16 k of bf16, 8 k of fp32): RT 32-row A fragments and NT 32-column B fragments of this wave
 // (row0, col0: first row / column of the wave's patch inside the tile).  A fragment is 16 bytes per lane: eight bf16
 // (k = 8 * (lane / 32) + 0..7 of the step) or four fp32 (k = 4 * (lane / 32) + 0..3).
-template <bool KC, int TS, bool F32>
+template <bool KC, int TS, int KB, bool F32>
 __device__ __forceinline__ u32x4 load_frag(const char *l, int first, int ks, int lane)
 {
-    if (KC) return *(const u32x4 *)(l + kc_frag_off(first + (lane & 31), ks, lane));
+    if (KC) return *(const u32x4 *)(l + kc_frag_off<KB>(first + (lane & 31), ks, lane));
     if (F32) {
         const char *q = l + (8 * ks + 4 * (lane >> 5)) * (TS * 4) + (first + (lane & 31)) * 4;
         u32x4 v;
@@ -154,13 +164,13 @@ __device__ __forceinline__ u32x4 load_frag(const char *l, int first, int ks, int
     return v;
 }
 
-template <bool A_KC, bool B_KC, int RT, int NT, int TS, bool F32>
+template <bool A_KC, bool B_KC, int RT, int NT, int TM, int TN, int KB, bool F32>
 __device__ __forceinline__ void load_frags(const char *la, const char *lb, int ks, u32x4 (&a)[RT], u32x4 (&b)[NT], int row0, int col0, int lane)
 {
 #pragma unroll
-    for (int i = 0; i < RT; i++) a[i] = load_frag<A_KC, TS, F32>(la, row0 + i * 32, ks, lane);
+    for (int i = 0; i < RT; i++) a[i] = load_frag<A_KC, TM, KB, F32>(la, row0 + i * 32, ks, lane);
 #pragma unroll
-    for (int j = 0; j < NT; j++) b[j] = load_frag<B_KC, TS, F32>(lb, col0 + j * 32, ks, lane);
+    for (int j = 0; j < NT; j++) b[j] = load_frag<B_KC, TN, KB, F32>(lb, col0 + j * 32, ks, lane);
 }
 
 // One 32x32 tile's share of a k-step.
@@ -197,30 +207,36 @@ struct TileInfo {
     int64_t bz, agg;         // Z element offset of the tuple's block and batch entry; aggIdx of the tuple
 };
 
-// Output tiles are TS x TS; the NW waves of a workgroup form a 2 x NW/2 grid of patches.
-//   TS = 256, NW = 8: two waves per SIMD, each owning 128 x 64; one wave's MFMAs cover the other's LDS reads and
-//       barrier waits.  The kernel for large blocks: one workgroup per compute unit (154 KiB of LDS).
-//   TS = 256, NW = 4: one wave per SIMD, each owning 128 x 128 (two thirds of the LDS read traffic, nothing to
+// Output tiles are TM x TN; the NW waves of a workgroup form a 2 x NW/2 grid of patches; a stage holds KB bytes of k per row.
+//   256 x 256, KB = 128, NW = 8: two waves per SIMD, each owning 128 x 64; one wave's MFMAs cover the other's LDS reads
+//       and barrier waits.  One workgroup per compute unit (154 KiB of LDS): every tile's addressing, first loads and
+//       epilogue run with the matrix pipes idle, which is what short reductions consist of.
+//   256 x 128, KB = 64, NW = 4: the same 128 x 64 patch per wave (the same LDS reads per MFMA), stages half as deep, 64 KiB
+//       of LDS: two workgroups per compute unit, not in step with each other, so one's per-tile phases and barrier waits
+//       run under the other's MFMAs.
+//   256 x 256, KB = 128, NW = 4: one wave per SIMD, each owning 128 x 128 (two thirds of the LDS read traffic, nothing to
 //       cover a wave's own waits); kept for comparison.
-//   TS = 128, NW = 4: patches of 64 x 64, 78 KiB of LDS, two workgroups per compute unit: one's epilogue and
-//       first loads run under the other's MFMAs.  For launches with too few 256 x 256 tiles to fill the chip
-//       and for short K, where a tile is mostly loading and storing.
+//   128 x 128, KB = 128, NW = 4: patches of 64 x 64, 78 KiB of LDS, two workgroups per compute unit.  For launches with too
+//       few larger tiles to fill the chip.
 //
 // The kernel is persistent: the workgroups of a compute unit walk over their share of the tiles.  While a tile's
 // epilogue runs, the first two stages of the workgroup's next tile are already on their way into LDS, and the
 // next tile's addressing was worked out while the current tile waited for its own first stage.
-template <int TS, int NW, bool A_KC, bool B_KC, bool ODD, bool F32>
-__global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(const ContractParams p)
+// LDS of one workgroup: two stages, two sets of Z offset tables, the waves' epilogue staging rows
+constexpr int lds_bytes(int TM, int TN, int KB, int NW) { return 2 * (TM + TN) * KB + 2 * (TM + TN) * 8 + NW * 8 * (32 * (TN / (NW / 2) / 32) * 4 + 32); }
+
+template <int TM, int TN, int KB, int NW, bool A_KC, bool B_KC, bool ODD, bool F32>
+__global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW) <= 160 * 1024 ? 2 : 1) void k_contract_dma(const ContractParams p)
 {
-    constexpr int ES = Elem<F32>::ES, EPC = Elem<F32>::EPC, BK = Elem<F32>::BK;
+    constexpr int ES = Elem<F32>::ES, EPC = Elem<F32>::EPC, BK = KB / ES;
+    constexpr int KS = KB / 32;                       // k-steps per stage (32 bytes of k each)
     constexpr int WN = NW / 2;                        // waves side by side
-    constexpr int RT = TS / 64, NT = TS / WN / 32;    // 32x32 MFMA tiles per wave: RT down, NT across
-    constexpr int LD = TS / 8 / NW;                   // direct loads per operand tile, wave and stage
-    constexpr int TILE_BYTES = TS * 128;              // one operand tile of one stage: 128 bytes of k per row
-    constexpr int STAGE_BYTES = 2 * TILE_BYTES;
-    constexpr int TBL = 2 * TS * 8;                   // one set of Z offset tables (TS rows, TS columns)
-    constexpr int DPM = 2 * LD / (RT * NT);           // direct loads issued after each MFMA of a stage's last k-step
-    static_assert(DPM * RT * NT == 2 * LD && DPM >= 1, "the last k-step's MFMAs carry all loads of a stage");
+    constexpr int RT = TM / 64, NT = TN / WN / 32;    // 32x32 MFMA tiles per wave: RT down, NT across
+    constexpr int LDA = TM * KB / 1024 / NW, LDB = TN * KB / 1024 / NW, NLD = LDA + LDB;   // direct loads per wave and stage
+    constexpr int TILE_BYTES = TM * KB;               // X's tile of one stage: KB bytes of k per row; Y's follows it
+    constexpr int STAGE_BYTES = (TM + TN) * KB;
+    constexpr int TBL = (TM + TN) * 8;                // one set of Z offset tables (TM rows, TN columns)
+    static_assert(KS == 4 || KS == 2, "a stage is four or two k-steps");
     constexpr int CW = 32 * NT, PITCH = CW * 4 + 32, WBUF = 8 * PITCH;   // epilogue staging: 8 rows of a wave's patch
     // Separate LDS objects for the two stages and for the epilogue: the compiler can then tell that the fragment
     // reads of one stage, or the epilogue's staging, never alias the direct loads in flight into another object,
@@ -228,6 +244,7 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
     __shared__ __attribute__((aligned(1024))) char lds0[STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) char lds1[STAGE_BYTES];
     __shared__ __attribute__((aligned(16))) char ldsx[2 * TBL + NW * WBUF];    // two sets of Z offset tables + staging
+    static_assert(2 * STAGE_BYTES + 2 * TBL + NW * WBUF == lds_bytes(TM, TN, KB, NW), "lds_bytes() is what decides the workgroups per compute unit");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int row0 = wm * (32 * RT), col0 = wn * (32 * NT);
@@ -274,8 +291,8 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
             by += (int64_t)k * p.batch.s1[i];
             bz += (int64_t)k * p.batch.s2[i];
         }
-        t.m0 = (int64_t)tile_m * TS;
-        t.n0 = (int64_t)tile_n * TS;
+        t.m0 = (int64_t)tile_m * TM;
+        t.n0 = (int64_t)tile_n * TN;
         // lane offsets are 32 bits and count from the tile's first row (an operand contiguous along M or N reads whole
         // 8-element chunks, so near the block's edge its first chunk may start up to 7 elements before the tile)
         int64_t unused;
@@ -292,8 +309,8 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
     const int64_t nk = (p.K / run) * ((run + BK - 1) / BK);          // stages: every run starts a stage of its own
 
     TileInfo cur, nxt;
-    Src<A_KC, NW, TS, F32> sa;
-    Src<B_KC, NW, TS, F32> sb;
+    Src<A_KC, NW, TM, KB, F32> sa;
+    Src<B_KC, NW, TN, KB, F32> sb;
     const char *xb, *yb;                              // bases the direct loads currently work from
 
     // Uniform source pointers of consecutive stages, and how many k each has (a full stage, less at the end of a run of
@@ -325,16 +342,16 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
             }
         }
     };
-    // direct load i (0..LD-1: X tile, LD..2LD-1: Y tile) of a stage into the LDS stage at `dst`: a 2 GiB buffer descriptor
+    // direct load i (0..LDA-1: X tile, LDA..NLD-1: Y tile) of a stage into the LDS stage at `dst`: a 2 GiB buffer descriptor
     // on the uniform stage base + a 32-bit lane offset (in-block offsets are below 2^31; 2^31 itself means "no fetch, zeros")
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
     auto dma = [&](int i, const char *ga, const char *gb, int krem, char *dst) {
-        if (i < LD) {
+        if (i < LDA) {
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)ga, 0, (int)0x80000000u, 0x00020000);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, EG_LDS(dst + (NW * i + wave_u) * 1024), 16, (int)sa.voff(i, krem), 0, 0, 0);
         } else {
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)gb, 0, (int)0x80000000u, 0x00020000);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, EG_LDS(dst + TILE_BYTES + (NW * (i - LD) + wave_u) * 1024), 16, (int)sb.voff(i - LD, krem), 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, EG_LDS(dst + TILE_BYTES + (NW * (i - LDA) + wave_u) * 1024), 16, (int)sb.voff(i - LDA, krem), 0, 0, 0);
         }
     };
     // The same load written out by hand, for the loads that travel during an epilogue: the compiler keeps track of
@@ -342,22 +359,22 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
     // are waited for by the explicit vmcnt(0) and barrier at the head of the tile loop.  M0 (the LDS base of a
     // direct load) is put back, so the compiler's own picture of it stays right.
     auto dma_untracked = [&](int i, const char *ga, const char *gb, int krem, char *dst) {
-        const bool isa = i < LD;
+        const bool isa = i < LDA;
         const uint64_t base = (uint64_t)(isa ? ga : gb);
         u32x4 rs;
         rs.x = (uint32_t)base;
         rs.y = (uint32_t)(base >> 32) & 0xffffu;       // stride 0
         rs.z = 0x80000000u;
         rs.w = 0x00020000u;
-        const uint32_t l = (uint32_t)(uintptr_t)EG_LDS(dst + (isa ? 0 : TILE_BYTES) + (NW * (isa ? i : i - LD) + wave_u) * 1024);
-        const uint32_t off = isa ? sa.voff(i, krem) : sb.voff(i - LD, krem);
+        const uint32_t l = (uint32_t)(uintptr_t)EG_LDS(dst + (isa ? 0 : TILE_BYTES) + (NW * (isa ? i : i - LDA) + wave_u) * 1024);
+        const uint32_t off = isa ? sa.voff(i, krem) : sb.voff(i - LDA, krem);
         uint32_t keep;
         asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
                      : "=&s"(keep) : "s"(l), "v"(off), "s"(rs) : "memory");
     };
     auto issue = [&](const char *ga, const char *gb, int krem, char *dst) {
 #pragma unroll
-        for (int i = 0; i < 2 * LD; i++) dma_untracked(i, ga, gb, krem, dst);
+        for (int i = 0; i < NLD; i++) dma_untracked(i, ga, gb, krem, dst);
     };
     const char *ga2, *gb2;
     int kr2;
@@ -382,32 +399,38 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
     f32x16 acc[RT][NT];
     u32x4 a0[RT], b0[NT], a1[RT], b1[NT];
 #define EG_PIN() __builtin_amdgcn_sched_barrier(0)
+#define EG_FRAGS(BUF, KSTEP, NA, NB) load_frags<A_KC, B_KC, RT, NT, TM, TN, KB, F32>(BUF, BUF + TILE_BYTES, KSTEP, NA, NB, row0, col0, lane)
 #define EG_KSTEP(FA, FB, NA, NB, BUF, KS_NEXT)                                                    \
     mfma_rows<0, 1, RT, NT, F32>(FA, FB, acc); EG_PIN();                                                   \
-    load_frags<A_KC, B_KC, RT, NT, TS, F32>(BUF, BUF + TILE_BYTES, KS_NEXT, NA, NB, row0, col0, lane); EG_PIN(); \
+    EG_FRAGS(BUF, KS_NEXT, NA, NB); EG_PIN();                                                      \
     mfma_rows<1, RT, RT, NT, F32>(FA, FB, acc); EG_PIN();
+    // the direct loads of a stage are spread over the RT * NT MFMAs of a k-step: those that follow MFMA q
+#define EG_DMA_AFTER(Q, C)                                                                        \
+    if (has2) { _Pragma("unroll") for (int d = (Q) * NLD / (RT * NT); d < ((Q) + 1) * NLD / (RT * NT); d++) dma(d, ga2, gb2, kr2, C); }
 #define EG_STAGE_NEXT(C, O, HAS_NEXT2) /* one stage; its successor is already in flight into O */     \
     do {                                                                                          \
         mfma_rows<0, 1, RT, NT, F32>(a0, b0, acc); EG_PIN();                                               \
         const bool has2 = (HAS_NEXT2);                                                            \
         next_stage(ga2, gb2, kr2);          /* scalar work rides under the MFMAs */               \
-        load_frags<A_KC, B_KC, RT, NT, TS, F32>(C, C + TILE_BYTES, 1, a1, b1, row0, col0, lane); EG_PIN();     \
+        EG_FRAGS(C, 1, a1, b1); EG_PIN();                                                         \
         mfma_rows<1, RT, RT, NT, F32>(a0, b0, acc); EG_PIN();                                               \
-        EG_KSTEP(a1, b1, a0, b0, C, 2)                                                            \
-        EG_KSTEP(a0, b0, a1, b1, C, 3)                                                            \
+        if constexpr (KS == 4) {                                                                  \
+            EG_KSTEP(a1, b1, a0, b0, C, 2)                                                        \
+            EG_KSTEP(a0, b0, a1, b1, C, 3)                                                        \
+        }                                                                                         \
         __builtin_amdgcn_s_waitcnt(0x0F70); /* vmcnt(0): this wave's deposits for O landed */     \
         __syncthreads();                    /* everybody's landed; everybody has left C */        \
         EG_PIN();                                                                                 \
-        /* last k-step: every MFMA is followed by DPM direct loads of the stage after next into C */ \
+        /* last k-step: the MFMAs carry the direct loads of the stage after next into C */        \
         _Pragma("unroll") for (int j = 0; j < NT; j++) {                                          \
             mma<F32>(a1[0], b1[j], acc[0][j]); EG_PIN();                                          \
-            if (has2) { _Pragma("unroll") for (int d = 0; d < DPM; d++) dma(DPM * j + d, ga2, gb2, kr2, C); } \
+            EG_DMA_AFTER(j, C)                                                                    \
             EG_PIN();                                                                             \
         }                                                                                         \
-        load_frags<A_KC, B_KC, RT, NT, TS, F32>(O, O + TILE_BYTES, 0, a0, b0, row0, col0, lane); EG_PIN();     \
+        EG_FRAGS(O, 0, a0, b0); EG_PIN();                                                         \
         _Pragma("unroll") for (int q = 0; q < (RT - 1) * NT; q++) {                               \
             mma<F32>(a1[1 + q / NT], b1[q % NT], acc[1 + q / NT][q % NT]); EG_PIN();              \
-            if (has2) { _Pragma("unroll") for (int d = 0; d < DPM; d++) dma(DPM * (NT + q) + d, ga2, gb2, kr2, C); } \
+            EG_DMA_AFTER(NT + q, C)                                                               \
             EG_PIN();                                                                             \
         }                                                                                         \
     } while (0)
@@ -421,14 +444,17 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
         // while the first stages travel: the next tile's uniform addressing and this tile's Z offset tables
         // (256 rows, 256 columns; two sets in turn, so a wave already in the next tile cannot disturb a slower one)
         if (more) tile_info(first + (it + 1) * stride, nxt);
-        int64_t *zrow = (int64_t *)(ldsx + (it & 1) * TBL), *zcol = zrow + TS;
-        if (tid < TS) {
+        int64_t *zrow = (int64_t *)(ldsx + (it & 1) * TBL), *zcol = zrow + TM;
+        for (int e = tid; e < TM + TN; e += NW * 64) {
             int64_t unused, z;
-            const int64_t m = cur.m0 + tid, n = cur.n0 + tid;
-            decode_group2(p.m, m < p.M ? m : 0, unused, z);
-            zrow[tid] = z;
-            decode_group2(p.n, n < p.N ? n : 0, unused, z);
-            zcol[tid] = z;
+            if (e < TM) {
+                const int64_t m = cur.m0 + e;
+                decode_group2(p.m, m < p.M ? m : 0, unused, z);
+            } else {
+                const int64_t n = cur.n0 + (e - TM);
+                decode_group2(p.n, n < p.N ? n : 0, unused, z);
+            }
+            zrow[e] = z;
         }
 #pragma unroll
         for (int i = 0; i < RT; i++)
@@ -438,7 +464,7 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
                 for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
         __builtin_amdgcn_s_waitcnt(0x0F70);           // both stages (and the previous tile's stores) are done
         __syncthreads();
-        load_frags<A_KC, B_KC, RT, NT, TS, F32>(lds0, lds0 + TILE_BYTES, 0, a0, b0, row0, col0, lane);
+        EG_FRAGS(lds0, 0, a0, b0);
         // Every stage, the last one included, runs the same straight-line code (the last one pays for one idle
         // barrier and a set of unused fragment reads): an MFMA under a branch inside the loop would make the
         // compiler shuffle the accumulator registers.  The stage count's parity is a template parameter.
@@ -467,8 +493,8 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
         const int lrow = elane & 31, lhalf = elane >> 5;
         char *wbuf = ldsx + 2 * TBL + wave_u * WBUF;   // this wave's staging rows
         const bool slab = p.out.slab_elems != 0;
-        const int mrem = (int)(p.M - cur.m0 < TS ? p.M - cur.m0 : TS);     // rows / columns of the tile inside the block
-        const int nrem = (int)(p.N - cur.n0 < TS ? p.N - cur.n0 : TS);
+        const int mrem = (int)(p.M - cur.m0 < TM ? p.M - cur.m0 : TM);     // rows / columns of the tile inside the block
+        const int nrem = (int)(p.N - cur.n0 < TN ? p.N - cur.n0 : TN);
         if (p.out_vec) {
             // Z is contiguous along the tile's columns: each wave stages 8 rows x CW columns of its patch at a time
             // in LDS (the row pitch leaves 32 bytes of padding, which keeps the two half-waves on different banks)
@@ -577,32 +603,35 @@ __global__ __launch_bounds__(NW * 64, TS == 128 ? 2 : 1) void k_contract_dma(con
         cur = nxt;
     }
 #undef EG_STAGE_NEXT
+#undef EG_DMA_AFTER
 #undef EG_KSTEP
+#undef EG_FRAGS
 #undef EG_PIN
 }
 
-template <int TS, int NW, bool A_KC, bool B_KC, bool ODD, bool F32>
+template <int TM, int TN, int KB, int NW, bool A_KC, bool B_KC, bool ODD, bool F32>
 static int launch_one(ContractParams &p, void *stream)
 {
-    hipLaunchKernelGGL((k_contract_dma<TS, NW, A_KC, B_KC, ODD, F32>), dim3((unsigned)p.grid), dim3(NW * 64), 0, (hipStream_t)stream, p);
+    hipLaunchKernelGGL((k_contract_dma<TM, TN, KB, NW, A_KC, B_KC, ODD, F32>), dim3((unsigned)p.grid), dim3(NW * 64), 0, (hipStream_t)stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(EG_ERR_HIP, "k_contract_dma launch failed: %s", hipGetErrorString(e));
     return EG_OK;
 }
 
-template <int TS, int NW, bool A_KC, bool B_KC, bool F32>
+template <int TM, int TN, int KB, int NW, bool A_KC, bool B_KC, bool F32>
 static int launch_parity(ContractParams &p, void *stream)
 {
-    constexpr int BK = Elem<F32>::BK;
+    constexpr int BK = KB / Elem<F32>::ES;
     const int64_t run = p.k.n == 1 ? p.K : p.k.ext[p.k.n - 1];
-    return (((p.K / run) * ((run + BK - 1) / BK)) & 1) ? launch_one<TS, NW, A_KC, B_KC, true, F32>(p, stream) : launch_one<TS, NW, A_KC, B_KC, false, F32>(p, stream);
+    return (((p.K / run) * ((run + BK - 1) / BK)) & 1) ? launch_one<TM, TN, KB, NW, A_KC, B_KC, true, F32>(p, stream)
+                                                       : launch_one<TM, TN, KB, NW, A_KC, B_KC, false, F32>(p, stream);
 }
 
-template <int TS, int NW, bool F32>
+template <int TM, int TN, int KB, int NW, bool F32>
 static int launch_layout(ContractParams &p, void *stream)
 {
-    if (p.a_kcontig) return p.b_kcontig ? launch_parity<TS, NW, true, true, F32>(p, stream) : launch_parity<TS, NW, true, false, F32>(p, stream);
-    return p.b_kcontig ? launch_parity<TS, NW, false, true, F32>(p, stream) : launch_parity<TS, NW, false, false, F32>(p, stream);
+    if (p.a_kcontig) return p.b_kcontig ? launch_parity<TM, TN, KB, NW, true, true, F32>(p, stream) : launch_parity<TM, TN, KB, NW, true, false, F32>(p, stream);
+    return p.b_kcontig ? launch_parity<TM, TN, KB, NW, false, true, F32>(p, stream) : launch_parity<TM, TN, KB, NW, false, false, F32>(p, stream);
 }
 
 }  // namespace dma
@@ -660,22 +689,30 @@ int launch_contract_dma(ContractParams &p, void *stream)
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return fail(EG_ERR_HIP, "cannot query the device");
         n_cu = prop.multiProcessorCount > 8 ? prop.multiProcessorCount / 8 * 8 : 8;
     }
-    // Tile size: 256 x 256, one workgroup per compute unit, is the faster kernel per flop (a quarter more, measured on
-    // large products).  128 x 128 tiles, two workgroups per unit, are taken when they are all resident at once, i.e. when
-    // the large tiles would leave at least half of the compute units without work (measured: 64 large tiles 1.5-1.8x
-    // faster as 256 small ones; 160 large tiles 1.4x slower as 640 small ones, which need a second round).
+    // Tile shape.  256 x 128 with two workgroups per compute unit is the kernel for bf16; 256 x 256 with one is the one for
+    // fp32.  128 x 128 tiles, two workgroups per unit, are taken when they are all resident at once, i.e. when larger
+    // tiles would leave at least half of the compute units without work (measured: 64 tiles of 256 x 256 ran 1.5-1.8x
+    // faster as 256 small ones; 160 of them 1.4x slower as 640 small ones, which need a second round), and when large
+    // tiles would be mostly padding (128 columns in a 256-wide tile).
+    const bool f32 = p.in_dtype == EG_F32;
     const int64_t tuples = p.n_tuples * p.n_batch;
-    const int64_t small = tuples * ((p.M + 127) / 128) * ((p.N + 127) / 128);
-    const int64_t large = tuples * ((p.M + 255) / 256) * ((p.N + 255) / 256);
-    // ... and when the large tiles would be mostly padding (128 columns in a 256-wide tile: config 4's P x V, 0.31 -> 0.29 ms)
-    int ts = (small <= 2 * n_cu || 4 * large * 10 > small * 14) ? 128 : 256;
-    if (p.force_tile == 128 || p.force_tile == 256) ts = p.force_tile;   // tr_set_contract_variant: comparisons and tests
-    p.tiles_m = (int32_t)((p.M + ts - 1) / ts);
-    p.tiles_n = (int32_t)((p.N + ts - 1) / ts);
+    auto count = [&](int tm, int tn) { return tuples * ((p.M + tm - 1) / tm) * ((p.N + tn - 1) / tn); };
+    const int64_t small = count(128, 128), large = count(256, 256);
+    int tm, tn;
+    if (small <= 2 * n_cu || 4 * large * 10 > small * 14) tm = tn = 128;
+    else if (f32) tm = tn = 256;
+    else { tm = 256; tn = 128; }
+    if (p.force_tile_m && p.force_tile_n) { tm = p.force_tile_m; tn = p.force_tile_n; }   // tr_set_contract_variant: comparisons and tests
+    if (f32 && tm != tn) tn = tm;
+    // the variant: stage depth and waves follow from the tile shape
+    const int kb = (tm == 256 && tn == 128) ? 64 : 128;
+    const int nw = (tm == 256 && tn == 256 && (f32 || p.force_waves != 4)) ? 8 : 4;
+    p.tiles_m = (int32_t)((p.M + tm - 1) / tm);
+    p.tiles_n = (int32_t)((p.N + tn - 1) / tn);
     const int64_t wgs = tuples * p.tiles_m * p.tiles_n;
     if (wgs < 1 || wgs >= (1ll << 31)) return fail(EG_ERR_LIMIT, "contraction has %lld output tiles", (long long)wgs);
     // persistent workgroups: as many as fit the chip at once, a multiple of 8 so that every XCD gets the same number
-    const int64_t resident = (ts == 128 ? 2 : 1) * (int64_t)n_cu;
+    const int64_t resident = (2 * dma::lds_bytes(tm, tn, kb, nw) <= 160 * 1024 ? 2 : 1) * (int64_t)n_cu;
     p.total_tiles = (int32_t)wgs;
     p.grid = (int32_t)(wgs < resident ? wgs : resident);
     // wide epilogue stores need Z contiguous along the innermost N label and every other Z offset a multiple of 8 elements
@@ -685,10 +722,11 @@ int launch_contract_dma(ContractParams &p, void *stream)
     for (int i = 0; i < p.batch.n; i++) vec = vec && p.batch.s2[i] % 8 == 0;
     for (int l = 0; l < p.ts.n; l++) vec = vec && p.ts.step_z[l] % 8 == 0;
     p.out_vec = vec ? 1 : 0;
-    if (p.in_dtype == EG_F32) return ts == 128 ? dma::launch_layout<128, 4, true>(p, stream) : dma::launch_layout<256, 8, true>(p, stream);
-    if (ts == 128) return dma::launch_layout<128, 4, false>(p, stream);
-    if (p.force_waves == 4) return dma::launch_layout<256, 4, false>(p, stream);
-    return dma::launch_layout<256, 8, false>(p, stream);
+    if (f32) return tm == 128 ? dma::launch_layout<128, 128, 128, 4, true>(p, stream) : dma::launch_layout<256, 256, 128, 8, true>(p, stream);
+    if (tm == 128) return dma::launch_layout<128, 128, 128, 4, false>(p, stream);
+    if (tn == 128) return dma::launch_layout<256, 128, 64, 4, false>(p, stream);
+    if (nw == 4) return dma::launch_layout<256, 256, 128, 4, false>(p, stream);
+    return dma::launch_layout<256, 256, 128, 8, false>(p, stream);
 }
 
 }  // namespace eg

@@ -64,6 +64,14 @@ def violations(got: np.ndarray, ref: np.ndarray, rtol: float, magnitude: Optiona
     return bad, worst
 
 
+def tile_of(text: str):
+    """'256x128' -> (256, 128), '128' -> (128, 128), '' -> 0: the tile argument of tr_set_contract_variant."""
+    if not text:
+        return 0
+    parts = [int(t) for t in str(text).split("x")]
+    return (parts[0], parts[-1])
+
+
 def tainted_by_bf16(w: Workload) -> Dict[str, bool]:
     """A vertex carries bf16 rounding error if it or any computed ancestor is stored in bf16."""
     t: Dict[str, bool] = {}

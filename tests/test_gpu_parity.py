@@ -8,7 +8,7 @@ import math
 import numpy as np
 import pytest
 
-from tests._parity import RTOL_BF16, RTOL_F32, rtol_for, single_vertex, violations
+from tests._parity import RTOL_BF16, RTOL_F32, rtol_for, single_vertex, tile_of, violations
 from oracle.einsum_ref import einsum_ref
 from oracle.graph_ref import make_inputs, run_graph, to_storage
 from synth_inputs import build_config
@@ -66,13 +66,13 @@ def test_config_every_vertex_matches_oracle(n, pname):
     print(f"config {n} {pname}: worst plain relative error on elements above the rms: {strict[worst_name]:.3f} of the bound ({worst_name})", flush=True)
 
 
-@pytest.mark.parametrize("tile", ["", "256"])
+@pytest.mark.parametrize("tile", ["", "256x128", "256"])
 @pytest.mark.parametrize("n,pname", CASES)
 def test_config_outputs_through_workspace_match_oracle(n, pname, tile):
-    # at these sizes the bf16 contraction kernel would always pick its small tile: the second pass forces the large one
+    # at these sizes the bf16 contraction kernel would always pick its small tile: the other passes force the larger ones
     w, inp, ref = _reference(n)
     print(f"config {n} partitioning {pname}: intermediates in the workspace, tile {tile or 'default'}", flush=True)
-    got = _run(w, pname, inp, contract=dict(tile=int(tile)) if tile else None)
+    got = _run(w, pname, inp, contract=dict(tile=tile_of(tile)) if tile else None)
     for name in w.outputs:
         bad, worst = violations(got[name].as_f64(), ref[name].as_f64(), rtol_for(w, name))
         assert bad == 0, f"config {n} {pname} output {name}: {bad} elements out of tolerance (worst {worst:.2f}x)"
@@ -114,13 +114,13 @@ LAYOUTS = [
 ]
 
 
-@pytest.mark.parametrize("dtype,tile", [("bf16", "128"), ("bf16", "256"), ("f32", "128"), ("f32", "256"), ("f32", "")])
+@pytest.mark.parametrize("dtype,tile", [("bf16", "128"), ("bf16", "256x128"), ("bf16", "256"), ("f32", "128"), ("f32", "256"), ("f32", "")])
 @pytest.mark.parametrize("spec,bx,by", LAYOUTS)
 def test_contraction_layouts(spec, bx, by, dtype, tile):
-    # the direct-to-LDS kernel has two tile sizes and would pick the small one (or, for fp32, the register-staged kernel)
+    # the direct-to-LDS kernel has three tile shapes and would pick the small one (or, for fp32, the register-staged kernel)
     # for products this small: each is run; ("f32", "") is the library's own choice
     print(f"contraction {spec} {bx} {by} {dtype} tile {tile or 'default'}", flush=True)
-    contract = dict(kernel="dma", tile=int(tile)) if tile else None      # the direct-to-LDS kernel wherever the layout is eligible for it
+    contract = dict(kernel="dma", tile=tile_of(tile)) if tile else None      # the direct-to-LDS kernel wherever the layout is eligible for it
     x = HostTensor.from_f32(uniform_pm1(11, 0, int(np.prod(bx))).reshape(bx), dtype)
     y = HostTensor.from_f32(uniform_pm1(11, 1, int(np.prod(by))).reshape(by), dtype)
     w = single_vertex(spec, x, y, "f32")

@@ -2,13 +2,13 @@
 workgroups, so that every workgroup walks over several tiles: the next tile's addressing worked out under the
 current one, its first stages issued before the current tile's epilogue, the two alternating sets of Z offset
 tables.  The reduction is short (a stage or two per tile), which keeps the loop-nest oracle at a few seconds and
-makes the per-tile phases, not the main loop, what the launch consists of.  Every case runs under both tile sizes
+makes the per-tile phases, not the main loop, what the launch consists of.  Every case runs under all tile shapes
 of the direct-to-LDS kernel and is compared with the oracle at every element (Section 4.3 of the paper: the
 per-block kernel K over every join tuple, then the aggregation of the partial blocks)."""
 import numpy as np
 import pytest
 
-from tests._parity import RTOL_BF16, RTOL_F32, single_vertex, violations
+from tests._parity import RTOL_BF16, RTOL_F32, single_vertex, tile_of, violations
 from oracle.graph_ref import run_graph
 from synth_inputs.prng import HostTensor, uniform_pm1
 
@@ -34,7 +34,7 @@ CASES = [
 _last = {}                                                   # the oracle's result for the case that ran last (the tile size varies fastest)
 
 
-@pytest.mark.parametrize("tile", [128, 256])
+@pytest.mark.parametrize("tile", ["128", "256x128", "256"])
 @pytest.mark.parametrize("spec,bx,by,part,out_dtype", CASES)
 def test_bf16_contraction_with_several_tiles_per_workgroup(spec, bx, by, part, out_dtype, tile):
     import torch
@@ -49,17 +49,18 @@ def test_bf16_contraction_with_several_tiles_per_workgroup(spec, bx, by, part, o
         _last.clear()
         _last.update(key=key, ref=run_graph(w, {"X": x, "Y": y})["Z"].as_f64())
     ref = _last["ref"]
-    r = GraphRunner(w, "d", contract=dict(kernel="dma", tile=tile))
+    tm, tn = tile_of(tile)
+    r = GraphRunner(w, "d", contract=dict(kernel="dma", tile=(tm, tn)))
     try:
         r.bind({"X": to_device(x), "Y": to_device(y)})
         pl = r.plan("Z")
         assert pl["kernel"] == "contract_mfma"
         # the launch must have more tiles than the chip holds workgroups of this kernel (one per compute unit for
-        # the large tile, two for the small one), or the case does not test what it is here for
+        # the 256 x 256 tile, two for the others), or the case does not test what it is here for
         bz = pl["block_z"]                                   # Z is (b,) i, k in every case: batch entries, rows, columns of a block
-        tiles = pl["n_tuples"] * int(np.prod(bz[:-2])) * (-(-bz[-2] // tile)) * (-(-bz[-1] // tile))
+        tiles = pl["n_tuples"] * int(np.prod(bz[:-2])) * (-(-bz[-2] // tm)) * (-(-bz[-1] // tn))
         cus = torch.cuda.get_device_properties(0).multi_processor_count
-        assert tiles > (2 if tile == 128 else 1) * cus, (tiles, cus)
+        assert tiles > (1 if tile == "256" else 2) * cus, (tiles, cus)
         E.tr_profile_enable(r.g, 4)
         r.run()
         torch.cuda.synchronize()

@@ -7,7 +7,7 @@ import os
 import numpy as np
 import pytest
 
-from tests._parity import RTOL_BF16, RTOL_F32, single_vertex, violations
+from tests._parity import RTOL_BF16, RTOL_F32, single_vertex, tile_of, violations
 from oracle.graph_ref import run_graph
 from synth_inputs.prng import HostTensor, small_ints, uniform_pm1
 
@@ -198,10 +198,10 @@ def draw_large_contraction(seed):
     return spec, tuple(bound[l] for l in lx), tuple(bound[l] for l in ly), part, dt_in, dt_out
 
 
-@pytest.mark.parametrize("tile", ["", "256"])
+@pytest.mark.parametrize("tile", ["", "256x128", "256"])
 @pytest.mark.parametrize("seed", range(max(24, N_CASES // 20)))
 def test_random_large_contraction_matches_oracle(seed, tile):
-    contract = dict(tile=int(tile)) if tile else None        # the large-tile variant too, mostly padding at these sizes
+    contract = dict(tile=tile_of(tile)) if tile else None    # the larger tiles too, mostly padding at these sizes
     spec, bx, by, part, dt_in, dt_out = draw_large_contraction(seed)
     x = HostTensor.from_f32(uniform_pm1(1300 + seed, 0, int(np.prod(bx))).reshape(bx), dt_in)
     y = HostTensor.from_f32(uniform_pm1(1300 + seed, 1, int(np.prod(by))).reshape(by), dt_in)
