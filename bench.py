@@ -130,6 +130,7 @@ def main():
     ap.add_argument("--partitioning", default=None)
     ap.add_argument("--fuse-aggregation", action="store_true",
                     help="alternative method, reported separately: contractions reduce over partitioned contracted labels inside the kernel (no partial slabs, no aggregation launch)")
+    ap.add_argument("--contract-tile", default=None, help="for comparisons: output tile of the block-contraction kernel, e.g. 256x256, 256x128, 128 (default: the library chooses)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true")
     args = ap.parse_args()
@@ -146,7 +147,11 @@ def main():
     w = build_config(args.config)
     pname = args.partitioning or DEFAULT_PART[args.config]
     dev = {v.name: prng_torch.make_tensor(v.recipe, v.bound, v.dtype, w.seed, w.tensor_id(v.name)) for v in w.vertices if v.is_input}
-    r = GraphRunner(w, pname)
+    contract = None
+    if args.contract_tile:
+        t = [int(x) for x in args.contract_tile.split("x")]
+        contract = dict(tile=(t[0], t[-1]))
+    r = GraphRunner(w, pname, contract=contract)
     if args.fuse_aggregation:
         E.tr_set_fused_aggregation(r.g, True)
     r.bind(dev)
@@ -159,7 +164,7 @@ def main():
     runners = [r]
     if working_set < (512 << 20):
         for _ in range(2):
-            r2 = GraphRunner(w, pname)
+            r2 = GraphRunner(w, pname, contract=contract)
             if args.fuse_aggregation:
                 E.tr_set_fused_aggregation(r2.g, True)
             r2.bind({k: t.clone() for k, t in dev.items()})

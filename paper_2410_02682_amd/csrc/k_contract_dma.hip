@@ -222,11 +222,16 @@ struct TileInfo {
 // The kernel is persistent: the workgroups of a compute unit walk over their share of the tiles.  While a tile's
 // epilogue runs, the first two stages of the workgroup's next tile are already on their way into LDS, and the
 // next tile's addressing was worked out while the current tile waited for its own first stage.
-// LDS of one workgroup: two stages, two sets of Z offset tables, the waves' epilogue staging rows
-constexpr int lds_bytes(int TM, int TN, int KB, int NW) { return 2 * (TM + TN) * KB + 2 * (TM + TN) * 8 + NW * 8 * (32 * (TN / (NW / 2) / 32) * 4 + 32); }
+// LDS of one workgroup: the stages, two sets of Z offset tables, the waves' epilogue staging rows
+// (with three stages the staging rows lie in the third stage's buffer, which is free while an epilogue runs)
+constexpr int lds_bytes(int TM, int TN, int KB, int NW, int NS)
+{
+    return NS * (TM + TN) * KB + 2 * (TM + TN) * 8 + (NS == 2 ? NW * 8 * (32 * (TN / (NW / 2) / 32) * 4 + 32) : 0);
+}
 
-template <int TM, int TN, int KB, int NW, bool A_KC, bool B_KC, bool ODD, bool F32>
-__global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW) <= 160 * 1024 ? 2 : 1) void k_contract_dma(const ContractParams p)
+// NS: LDS stages (2 or 3); REM: the stage count modulo NS.
+template <int TM, int TN, int KB, int NS, int NW, bool A_KC, bool B_KC, int REM, bool F32>
+__global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW, NS) <= 160 * 1024 ? 2 : 1) void k_contract_dma(const ContractParams p)
 {
     constexpr int ES = Elem<F32>::ES, EPC = Elem<F32>::EPC, BK = KB / ES;
     constexpr int KS = KB / 32;                       // k-steps per stage (32 bytes of k each)
@@ -243,8 +248,11 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW) <= 160 * 102
     // and does not wait for them.
     __shared__ __attribute__((aligned(1024))) char lds0[STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) char lds1[STAGE_BYTES];
-    __shared__ __attribute__((aligned(16))) char ldsx[2 * TBL + NW * WBUF];    // two sets of Z offset tables + staging
-    static_assert(2 * STAGE_BYTES + 2 * TBL + NW * WBUF == lds_bytes(TM, TN, KB, NW), "lds_bytes() is what decides the workgroups per compute unit");
+    __shared__ __attribute__((aligned(1024))) char lds2[NS == 3 ? STAGE_BYTES : 16];
+    __shared__ __attribute__((aligned(16))) char ldsx[2 * TBL + (NS == 2 ? NW * WBUF : 0)];    // two sets of Z offset tables (+ staging)
+    static_assert(NS == 2 || (NS == 3 && KS == 2 && NW * WBUF <= STAGE_BYTES), "three stages: half-depth stages, staging rows fit one of them");
+    static_assert(REM >= 0 && REM < NS, "REM is the stage count modulo NS");
+    static_assert(NS * STAGE_BYTES + 2 * TBL + (NS == 2 ? NW * WBUF : 0) == lds_bytes(TM, TN, KB, NW, NS), "lds_bytes() is what decides the workgroups per compute unit");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int row0 = wm * (32 * RT), col0 = wn * (32 * NT);
@@ -435,6 +443,35 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW) <= 160 * 102
         }                                                                                         \
     } while (0)
 
+    // Three stages (two k-steps each): while stage s is computed, stage s+1 has landed or is landing and stage s+2 is in
+    // flight; the loads of stage s+3 go into s's buffer once every wave has its last fragments of s in registers.  A load
+    // has two full stages to arrive.  The wait before the barrier leaves the youngest stage's loads outstanding.
+#define EG_STAGE3(C, O, HAS_NEXT2, HAS_NEXT3)                                                     \
+    do {                                                                                          \
+        mfma_rows<0, 1, RT, NT, F32>(a0, b0, acc); EG_PIN();                                               \
+        const bool has2 = (HAS_NEXT3);      /* what EG_DMA_AFTER issues: stage s+3 into C */      \
+        next_stage(ga2, gb2, kr2);                                                                \
+        EG_FRAGS(C, 1, a1, b1); EG_PIN();                                                         \
+        mfma_rows<1, RT, RT, NT, F32>(a0, b0, acc); EG_PIN();                                               \
+        /* vmcnt(NLD): stage s+1 has landed, stage s+2 may still travel; lgkmcnt(0): this wave's reads of C have returned. */ \
+        /* A bare barrier: __syncthreads() would add a fence that waits for every outstanding load. */ \
+        if (HAS_NEXT2) __builtin_amdgcn_s_waitcnt(0x0070 | (NLD & 15) | ((NLD >> 4) << 14));      \
+        else __builtin_amdgcn_s_waitcnt(0x0070);                                                  \
+        __builtin_amdgcn_s_barrier();                                                             \
+        EG_PIN();                                                                                 \
+        _Pragma("unroll") for (int j = 0; j < NT; j++) {                                          \
+            mma<F32>(a1[0], b1[j], acc[0][j]); EG_PIN();                                          \
+            EG_DMA_AFTER(j, C)                                                                    \
+            EG_PIN();                                                                             \
+        }                                                                                         \
+        EG_FRAGS(O, 0, a0, b0); EG_PIN();                                                         \
+        _Pragma("unroll") for (int q = 0; q < (RT - 1) * NT; q++) {                               \
+            mma<F32>(a1[1 + q / NT], b1[q % NT], acc[1 + q / NT][q % NT]); EG_PIN();              \
+            EG_DMA_AFTER(NT + q, C)                                                               \
+            EG_PIN();                                                                             \
+        }                                                                                         \
+    } while (0)
+
     const bool out_bf16 = p.out.dtype == EG_BF16;
 
     tile_info(first, cur);
@@ -462,25 +499,47 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW) <= 160 * 102
             for (int j = 0; j < NT; j++)
 #pragma unroll
                 for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
-        __builtin_amdgcn_s_waitcnt(0x0F70);           // both stages (and the previous tile's stores) are done
+        __builtin_amdgcn_s_waitcnt(0x0F70);           // the first two stages (and the previous tile's stores) are done
         __syncthreads();
+        if constexpr (NS == 3) {
+            // the third buffer held the previous tile's staging rows until this barrier: its stage goes out now
+            next_stage(ga2, gb2, kr2);
+            if (nk > 2) {
+#pragma unroll
+                for (int i = 0; i < NLD; i++) dma(i, ga2, gb2, kr2, lds2);
+            }
+        }
         EG_FRAGS(lds0, 0, a0, b0);
         // Every stage, the last one included, runs the same straight-line code (the last one pays for one idle
         // barrier and a set of unused fragment reads): an MFMA under a branch inside the loop would make the
-        // compiler shuffle the accumulator registers.  The stage count's parity is a template parameter.
-        if (ODD) {
-            EG_STAGE_NEXT(lds0, lds1, 2 < nk);
-            for (int64_t st = 1; st < nk; st += 2) {
-                EG_STAGE_NEXT(lds1, lds0, st + 2 < nk);
-                EG_STAGE_NEXT(lds0, lds1, st + 3 < nk);
+        // compiler shuffle the accumulator registers.  The stage count modulo the number of buffers is a template parameter.
+        if constexpr (NS == 2) {
+            if (REM) {
+                EG_STAGE_NEXT(lds0, lds1, 2 < nk);
+                for (int64_t st = 1; st < nk; st += 2) {
+                    EG_STAGE_NEXT(lds1, lds0, st + 2 < nk);
+                    EG_STAGE_NEXT(lds0, lds1, st + 3 < nk);
+                }
+            } else {
+                for (int64_t st = 0; st < nk; st += 2) {
+                    EG_STAGE_NEXT(lds0, lds1, st + 2 < nk);
+                    EG_STAGE_NEXT(lds1, lds0, st + 3 < nk);
+                }
             }
         } else {
-            for (int64_t st = 0; st < nk; st += 2) {
-                EG_STAGE_NEXT(lds0, lds1, st + 2 < nk);
-                EG_STAGE_NEXT(lds1, lds0, st + 3 < nk);
+            int64_t st = 0;
+            for (; st + 3 <= nk; st += 3) {
+                EG_STAGE3(lds0, lds1, st + 2 < nk, st + 3 < nk);
+                EG_STAGE3(lds1, lds2, st + 3 < nk, st + 4 < nk);
+                EG_STAGE3(lds2, lds0, st + 4 < nk, st + 5 < nk);
             }
+            if constexpr (REM >= 1) EG_STAGE3(lds0, lds1, st + 2 < nk, false);
+            if constexpr (REM == 2) EG_STAGE3(lds1, lds2, false, false);
         }
-        __syncthreads();                              // every wave has left both stages
+        __syncthreads();                              // every wave has left the stages
+        // (three stages: the staging rows lie in a stage buffer the compiler has seen direct loads go into; all of those have
+        // landed, and saying so here keeps it from waiting again, for the next tile's loads too, in front of the staging)
+        if constexpr (NS == 3) __builtin_amdgcn_s_waitcnt(0x0F70);
         if (more) start_tile(nxt);                    // travels during the epilogue
 
         // ---- epilogue of the current tile -----------------------------------------------------------
@@ -491,7 +550,7 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW) <= 160 * 102
         int elane = lane;
         asm volatile("" : "+v"(elane));
         const int lrow = elane & 31, lhalf = elane >> 5;
-        char *wbuf = ldsx + 2 * TBL + wave_u * WBUF;   // this wave's staging rows
+        char *wbuf = (NS == 3 ? lds2 : ldsx + 2 * TBL) + wave_u * WBUF;   // this wave's staging rows
         const bool slab = p.out.slab_elems != 0;
         const int mrem = (int)(p.M - cur.m0 < TM ? p.M - cur.m0 : TM);     // rows / columns of the tile inside the block
         const int nrem = (int)(p.N - cur.n0 < TN ? p.N - cur.n0 : TN);
@@ -602,6 +661,7 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW) <= 160 * 102
         if (!more) break;
         cur = nxt;
     }
+#undef EG_STAGE3
 #undef EG_STAGE_NEXT
 #undef EG_DMA_AFTER
 #undef EG_KSTEP
@@ -609,29 +669,32 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW) <= 160 * 102
 #undef EG_PIN
 }
 
-template <int TM, int TN, int KB, int NW, bool A_KC, bool B_KC, bool ODD, bool F32>
+template <int TM, int TN, int KB, int NS, int NW, bool A_KC, bool B_KC, int REM, bool F32>
 static int launch_one(ContractParams &p, void *stream)
 {
-    hipLaunchKernelGGL((k_contract_dma<TM, TN, KB, NW, A_KC, B_KC, ODD, F32>), dim3((unsigned)p.grid), dim3(NW * 64), 0, (hipStream_t)stream, p);
+    hipLaunchKernelGGL((k_contract_dma<TM, TN, KB, NS, NW, A_KC, B_KC, REM, F32>), dim3((unsigned)p.grid), dim3(NW * 64), 0, (hipStream_t)stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(EG_ERR_HIP, "k_contract_dma launch failed: %s", hipGetErrorString(e));
     return EG_OK;
 }
 
-template <int TM, int TN, int KB, int NW, bool A_KC, bool B_KC, bool F32>
-static int launch_parity(ContractParams &p, void *stream)
+template <int TM, int TN, int KB, int NS, int NW, bool A_KC, bool B_KC, bool F32>
+static int launch_rem(ContractParams &p, void *stream)
 {
     constexpr int BK = KB / Elem<F32>::ES;
     const int64_t run = p.k.n == 1 ? p.K : p.k.ext[p.k.n - 1];
-    return (((p.K / run) * ((run + BK - 1) / BK)) & 1) ? launch_one<TM, TN, KB, NW, A_KC, B_KC, true, F32>(p, stream)
-                                                       : launch_one<TM, TN, KB, NW, A_KC, B_KC, false, F32>(p, stream);
+    const int rem = (int)(((p.K / run) * ((run + BK - 1) / BK)) % NS);
+    if (rem == 0) return launch_one<TM, TN, KB, NS, NW, A_KC, B_KC, 0, F32>(p, stream);
+    if (rem == 1) return launch_one<TM, TN, KB, NS, NW, A_KC, B_KC, 1, F32>(p, stream);
+    if constexpr (NS == 3) return launch_one<TM, TN, KB, NS, NW, A_KC, B_KC, 2, F32>(p, stream);
+    return fail(EG_ERR_LIMIT, "k_contract_dma: stage count");
 }
 
-template <int TM, int TN, int KB, int NW, bool F32>
+template <int TM, int TN, int KB, int NS, int NW, bool F32>
 static int launch_layout(ContractParams &p, void *stream)
 {
-    if (p.a_kcontig) return p.b_kcontig ? launch_parity<TM, TN, KB, NW, true, true, F32>(p, stream) : launch_parity<TM, TN, KB, NW, true, false, F32>(p, stream);
-    return p.b_kcontig ? launch_parity<TM, TN, KB, NW, false, true, F32>(p, stream) : launch_parity<TM, TN, KB, NW, false, false, F32>(p, stream);
+    if (p.a_kcontig) return p.b_kcontig ? launch_rem<TM, TN, KB, NS, NW, true, true, F32>(p, stream) : launch_rem<TM, TN, KB, NS, NW, true, false, F32>(p, stream);
+    return p.b_kcontig ? launch_rem<TM, TN, KB, NS, NW, false, true, F32>(p, stream) : launch_rem<TM, TN, KB, NS, NW, false, false, F32>(p, stream);
 }
 
 }  // namespace dma
@@ -689,19 +752,25 @@ int launch_contract_dma(ContractParams &p, void *stream)
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return fail(EG_ERR_HIP, "cannot query the device");
         n_cu = prop.multiProcessorCount > 8 ? prop.multiProcessorCount / 8 * 8 : 8;
     }
-    // Tile shape.  256 x 128 with two workgroups per compute unit is the kernel for bf16; 256 x 256 with one is the one for
-    // fp32.  128 x 128 tiles, two workgroups per unit, are taken when they are all resident at once, i.e. when larger
-    // tiles would leave at least half of the compute units without work (measured: 64 tiles of 256 x 256 ran 1.5-1.8x
-    // faster as 256 small ones; 160 of them 1.4x slower as 640 small ones, which need a second round), and when large
-    // tiles would be mostly padding (128 columns in a 256-wide tile).
+    // Tile shape.  256 x 256, one workgroup per compute unit, is the fastest per flop on long reductions (fewest bytes into LDS per
+    // flop, full 128-byte lines from operands contiguous along K).  256 x 128 with half-depth stages runs two workgroups per unit,
+    // one's per-tile phases under the other's MFMAs; its main loop is a fifth slower (64-byte requests for operands contiguous
+    // along K, a barrier every 16 MFMAs), so it is taken only where tiles are mostly per-tile work or where the wider tile would be
+    // padding: reductions of up to 128 elements (config 4's scores: 0.42 -> 0.38 ms) and blocks whose last 256 columns are at most
+    // half filled (config 4's P x V with 128 columns: 0.31 -> 0.30 ms).  128 x 128 tiles, two workgroups per unit, are taken
+    // when they are all resident at once, i.e. when larger tiles would leave at least half of the compute units without work
+    // (measured: 64 tiles of 256 x 256 ran 1.5-1.8x faster as 256 small ones; 160 of them 1.4x slower as 640 small ones, which
+    // need a second round).
     const bool f32 = p.in_dtype == EG_F32;
     const int64_t tuples = p.n_tuples * p.n_batch;
     auto count = [&](int tm, int tn) { return tuples * ((p.M + tm - 1) / tm) * ((p.N + tn - 1) / tn); };
-    const int64_t small = count(128, 128), large = count(256, 256);
+    const int64_t small = count(128, 128);
+    const int64_t ntail = p.N % 256;
     int tm, tn;
-    if (small <= 2 * n_cu || 4 * large * 10 > small * 14) tm = tn = 128;
-    else if (f32) tm = tn = 256;
-    else { tm = 256; tn = 128; }
+    if (small <= 2 * n_cu) tm = tn = 128;
+    else if (!f32 && (p.K <= 128 || (ntail > 0 && ntail <= 128 && p.N < 1024))) { tm = 256; tn = 128; }
+    else if (4 * count(256, 256) * 10 > small * 14) tm = tn = 128;
+    else tm = tn = 256;
     if (p.force_tile_m && p.force_tile_n) { tm = p.force_tile_m; tn = p.force_tile_n; }   // tr_set_contract_variant: comparisons and tests
     if (f32 && tm != tn) tn = tm;
     // the variant: stage depth and waves follow from the tile shape
@@ -712,7 +781,8 @@ int launch_contract_dma(ContractParams &p, void *stream)
     const int64_t wgs = tuples * p.tiles_m * p.tiles_n;
     if (wgs < 1 || wgs >= (1ll << 31)) return fail(EG_ERR_LIMIT, "contraction has %lld output tiles", (long long)wgs);
     // persistent workgroups: as many as fit the chip at once, a multiple of 8 so that every XCD gets the same number
-    const int64_t resident = (2 * dma::lds_bytes(tm, tn, kb, nw) <= 160 * 1024 ? 2 : 1) * (int64_t)n_cu;
+    const int ns = kb == 64 ? 3 : 2;
+    const int64_t resident = (2 * dma::lds_bytes(tm, tn, kb, nw, ns) <= 160 * 1024 ? 2 : 1) * (int64_t)n_cu;
     p.total_tiles = (int32_t)wgs;
     p.grid = (int32_t)(wgs < resident ? wgs : resident);
     // wide epilogue stores need Z contiguous along the innermost N label and every other Z offset a multiple of 8 elements
@@ -722,11 +792,11 @@ int launch_contract_dma(ContractParams &p, void *stream)
     for (int i = 0; i < p.batch.n; i++) vec = vec && p.batch.s2[i] % 8 == 0;
     for (int l = 0; l < p.ts.n; l++) vec = vec && p.ts.step_z[l] % 8 == 0;
     p.out_vec = vec ? 1 : 0;
-    if (f32) return tm == 128 ? dma::launch_layout<128, 128, 128, 4, true>(p, stream) : dma::launch_layout<256, 256, 128, 8, true>(p, stream);
-    if (tm == 128) return dma::launch_layout<128, 128, 128, 4, false>(p, stream);
-    if (tn == 128) return dma::launch_layout<256, 128, 64, 4, false>(p, stream);
-    if (nw == 4) return dma::launch_layout<256, 256, 128, 4, false>(p, stream);
-    return dma::launch_layout<256, 256, 128, 8, false>(p, stream);
+    if (f32) return tm == 128 ? dma::launch_layout<128, 128, 128, 2, 4, true>(p, stream) : dma::launch_layout<256, 256, 128, 2, 8, true>(p, stream);
+    if (tm == 128) return dma::launch_layout<128, 128, 128, 2, 4, false>(p, stream);
+    if (tn == 128) return dma::launch_layout<256, 128, 64, 3, 4, false>(p, stream);
+    if (nw == 4) return dma::launch_layout<256, 256, 128, 2, 4, false>(p, stream);
+    return dma::launch_layout<256, 256, 128, 2, 8, false>(p, stream);
 }
 
 }  // namespace eg
