@@ -27,9 +27,13 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E (datasheet)
 # multiply-add alone), and is counted as three operations (subtract, multiply, add)
 PEAK_ALU_TFLOPS = 256 * 4 * 16 * 2.4e9 * 3 / 1e12
 DEFAULT_PART = {1: "d222", 2: "mix", 3: "batch8", 4: "heads8", 5: "k16", 6: "splitn8", 7: "d222"}
-# HBM bytes per launch of the dominant kernel of the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
-# (see profiles/); None until measured for the chosen workload.
-MEASURED_TRAFFIC = {("c2", "mix"): 1690 * 2**20 + 512 * 2**20}   # contraction launch: 1690 MiB fetched (1617 on another box) + 512 MiB written
+# HBM-side bytes per launch (mean over the family's launches of a step) from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
+# file, scaled by what the same counters read for the plain 1 GiB copy kernel (see profiles/); a family that is not listed
+# reports null.  Keys: (workload, partitioning, kernel family).
+MEASURED_TRAFFIC = {
+    ("c2", "mix", "contract_mfma"): 1690 * 2**20 + 512 * 2**20,   # 1690 MiB fetched (1617 on another box) + 512 MiB written
+    ("c2", "mix", "aggregate"): 512 * 2**20 + 192 * 2**20,
+}
 
 
 def prod(xs):
@@ -68,7 +72,9 @@ def cpu_baseline(w, dev, budget_s=15.0):
     rows = int(max(r0, min(X.shape[0], r0 * budget_s / max(t, 1e-3))))
     t = run(rows)
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    from oracle import build as oracle_build
     return {"value": per_row * rows / t / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "build": "gcc " + " ".join(oracle_build.FLAGS) + " (oracle/einsum_ref.c as it stands; x86-64-v2 because the library is built on another machine than it is timed on)",
             "sample": f"vertex {v.name} '{v.spec}': {rows} of {X.shape[0]} outer rows at full reduction length "
                       f"(einsum_ref loop nest, double accumulation), {t:.1f} s"}
 
@@ -121,6 +127,112 @@ def ceilings():
     return out
 
 
+KERNEL_TEXT = {"contract_mfma": "k_contract_dma / k_contract (block contraction on MFMA, all tuples of a vertex per launch)",
+               "aggregate": "k_aggregate_vec4", "map": "k_map", "reduce_row": "k_reduce_row", "generic": "k_generic",
+               "contract_alu": "k_contract_alu (contraction-shaped vertex with another scalar function, vector ALU)",
+               "softmax_fused": "k_softmax_rows"}
+
+
+def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None):
+    """Times `steps` passes of one workload under one partitioning: (per-step ms, per-family kernel records, flops per step,
+    workload description, device inputs, the workload)."""
+    import torch
+    import paper_2410_02682_amd as E
+    from paper_2410_02682_amd.runner import GraphRunner
+    from synth_inputs import build_config, prng_torch
+
+    w = build_config(config)
+    dev = {v.name: prng_torch.make_tensor(v.recipe, v.bound, v.dtype, w.seed, w.tensor_id(v.name)) for v in w.vertices if v.is_input}
+    r = GraphRunner(w, pname, contract=contract, fuse_aggregation=True if fuse_aggregation else None)
+    r.bind(dev)
+    stream = torch.cuda.current_stream()
+    # A working set that the 256 MiB Infinity Cache could hold between steps is rotated over three copies (inputs,
+    # workspace and outputs), so that no step finds its operands left there by the previous one.
+    esz = {"f32": 4, "bf16": 2}
+    working_set = sum(prod(v.bound) * esz[v.dtype] for v in w.vertices if v.is_input) + r.workspace_bytes \
+        + sum(r.output(n).numel() * r.output(n).element_size() for n in r.out_names)
+    runners = [r]
+    if working_set < (512 << 20):
+        for _ in range(2):
+            r2 = GraphRunner(w, pname, contract=contract, fuse_aggregation=True if fuse_aggregation else None)
+            r2.bind({k: t.clone() for k, t in dev.items()})
+            runners.append(r2)
+    for i in range(warmup * len(runners)):
+        runners[i % len(runners)].run(stream)
+    torch.cuda.synchronize()
+
+    # per-vertex accounting: flops of contractions, algorithmic bytes of every launch
+    acct = {}
+    for v in w.einsum_vertices():
+        pl = r.plan(v.name)
+        nz = prod(pl["bound_z"])
+        in_bytes = sum(prod(w.vertex(i).bound if w.vertex(i).is_input else r.plan(i)["bound_z"]) * esz[w.vertex(i).dtype] for i in v.inputs)
+        acct[r.vid[v.name]] = {
+            "name": v.name, "kind": pl["kernel"], "nz": nz, "esz": esz[v.dtype], "in_bytes": in_bytes,
+            # a multiply-add per label combination on the matrix pipes; subtract, square (or magnitude), add (or max) on the vector ALU
+            "flops": {"contract_mfma": 2.0, "contract_alu": 3.0}.get(pl["kernel"], 0.0) * prod(pl["bound"]),
+            # a fused softmax pass is credited its own minimal traffic: one tensor of the result's shape in, the result out
+            "fused_bytes": nz * (esz[v.dtype] + esz[w.vertex(v.inputs[0]).dtype]),
+        }
+    # the event log is sized generously (the execution adds aggregation launches of its own to vertices whose reduction
+    # it cuts further, and runs a fused softmax chain as one launch); what was recorded is read back, never assumed
+    capacity = 4 * len(acct) * steps + 16
+    for q in runners:
+        E.tr_profile_enable(q.g, capacity)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        runners[i % len(runners)].run(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    rec = [x for q in runners for x in E.tr_profile_read(q.g)]        # vertex ids are the same in every copy
+    assert len(rec) % steps == 0 and all(len(E.tr_profile_read(q.g)) < capacity for q in runners), "launch log overflow"
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    flops_per_step = sum(a["flops"] for a in acct.values())
+
+    # aggregate the recorded launches by kernel family; bytes as the execution really ran them: a join launch reads its
+    # inputs and writes `slabs` fp32 partial slabs (or its tensor), an aggregation reads `slabs` slabs and writes the tensor
+    fam = {}
+    for x in rec:
+        a = acct[x["vertex"]]
+        key = "aggregate" if x["stage"] == "aggregate" else ("softmax_fused" if x["kernel"] == "softmax_fused" else x["kernel"])
+        f = fam.setdefault(key, {"ms": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0, "each": []})
+        f["each"].append(x["ms"])
+        f["ms"] += x["ms"]
+        f["launches"] += 1
+        if x["stage"] == "aggregate":
+            f["bytes"] += x["slabs"] * a["nz"] * 4 + a["nz"] * a["esz"]
+        elif key == "softmax_fused":
+            f["bytes"] += a["fused_bytes"]
+        else:
+            f["flops"] += a["flops"]
+            f["bytes"] += a["in_bytes"] + (x["slabs"] * a["nz"] * 4 if x["slabs"] else a["nz"] * a["esz"])
+    kernels = {}
+    for key, f in fam.items():
+        each = sorted(f["each"])
+        k = {"launches_per_step": f["launches"] / steps, "avg_launch_ms": f["ms"] / f["launches"],
+             "median_launch_ms": each[len(each) // 2], "min_launch_ms": each[0],
+             "share_of_step": f["ms"] / steps / ms_per_step}
+        if key == "contract_mfma":
+            k.update({"bound": "mfma", "achieved": f["flops"] / (f["ms"] * 1e-3) / 1e12,
+                      "peak": PEAK_F32_TFLOPS if config == 1 else PEAK_BF16_TFLOPS, "unit": "TFLOP/s"})
+        elif key == "contract_alu":
+            k.update({"bound": "alu", "achieved": f["flops"] / (f["ms"] * 1e-3) / 1e12, "peak": PEAK_ALU_TFLOPS, "unit": "TFLOP/s"})
+        else:
+            k.update({"bound": "hbm", "achieved": f["bytes"] / (f["ms"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"})
+        k["frac"] = k["achieved"] / k["peak"]
+        t = MEASURED_TRAFFIC.get((f"c{config}", pname, key))
+        k["traffic"] = t
+        kernels[key] = k
+    desc = f"{w.name} dims {json.dumps(w.dims)}, partitioning '{pname}': {json.dumps(r.part)}" \
+        + (" [alternative method: aggregation inside the contraction kernels]" if fuse_aggregation else "")
+    n_sets = len(runners)
+    for q in runners[1:]:
+        q.close()
+    r.close()
+    return ms_per_step, kernels, flops_per_step, desc, dev, w, n_sets
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -131,6 +243,7 @@ def main():
     ap.add_argument("--fuse-aggregation", action="store_true",
                     help="alternative method, reported separately: contractions reduce over partitioned contracted labels inside the kernel (no partial slabs, no aggregation launch)")
     ap.add_argument("--contract-tile", default=None, help="for comparisons: output tile of the block-contraction kernel, e.g. 256x256, 256x128, 128 (default: the library chooses)")
+    ap.add_argument("--no-other-workloads", action="store_true", help="skip the short runs of configs 3, 4 and 5 that follow the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true")
     args = ap.parse_args()
@@ -139,127 +252,47 @@ def main():
         sys.exit(2)
 
     import torch
-    import paper_2410_02682_amd as E
-    from paper_2410_02682_amd.runner import GraphRunner
-    from synth_inputs import build_config, prng_torch
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    w = build_config(args.config)
     pname = args.partitioning or DEFAULT_PART[args.config]
-    dev = {v.name: prng_torch.make_tensor(v.recipe, v.bound, v.dtype, w.seed, w.tensor_id(v.name)) for v in w.vertices if v.is_input}
     contract = None
     if args.contract_tile:
         t = [int(x) for x in args.contract_tile.split("x")]
         contract = dict(tile=(t[0], t[-1]))
-    r = GraphRunner(w, pname, contract=contract)
-    if args.fuse_aggregation:
-        E.tr_set_fused_aggregation(r.g, True)
-    r.bind(dev)
-    stream = torch.cuda.current_stream()
-    # A working set that the 256 MiB Infinity Cache could hold between steps is rotated over three copies (inputs,
-    # workspace and outputs), so that no step finds its operands left there by the previous one.
-    esz0 = {"f32": 4, "bf16": 2}
-    working_set = sum(prod(v.bound) * esz0[v.dtype] for v in w.vertices if v.is_input) + r.workspace_bytes \
-        + sum(r.output(n).numel() * r.output(n).element_size() for n in r.out_names)
-    runners = [r]
-    if working_set < (512 << 20):
-        for _ in range(2):
-            r2 = GraphRunner(w, pname, contract=contract)
-            if args.fuse_aggregation:
-                E.tr_set_fused_aggregation(r2.g, True)
-            r2.bind({k: t.clone() for k, t in dev.items()})
-            runners.append(r2)
-    for i in range(args.warmup * len(runners)):
-        runners[i % len(runners)].run(stream)
-    torch.cuda.synchronize()
-
-    # per-vertex accounting: flops of contractions, algorithmic bytes of every launch
-    esz = {"f32": 4, "bf16": 2}
-    acct = {}
-    launches_per_step = 0
-    for v in w.einsum_vertices():
-        pl = r.plan(v.name)
-        nz = prod(pl["bound_z"])
-        in_bytes = sum(prod(w.vertex(i).bound if w.vertex(i).is_input else r.plan(i)["bound_z"]) * esz[w.vertex(i).dtype] for i in v.inputs)
-        partial = pl["n_agg"] > 1 and not (args.fuse_aggregation and pl["kernel"] in ("contract_mfma", "contract_alu"))
-        join_out = pl["n_agg"] * nz * 4 if partial else nz * esz[v.dtype]
-        acct[r.vid[v.name]] = {
-            "name": v.name, "kind": pl["kernel"],
-            # a multiply-add per label combination on the matrix pipes; subtract, square (or magnitude), add (or max) on the vector ALU
-            "flops": {"contract_mfma": 2.0, "contract_alu": 3.0}.get(pl["kernel"], 0.0) * prod(pl["bound"]),
-            "join_bytes": in_bytes + join_out,
-            "agg_bytes": (pl["n_agg"] * nz * 4 + nz * esz[v.dtype]) if partial else 0,
-            # a fused softmax pass is credited its own minimal traffic: one tensor of the result's shape in, the result out
-            "fused_bytes": nz * (esz[v.dtype] + esz[w.vertex(v.inputs[0]).dtype]),
-        }
-        launches_per_step += 2 if partial else 1
-
-    for q in runners:
-        E.tr_profile_enable(q.g, launches_per_step * args.steps)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        runners[i % len(runners)].run(stream)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    rec = [x for q in runners for x in E.tr_profile_read(q.g)]        # vertex ids are the same in every copy
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    flops_per_step = sum(a["flops"] for a in acct.values())
+    ms_per_step, kernels, flops_per_step, desc, dev, w, n_sets = measure(args.config, pname, args.steps, args.warmup, args.fuse_aggregation, contract)
     value = flops_per_step / (ms_per_step * 1e-3) / 1e12
-
-    # aggregate the recorded launches by kernel family
-    fam = {}
-    for x in rec:
-        a = acct[x["vertex"]]
-        key = "aggregate" if x["stage"] == "aggregate" else ("softmax_fused" if x["kernel"] == "softmax_fused" else a["kind"])
-        f = fam.setdefault(key, {"ms": 0.0, "launches": 0, "flops": 0.0, "bytes": 0.0, "each": []})
-        f["each"].append(x["ms"])
-        f["ms"] += x["ms"]
-        f["launches"] += 1
-        if x["stage"] == "aggregate":
-            f["bytes"] += a["agg_bytes"]
-        else:
-            f["flops"] += a["flops"]
-            f["bytes"] += a["fused_bytes"] if key == "softmax_fused" else a["join_bytes"]
-    kernels = {}
-    for key, f in fam.items():
-        each = sorted(f["each"])
-        k = {"launches_per_step": f["launches"] // args.steps, "avg_launch_ms": f["ms"] / f["launches"],
-             "median_launch_ms": each[len(each) // 2], "min_launch_ms": each[0],
-             "share_of_step": f["ms"] / args.steps / ms_per_step}
-        if key == "contract_mfma":
-            k.update({"bound": "mfma", "achieved": f["flops"] / (f["ms"] * 1e-3) / 1e12,
-                      "peak": PEAK_F32_TFLOPS if args.config == 1 else PEAK_BF16_TFLOPS, "unit": "TFLOP/s"})
-        elif key == "contract_alu":
-            k.update({"bound": "alu", "achieved": f["flops"] / (f["ms"] * 1e-3) / 1e12, "peak": PEAK_ALU_TFLOPS, "unit": "TFLOP/s"})
-        else:
-            k.update({"bound": "hbm", "achieved": f["bytes"] / (f["ms"] * 1e-3) / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"})
-        k["frac"] = k["achieved"] / k["peak"]
-        kernels[key] = k
 
     dom = "contract_mfma" if "contract_mfma" in kernels else max(kernels, key=lambda k: kernels[k]["share_of_step"])
     if args.config == 7:
         dom = "contract_alu"
     roofline = dict(kernels[dom])
-    roofline["kernel"] = {"contract_mfma": "k_contract_dma / k_contract (block contraction on MFMA, all tuples of a vertex per launch)",
-                          "aggregate": "k_aggregate_vec4", "map": "k_map", "reduce_row": "k_reduce_row", "generic": "k_generic",
-                          "contract_alu": "k_contract_alu (contraction-shaped vertex with another scalar function, vector ALU)",
-                          "softmax_fused": "k_softmax_rows"}[dom]
-    roofline["traffic"] = MEASURED_TRAFFIC.get((f"c{args.config}", pname))
+    roofline["kernel"] = KERNEL_TEXT[dom]
     out = {"metric": "einsum-graph TFLOP/s (contractions) + GB/s (maps/aggregations), % of roofline", "value": value,
            "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32" if args.config == 1 else "bf16", "data": "synthetic",
-           "config": {"workload": f"{w.name} dims {json.dumps(w.dims)}, partitioning '{pname}': {json.dumps(r.part)}"
-                                  + (" [alternative method: aggregation inside the contraction kernels]" if args.fuse_aggregation else "")},
-           "roofline": roofline, "kernels": kernels, "buffer_sets": len(runners)}
-    for q in runners[1:]:
-        q.close()
-    r.close()
+           "config": {"workload": desc},
+           "roofline": roofline, "kernels": kernels, "buffer_sets": n_sets}
     if not args.no_ceilings:
         out["measured_ceilings"] = ceilings()
+        if dom == "contract_mfma" and args.config != 1:
+            # the rate a contraction on real data can be held against on this machine: the register-resident MFMA loop on random operands
+            out["roofline"]["frac_of_measured_mfma_ceiling"] = roofline["achieved"] / out["measured_ceilings"]["mfma_bf16_random_operands_tflops"]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, dev)
+    del dev
+    torch.cuda.empty_cache()
+    if not args.no_other_workloads and args.config == 2 and not args.fuse_aggregation and contract is None:
+        # the other full-size workloads, a few steps each, so that their kernel families are measured in the same run
+        others = {}
+        for c in (3, 4, 5):
+            ms, ks, fl, d, dv, _, _ = measure(c, DEFAULT_PART[c], 5, 2)
+            del dv
+            torch.cuda.empty_cache()
+            others[f"c{c}"] = {"workload": d, "ms_per_step": ms, "contraction_tflops_per_step": fl / (ms * 1e-3) / 1e12,
+                               "kernels": {k: {f: v[f] for f in ("launches_per_step", "avg_launch_ms", "bound", "achieved", "peak", "unit", "frac", "traffic")}
+                                           for k, v in ks.items()}}
+        out["other_workloads"] = others
     print(json.dumps(out))
 
 

@@ -264,6 +264,11 @@ int tr_profile_count(eg_graph *g);
  * synchronised the stream.  Host outputs, any may be NULL. */
 int tr_profile_get(eg_graph *g, int i, int *vertex, int *stage, int *kernel, float *ms);
 
+/* Recorded launch i: the number of fp32 partial slabs it wrote (a join kernel whose vertex has a partitioned aggregated
+ * label, or whose reduction the execution cut further) or read (an aggregation); 0 for a join kernel that wrote its
+ * vertex's tensor directly.  With the vertex's bound this gives the bytes the launch moved.  *slabs: host. */
+int tr_profile_get_slabs(eg_graph *g, int i, int64_t *slabs);
+
 /* ---- Choosing the partitioning vectors: EinDecomp (Sections 6-8 of the paper) ------------------------------
  *
  * Host-only integer code.  A cost is an upper bound on the floating point numbers that would travel between

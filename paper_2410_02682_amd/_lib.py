@@ -62,6 +62,7 @@ EXPORTS = {
     "tr_profile_count": (ctypes.c_int, [ctypes.c_void_p]),
     "tr_profile_get": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int),
                                       ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float)]),
+    "tr_profile_get_slabs": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]),
     "eg_cost_join": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, c_i32p, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]),
     "eg_cost_agg": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, c_i32p, ctypes.c_int, ctypes.POINTER(ctypes.c_int64)]),
     "eg_cost_repart": (ctypes.c_int, [ctypes.c_int, c_i64p, c_i32p, c_i32p, ctypes.POINTER(ctypes.c_int64)]),

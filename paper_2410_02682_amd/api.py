@@ -216,7 +216,10 @@ def tr_profile_read(g) -> List[dict]:
     for i in range(n):
         v, s, k, ms = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_float()
         _check(lib.tr_profile_get(g, i, ctypes.byref(v), ctypes.byref(s), ctypes.byref(k), ctypes.byref(ms)))
-        out.append(dict(vertex=v.value, stage="join" if s.value == 0 else "aggregate", kernel=KERNEL_NAMES[k.value], ms=ms.value))
+        slabs = ctypes.c_int64()
+        _check(lib.tr_profile_get_slabs(g, i, ctypes.byref(slabs)))
+        out.append(dict(vertex=v.value, stage="join" if s.value == 0 else "aggregate", kernel=KERNEL_NAMES[k.value], ms=ms.value,
+                        slabs=slabs.value))
     return out
 
 

@@ -1113,7 +1113,7 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
         steps.push_back(std::move(s));
     }
     hipStream_t st = (hipStream_t)hip_stream;
-    auto timed = [&](int vertex, int stage, int kernel, auto &&fn) -> int {
+    auto timed = [&](int vertex, int stage, int kernel, int64_t slabs, auto &&fn) -> int {
         const size_t idx = g->launches.size();
         const bool rec = g->profile && idx < g->ev_start.size();
         if (rec && hipEventRecord((hipEvent_t)g->ev_start[idx], st) != hipSuccess) return fail(EG_ERR_HIP, "hipEventRecord failed");
@@ -1121,17 +1121,17 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
         if (rc) return rc;
         if (rec) {
             if (hipEventRecord((hipEvent_t)g->ev_stop[idx], st) != hipSuccess) return fail(EG_ERR_HIP, "hipEventRecord failed");
-            g->launches.push_back({vertex, stage, kernel});
+            g->launches.push_back({vertex, stage, kernel, slabs});
         }
         return EG_OK;
     };
     for (Step &s : steps) {
         const Vertex &v = g->v[s.vertex];
-        int rc = s.fused ? timed(s.vertex, 0, EG_KERNEL_SOFTMAX_FUSED, [&] { return launch_softmax_rows(s.sp, hip_stream); })
-                         : timed(s.vertex, 0, s.r.kind, [&] { return launch_routed(s.r, hip_stream); });
+        int rc = s.fused ? timed(s.vertex, 0, EG_KERNEL_SOFTMAX_FUSED, 0, [&] { return launch_softmax_rows(s.sp, hip_stream); })
+                         : timed(s.vertex, 0, s.r.kind, s.agg ? s.slabs : 0, [&] { return launch_routed(s.r, hip_stream); });
         if (rc) return rc;
         if (s.agg) {
-            rc = timed(s.vertex, 1, EG_KERNEL_NONE, [&] {
+            rc = timed(s.vertex, 1, EG_KERNEL_NONE, s.slabs, [&] {
                 return aggregate_into(v.oplus, s.partials, s.slabs, numel(v.bound), s.stride, s.dst, v.dtype, v.bound, s.dst_stride, hip_stream);
             });
             if (rc) return rc;
@@ -1141,6 +1141,14 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
 }
 
 extern "C" {
+
+int tr_profile_get_slabs(eg_graph *g, int i, int64_t *slabs)
+{
+    if (!g || !slabs) return fail(EG_ERR_NULL, "tr_profile_get_slabs: NULL argument");
+    if (!g->profile || i < 0 || i >= (int)g->launches.size()) return fail(EG_ERR_BAD_VERTEX, "no recorded launch %d", i);
+    *slabs = g->launches[i].slabs;
+    return EG_OK;
+}
 
 int tr_execute(eg_graph *g, eg_relation *const *inputs, int n_inputs, eg_relation *const *outputs, int n_outputs,
                void *workspace, size_t workspace_bytes, void *hip_stream)

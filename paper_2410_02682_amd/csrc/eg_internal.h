@@ -214,7 +214,7 @@ struct eg_graph {
     int contract_kernel = 0, contract_tile_m = 0, contract_tile_n = 0, contract_waves = 0;   // tr_set_contract_variant (0: the launchers choose)
     bool profile = false;
     std::vector<void *> ev_start, ev_stop;          // hipEvent_t pool
-    struct Launch { int vertex, stage, kernel; };
+    struct Launch { int vertex, stage, kernel; int64_t slabs; };   // slabs: partial slabs the launch wrote (join) or read (aggregation); 0 = none
     std::vector<Launch> launches;                   // of the last tr_execute
 };
 
