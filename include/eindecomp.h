@@ -18,8 +18,12 @@
  *     stream always belong to the caller; the library never allocates, frees or
  *     synchronises device memory.  Handles (eg_graph, eg_relation) own host
  *     memory only and are released by their *_destroy call.
- *   - All validation happens on the host before any launch: a failing call
- *     leaves device memory untouched.
+ *   - All validation happens on the host before any launch: tr_execute routes
+ *     every vertex and runs every kernel launcher's checks (shapes, limits,
+ *     grid sizes) once without launching before it enqueues anything, so a
+ *     call that fails for such a reason leaves device memory untouched.  Only
+ *     an error of the HIP runtime at an actual launch (EG_ERR_HIP) can occur
+ *     after earlier vertices have been enqueued.
  *   - Tensors are dense with element strides (row-major unless strides are
  *     given).  A block of a relation is a strided view into that buffer, so
  *     partitioning and repartitioning move no data.

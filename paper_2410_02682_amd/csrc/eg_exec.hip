@@ -1054,6 +1054,7 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
             sp.n = (int32_t)li.ext[r - 1];
             sp.sx_last = li.sx[r - 1]; sp.sy_last = li.sy[r - 1]; sp.sz_last = li.sz[r - 1];
             sp.dt_src = src.dtype; sp.dt_e = E.dtype; sp.dt_p = res.dtype;
+            sp.dt_max = g->v[f.vmax].dtype; sp.dt_sum = g->v[f.vsum].dtype;     // the statistics are rounded as their vertices store them, written or not
             if (!sp.has_add) sp.dt_t = src.dtype;
             sp.src = src.ptr; sp.p = (void *)res.ptr;
             sp.n_tuples = P.plan.n_tuples;
@@ -1125,6 +1126,20 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
         }
         return EG_OK;
     };
+    // every launcher once without launching: limits that only show when the grid is sized (tile counts, row lengths,
+    // 32-bit grid bounds, kernel attributes) are found before anything has been enqueued
+    {
+        struct Guard { Guard() { set_validate_only(true); } ~Guard() { set_validate_only(false); } } guard;
+        for (Step &s : steps) {
+            const Vertex &v = g->v[s.vertex];
+            int rc = s.fused ? launch_softmax_rows(s.sp, hip_stream) : launch_routed(s.r, hip_stream);
+            if (rc) return rc;
+            if (s.agg) {
+                rc = aggregate_into(v.oplus, s.partials, s.slabs, numel(v.bound), s.stride, s.dst, v.dtype, v.bound, s.dst_stride, hip_stream);
+                if (rc) return rc;
+            }
+        }
+    }
     for (Step &s : steps) {
         const Vertex &v = g->v[s.vertex];
         int rc = s.fused ? timed(s.vertex, 0, EG_KERNEL_SOFTMAX_FUSED, 0, [&] { return launch_softmax_rows(s.sp, hip_stream); })

@@ -24,6 +24,10 @@ int fail(int code, const char *fmt, ...)
     return code;
 }
 
+static thread_local bool g_validate_only = false;
+bool validate_only() { return g_validate_only; }
+void set_validate_only(bool on) { g_validate_only = on; }
+
 // Parses "ij,jk->ik" / "ij->i" / "bc,bc->" into label characters per operand.
 static int parse_spec(const char *spec, std::string &sx, std::string &sy, std::string &sz, bool &binary)
 {

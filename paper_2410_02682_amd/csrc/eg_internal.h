@@ -163,6 +163,12 @@ struct AggregateParams {          // out[e] = oplus_a partials[a][e], ascending 
     StridedDims dims;             // out's index space (sz = out strides), used when not contiguous
 };
 
+// tr_execute runs every launcher twice: first with this thread-local flag set, so that each one makes all its checks
+// and grid computations but enqueues nothing (an error then leaves device memory untouched), then for real.
+bool validate_only();
+void set_validate_only(bool on);
+#define EG_LAUNCH(...) do { if (!eg::validate_only()) hipLaunchKernelGGL(__VA_ARGS__); } while (0)
+
 // launchers (defined in the .hip files); each validates what its kernel assumes and returns eg_status
 int launch_contract(ContractParams &p, void *stream);
 int launch_contract_dma(ContractParams &p, void *stream);     // bf16, direct global->LDS staging; see k_contract_dma.hip

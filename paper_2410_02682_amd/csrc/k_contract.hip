@@ -440,7 +440,7 @@ static int launch_alu(ContractParams &p, void *stream)
             return fail(EG_ERR_HIP, "cannot reserve %d bytes of LDS", C::LDS_A + C::LDS_B);
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_contract_alu<C, OT, OP>), dim3((unsigned)wgs), dim3(C::THREADS), C::LDS_A + C::LDS_B, (hipStream_t)stream, p);
+    EG_LAUNCH((k_contract_alu<C, OT, OP>), dim3((unsigned)wgs), dim3(C::THREADS), C::LDS_A + C::LDS_B, (hipStream_t)stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(EG_ERR_HIP, "k_contract_alu launch failed: %s", hipGetErrorString(e));
     return EG_OK;
@@ -468,7 +468,7 @@ static int launch_cfg(ContractParams &p, void *stream)
             return fail(EG_ERR_HIP, "cannot reserve %d bytes of LDS", C::LDS_BYTES);
         attr_set = true;
     }
-    hipLaunchKernelGGL(k_contract<C>, dim3((unsigned)wgs), dim3(C::THREADS), C::LDS_BYTES, (hipStream_t)stream, p);
+    EG_LAUNCH(k_contract<C>, dim3((unsigned)wgs), dim3(C::THREADS), C::LDS_BYTES, (hipStream_t)stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(EG_ERR_HIP, "k_contract launch failed: %s", hipGetErrorString(e));
     return EG_OK;

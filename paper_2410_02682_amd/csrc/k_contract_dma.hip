@@ -672,7 +672,7 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW, NS) <= 160 *
 template <int TM, int TN, int KB, int NS, int NW, bool A_KC, bool B_KC, int REM, bool F32>
 static int launch_one(ContractParams &p, void *stream)
 {
-    hipLaunchKernelGGL((k_contract_dma<TM, TN, KB, NS, NW, A_KC, B_KC, REM, F32>), dim3((unsigned)p.grid), dim3(NW * 64), 0, (hipStream_t)stream, p);
+    EG_LAUNCH((k_contract_dma<TM, TN, KB, NS, NW, A_KC, B_KC, REM, F32>), dim3((unsigned)p.grid), dim3(NW * 64), 0, (hipStream_t)stream, p);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(EG_ERR_HIP, "k_contract_dma launch failed: %s", hipGetErrorString(e));
     return EG_OK;

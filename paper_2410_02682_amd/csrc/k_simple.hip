@@ -647,7 +647,7 @@ int launch_generic(const GenericParams &p, void *stream)
     unsigned grid;
     int rc = grid_for(p.n_tuples * p.outs_per_block, kThreads, grid);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_generic, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, p);
+    EG_LAUNCH(k_generic, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, p);
     return check_launch("k_generic");
 }
 
@@ -668,15 +668,15 @@ template <int OP>
 static void launch_map_vec(const MapParams &p, dim3 grid, hipStream_t st)
 {
     const bool fast = p.out.dtype == EG_BF16;     // hardware exponential only where the result is rounded to bf16
-    if (fast) hipLaunchKernelGGL((k_map<8, OP, true>), grid, dim3(kThreads), 0, st, p);
-    else hipLaunchKernelGGL((k_map<8, OP, false>), grid, dim3(kThreads), 0, st, p);
+    if (fast) EG_LAUNCH((k_map<8, OP, true>), grid, dim3(kThreads), 0, st, p);
+    else EG_LAUNCH((k_map<8, OP, false>), grid, dim3(kThreads), 0, st, p);
 }
 
 template <int OP>
 static void launch_map_tr(const MapParams &p, dim3 grid, hipStream_t st)
 {
-    if (p.out.dtype == EG_BF16) hipLaunchKernelGGL((k_map_tr<OP, true>), grid, dim3(kThreads), 0, st, p);
-    else hipLaunchKernelGGL((k_map_tr<OP, false>), grid, dim3(kThreads), 0, st, p);
+    if (p.out.dtype == EG_BF16) EG_LAUNCH((k_map_tr<OP, true>), grid, dim3(kThreads), 0, st, p);
+    else EG_LAUNCH((k_map_tr<OP, false>), grid, dim3(kThreads), 0, st, p);
 }
 
 int launch_map(const MapParams &p, void *stream)
@@ -708,7 +708,7 @@ int launch_map(const MapParams &p, void *stream)
     int rc = tuple_grid(p.vecs_per_block, kThreads, p.n_tuples, grid);
     if (rc) return rc;
     if (p.vec == 1) {
-        hipLaunchKernelGGL((k_map<1, -1, false>), grid, dim3(kThreads), 0, st, p);
+        EG_LAUNCH((k_map<1, -1, false>), grid, dim3(kThreads), 0, st, p);
         return check_launch("k_map");
     }
     switch (p.otimes) {
@@ -725,20 +725,20 @@ int launch_map(const MapParams &p, void *stream)
 template <int LANES, int R>
 static void launch_reduce_short(const ReduceParams &p, dim3 grid, hipStream_t st)
 {
-    if (p.otimes == EG_IDENT && p.oplus == EG_AGG_MAX) hipLaunchKernelGGL((k_reduce_short<LANES, EG_IDENT, EG_AGG_MAX, R>), grid, dim3(kThreads), 0, st, p);
-    else if (p.otimes == EG_IDENT && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_short<LANES, EG_IDENT, EG_AGG_SUM, R>), grid, dim3(kThreads), 0, st, p);
-    else if (p.otimes == EG_MUL && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_short<LANES, EG_MUL, EG_AGG_SUM, R>), grid, dim3(kThreads), 0, st, p);
-    else hipLaunchKernelGGL((k_reduce_short<LANES, -1, -1, R>), grid, dim3(kThreads), 0, st, p);
+    if (p.otimes == EG_IDENT && p.oplus == EG_AGG_MAX) EG_LAUNCH((k_reduce_short<LANES, EG_IDENT, EG_AGG_MAX, R>), grid, dim3(kThreads), 0, st, p);
+    else if (p.otimes == EG_IDENT && p.oplus == EG_AGG_SUM) EG_LAUNCH((k_reduce_short<LANES, EG_IDENT, EG_AGG_SUM, R>), grid, dim3(kThreads), 0, st, p);
+    else if (p.otimes == EG_MUL && p.oplus == EG_AGG_SUM) EG_LAUNCH((k_reduce_short<LANES, EG_MUL, EG_AGG_SUM, R>), grid, dim3(kThreads), 0, st, p);
+    else EG_LAUNCH((k_reduce_short<LANES, -1, -1, R>), grid, dim3(kThreads), 0, st, p);
 }
 
 template <int LANES, int VEC, int U>
 static void launch_reduce_ops(const ReduceParams &p, dim3 grid, hipStream_t st)
 {
     // the common (x)/(+) pairs are compiled in; anything else reads them at run time
-    if (p.otimes == EG_IDENT && p.oplus == EG_AGG_MAX) hipLaunchKernelGGL((k_reduce_row<LANES, VEC, EG_IDENT, EG_AGG_MAX, U>), grid, dim3(kThreads), 0, st, p);
-    else if (p.otimes == EG_IDENT && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_row<LANES, VEC, EG_IDENT, EG_AGG_SUM, U>), grid, dim3(kThreads), 0, st, p);
-    else if (p.otimes == EG_MUL && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_row<LANES, VEC, EG_MUL, EG_AGG_SUM, U>), grid, dim3(kThreads), 0, st, p);
-    else hipLaunchKernelGGL((k_reduce_row<LANES, VEC, -1, -1, U>), grid, dim3(kThreads), 0, st, p);
+    if (p.otimes == EG_IDENT && p.oplus == EG_AGG_MAX) EG_LAUNCH((k_reduce_row<LANES, VEC, EG_IDENT, EG_AGG_MAX, U>), grid, dim3(kThreads), 0, st, p);
+    else if (p.otimes == EG_IDENT && p.oplus == EG_AGG_SUM) EG_LAUNCH((k_reduce_row<LANES, VEC, EG_IDENT, EG_AGG_SUM, U>), grid, dim3(kThreads), 0, st, p);
+    else if (p.otimes == EG_MUL && p.oplus == EG_AGG_SUM) EG_LAUNCH((k_reduce_row<LANES, VEC, EG_MUL, EG_AGG_SUM, U>), grid, dim3(kThreads), 0, st, p);
+    else EG_LAUNCH((k_reduce_row<LANES, VEC, -1, -1, U>), grid, dim3(kThreads), 0, st, p);
 }
 
 int launch_reduce_row(const ReduceParams &p, void *stream)
@@ -755,10 +755,10 @@ int launch_reduce_row(const ReduceParams &p, void *stream)
         dim3 grid;
         int rc = tuple_grid((p.outs_per_block / 8 + kColStrip - 1) / kColStrip * p.split, 1, p.n_tuples, grid);
         if (rc) return rc;
-        if (p.otimes == EG_IDENT && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_col<EG_IDENT, EG_AGG_SUM>), grid, dim3(kThreads), 0, st, p);
-        else if (p.otimes == EG_IDENT && p.oplus == EG_AGG_MAX) hipLaunchKernelGGL((k_reduce_col<EG_IDENT, EG_AGG_MAX>), grid, dim3(kThreads), 0, st, p);
-        else if (p.otimes == EG_MUL && p.oplus == EG_AGG_SUM) hipLaunchKernelGGL((k_reduce_col<EG_MUL, EG_AGG_SUM>), grid, dim3(kThreads), 0, st, p);
-        else hipLaunchKernelGGL((k_reduce_col<-1, -1>), grid, dim3(kThreads), 0, st, p);
+        if (p.otimes == EG_IDENT && p.oplus == EG_AGG_SUM) EG_LAUNCH((k_reduce_col<EG_IDENT, EG_AGG_SUM>), grid, dim3(kThreads), 0, st, p);
+        else if (p.otimes == EG_IDENT && p.oplus == EG_AGG_MAX) EG_LAUNCH((k_reduce_col<EG_IDENT, EG_AGG_MAX>), grid, dim3(kThreads), 0, st, p);
+        else if (p.otimes == EG_MUL && p.oplus == EG_AGG_SUM) EG_LAUNCH((k_reduce_col<EG_MUL, EG_AGG_SUM>), grid, dim3(kThreads), 0, st, p);
+        else EG_LAUNCH((k_reduce_col<-1, -1>), grid, dim3(kThreads), 0, st, p);
         return check_launch("k_reduce_col");
     }
     const int64_t slots = p.outs_per_block * p.split;
@@ -804,7 +804,7 @@ int launch_aggregate(const AggregateParams &p, void *stream)
                      ((uintptr_t)p.out & 15) == 0;
     unsigned grid;
     if (p.n_agg >= 32 && p.slab_elems <= 4096) {                    // too few outputs for one lane per output to hide the loads
-        hipLaunchKernelGGL(k_aggregate_wave, dim3((unsigned)p.slab_elems), dim3(64), 0, (hipStream_t)stream, p);
+        EG_LAUNCH(k_aggregate_wave, dim3((unsigned)p.slab_elems), dim3(64), 0, (hipStream_t)stream, p);
         return check_launch("k_aggregate");
     }
     int rc = grid_for(vec ? p.slab_elems / 4 : p.slab_elems, kThreads, grid);
@@ -812,13 +812,13 @@ int launch_aggregate(const AggregateParams &p, void *stream)
     if (vec) {
         hipStream_t st = (hipStream_t)stream;
         switch (p.n_agg) {
-        case 2: hipLaunchKernelGGL(k_aggregate_vec4<2>, dim3(grid), dim3(kThreads), 0, st, p); break;
-        case 4: hipLaunchKernelGGL(k_aggregate_vec4<4>, dim3(grid), dim3(kThreads), 0, st, p); break;
-        case 8: hipLaunchKernelGGL(k_aggregate_vec4<8>, dim3(grid), dim3(kThreads), 0, st, p); break;
-        case 16: hipLaunchKernelGGL(k_aggregate_vec4<16>, dim3(grid), dim3(kThreads), 0, st, p); break;
-        default: hipLaunchKernelGGL(k_aggregate_vec4<0>, dim3(grid), dim3(kThreads), 0, st, p); break;
+        case 2: EG_LAUNCH(k_aggregate_vec4<2>, dim3(grid), dim3(kThreads), 0, st, p); break;
+        case 4: EG_LAUNCH(k_aggregate_vec4<4>, dim3(grid), dim3(kThreads), 0, st, p); break;
+        case 8: EG_LAUNCH(k_aggregate_vec4<8>, dim3(grid), dim3(kThreads), 0, st, p); break;
+        case 16: EG_LAUNCH(k_aggregate_vec4<16>, dim3(grid), dim3(kThreads), 0, st, p); break;
+        default: EG_LAUNCH(k_aggregate_vec4<0>, dim3(grid), dim3(kThreads), 0, st, p); break;
         }
-    } else hipLaunchKernelGGL(k_aggregate_scalar, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, p);
+    } else EG_LAUNCH(k_aggregate_scalar, dim3(grid), dim3(kThreads), 0, (hipStream_t)stream, p);
     return check_launch("k_aggregate");
 }
 
@@ -900,7 +900,7 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p
             for (int i = 0; i < 8; i++) m = fmaxf(m, v[u][i]);
         }
     }
-    m = wave_reduce<EG_AGG_MAX>(EG_AGG_MAX, m);
+    m = round_as(wave_reduce<EG_AGG_MAX>(EG_AGG_MAX, m), p.dt_max);       // the exponentials see the maximum as its vertex stores it
     const bool fast_e = dt_e == EG_BF16, fast_p = dt_p == EG_BF16;         // as the separate vertices choose
     const float neg_m_log2e = -(m * kLog2e);
     float sum = 0.f;
@@ -917,7 +917,7 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p
             for (int i = 0; i < 8; i++) sum += v[u][i];
         }
     }
-    sum = wave_reduce<EG_AGG_SUM>(EG_AGG_SUM, sum);
+    sum = round_as(wave_reduce<EG_AGG_SUM>(EG_AGG_SUM, sum), p.dt_sum);   // ... and the division the sum as its vertex stores it
     const float inv = __frcp_rn(sum);
 #pragma unroll
     for (int u = 0; u < VPL; u++) {
@@ -965,7 +965,7 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows_scalar(const SoftmaxP
         buf[c] = x;
         m = fmaxf(m, x);
     }
-    m = block_reduce(m, EG_AGG_MAX, red);
+    m = round_as(block_reduce(m, EG_AGG_MAX, red), p.dt_max);
     const bool fast_e = p.dt_e == EG_BF16, fast_p = p.dt_p == EG_BF16;
     float sum = 0.f;
     for (int c = threadIdx.x; c < p.n; c += kThreads) {
@@ -973,7 +973,7 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows_scalar(const SoftmaxP
         buf[c] = e;
         sum += e;
     }
-    sum = block_reduce(sum, EG_AGG_SUM, red);
+    sum = round_as(block_reduce(sum, EG_AGG_SUM, red), p.dt_sum);
     const float inv = __frcp_rn(sum);
     for (int c = threadIdx.x; c < p.n; c += kThreads) store_elem(p.p, p.dt_p, oz + c * p.sz_last, fast_p ? buf[c] * inv : buf[c] / sum);
     if (threadIdx.x == 0) {
@@ -1007,7 +1007,7 @@ int launch_softmax_rows(SoftmaxParams &p, void *stream)
     if (!vec) {
         int rc = tuple_grid(p.rows_per_block, 1, p.n_tuples, grid);
         if (rc) return rc;
-        hipLaunchKernelGGL(k_softmax_rows_scalar, grid, dim3(kThreads), 0, st, p);
+        EG_LAUNCH(k_softmax_rows_scalar, grid, dim3(kThreads), 0, st, p);
         return check_launch("k_softmax_rows_scalar");
     }
     int rc = tuple_grid(p.rows_per_block, kThreads / 64, p.n_tuples, grid);
@@ -1016,9 +1016,9 @@ int launch_softmax_rows(SoftmaxParams &p, void *stream)
     const bool all_bf16 = p.dt_src == EG_BF16 && p.dt_t == EG_BF16 && p.dt_e == EG_BF16 && p.dt_p == EG_BF16;
     const bool all_f32 = p.dt_src == EG_F32 && p.dt_t == EG_F32 && p.dt_e == EG_F32 && p.dt_p == EG_F32;
     const int mode = all_bf16 ? 0 : all_f32 ? 1 : 2;
-#define EG_SM(V) do { if (mode == 0) hipLaunchKernelGGL((k_softmax_rows<V, 0>), grid, dim3(kThreads), 0, st, p); \
-                      else if (mode == 1) hipLaunchKernelGGL((k_softmax_rows<V, 1>), grid, dim3(kThreads), 0, st, p); \
-                      else hipLaunchKernelGGL((k_softmax_rows<V, 2>), grid, dim3(kThreads), 0, st, p); } while (0)
+#define EG_SM(V) do { if (mode == 0) EG_LAUNCH((k_softmax_rows<V, 0>), grid, dim3(kThreads), 0, st, p); \
+                      else if (mode == 1) EG_LAUNCH((k_softmax_rows<V, 1>), grid, dim3(kThreads), 0, st, p); \
+                      else EG_LAUNCH((k_softmax_rows<V, 2>), grid, dim3(kThreads), 0, st, p); } while (0)
     if (vpl <= 1) EG_SM(1);
     else if (vpl <= 2) EG_SM(2);
     else if (vpl <= 4) EG_SM(4);
