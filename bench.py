@@ -254,6 +254,7 @@ def main():
     ap.add_argument("--fuse-aggregation", action="store_true",
                     help="alternative method, reported separately: contractions reduce over partitioned contracted labels inside the kernel (no partial slabs, no aggregation launch)")
     ap.add_argument("--contract-tile", default=None, help="for comparisons: output tile of the block-contraction kernel, e.g. 256x256, 256x128, 128 (default: the library chooses)")
+    ap.add_argument("--contract-waves", type=int, default=0, help="for comparisons: 4 or 8 waves per workgroup of the 256 x 256 tile")
     ap.add_argument("--no-other-workloads", action="store_true", help="skip the short runs of configs 3, 4 and 5 that follow the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true")
@@ -269,7 +270,7 @@ def main():
     contract = None
     if args.contract_tile:
         t = [int(x) for x in args.contract_tile.split("x")]
-        contract = dict(tile=(t[0], t[-1]))
+        contract = dict(tile=(t[0], t[-1]), waves=args.contract_waves)
     ms_per_step, kernels, flops_per_step, desc, dev, w, n_sets = measure(args.config, pname, args.steps, args.warmup, args.fuse_aggregation, contract)
     value = flops_per_step / (ms_per_step * 1e-3) / 1e12
 
