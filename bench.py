@@ -141,10 +141,11 @@ def ceilings():
 KERNEL_TEXT = {"contract_mfma": "k_contract_dma / k_contract (block contraction on MFMA, all tuples of a vertex per launch)",
                "aggregate": "k_aggregate_vec4", "map": "k_map", "reduce_row": "k_reduce_row", "generic": "k_generic",
                "contract_alu": "k_contract_alu (contraction-shaped vertex with another scalar function, vector ALU)",
-               "softmax_fused": "k_softmax_rows"}
+               "softmax_fused": "k_softmax_rows",
+               "attention_fused": "k_attention (scores contraction, softmax chain and weighted sum in one pass; alternative, off by default)"}
 
 
-def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None):
+def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None, fuse_attention=False):
     """Times `steps` passes of one workload under one partitioning: (per-step ms, per-family kernel records, flops per step,
     workload description, device inputs, the workload)."""
     import torch
@@ -154,7 +155,7 @@ def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None)
 
     w = build_config(config)
     dev = {v.name: prng_torch.make_tensor(v.recipe, v.bound, v.dtype, w.seed, w.tensor_id(v.name)) for v in w.vertices if v.is_input}
-    r = GraphRunner(w, pname, contract=contract, fuse_aggregation=True if fuse_aggregation else None)
+    r = GraphRunner(w, pname, contract=contract, fuse_aggregation=True if fuse_aggregation else None, fuse_attention=True if fuse_attention else None)
     r.bind(dev)
     stream = torch.cuda.current_stream()
     # A working set that the 256 MiB Infinity Cache could hold between steps is rotated over three copies (inputs,
@@ -165,7 +166,7 @@ def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None)
     runners = [r]
     if working_set < (512 << 20):
         for _ in range(2):
-            r2 = GraphRunner(w, pname, contract=contract, fuse_aggregation=True if fuse_aggregation else None)
+            r2 = GraphRunner(w, pname, contract=contract, fuse_aggregation=True if fuse_aggregation else None, fuse_attention=True if fuse_attention else None)
             r2.bind({k: t.clone() for k, t in dev.items()})
             runners.append(r2)
     for i in range(warmup * len(runners)):
@@ -215,6 +216,10 @@ def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None)
             f["bytes"] += x["slabs"] * a["nz"] * 4 + a["nz"] * a["esz"]
         elif key == "softmax_fused":
             f["bytes"] += a["fused_bytes"]
+        elif key == "attention_fused":
+            # recorded at the second contraction; the first one runs over the same label combinations, so the launch
+            # does twice that vertex's operations (no key block is skipped under a causal mask)
+            f["flops"] += 2 * a["flops"]
         else:
             f["flops"] += a["flops"]
             f["bytes"] += a["in_bytes"] + (x["slabs"] * a["nz"] * 4 if x["slabs"] else a["nz"] * a["esz"])
@@ -224,7 +229,7 @@ def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None)
         k = {"launches_per_step": f["launches"] / steps, "avg_launch_ms": f["ms"] / f["launches"],
              "median_launch_ms": each[len(each) // 2], "min_launch_ms": each[0],
              "share_of_step": f["ms"] / steps / ms_per_step}
-        if key == "contract_mfma":
+        if key in ("contract_mfma", "attention_fused"):
             k.update({"bound": "mfma", "achieved": f["flops"] / (f["ms"] * 1e-3) / 1e12,
                       "peak": PEAK_F32_TFLOPS if config == 1 else PEAK_BF16_TFLOPS, "unit": "TFLOP/s"})
         elif key == "contract_alu":
@@ -236,7 +241,8 @@ def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None)
         k["traffic"] = t
         kernels[key] = k
     desc = f"{w.name} dims {json.dumps(w.dims)}, partitioning '{pname}': {json.dumps(r.part)}" \
-        + (" [alternative method: aggregation inside the contraction kernels]" if fuse_aggregation else "")
+        + (" [alternative method: aggregation inside the contraction kernels]" if fuse_aggregation else "") \
+        + (" [alternative: attention as one pass]" if fuse_attention else "")
     n_sets = len(runners)
     for q in runners[1:]:
         q.close()
@@ -253,6 +259,8 @@ def main():
     ap.add_argument("--partitioning", default=None)
     ap.add_argument("--fuse-aggregation", action="store_true",
                     help="alternative method, reported separately: contractions reduce over partitioned contracted labels inside the kernel (no partial slabs, no aggregation launch)")
+    ap.add_argument("--fuse-attention", action="store_true",
+                    help="alternative, reported separately: attention groups (scores contraction, softmax chain, weighted sum) run as one kernel")
     ap.add_argument("--contract-tile", default=None, help="for comparisons: output tile of the block-contraction kernel, e.g. 256x256, 256x128, 128 (default: the library chooses)")
     ap.add_argument("--contract-waves", type=int, default=0, help="for comparisons: 4 or 8 waves per workgroup of the 256 x 256 tile")
     ap.add_argument("--no-other-workloads", action="store_true", help="skip the short runs of configs 3, 4 and 5 that follow the headline workload")
@@ -271,7 +279,7 @@ def main():
     if args.contract_tile:
         t = [int(x) for x in args.contract_tile.split("x")]
         contract = dict(tile=(t[0], t[-1]), waves=args.contract_waves)
-    ms_per_step, kernels, flops_per_step, desc, dev, w, n_sets = measure(args.config, pname, args.steps, args.warmup, args.fuse_aggregation, contract)
+    ms_per_step, kernels, flops_per_step, desc, dev, w, n_sets = measure(args.config, pname, args.steps, args.warmup, args.fuse_aggregation, contract, args.fuse_attention)
     value = flops_per_step / (ms_per_step * 1e-3) / 1e12
 
     dom = "contract_mfma" if "contract_mfma" in kernels else max(kernels, key=lambda k: kernels[k]["share_of_step"])
@@ -294,14 +302,14 @@ def main():
         out["cpu_baseline"] = cpu_baseline(w, dev)
     del dev
     torch.cuda.empty_cache()
-    if not args.no_other_workloads and args.config == 2 and not args.fuse_aggregation and contract is None:
+    if not args.no_other_workloads and args.config == 2 and not args.fuse_aggregation and not args.fuse_attention and contract is None:
         # the other full-size workloads, a few steps each, so that their kernel families are measured in the same run
         others = {}
-        for c in (3, 4, 5):
-            ms, ks, fl, d, dv, _, _ = measure(c, DEFAULT_PART[c], 5, 2)
+        for c, alt in ((3, False), (4, False), (5, False), (4, True)):
+            ms, ks, fl, d, dv, _, _ = measure(c, DEFAULT_PART[c], 5, 2, fuse_attention=alt)
             del dv
             torch.cuda.empty_cache()
-            others[f"c{c}"] = {"workload": d, "ms_per_step": ms, "contraction_tflops_per_step": fl / (ms * 1e-3) / 1e12,
+            others[f"c{c}" + ("_attention_as_one_pass" if alt else "")] = {"workload": d, "ms_per_step": ms, "contraction_tflops_per_step": fl / (ms * 1e-3) / 1e12,
                                "kernels": {k: {f: v[f] for f in ("launches_per_step", "avg_launch_ms", "bound", "achieved", "peak", "unit", "frac", "traffic")}
                                            for k, v in ks.items()}}
         out["other_workloads"] = others

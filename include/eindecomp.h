@@ -102,7 +102,8 @@ typedef enum {
     EG_KERNEL_REDUCE_ROW = 3,      /* aggregated labels are the contiguous tail of X: wave reductions */
     EG_KERNEL_GENERIC = 4,         /* any EinSum: one output element per lane, loop over l_agg       */
     EG_KERNEL_CONTRACT_ALU = 5,    /* contraction-shaped EinSum with another (x)/(+) pair (squared L2, L-infinity, ...): LDS tiles, vector ALU */
-    EG_KERNEL_SOFTMAX_FUSED = 6    /* the softmax vertices max, exp(x - max), sum, division (and a preceding alpha*x + y) in one pass per row */
+    EG_KERNEL_SOFTMAX_FUSED = 6,   /* the softmax vertices max, exp(x - max), sum, division (and a preceding alpha*x + y) in one pass per row */
+    EG_KERNEL_ATTENTION_FUSED = 7  /* Section 3's attention, scores contraction to weighted sum, in one pass (tr_set_fused_attention) */
 } eg_kernel_kind;
 
 /* Read-only view of one vertex's plan.  All pointers are host memory owned by the graph and stay
@@ -240,6 +241,23 @@ int tr_set_fusion(eg_graph *g, int enable);
  * written, no aggregation launch follows, and the floating-point summation order is that of the unpartitioned
  * contraction.  Other vertices are not affected.  Changes the workspace size. */
 int tr_set_fused_aggregation(eg_graph *g, int enable);
+
+/* Another alternative for comparison, off by default.  Section 3 writes attention as a contraction Q x K^T over the head
+ * dimension, the softmax chain over the key label (with alpha * x + mask in front when the graph has it) and a second
+ * contraction with V over the key label.  With enable != 0 (and tr_set_fusion on) tr_execute runs such a group as one
+ * kernel per graph execution, reported at the second contraction's vertex: the scores, exponentials and probabilities are
+ * never stored.  Conditions: the group's intermediate tensors have no consumer outside it and are no outputs; neither
+ * the head dimension nor the key label is partitioned at the two contractions (other labels may be: the pass covers all
+ * their blocks); Q, K, V and the exponentials' vertex are bf16, the row statistics fp32; the head dimension is 32, 64 or
+ * 128 and contiguous in Q, K, V and the result; at most two batch labels; the added operand carries only the query and
+ * key labels.  Groups that do not qualify run as without this setting, except that non-contiguous head dimensions
+ * of bound relations are reported by tr_execute as EG_ERR_LIMIT.
+ * Arithmetic: scores and alpha * x + mask are rounded to their vertices' dtypes and the exponentials to bf16, as the
+ * separate vertices do; the maximum a row's exponentials are taken against is the running one (rescaled as it grows),
+ * and the division by the row sum is applied to the fp32 result of the second contraction instead of to bf16-rounded
+ * probabilities, so results differ from the separate vertices' by a few bf16 units in the last place.  A query row whose
+ * scores are all -inf gives NaN, as the separate vertices do.  Changes the workspace size. */
+int tr_set_fused_attention(eg_graph *g, int enable);
 
 /* Which variant of the block-contraction kernel the (x) = multiply, (+) = sum vertices of this graph run on, for
  * comparisons and for tests that must reach every variant at sizes the library would route elsewhere; results are

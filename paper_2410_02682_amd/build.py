@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(ROOT, "include")
 LIB = os.path.join(HERE, "libeindecomp.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["eg_graph.cpp", "eg_planner.cpp", "eg_exec.hip", "k_simple.hip", "k_contract.hip", "k_contract_dma.hip", "k_ceilings.hip"]
+SOURCES = ["eg_graph.cpp", "eg_planner.cpp", "eg_exec.hip", "k_simple.hip", "k_contract.hip", "k_contract_dma.hip", "k_attention.hip", "k_ceilings.hip"]
 HEADERS = [os.path.join(CSRC, "eg_internal.h"), os.path.join(CSRC, "eg_device.h"), os.path.join(INCLUDE, "eindecomp.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE, "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function",

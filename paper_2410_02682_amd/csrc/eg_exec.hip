@@ -476,6 +476,7 @@ struct Layout {
     std::vector<int64_t> partial_off;   // per vertex: byte offset of its partial slabs (-1: none)
     std::vector<int> split;             // per vertex: extra slabs per aggIdx from a split row reduction or contraction (1: none)
     std::vector<int> split_label;       // contraction: the contracted label that is cut `split` times finer
+    std::vector<int64_t> aux_off;       // per vertex: byte offset of a launch's own scratch (the one-pass attention's mask classes; -1: none)
     int64_t total = 0;
 };
 
@@ -541,6 +542,35 @@ struct FuseGroup {
     int vmax = -1, vexp = -1, vsum = -1, vdiv = -1;
     int src = -1, addend = -1; // what the chain reads: the source tensor and the added operand (or -1)
     bool emit_max = false, emit_sum = false;
+    // attention as one pass (tr_set_fused_attention): the contraction that produces the chain's source and the contraction
+    // that consumes its result join the group; the pass then stands at the second contraction
+    int qk = -1, pv = -1;
+    int q = -1, k = -1, v = -1;                 // the tensors it reads besides the added operand
+    int lab_s = -1, lab_t = -1, lab_d = -1;     // qk's schema indices of the query, key and contracted label
+    int lab_dv = -1;                            // pv's schema index of V's own label (the head dimension of the result)
+    int anchor() const { return pv >= 0 ? pv : vdiv; }
+    std::vector<int> members() const
+    {
+        std::vector<int> m;
+        for (int u : {qk, add, vmax, vexp, vsum, vdiv, pv})
+            if (u >= 0) m.push_back(u);
+        return m;
+    }
+    std::vector<int> reads() const
+    {
+        std::vector<int> r;
+        if (pv >= 0) { r = {q, k}; if (addend >= 0) r.push_back(addend); r.push_back(v); }
+        else { r.push_back(src); if (addend >= 0) r.push_back(addend); }
+        return r;
+    }
+    std::vector<int> writes() const
+    {
+        if (pv >= 0) return {pv};
+        std::vector<int> w = {vdiv};
+        if (emit_max) w.push_back(vmax);
+        if (emit_sum) w.push_back(vsum);
+        return w;
+    }
 };
 
 static bool is_iota(const std::vector<int> &l, size_t n)
@@ -617,6 +647,63 @@ static std::vector<FuseGroup> find_fusions(const eg_graph *g)
             if (u >= 0) taken[u] = 1;
         out.push_back(grp);
     }
+    if (!g->fuse_attention) return out;
+    // Attention (Section 3): scores = a contraction whose result [batch.., s, t] feeds nothing but the chain, and a
+    // contraction of the chain's result with V over t.  Structural conditions only, as above.
+    for (FuseGroup &f : out) {
+        if (f.emit_max || f.emit_sum) continue;
+        const int t1 = f.src, p = f.vdiv;
+        if (t1 < 0 || g->v[t1].is_input || taken[t1]) continue;
+        const Vertex &T1 = g->v[t1], &P = g->v[p];
+        if (T1.n_in != 2 || T1.otimes != EG_MUL || T1.oplus != EG_AGG_SUM || T1.is_output || P.is_output || T1.in[0] == T1.in[1]) continue;
+        if (f.add >= 0 ? !only(t1, {f.add}) : !only(t1, {f.vmax, f.vexp})) continue;
+        const size_t r = T1.lz.size();
+        if (r < 2 || r > 4 || r != g->v[f.vexp].lx.size()) continue;
+        // label roles in the first contraction
+        const int nl = (int)T1.labels.size();
+        std::vector<int> inx(nl, 0), iny(nl, 0), inz(nl, 0);
+        for (int l : T1.lx) inx[l] = 1;
+        for (int l : T1.ly) iny[l] = 1;
+        for (int l : T1.lz) inz[l] = 1;
+        int ls = T1.lz[r - 2], lt = T1.lz[r - 1], ld = -1, nk = 0;
+        bool ok = inx[ls] && !iny[ls] && iny[lt] && !inx[lt];
+        for (int l = 0; l < nl; l++)
+            if (inx[l] && iny[l] && !inz[l]) { ld = l; nk++; }
+        for (size_t i = 0; i + 2 < r; i++) ok = ok && inx[T1.lz[i]] && iny[T1.lz[i]];          // leading labels: batch
+        ok = ok && nk == 1 && T1.lx.size() == r && T1.ly.size() == r && (int)T1.agg.size() == 1;   // X: batch labels, s, d;  Y: batch labels, t, d (any order)
+        if (!ok || T1.d[ld] != 1) continue;
+        const int64_t D = T1.lbound[ld];
+        if (D != 32 && D != 64 && D != 128) continue;
+        if (f.addend >= 0) {                    // the added operand may carry the query and key labels only
+            const Vertex &A = g->v[f.add];
+            bool fits = true;
+            for (int l : A.ly) fits = fits && (l == (int)r - 2 || l == (int)r - 1);
+            if (!fits) continue;
+        }
+        // the consumer of the chain's result
+        if (cons[p].size() != 1) continue;
+        const int o = cons[p][0];
+        const Vertex &O = g->v[o];
+        if (taken[o] || O.n_in != 2 || O.in[0] != p || O.in[1] == p || O.otimes != EG_MUL || O.oplus != EG_AGG_SUM || O.lx.size() != r) continue;
+        const int no = (int)O.labels.size();
+        std::vector<int> oy(no, 0), oz(no, 0);
+        for (int l : O.ly) oy[l] = 1;
+        for (int l : O.lz) oz[l] = 1;
+        const int os = O.lx[r - 2], ot = O.lx[r - 1];
+        bool ok2 = oy[ot] && !oz[ot] && !oy[os] && oz[os];
+        for (size_t i = 0; i + 2 < r; i++) ok2 = ok2 && oy[O.lx[i]] && oz[O.lx[i]];
+        int ldv = -1, nn = 0;
+        for (int l = 0; l < no; l++)
+            if (oy[l] && oz[l] && std::find(O.lx.begin(), O.lx.end(), l) == O.lx.end()) { ldv = l; nn++; }
+        ok2 = ok2 && nn == 1 && O.ly.size() == r && O.lz.size() == r && (int)O.agg.size() == 1;
+        if (!ok2 || O.d[ot] != 1 || O.lbound[ldv] != D) continue;
+        if (g->v[T1.in[0]].dtype != EG_BF16 || g->v[T1.in[1]].dtype != EG_BF16 || g->v[O.in[1]].dtype != EG_BF16 || g->v[f.vexp].dtype != EG_BF16) continue;
+        if (g->v[f.vmax].dtype != EG_F32 || g->v[f.vsum].dtype != EG_F32) continue;     // the pass keeps the row statistics in fp32
+        if (f.add >= 0 && g->v[f.add].dtype != T1.dtype) continue;                      // one rounding rule for the scores before and after the added operand
+        f.qk = t1; f.pv = o; f.q = T1.in[0]; f.k = T1.in[1]; f.v = O.in[1];
+        f.lab_s = ls; f.lab_t = lt; f.lab_d = ld; f.lab_dv = ldv;
+        taken[t1] = taken[o] = 1;
+    }
     return out;
 }
 
@@ -690,18 +777,18 @@ static Layout make_layout(const eg_graph *g)
     L.partial_off.assign(nv, -1);
     L.split.assign(nv, 1);
     L.split_label.assign(nv, -1);
+    L.aux_off.assign(nv, -1);
     // a fused chain runs where its last vertex stands: it reads the chain's outside operands there and writes the
     // result (and the row statistics that are still wanted); the other tensors of the chain never exist
     const std::vector<FuseGroup> groups = find_fusions(g);
     std::vector<int> group_of(nv, -1);
     for (size_t k = 0; k < groups.size(); k++)
-        for (int u : {groups[k].add, groups[k].vmax, groups[k].vexp, groups[k].vsum, groups[k].vdiv})
-            if (u >= 0) group_of[u] = (int)k;
+        for (int u : groups[k].members()) group_of[u] = (int)k;
     auto reads_of = [&](int i) {                      // what executes at position i reads these tensors
         std::vector<int> in;
         if (group_of[i] >= 0) {
             const FuseGroup &f = groups[group_of[i]];
-            if (i == f.vdiv) { in.push_back(f.src); if (f.addend >= 0) in.push_back(f.addend); }
+            if (i == f.anchor()) in = f.reads();
         } else {
             for (int k = 0; k < g->v[i].n_in; k++) in.push_back(g->v[i].in[k]);
         }
@@ -716,13 +803,18 @@ static Layout make_layout(const eg_graph *g)
         if (v.is_input) continue;
         if (group_of[i] >= 0) {
             const FuseGroup &f = groups[group_of[i]];
-            if (i != f.vdiv) continue;
-            for (int u : {f.vdiv, f.emit_max ? f.vmax : -1, f.emit_sum ? f.vsum : -1})
-                if (u >= 0 && !g->v[u].is_output) L.result_off[u] = arena.alloc(numel(g->v[u].bound) * dtype_size(g->v[u].dtype));
+            if (i != f.anchor()) continue;
+            for (int u : f.writes())
+                if (!g->v[u].is_output) L.result_off[u] = arena.alloc(numel(g->v[u].bound) * dtype_size(g->v[u].dtype));
+            if (f.pv >= 0 && f.addend >= 0) {          // the classes of the mask's tiles live for this launch only
+                const Vertex &T1 = g->v[f.qk];
+                L.aux_off[i] = arena.alloc((int64_t)attention_mask_class_bytes(T1.lbound[f.lab_s], T1.lbound[f.lab_t]));
+                arena.release(L.aux_off[i]);
+            }
             for (int u : reads_of(i))
                 if (last_use[u] == i && L.result_off[u] >= 0) arena.release(L.result_off[u]);
-            for (int u : {f.vdiv, f.emit_max ? f.vmax : -1, f.emit_sum ? f.vsum : -1})
-                if (u >= 0 && !g->v[u].is_output && last_use[u] < 0) arena.release(L.result_off[u]);
+            for (int u : f.writes())
+                if (!g->v[u].is_output && last_use[u] < 0) arena.release(L.result_off[u]);
             continue;
         }
         if (!v.is_output) L.result_off[i] = arena.alloc(numel(v.bound) * dtype_size(v.dtype));
@@ -854,6 +946,13 @@ int tr_set_fused_aggregation(eg_graph *g, int enable)
     return EG_OK;
 }
 
+int tr_set_fused_attention(eg_graph *g, int enable)
+{
+    if (!g) return fail(EG_ERR_NULL, "graph is NULL");
+    g->fuse_attention = enable != 0;
+    return EG_OK;
+}
+
 int tr_set_contract_variant(eg_graph *g, int kernel, int tile_m, int tile_n, int waves)
 {
     if (!g) return fail(EG_ERR_NULL, "graph is NULL");
@@ -977,7 +1076,7 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
 
     // route everything first so that a failure launches nothing
     struct Step { int vertex; Routed r; bool agg; int64_t slabs, stride; const void *partials; void *dst; std::vector<int64_t> dst_stride;
-                  bool fused = false; SoftmaxParams sp; };
+                  bool fused = false; SoftmaxParams sp; bool attn = false; AttnParams ap; };
     std::vector<Step> steps;
     auto operand_of = [&](int u) {
         Operand o;
@@ -990,12 +1089,66 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
     const std::vector<FuseGroup> groups = find_fusions(g);
     std::vector<int> group_of(nv, -1);
     for (size_t k = 0; k < groups.size(); k++)
-        for (int u : {groups[k].add, groups[k].vmax, groups[k].vexp, groups[k].vsum, groups[k].vdiv})
-            if (u >= 0) group_of[u] = (int)k;
+        for (int u : groups[k].members()) group_of[u] = (int)k;
     for (int i = 0; i < nv; i++) {
         Vertex &v = g->v[i];
         if (v.is_input) continue;
         if (!v.plan.valid) return fail(EG_ERR_BAD_PARTITION, "vertex %d has no plan", i);
+        if (group_of[i] >= 0 && groups[group_of[i]].pv >= 0) {
+            const FuseGroup &f = groups[group_of[i]];
+            if (i != f.pv) continue;                   // runs as part of the pass that stands at the second contraction
+            Step s;
+            s.vertex = i;
+            s.attn = true;
+            s.agg = false;
+            AttnParams &ap = s.ap;
+            memset(&ap, 0, sizeof ap);
+            const Vertex &T1 = g->v[f.qk], &O = g->v[f.pv];
+            const int r = (int)T1.lz.size(), nb = r - 2;
+            const Operand q = operand_of(f.q), k = operand_of(f.k), vv = operand_of(f.v), o = operand_of(f.pv);
+            auto stride_of = [](const std::vector<int> &labels, const Operand &op, int label) -> int64_t {
+                for (size_t a = 0; a < labels.size(); a++)
+                    if (labels[a] == label) return op.stride[a];
+                return 0;
+            };
+            // the leading (batch) labels of the scores, at most two; O's schema names them O.lx[0..nb)
+            int64_t ext[2] = {1, 1}, qs[2] = {0, 0}, ks[2] = {0, 0}, vst[2] = {0, 0}, os[2] = {0, 0};
+            for (int a = 0; a < nb; a++) {
+                const int at = 2 - nb + a;
+                ext[at] = T1.lbound[T1.lz[a]];
+                qs[at] = stride_of(T1.lx, q, T1.lz[a]);
+                ks[at] = stride_of(T1.ly, k, T1.lz[a]);
+                vst[at] = stride_of(O.ly, vv, O.lx[a]);
+                os[at] = stride_of(O.lz, o, O.lx[a]);
+            }
+            if (stride_of(T1.lx, q, f.lab_d) != 1 || stride_of(T1.ly, k, f.lab_d) != 1 || stride_of(O.ly, vv, f.lab_dv) != 1 || stride_of(O.lz, o, f.lab_dv) != 1)
+                return fail(EG_ERR_LIMIT, "vertex %d: the one-pass attention needs the head dimension contiguous in Q, K, V and the result; turn tr_set_fused_attention off", i);
+            if (T1.lbound[f.lab_s] > INT32_MAX || T1.lbound[f.lab_t] > INT32_MAX || ext[0] > INT32_MAX || ext[1] > INT32_MAX)
+                return fail(EG_ERR_LIMIT, "vertex %d: the one-pass attention indexes queries, keys and batch entries with 32 bits", i);
+            ap.q = q.ptr; ap.k = k.ptr; ap.v = vv.ptr; ap.o = (void *)o.ptr;
+            ap.S = (int32_t)T1.lbound[f.lab_s]; ap.T = (int32_t)T1.lbound[f.lab_t]; ap.D = (int32_t)T1.lbound[f.lab_d];
+            ap.nb0 = (int32_t)ext[0]; ap.nb1 = (int32_t)ext[1];
+            ap.q_sb0 = qs[0]; ap.q_sb1 = qs[1]; ap.q_ss = stride_of(T1.lx, q, f.lab_s);
+            ap.k_sb0 = ks[0]; ap.k_sb1 = ks[1]; ap.k_st = stride_of(T1.ly, k, f.lab_t);
+            ap.v_sb0 = vst[0]; ap.v_sb1 = vst[1]; ap.v_st = stride_of(O.ly, vv, O.lx[r - 1]);
+            ap.o_sb0 = os[0]; ap.o_sb1 = os[1]; ap.o_ss = stride_of(O.lz, o, O.lx[r - 2]);
+            ap.alpha_qk = (float)T1.alpha;
+            ap.alpha = 1.f;
+            ap.dt_t1 = T1.dtype; ap.dt_t2 = T1.dtype;
+            if (f.add >= 0) {
+                const Vertex &A = g->v[f.add];
+                const Operand m = operand_of(f.addend);
+                ap.has_mask = 1; ap.mask = m.ptr; ap.mask_dtype = m.dtype;
+                ap.cls = (uint8_t *)(ws + L.aux_off[i]);
+                ap.m_ss = stride_of(A.ly, m, r - 2); ap.m_st = stride_of(A.ly, m, r - 1);
+                ap.alpha = (float)A.alpha; ap.dt_t2 = A.dtype;
+                if (m.dtype != EG_F32 && m.dtype != EG_BF16)
+                    return fail(EG_ERR_LIMIT, "vertex %d: the one-pass attention adds an fp32 or bf16 operand; turn tr_set_fused_attention off", i);
+            }
+            ap.out_dtype = o.dtype;
+            steps.push_back(std::move(s));
+            continue;
+        }
         if (group_of[i] >= 0) {
             const FuseGroup &f = groups[group_of[i]];
             if (i != f.vdiv) continue;                 // runs as part of the pass that stands at the division
@@ -1132,7 +1285,7 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
         struct Guard { Guard() { set_validate_only(true); } ~Guard() { set_validate_only(false); } } guard;
         for (Step &s : steps) {
             const Vertex &v = g->v[s.vertex];
-            int rc = s.fused ? launch_softmax_rows(s.sp, hip_stream) : launch_routed(s.r, hip_stream);
+            int rc = s.attn ? launch_attention(s.ap, hip_stream) : s.fused ? launch_softmax_rows(s.sp, hip_stream) : launch_routed(s.r, hip_stream);
             if (rc) return rc;
             if (s.agg) {
                 rc = aggregate_into(v.oplus, s.partials, s.slabs, numel(v.bound), s.stride, s.dst, v.dtype, v.bound, s.dst_stride, hip_stream);
@@ -1142,7 +1295,8 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
     }
     for (Step &s : steps) {
         const Vertex &v = g->v[s.vertex];
-        int rc = s.fused ? timed(s.vertex, 0, EG_KERNEL_SOFTMAX_FUSED, 0, [&] { return launch_softmax_rows(s.sp, hip_stream); })
+        int rc = s.attn  ? timed(s.vertex, 0, EG_KERNEL_ATTENTION_FUSED, 0, [&] { return launch_attention(s.ap, hip_stream); })
+               : s.fused ? timed(s.vertex, 0, EG_KERNEL_SOFTMAX_FUSED, 0, [&] { return launch_softmax_rows(s.sp, hip_stream); })
                          : timed(s.vertex, 0, s.r.kind, s.agg ? s.slabs : 0, [&] { return launch_routed(s.r, hip_stream); });
         if (rc) return rc;
         if (s.agg) {

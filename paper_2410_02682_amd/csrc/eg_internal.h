@@ -151,6 +151,25 @@ struct SoftmaxParams {
     int32_t share_add;            // filled by the launcher: the rows of a workgroup take the same row of the added operand
 };
 
+// Attention as one pass (see k_attention.hip): O[b.., q, :] = softmax_t(alpha * (alpha_qk * Q K^T) + mask) V per batch entry.
+struct AttnParams {
+    const void *q, *k, *v, *mask;
+    void *o;
+    uint8_t *cls;                     // with a mask: attention_mask_class_bytes(S, T) bytes of scratch, written and read by the launch
+    int32_t cls_stride;               // filled by the launcher
+    int32_t S, T, D;                  // query rows, key rows, head dimension
+    int32_t nb0, nb1;                 // extents of up to two batch labels (nb1 varies fastest over blockIdx.y)
+    int64_t q_sb0, q_sb1, q_ss;       // element strides of the batch labels and of the query label in Q (the head dimension has stride 1)
+    int64_t k_sb0, k_sb1, k_st;       // ... of the key label in K
+    int64_t v_sb0, v_sb1, v_st;
+    int64_t o_sb0, o_sb1, o_ss;
+    int64_t m_ss, m_st;               // element strides of the query and key labels in the mask (0: the mask lacks the label)
+    int32_t has_mask, mask_dtype, mask_vec;   // mask_vec: filled by the launcher (16-byte reads of four consecutive keys)
+    int32_t out_dtype;
+    int32_t dt_t1, dt_t2;             // storage dtypes of the scores and of the scaled, masked scores: where the separate vertices round
+    float alpha_qk, alpha;            // scalar of the first contraction, scalar of the scale-and-add vertex
+};
+
 struct AggregateParams {          // out[e] = oplus_a partials[a][e], ascending a, fp32, one final cast
     const float *partials;
     int64_t n_agg;
@@ -178,6 +197,8 @@ int launch_reduce_row(const ReduceParams &p, void *stream);
 int launch_generic(const GenericParams &p, void *stream);
 int launch_aggregate(const AggregateParams &p, void *stream);
 int launch_softmax_rows(SoftmaxParams &p, void *stream);
+int launch_attention(AttnParams &p, void *stream);
+size_t attention_mask_class_bytes(int64_t S, int64_t T);
 
 // ------------------------------------------------------------------------------------------------
 // host-side graph
@@ -216,6 +237,7 @@ struct eg_graph {
     std::vector<int> outputs;     // marked outputs, marking order
     // executor state
     bool fuse = true;                               // fuse softmax chains where the partitioning allows (tr_set_fusion)
+    bool fuse_attention = false;                    // scores, softmax chain and weighted sum as one pass (tr_set_fused_attention)
     bool agg_in_kernel = false;                     // contractions sum over partitioned contracted labels inside the kernel (tr_set_fused_aggregation)
     int contract_kernel = 0, contract_tile_m = 0, contract_tile_n = 0, contract_waves = 0;   // tr_set_contract_variant (0: the launchers choose)
     bool profile = false;
