@@ -699,6 +699,7 @@ static std::vector<FuseGroup> find_fusions(const eg_graph *g)
         if (!ok2 || O.d[ot] != 1 || O.lbound[ldv] != D) continue;
         if (g->v[T1.in[0]].dtype != EG_BF16 || g->v[T1.in[1]].dtype != EG_BF16 || g->v[O.in[1]].dtype != EG_BF16 || g->v[f.vexp].dtype != EG_BF16) continue;
         if (g->v[f.vmax].dtype != EG_F32 || g->v[f.vsum].dtype != EG_F32) continue;     // the pass keeps the row statistics in fp32
+        if (f.add >= 0 && T1.lbound[lt] > 65536) continue;                              // the pass keeps a table of the mask's key blocks on chip
         if (f.add >= 0 && g->v[f.add].dtype != T1.dtype) continue;                      // one rounding rule for the scores before and after the added operand
         f.qk = t1; f.pv = o; f.q = T1.in[0]; f.k = T1.in[1]; f.v = O.in[1];
         f.lab_s = ls; f.lab_t = lt; f.lab_d = ld; f.lab_dv = ldv;

@@ -33,6 +33,9 @@ typedef uint32_t at_u32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 at_bf16x2 __attribute__((ext_vector_type(2)));
 typedef float at_f32x4 __attribute__((ext_vector_type(4)));
 
+#define EG_AT_LDS(p) ((__attribute__((address_space(3))) void *)(p))
+constexpr int kAttnMaxKeyBlocks = 1024;             // key blocks (of 64) whose mask classes a workgroup keeps in LDS
+
 namespace {
 
 __device__ __forceinline__ at_f32x16 at_mfma(const at_u32x4 &a, const at_u32x4 &b, at_f32x16 acc)
@@ -55,27 +58,49 @@ enum { AT_DEAD = 0,      // -inf throughout: the keys add nothing to these queri
        AT_PLAIN = 1,     // zero throughout: nothing to load or add
        AT_MIXED = 2 };
 
-// One wave per tile; lane = key, so a row's 64 entries are read as one contiguous piece when the key stride is 1.
-// cls[key block][query group], a byte per tile; groups beyond the last query (the row is padded to a multiple of four
-// groups) come out dead.
-__global__ __launch_bounds__(64) void k_attention_mask_classes(const AttnParams p)
+// One workgroup per tile, eight rows per wave; lane = key, so a row's 64 entries are read as one contiguous piece when
+// the key stride is 1.  cls[key block][query group], a byte per tile; groups beyond the last query (the row is padded to
+// a multiple of four groups) come out dead.
+__global__ __launch_bounds__(256) void k_attention_mask_classes(const AttnParams p)
 {
-    const int group = blockIdx.x, blk = blockIdx.y, lane = threadIdx.x;
+    __shared__ int seen[4];
+    const int group = blockIdx.x, blk = blockIdx.y, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int t = blk * 64 + lane;
     bool dead = true, zero = true;
-    if (t < p.T) {
-#pragma unroll 8
-        for (int r = 0; r < 32; r++) {
-            const int row = group * 32 + r;
-            if (row < p.S) {
-                const float m = load_elem(p.mask, p.mask_dtype, (int64_t)row * p.m_ss + (int64_t)t * p.m_st);
-                dead = dead && m == -INFINITY;
-                zero = zero && m == 0.f;
-            }
+#pragma unroll
+    for (int r = 0; r < 8; r++) {
+        const int row = group * 32 + wave * 8 + r;
+        if (t < p.T && row < p.S) {
+            const float m = load_elem(p.mask, p.mask_dtype, (int64_t)row * p.m_ss + (int64_t)t * p.m_st);
+            dead = dead && m == -INFINITY;
+            zero = zero && m == 0.f;
         }
     }
-    const bool any_alive = __builtin_amdgcn_ballot_w64(!dead) != 0, any_nonzero = __builtin_amdgcn_ballot_w64(!zero) != 0;
-    if (lane == 0) p.cls[(int64_t)blk * p.cls_stride + group] = !any_alive ? AT_DEAD : !any_nonzero ? AT_PLAIN : AT_MIXED;
+    const int mine = (__builtin_amdgcn_ballot_w64(!dead) != 0 ? 1 : 0) | (__builtin_amdgcn_ballot_w64(!zero) != 0 ? 2 : 0);
+    if (lane == 0) seen[wave] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int all = seen[0] | seen[1] | seen[2] | seen[3];      // bit 0: some entry above -inf; bit 1: some entry not zero
+        p.cls[(int64_t)blk * p.cls_stride + group] = !(all & 1) ? AT_DEAD : !(all & 2) ? AT_PLAIN : AT_MIXED;
+    }
+}
+
+// One direct load from memory to LDS: the wave's 64 lanes fetch 16 bytes each from base + voff (zeros where voff + 16 goes
+// beyond `bytes`) into the 1 KiB of LDS at lds_addr, lane after lane.  Written out by hand so that the compiler does not
+// hold later LDS reads of the other stage until the load has landed; whoever reads the destination waits for vmcnt(0)
+// and a barrier first.  M0 (the LDS base of a direct load) is put back.
+__device__ __forceinline__ void at_load_lds(const void *base, uint32_t bytes, uint32_t lds_addr, uint32_t voff)
+{
+    const uint64_t b = (uint64_t)base;
+    at_u32x4 rs;
+    rs.x = __builtin_amdgcn_readfirstlane((uint32_t)b);
+    rs.y = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32)) & 0xffffu;      // stride 0: a raw buffer
+    rs.z = __builtin_amdgcn_readfirstlane(bytes);
+    rs.w = 0x00020000u;
+    const uint32_t l = __builtin_amdgcn_readfirstlane(lds_addr);
+    uint32_t keep;
+    asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
+                 : "=&s"(keep) : "s"(l), "v"(voff), "s"(rs) : "memory");
 }
 
 // MASK: 0 = the group has no added operand; 1 = fp32 mask read 16 bytes (four consecutive keys) at a time; 2 = any
@@ -86,26 +111,64 @@ __global__ __launch_bounds__(256, 2) void k_attention(const AttnParams p)
     constexpr int BM = 128, BN = 64;                   // query rows per workgroup, key rows per block
     constexpr int RB = D * 2, CH = D / 8;              // bytes and 16-byte chunks of a K / V row
     constexpr int RPB = RB >= 256 ? 1 : 256 / RB;      // rows per 256 bytes
-    constexpr int NCH = BN * CH / 256;                 // chunks of a block each thread moves
+    constexpr int TILE = BN * RB;                      // bytes of a K or V tile
+    constexpr int NLD = TILE / 1024 / 4;               // direct loads (1 KiB each) per wave and tile
     constexpr int KT = D / 16, DT = D / 32;            // k-steps of the first product, 32-row tiles of O^T
     static_assert(D == 32 || D == 64 || D == 128, "head dimension");
-    __shared__ __attribute__((aligned(16))) char ks[BN * RB];
-    __shared__ __attribute__((aligned(16))) char vs[BN * RB];
+    __shared__ __attribute__((aligned(1024))) char lds[2][2][TILE];     // two stages of a K tile and a V tile
+    __shared__ uint8_t ctab[MASK ? kAttnMaxKeyBlocks : 4];              // per key block: the classes of the four query groups, two bits each
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lrow = lane & 31, lhalf = lane >> 5;
-    const int b0 = blockIdx.y / p.nb1, b1 = blockIdx.y - b0 * p.nb1;
+    // Workgroups go to the chip's eight dies in turn (each with an L2 of its own).  A batch entry's query blocks all run on
+    // one die, so that its K and V are fetched from memory once; there they start with the last query block, which under a
+    // causal mask has the most live key blocks.
+    const int nq = (p.S + BM - 1) / BM, nbatch = p.nb0 * p.nb1;
+    const int die = blockIdx.x & 7, turn = blockIdx.x >> 3;
+    const int bh = (turn / nq) * 8 + die;
+    if (bh >= nbatch) return;                          // the grid is rounded up to whole rounds over the dies
+    const int qblk = nq - 1 - turn % nq;
+    const int b0 = bh / p.nb1, b1 = bh - b0 * p.nb1;
     const uint16_t *Q = (const uint16_t *)p.q + b0 * p.q_sb0 + b1 * p.q_sb1;
     const uint16_t *K = (const uint16_t *)p.k + b0 * p.k_sb0 + b1 * p.k_sb1;
     const uint16_t *V = (const uint16_t *)p.v + b0 * p.v_sb0 + b1 * p.v_sb1;
-    // Under a causal mask the last query blocks have the most live key blocks: they start first.
-    const int qblk = gridDim.x - 1 - blockIdx.x;
     const int qrow = qblk * BM + wave * 32 + lrow;                     // this lane's query
     const int qr = qrow < p.S ? qrow : p.S - 1;
+    const int nblocks = (p.T + BN - 1) / BN;
+
+    // K rows are read 16 bytes at a time by 16 lanes holding 16 consecutive rows: the chunk index is XOR-ed with the row
+    // (per 256 bytes) so that they fall into 16 different bank groups.  V rows are read by the transposing 8-byte reads,
+    // 4 consecutive rows x 32 bytes per 16 lanes: rows of a group of four are moved apart by multiples of 64 bytes.
+    // A direct load fills LDS lane after lane, so the swizzle is applied to what a lane fetches: the lane whose 16 bytes
+    // land in chunk position c of row r fetches chunk c ^ key(r) of that row.
+#define EG_AT_KKEY(row) (((row) / RPB) % CH)
+#define EG_AT_VKEY(row) ((((row) & 3) * (RB / 64)) & (CH - 1))
+    uint32_t koff[NLD], voff[NLD];                     // byte offsets of this lane's fetches from the block's first row
+#pragma unroll
+    for (int c = 0; c < NLD; c++) {
+        const int byte = (c * 4 + wave) * 1024 + lane * 16, row = byte / RB, ch = (byte % RB) >> 4;
+        koff[c] = (uint32_t)(row * (int)p.k_st * 2 + ((ch ^ EG_AT_KKEY(row)) << 4));
+        voff[c] = (uint32_t)(row * (int)p.v_st * 2 + ((ch ^ EG_AT_VKEY(row)) << 4));
+    }
+    // key block B -> LDS stage S: rows past the last key come in as zeros
+#define EG_AT_ISSUE(B, S)                                                                                       \
+    {                                                                                                           \
+        const int left = p.T - (B) * BN < BN ? p.T - (B) * BN : BN;                                              \
+        const uint32_t kbytes = (uint32_t)((left - 1) * (int)p.k_st * 2 + RB), vbytes = (uint32_t)((left - 1) * (int)p.v_st * 2 + RB); \
+        const uint16_t *kb = K + (int64_t)(B) * BN * p.k_st, *vb = V + (int64_t)(B) * BN * p.v_st;                \
+        _Pragma("unroll") for (int c = 0; c < NLD; c++) {                                                        \
+            at_load_lds(kb, kbytes, (uint32_t)(uintptr_t)EG_AT_LDS(lds[S][0] + (c * 4 + wave) * 1024), koff[c]); \
+            at_load_lds(vb, vbytes, (uint32_t)(uintptr_t)EG_AT_LDS(lds[S][1] + (c * 4 + wave) * 1024), voff[c]); \
+        }                                                                                                       \
+    }
+#define EG_AT_LANDED() { __builtin_amdgcn_s_waitcnt(0x0f70); __syncthreads(); }   /* vmcnt(0): this wave's direct loads; then everybody's */
 
     // Q's fragments for all k-steps: column operand, lane = query, 8 consecutive d
     at_u32x4 qf[KT];
 #pragma unroll
     for (int kk = 0; kk < KT; kk++) qf[kk] = *(const at_u32x4 *)(Q + (int64_t)qr * p.q_ss + 16 * kk + 8 * lhalf);
+    // Waited for here, once: the compiler would otherwise wait for them in front of every block's first product, and
+    // that wait (the counter runs in order) would take the direct loads of the next block with it.
+    __builtin_amdgcn_s_waitcnt(0x0f70);
 
     at_f32x16 oacc[DT];
 #pragma unroll
@@ -114,43 +177,31 @@ __global__ __launch_bounds__(256, 2) void k_attention(const AttnParams p)
         for (int r = 0; r < 16; r++) oacc[dt][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    // K rows are read 16 bytes at a time by 16 lanes holding 16 consecutive rows: the chunk index is XOR-ed with the row
-    // (per 256 bytes) so that they fall into 16 different bank groups.  V rows are read by the transposing 8-byte reads,
-    // 4 consecutive rows x 32 bytes per 16 lanes: rows of a group of four are moved apart by multiples of 64 bytes.
-#define EG_AT_KKEY(row) (((row) / RPB) % CH)
-#define EG_AT_VKEY(row) ((((row) & 3) * (RB / 64)) & (CH - 1))
-    at_u32x4 kreg[NCH], vreg[NCH];
-#define EG_AT_GLOAD(BLK)                                                                          \
-    _Pragma("unroll") for (int c = 0; c < NCH; c++) {                                              \
-        const int idx = c * 256 + tid, row = idx / CH, ch = idx - row * CH;                        \
-        int t = (BLK) * BN + row;                                                                  \
-        t = t < p.T ? t : p.T - 1;                                                                 \
-        kreg[c] = *(const at_u32x4 *)(K + (int64_t)t * p.k_st + ch * 8);                             \
-        vreg[c] = *(const at_u32x4 *)(V + (int64_t)t * p.v_st + ch * 8);                             \
-    }
-#define EG_AT_LSTORE()                                                                            \
-    _Pragma("unroll") for (int c = 0; c < NCH; c++) {                                              \
-        const int idx = c * 256 + tid, row = idx / CH, ch = idx - row * CH;                        \
-        *(at_u32x4 *)(ks + row * RB + ((ch ^ EG_AT_KKEY(row)) << 4)) = kreg[c];                     \
-        *(at_u32x4 *)(vs + row * RB + ((ch ^ EG_AT_VKEY(row)) << 4)) = vreg[c];                     \
-    }
-
-    const int nblocks = (p.T + BN - 1) / BN;
-    // classes of this workgroup's four query groups in a key block, a byte each (the same word for every lane)
-    const uint8_t *cls = MASK ? p.cls + qblk * 4 : nullptr;
-#define EG_AT_CLASSES(B) (MASK ? *(const uint32_t *)(cls + (int64_t)(B) * p.cls_stride) : 0x01010101u)
-    int blk = 0;
-    while (blk < nblocks && EG_AT_CLASSES(blk) == 0) blk++;
-    if (blk < nblocks) { EG_AT_GLOAD(blk) }
-    while (blk < nblocks) {
-        int nxt = blk + 1;                              // the next key block that is live for any of the four groups
-        while (nxt < nblocks && EG_AT_CLASSES(nxt) == 0) nxt++;
-        const int my = __builtin_amdgcn_readfirstlane((EG_AT_CLASSES(blk) >> (8 * wave)) & 0xff);
-        const bool tail = blk == nblocks - 1 && (p.T & (BN - 1)) != 0;
-        __syncthreads();                               // every wave has read the previous block's tiles
-        EG_AT_LSTORE()
+    // classes of this workgroup's four query groups in every key block (a word per block in memory), two bits each
+    if (MASK) {
+        for (int b = tid; b < nblocks; b += 256) {
+            const uint32_t w = *(const uint32_t *)(p.cls + (int64_t)b * p.cls_stride + qblk * 4);
+            ctab[b] = (uint8_t)((w & 3) | ((w >> 6) & 0xc) | ((w >> 12) & 0x30) | ((w >> 18) & 0xc0));
+        }
         __syncthreads();
-        if (nxt < nblocks) { EG_AT_GLOAD(nxt) }          // travels under this block's arithmetic
+    }
+#define EG_AT_SKIP_DEAD(B) { if (MASK) while ((B) < nblocks && ctab[B] == 0) (B)++; }
+    // Key blocks that are dead for all four query groups are left out altogether.  A live block's tiles are in LDS stage
+    // `stage` while the block is worked on; the next live block's travel from memory into the other stage meanwhile, which
+    // the barrier at the end of the previous block has freed of its readers.
+    int blk = 0, stage = 0;
+    EG_AT_SKIP_DEAD(blk)
+    int nxt = blk + 1;
+    if (blk < nblocks) {
+        EG_AT_ISSUE(blk, 0)
+        EG_AT_SKIP_DEAD(nxt)
+        EG_AT_LANDED()
+    }
+    while (blk < nblocks) {
+        if (nxt < nblocks) { EG_AT_ISSUE(nxt, stage ^ 1) }
+        const int my = MASK ? __builtin_amdgcn_readfirstlane((ctab[blk] >> (2 * wave)) & 3) : (int)AT_PLAIN;
+        const bool tail = blk == nblocks - 1 && (p.T & (BN - 1)) != 0;
+        const char *ks = lds[stage][0], *vs = lds[stage][1];
         if (my != AT_DEAD) {
             // ---- the mask's entries of a mixed tile, fetched first so that they travel under the scores' product ----
             float mk[2][16];
@@ -167,24 +218,33 @@ __global__ __launch_bounds__(256, 2) void k_attention(const AttnParams p)
                     }
             }
 
-            // ---- scores: S^T (keys x queries) = K Q^T ---------------------------------------------------
+            // ---- scores: S^T (keys x queries) = K Q^T; the fragments of the next k-step are read under this one's products ----
             at_f32x16 sacc[2];
             const at_f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            at_u32x4 kf[2][2];
+#define EG_AT_KFRAG(KK, I) (*(const at_u32x4 *)(ks + ((I) * 32 + lrow) * RB + (((2 * (KK) + lhalf) ^ EG_AT_KKEY((I) * 32 + lrow)) << 4)))
+            kf[0][0] = EG_AT_KFRAG(0, 0);
+            kf[0][1] = EG_AT_KFRAG(0, 1);
 #pragma unroll
-            for (int kk = 0; kk < KT; kk++)
-#pragma unroll
-                for (int i = 0; i < 2; i++) {
-                    const int row = i * 32 + lrow;
-                    const at_u32x4 a = *(const at_u32x4 *)(ks + row * RB + (((2 * kk + lhalf) ^ EG_AT_KKEY(row)) << 4));
-                    sacc[i] = at_mfma(a, qf[kk], kk == 0 ? zero : sacc[i]);
+            for (int kk = 0; kk < KT; kk++) {
+                if (kk + 1 < KT) {
+                    kf[(kk + 1) & 1][0] = EG_AT_KFRAG(kk + 1, 0);
+                    kf[(kk + 1) & 1][1] = EG_AT_KFRAG(kk + 1, 1);
                 }
+                sacc[0] = at_mfma(kf[kk & 1][0], qf[kk], kk == 0 ? zero : sacc[0]);
+                sacc[1] = at_mfma(kf[kk & 1][1], qf[kk], kk == 0 ? zero : sacc[1]);
+            }
+#undef EG_AT_KFRAG
 
             // ---- the chain's element-wise steps on this lane's 32 keys: key of (i, r) = 32 i + 8 (r / 4) + 4 half + r % 4 ----
             float x[2][16];
 #pragma unroll
             for (int i = 0; i < 2; i++) {
 #pragma unroll
-                for (int r = 0; r < 16; r++) x[i][r] = p.alpha_qk * sacc[i][r];
+                for (int r = 0; r < 16; r++) x[i][r] = sacc[i][r];
+                if (p.alpha_qk != 1.f)
+#pragma unroll
+                    for (int r = 0; r < 16; r++) x[i][r] *= p.alpha_qk;
                 if (RND)
 #pragma unroll
                     for (int r = 0; r < 16; r += 2) round_pair_bf16(x[i][r], x[i][r + 1]);
@@ -261,29 +321,39 @@ __global__ __launch_bounds__(256, 2) void k_attention(const AttnParams p)
             }
 
             // ---- O^T (head dimension x queries) += V^T P^T ---------------------------------------------
-            // k-slot (half h, i) of step (i32, j) stands for key 32 i32 + 16 j + 8 (i / 4) + 4 h + i % 4, as the scores came out
+            // k-slot (half h, i) of step (i32, j) stands for key 32 i32 + 16 j + 8 (i / 4) + 4 h + i % 4, as the scores came out;
+            // step n = (i32, j, dt), the fragment of step n + 1 read under step n's product
             const int s16 = lane & 15;
+            typedef short at_short8 __attribute__((ext_vector_type(8)));
+            auto vfrag = [&](int n) -> at_u32x4 {
+                const int ij = n / DT, dt = n % DT, i = ij >> 1, j = ij & 1;
+                const int col = dt * 32 + 16 * ((lane >> 4) & 1) + 4 * (s16 & 3);           // first of this lane's four d
+                at_short4 part[2];
 #pragma unroll
-            for (int i = 0; i < 2; i++)
+                for (int sec = 0; sec < 2; sec++) {
+                    const int row = i * 32 + 16 * j + 8 * sec + 4 * lhalf + (s16 >> 2);
+                    const char *addr = vs + row * RB + (((col >> 3) ^ EG_AT_VKEY(row)) << 4) + ((col & 7) << 1);
+                    part[sec] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) at_short4 *)((__attribute__((address_space(3))) void *)addr));
+                }
+                const at_short8 both = __builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7);
+                return __builtin_bit_cast(at_u32x4, both);
+            };
+            at_u32x4 vf[2];
+            vf[0] = vfrag(0);
 #pragma unroll
-                for (int j = 0; j < 2; j++)
-#pragma unroll
-                    for (int dt = 0; dt < DT; dt++) {
-                        const int n = dt * 32 + 16 * ((lane >> 4) & 1) + 4 * (s16 & 3);         // first of this lane's four d
-                        at_short4 part[2];
-#pragma unroll
-                        for (int sec = 0; sec < 2; sec++) {
-                            const int row = i * 32 + 16 * j + 8 * sec + 4 * lhalf + (s16 >> 2);
-                            const char *addr = vs + row * RB + (((n >> 3) ^ EG_AT_VKEY(row)) << 4) + ((n & 7) << 1);
-                            part[sec] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) at_short4 *)((__attribute__((address_space(3))) void *)addr));
-                        }
-                        typedef short at_short8 __attribute__((ext_vector_type(8)));
-                        const at_short8 both = __builtin_shufflevector(part[0], part[1], 0, 1, 2, 3, 4, 5, 6, 7);
-                        const at_u32x4 a = __builtin_bit_cast(at_u32x4, both);
-                        oacc[dt] = at_mfma(a, pf[i][j], oacc[dt]);
-                    }
+            for (int n = 0; n < 4 * DT; n++) {
+                if (n + 1 < 4 * DT) vf[(n + 1) & 1] = vfrag(n + 1);
+                const int ij = n / DT, dt = n % DT;
+                oacc[dt] = at_mfma(vf[n & 1], pf[ij >> 1][ij & 1], oacc[dt]);
+            }
         }
         blk = nxt;
+        if (blk < nblocks) {
+            nxt = blk + 1;
+            EG_AT_SKIP_DEAD(nxt)
+            EG_AT_LANDED()
+            stage ^= 1;
+        }
     }
 
     // ---- division by the row sum, store: lane holds query qrow and, per tile, d = 32 dt + 8 (r / 4) + 4 half + r % 4 ----
@@ -315,11 +385,11 @@ __global__ __launch_bounds__(256, 2) void k_attention(const AttnParams p)
     }
 }
 
-#undef EG_AT_GLOAD
-#undef EG_AT_LSTORE
+#undef EG_AT_ISSUE
+#undef EG_AT_LANDED
+#undef EG_AT_SKIP_DEAD
 #undef EG_AT_KKEY
 #undef EG_AT_VKEY
-#undef EG_AT_CLASSES
 
 size_t attention_mask_class_bytes(int64_t S, int64_t T)
 {
@@ -347,16 +417,20 @@ int launch_attention(AttnParams &p, void *stream)
         return fail(EG_ERR_LIMIT, "attention kernel: operands must be 16-byte aligned");
     if (p.has_mask && p.dt_t1 != p.dt_t2) return fail(EG_ERR_LIMIT, "attention kernel: the scores and the scaled, masked scores must have one storage dtype");
     const int64_t qblocks = ((int64_t)p.S + 127) / 128, nb = (int64_t)p.nb0 * p.nb1, kblocks = ((int64_t)p.T + 63) / 64;
-    if (qblocks >= (1ll << 31) || nb > 65535 || kblocks > 65535)
+    if (p.k_st >= (1ll << 23) || p.v_st >= (1ll << 23)) return fail(EG_ERR_LIMIT, "attention kernel: key strides of K and V must stay below 2^23 elements");
+    if (p.has_mask && kblocks > kAttnMaxKeyBlocks) return fail(EG_ERR_LIMIT, "attention kernel: at most %d keys with an added operand", kAttnMaxKeyBlocks * 64);
+    if (qblocks >= (1ll << 29) || nb >= (1ll << 31) || kblocks > 65535)
         return fail(EG_ERR_LIMIT, "attention kernel: %lld query blocks x %lld batch entries, %lld key blocks", (long long)qblocks, (long long)nb, (long long)kblocks);
     p.mask_vec = p.has_mask && p.m_st == 1 && p.mask_dtype == EG_F32 && ((uintptr_t)p.mask & 15) == 0 && p.m_ss % 4 == 0 && p.T % 4 == 0;
     hipStream_t st = (hipStream_t)stream;
     if (p.has_mask) {
         if ((uintptr_t)p.cls & 3) return fail(EG_ERR_LIMIT, "attention kernel: the class table must be 4-byte aligned");
         p.cls_stride = (int32_t)(qblocks * 4);
-        EG_LAUNCH(k_attention_mask_classes, dim3((unsigned)(qblocks * 4), (unsigned)kblocks), dim3(64), 0, st, p);
+        EG_LAUNCH(k_attention_mask_classes, dim3((unsigned)(qblocks * 4), (unsigned)kblocks), dim3(256), 0, st, p);
     }
-    const dim3 grid((unsigned)qblocks, (unsigned)nb);
+    const int64_t wgs = qblocks * ((nb + 7) / 8 * 8);
+    if (wgs >= (1ll << 31)) return fail(EG_ERR_LIMIT, "attention kernel: %lld workgroups", (long long)wgs);
+    const dim3 grid((unsigned)wgs);
     const int mask = !p.has_mask ? 0 : p.mask_vec ? 1 : 2;
     const bool rnd = p.dt_t1 == EG_BF16;
     if (p.D == 128) launch_attention_d<128>(p, mask, rnd, grid, st);
