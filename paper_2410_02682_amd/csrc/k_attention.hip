@@ -34,6 +34,7 @@ typedef __bf16 at_bf16x2 __attribute__((ext_vector_type(2)));
 typedef float at_f32x4 __attribute__((ext_vector_type(4)));
 
 #define EG_AT_LDS(p) ((__attribute__((address_space(3))) void *)(p))
+constexpr float kAttnSlack = 5.f;                   // how far a row's maximum may rise above the value its exponentials are taken against
 constexpr int kAttnMaxKeyBlocks = 1024;             // key blocks (of 64) whose mask classes a workgroup keeps in LDS
 
 namespace {
@@ -124,9 +125,10 @@ __global__ __launch_bounds__(256, 2) void k_attention(const AttnParams p)
     // causal mask has the most live key blocks.
     const int nq = (p.S + BM - 1) / BM, nbatch = p.nb0 * p.nb1;
     const int die = blockIdx.x & 7, turn = blockIdx.x >> 3;
-    const int bh = (turn / nq) * 8 + die;
+    const int per_die = (nbatch + 7) / 8;
+    const int bh = (turn % per_die) * 8 + die;
     if (bh >= nbatch) return;                          // the grid is rounded up to whole rounds over the dies
-    const int qblk = nq - 1 - turn % nq;
+    const int qblk = nq - 1 - turn / per_die;
     const int b0 = bh / p.nb1, b1 = bh - b0 * p.nb1;
     const uint16_t *Q = (const uint16_t *)p.q + b0 * p.q_sb0 + b1 * p.q_sb1;
     const uint16_t *K = (const uint16_t *)p.k + b0 * p.k_sb0 + b1 * p.k_sb1;
@@ -278,6 +280,7 @@ __global__ __launch_bounds__(256, 2) void k_attention(const AttnParams p)
                         for (int r = 0; r < 16; r += 2) round_pair_bf16(x[i][r], x[i][r + 1]);
             }
             if (tail) {                                 // keys past the end take no part
+                asm volatile("" ::: "memory");          // a branch taken once, not 32 selects in every block
 #pragma unroll
                 for (int i = 0; i < 2; i++)
 #pragma unroll
@@ -290,7 +293,9 @@ __global__ __launch_bounds__(256, 2) void k_attention(const AttnParams p)
 #pragma unroll
                 for (int r = 0; r < 16; r++) bmax = fmaxf(bmax, x[i][r]);
             bmax = fmaxf(bmax, other_half(bmax));
-            const float m_new = fmaxf(m_run, bmax);
+            // The reference value follows the maximum only when that has risen by more than kAttnSlack since it was last set:
+            // exponentials then reach e^slack at most, and the accumulators are rescaled on few blocks instead of nearly all.
+            const float m_new = bmax - m_run > kAttnSlack ? bmax : m_run;           // (-inf - -inf is NaN: stays at -inf)
             const float m_safe = m_new == -INFINITY ? 0.f : m_new;                  // a row that has seen only -inf so far
             const float scale = __builtin_amdgcn_exp2f((m_run - m_safe) * kLog2e);  // 0 while m_run is -inf
             const float nml = -(m_safe * kLog2e);
@@ -314,6 +319,7 @@ __global__ __launch_bounds__(256, 2) void k_attention(const AttnParams p)
             l_run = l_run * scale + psum;
             m_run = m_new;
             if (__builtin_amdgcn_ballot_w64(scale != 1.f) != 0) {      // some query's maximum rose
+                asm volatile("" ::: "memory");          // (a branch: rare after the first blocks)
 #pragma unroll
                 for (int dt = 0; dt < DT; dt++)
 #pragma unroll

@@ -164,21 +164,23 @@ def test_config3_ffnn_step_sampled_rows_under_every_partitioning():
         torch.cuda.empty_cache()
 
 
-def test_config4_decoder_block_sampled_rows_under_every_partitioning():
-    import torch
-    w, dev = _inputs(4)
+_C4_HEADS = [(0, 0), (3, 31), (1, 17)]
+_C4_SROWS = [0, 1, 127, 128, 255, 256, 1023, 2047]         # block boundaries of the 8-way cuts of s and of t
+_C4_PICKS = [(0, 0), (0, 255), (1, 256), (2, 1023), (3, 1024), (3, 2047)]   # (b, s) rows of the projections and the FFN
+
+
+def _c4_attention_reference(w, dev):
+    """The oracle's chain from the inputs for three (batch entry, head) pairs: Q whole, P and O on sampled query rows."""
     d = w.dims["d"]
-    heads = [(0, 0), (3, 31), (1, 17)]
-    srows = [0, 1, 127, 128, 255, 256, 1023, 2047]       # block boundaries of the 8-way cuts of s and of t
     ref = {}
-    for (b, h) in heads:                                  # the oracle's chain from the inputs, once
+    for (b, h) in _C4_HEADS:
         Xb = _host(dev["X"][b])                            # [s, a]
         Wq, Wk, Wv = (_host(dev[n][:, h, :]) for n in ("Wq", "Wk", "Wv"))
         q = einsum_ref("sa,ad->sd", Xb, Wq, out_dtype="bf16")
         k = einsum_ref("ta,ad->td", Xb, Wk, out_dtype="bf16")
         v = einsum_ref("ta,ad->td", Xb, Wv, out_dtype="bf16")
-        t1 = einsum_ref("sd,td->st", _st(q[srows], "bf16"), _st(k, "bf16"), out_dtype="bf16")
-        t2 = einsum_ref("st,st->st", _st(t1, "bf16"), _host(dev["M"][srows]), otimes="add", oplus="none", alpha=1.0 / d ** 0.5, out_dtype="bf16")
+        t1 = einsum_ref("sd,td->st", _st(q[_C4_SROWS], "bf16"), _st(k, "bf16"), out_dtype="bf16")
+        t2 = einsum_ref("st,st->st", _st(t1, "bf16"), _host(dev["M"][_C4_SROWS]), otimes="add", oplus="none", alpha=1.0 / d ** 0.5, out_dtype="bf16")
         t2s = _st(t2, "bf16")
         c = einsum_ref("st->s", t2s, otimes="ident", oplus="max", out_dtype="f32")
         e = einsum_ref("st,s->st", t2s, _st(c, "f32"), otimes="exp_sub", oplus="none", out_dtype="bf16")
@@ -186,35 +188,77 @@ def test_config4_decoder_block_sampled_rows_under_every_partitioning():
         p = einsum_ref("st,s->st", _st(e, "bf16"), _st(s_, "f32"), otimes="div", oplus="none", out_dtype="bf16")
         o = einsum_ref("st,td->sd", _st(p, "bf16"), _st(v, "bf16"), out_dtype="bf16")
         ref[(b, h)] = (q, p, o)
-    Wo, Wg, Wu, Wd = (_host(dev[n]) for n in ("Wo", "Wg", "Wu", "Wd"))
-    picks = [(0, 0), (0, 255), (1, 256), (2, 1023), (3, 1024), (3, 2047)]   # (b, s) rows of the projections and the FFN
-    bi = [b for b, _ in picks]
-    si = [s for _, s in picks]
+    return ref
+
+
+def _c4_check_after_attention(pname, r, weights):
+    """Output projection and SwiGLU FFN on sampled (b, s) rows: every row crosses all eight 1376-wide blocks of f; the
+    oracle starts from the attention output the GPU wrote in this run (checked per head by the caller)."""
+    Wo, Wg, Wu, Wd = weights
+    bi = [b for b, _ in _C4_PICKS]
+    si = [s for _, s in _C4_PICKS]
+    Og = _host(r.output("O")[bi, si])                                       # [rows, h, d]
+    yatt = einsum_ref("rhd,ahd->ra", Og, Wo, out_dtype="bf16")
+    g = einsum_ref("ra,af->rf", _st(yatt, "bf16"), Wg, out_dtype="bf16")
+    u = einsum_ref("ra,af->rf", _st(yatt, "bf16"), Wu, out_dtype="bf16")
+    hh = einsum_ref("rf,rf->rf", _st(g, "bf16"), _st(u, "bf16"), otimes="silu_mul", oplus="none", out_dtype="bf16")
+    out = einsum_ref("rf,fa->ra", _st(hh, "bf16"), Wd, out_dtype="f32")
+    for name, want in (("Yatt", yatt), ("G", g), ("U", u), ("Hh", hh), ("Out", out)):
+        _check(f"{pname} {name} rows", _f64(_host(r.output(name)[bi, si])), want, RTOL_BF16)
+
+
+def test_config4_decoder_block_sampled_rows_under_every_partitioning():
+    import torch
+    w, dev = _inputs(4)
+    ref = _c4_attention_reference(w, dev)
+    weights = tuple(_host(dev[n]) for n in ("Wo", "Wg", "Wu", "Wd"))
     for pname in list(w.partitionings) + ["eindecomp:8"]:
         print(f"config 4 full size, partitioning {pname}", flush=True)
         r = _run(w, dev, pname, ["Q", "P", "O", "Yatt", "G", "U", "Hh", "Out"])
         try:
-            for (b, h) in heads:
+            for (b, h) in _C4_HEADS:
                 q, p, o = ref[(b, h)]
                 _check(f"{pname} Q[{b},:,{h},:]", _f64(_host(r.output("Q")[b, :, h, :])), q, RTOL_BF16)
-                _check(f"{pname} P[{b},{h}]", _f64(_host(r.output("P")[b, h][srows])), p, RTOL_BF16)
-                _check(f"{pname} O[{b},:,{h},:]", _f64(_host(r.output("O")[b, srows, h, :])), o, RTOL_BF16)
+                _check(f"{pname} P[{b},{h}]", _f64(_host(r.output("P")[b, h][_C4_SROWS])), p, RTOL_BF16)
+                _check(f"{pname} O[{b},:,{h},:]", _f64(_host(r.output("O")[b, _C4_SROWS, h, :])), o, RTOL_BF16)
             P = r.output("P")
             assert float((P[0, 0].float().sum(dim=1) - 1.0).abs().max()) < 2e-2     # rows sum to one up to bf16 rounding
             s_len = P.shape[2]
             mask = torch.triu(torch.ones(s_len, s_len, dtype=torch.bool, device=P.device), diagonal=1)
             assert float(P[2, 5][mask].abs().max()) == 0.0                            # future positions: exactly zero
             del mask
-            # output projection and SwiGLU FFN on sampled (b, s) rows: every row crosses all eight 1376-wide blocks of f;
-            # the oracle starts from the attention output the GPU wrote in this run (checked per head above)
-            Og = _host(r.output("O")[bi, si])                                       # [rows, h, d]
-            yatt = einsum_ref("rhd,ahd->ra", Og, Wo, out_dtype="bf16")
-            g = einsum_ref("ra,af->rf", _st(yatt, "bf16"), Wg, out_dtype="bf16")
-            u = einsum_ref("ra,af->rf", _st(yatt, "bf16"), Wu, out_dtype="bf16")
-            hh = einsum_ref("rf,rf->rf", _st(g, "bf16"), _st(u, "bf16"), otimes="silu_mul", oplus="none", out_dtype="bf16")
-            out = einsum_ref("rf,fa->ra", _st(hh, "bf16"), Wd, out_dtype="f32")
-            for name, want in (("Yatt", yatt), ("G", g), ("U", u), ("Hh", hh), ("Out", out)):
-                _check(f"{pname} {name} rows", _f64(_host(r.output(name)[bi, si])), want, RTOL_BF16)
+            _c4_check_after_attention(pname, r, weights)
+        finally:
+            r.close()
+        torch.cuda.empty_cache()
+
+
+def test_config4_decoder_block_with_attention_as_one_pass():
+    """The same workload with tr_set_fused_attention: the scores, exponentials and probabilities are never stored, so what
+    is compared is the attention output (sampled query rows of three heads against the oracle's vertex-by-vertex chain
+    from the inputs) and everything after it.  Under `tsplit8` the key label is cut and the group runs on its separate
+    vertices, which the launch log must show."""
+    import torch
+    import paper_2410_02682_amd as E
+    from paper_2410_02682_amd.runner import GraphRunner
+    w, dev = _inputs(4)
+    ref = _c4_attention_reference(w, dev)
+    weights = tuple(_host(dev[n]) for n in ("Wo", "Wg", "Wu", "Wd"))
+    for pname in w.partitionings:
+        print(f"config 4 full size, attention as one pass, partitioning {pname}", flush=True)
+        r = GraphRunner(w, pname, outputs=["Q", "O", "Yatt", "G", "U", "Hh", "Out"], fuse_attention=True)
+        try:
+            r.bind(dev)
+            E.tr_profile_enable(r.g, 64)
+            r.run()
+            torch.cuda.synchronize()
+            kernels = [rec["kernel"] for rec in E.tr_profile_read(r.g)]
+            assert kernels.count("attention_fused") == (0 if pname == "tsplit8" else 1), (pname, kernels)
+            for (b, h) in _C4_HEADS:
+                q, _, o = ref[(b, h)]
+                _check(f"{pname} Q[{b},:,{h},:]", _f64(_host(r.output("Q")[b, :, h, :])), q, RTOL_BF16)
+                _check(f"{pname} O[{b},:,{h},:]", _f64(_host(r.output("O")[b, _C4_SROWS, h, :])), o, RTOL_BF16)
+            _c4_check_after_attention(pname, r, weights)
         finally:
             r.close()
         torch.cuda.empty_cache()
