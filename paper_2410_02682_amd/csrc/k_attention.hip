@@ -223,18 +223,18 @@ __global__ __launch_bounds__(256, 2) void k_attention(const AttnParams p)
             // ---- scores: S^T (keys x queries) = K Q^T; the fragments of the next k-step are read under this one's products ----
             at_f32x16 sacc[2];
             const at_f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            at_u32x4 kf[2][2];
+            at_u32x4 kf[KT][2];
 #define EG_AT_KFRAG(KK, I) (*(const at_u32x4 *)(ks + ((I) * 32 + lrow) * RB + (((2 * (KK) + lhalf) ^ EG_AT_KKEY((I) * 32 + lrow)) << 4)))
-            kf[0][0] = EG_AT_KFRAG(0, 0);
-            kf[0][1] = EG_AT_KFRAG(0, 1);
 #pragma unroll
             for (int kk = 0; kk < KT; kk++) {
-                if (kk + 1 < KT) {
-                    kf[(kk + 1) & 1][0] = EG_AT_KFRAG(kk + 1, 0);
-                    kf[(kk + 1) & 1][1] = EG_AT_KFRAG(kk + 1, 1);
-                }
-                sacc[0] = at_mfma(kf[kk & 1][0], qf[kk], kk == 0 ? zero : sacc[0]);
-                sacc[1] = at_mfma(kf[kk & 1][1], qf[kk], kk == 0 ? zero : sacc[1]);
+                kf[kk][0] = EG_AT_KFRAG(kk, 0);
+                kf[kk][1] = EG_AT_KFRAG(kk, 1);
+            }
+            __builtin_amdgcn_sched_barrier(0);          // all reads on their way before the first product waits for one
+#pragma unroll
+            for (int kk = 0; kk < KT; kk++) {
+                sacc[0] = at_mfma(kf[kk][0], qf[kk], kk == 0 ? zero : sacc[0]);
+                sacc[1] = at_mfma(kf[kk][1], qf[kk], kk == 0 ? zero : sacc[1]);
             }
 #undef EG_AT_KFRAG
 
