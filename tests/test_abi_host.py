@@ -271,3 +271,60 @@ def test_fusion_of_softmax_chains_shrinks_the_workspace_and_can_be_switched_off(
     # fused, none of the chain's intermediate tensors exists and the result goes straight to the caller's relation
     assert sizes[True] == 0
     assert sizes[False] >= 2 * 64 * 256 * 2
+
+
+def _attention_graph(d_head, parts=None, fuse_attention=True, fuse=True, extra_output=None, mask_labels="st", t_len=192):
+    """Section 3's attention for 2 x 3 (batch, head) entries as its seven EinSums; returns (graph, vertex ids)."""
+    g = E.einsum_graph_create()
+    E.tr_set_fusion(g, fuse)
+    E.tr_set_fused_attention(g, fuse_attention)
+    dims = {"b": 2, "h": 3, "s": 160, "t": t_len, "d": d_head}
+    vid = {}
+    vid["Q"] = E.einsum_graph_add_input(g, [dims[l] for l in "bshd"], "bf16")
+    vid["K"] = E.einsum_graph_add_input(g, [dims[l] for l in "bthd"], "bf16")
+    vid["V"] = E.einsum_graph_add_input(g, [dims[l] for l in "bthd"], "bf16")
+    vid["M"] = E.einsum_graph_add_input(g, [dims[l] for l in mask_labels], "f32")
+    specs = [("T1", "bshd,bthd->bhst", "mul", "sum", 1.0, ("Q", "K"), "bf16"),
+             ("T2", f"bhst,{mask_labels}->bhst", "add", "none", d_head ** -0.5, ("T1", "M"), "bf16"),
+             ("C", "bhst->bhs", "ident", "max", 1.0, ("T2",), "f32"),
+             ("E", "bhst,bhs->bhst", "exp_sub", "none", 1.0, ("T2", "C"), "bf16"),
+             ("S", "bhst->bhs", "ident", "sum", 1.0, ("E",), "f32"),
+             ("P", "bhst,bhs->bhst", "div", "none", 1.0, ("E", "S"), "bf16"),
+             ("O", "bhst,bthd->bshd", "mul", "sum", 1.0, ("P", "V"), "bf16")]
+    for name, spec, ot, op, alpha, ins, dt in specs:
+        vid[name] = E.einsum_graph_add_einsum(g, spec, ot, op, alpha, [vid[i] for i in ins], dt)
+        E.einsum_graph_set_partition(g, vid[name], d_vector(spec, {l: c for l, c in (parts or {}).items() if l in spec}))
+    E.einsum_graph_mark_output(g, vid["O"])
+    if extra_output:
+        E.einsum_graph_mark_output(g, vid[extra_output])
+    return g, vid
+
+
+def test_attention_as_one_pass_keeps_no_intermediate_tensor_where_it_applies():
+    """What tr_set_fused_attention decides shows in the workspace size without a GPU: a group it takes needs only the
+    classes of the mask's tiles (a byte per 32 queries x 64 keys, four query groups to a word), a group it declines
+    needs what the separate vertices need."""
+    def size(**kw):
+        g, _ = _attention_graph(**kw)
+        n = E.tr_workspace_bytes(g)
+        E.einsum_graph_destroy(g)
+        return n
+    scores = 2 * 3 * 160 * 192 * 2                      # one bf16 tensor of the scores' shape
+    table = 256                                         # 8 query groups x 3 key blocks = 24 bytes, rounded to the arena's granule
+    for d_head in (32, 64, 128):
+        assert size(d_head=d_head) == table
+        assert size(d_head=d_head, parts={"b": 2, "h": 3, "s": 5}) == table      # cuts of batch and query labels are views
+    unfused = size(d_head=64, fuse_attention=False)
+    assert unfused >= scores                            # the scores at least (the softmax chain itself still runs as one pass)
+    # declined: the key label or the head dimension is cut, the head dimension has no variant, an intermediate is wanted,
+    # softmax fusion is off altogether, the added operand carries a batch label
+    assert size(d_head=64, parts={"t": 2}) >= scores
+    assert size(d_head=64, parts={"d": 2}) >= scores
+    assert size(d_head=48) == size(d_head=48, fuse_attention=False) >= scores
+    assert size(d_head=64, extra_output="P") >= scores
+    assert size(d_head=64, extra_output="C") >= scores
+    assert size(d_head=64, fuse=False) >= 3 * scores
+    assert size(d_head=64, mask_labels="hst") >= scores
+    with pytest.raises(E.EgError):
+        E.tr_set_fused_attention(None, True)
+
