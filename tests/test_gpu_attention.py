@@ -16,7 +16,8 @@ from synth_inputs.workloads import Vertex, Workload
 pytestmark = pytest.mark.gpu
 
 
-def attention_graph(q_spec, k_spec, v_spec, o_spec, dims, mask=None, t_dtype="bf16", o_dtype="bf16", parts=None, extra_output=None):
+def attention_graph(q_spec, k_spec, v_spec, o_spec, dims, mask=None, t_dtype="bf16", o_dtype="bf16", parts=None, extra_output=None,
+                    mask_dtype="f32"):
     """q_spec etc.: label strings of Q, K, V and the result over b, h (batch), s, t, d; the scores are (batch..)st.
     mask: None or the label string of the added operand."""
     batch = "".join(l for l in "bh" if l in q_spec)
@@ -25,7 +26,7 @@ def attention_graph(q_spec, k_spec, v_spec, o_spec, dims, mask=None, t_dtype="bf
     vs = [Vertex("Q", "bf16", bound=shape(q_spec)), Vertex("K", "bf16", bound=shape(k_spec)), Vertex("V", "bf16", bound=shape(v_spec))]
     alpha = 1.0 / dims["d"] ** 0.5
     if mask:
-        vs.append(Vertex("M", "f32", bound=shape(mask)))
+        vs.append(Vertex("M", mask_dtype, bound=shape(mask)))
         vs.append(Vertex("T1", t_dtype, spec=f"{q_spec},{k_spec}->{z}", inputs=("Q", "K")))
         vs.append(Vertex("T2", t_dtype, spec=f"{z},{mask}->{z}", otimes="add", oplus="none", alpha=alpha, inputs=("T1", "M")))
         src = "T2"
@@ -60,7 +61,7 @@ def inputs_of(w, mask_kind):
                 m[hole] = -np.inf
                 if mask_kind == "dead_row" and len(v.bound) == 2:
                     m[min(5, v.bound[0] - 1), :] = -np.inf     # one query with no admissible key: NaN on both sides
-            ins[v.name] = HostTensor.from_f32(m, "f32")
+            ins[v.name] = HostTensor.from_f32(m, v.dtype)
         else:
             ins[v.name] = HostTensor.from_f32(normal(w.seed, i, n, 1.0).reshape(v.bound), "bf16")
     return ins
@@ -146,6 +147,48 @@ def test_groups_the_pass_cannot_take_run_on_the_separate_vertices(kw, outputs):
     assert "attention_fused" not in kernels, kernels
     for n in outputs:
         check(got, ref, n)
+
+
+def test_mask_stored_as_bf16():
+    print("one-pass attention with a bf16 mask", flush=True)
+    w = attention_graph("bhsd", "bhtd", "bhtd", "bhsd", dict(b=2, h=2, s=190, t=256, d=64), "st", mask_dtype="bf16")
+    ins = inputs_of(w, "random")
+    ref = run_graph(w, ins)
+    got, kernels = run_fused(w, ins)
+    assert kernels == ["attention_fused"], kernels
+    check(got, ref)
+
+
+def test_operands_the_pass_cannot_address_are_refused_before_anything_runs():
+    """A group the structural test takes, bound to a V whose head dimension is not contiguous: tr_execute reports
+    EG_ERR_LIMIT (the message says which switch to turn off) and has launched nothing."""
+    import torch
+    import paper_2410_02682_amd as E
+    from paper_2410_02682_amd.runner import GraphRunner, to_device, to_host
+    print("one-pass attention bound to a V with a strided head dimension", flush=True)
+    w = attention_graph("hsd", "htd", "htd", "hsd", dict(h=2, s=64, t=64, d=64))
+    ins = inputs_of(w, None)
+    dev = {k: to_device(t) for k, t in ins.items()}
+    dev["V"] = dev["V"].transpose(1, 2).contiguous().transpose(1, 2)           # same values, d no longer the fastest label
+    for fuse_attention, fails in ((True, True), (False, False)):
+        r = GraphRunner(w, "d", fuse_attention=fuse_attention)
+        try:
+            r.bind(dev)
+            out = r.output("O")
+            out.fill_(7.0)
+            torch.cuda.synchronize()
+            if fails:
+                with pytest.raises(E.EgError) as err:
+                    r.run()
+                assert err.value.code == -13 and "tr_set_fused_attention" in str(err.value)      # EG_ERR_LIMIT
+                torch.cuda.synchronize()
+                assert bool((out == 7.0).all())
+            else:
+                r.run()
+                torch.cuda.synchronize()
+                check({"O": to_host(out)}, run_graph(w, ins))
+        finally:
+            r.close()
 
 
 def test_decoder_block_with_one_pass_attention():
