@@ -240,6 +240,32 @@ def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None,
         t = MEASURED_TRAFFIC.get((f"c{config}", pname, key))
         k["traffic"] = t
         kernels[key] = k
+    # The same steps once more as replays of captured HIP graphs (one graph per buffer set; tr_execute only enqueues
+    # kernels, so a caller may capture it): what launch gaps cost.  Reported beside the eager figure, never instead of it.
+    graph_ms = None
+    try:
+        for q in runners:
+            E.tr_profile_enable(q.g, 0)
+        side = torch.cuda.Stream()
+        graphs = []
+        with torch.cuda.stream(side):
+            for q in runners:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    q.run(torch.cuda.current_stream())
+                graphs.append(g)
+        torch.cuda.synchronize()
+        for i in range(max(warmup, 1) * len(graphs)):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        g0 = time.perf_counter()
+        for i in range(steps):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - g0) * 1e3 / steps
+        del graphs
+    except Exception as e:                               # the eager figures above stand on their own
+        print(f"bench.py: HIP graph replay not measured ({e})", file=sys.stderr)
     desc = f"{w.name} dims {json.dumps(w.dims)}, partitioning '{pname}': {json.dumps(r.part)}" \
         + (" [alternative method: aggregation inside the contraction kernels]" if fuse_aggregation else "") \
         + (" [alternative: attention as one pass]" if fuse_attention else "")
@@ -247,7 +273,7 @@ def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None,
     for q in runners[1:]:
         q.close()
     r.close()
-    return ms_per_step, kernels, flops_per_step, desc, dev, w, n_sets
+    return ms_per_step, kernels, flops_per_step, desc, dev, w, (n_sets, graph_ms)
 
 
 def main():
@@ -279,7 +305,7 @@ def main():
     if args.contract_tile:
         t = [int(x) for x in args.contract_tile.split("x")]
         contract = dict(tile=(t[0], t[-1]), waves=args.contract_waves)
-    ms_per_step, kernels, flops_per_step, desc, dev, w, n_sets = measure(args.config, pname, args.steps, args.warmup, args.fuse_aggregation, contract, args.fuse_attention)
+    ms_per_step, kernels, flops_per_step, desc, dev, w, (n_sets, graph_ms) = measure(args.config, pname, args.steps, args.warmup, args.fuse_aggregation, contract, args.fuse_attention)
     value = flops_per_step / (ms_per_step * 1e-3) / 1e12
 
     dom = "contract_mfma" if "contract_mfma" in kernels else max(kernels, key=lambda k: kernels[k]["share_of_step"])
@@ -292,7 +318,7 @@ def main():
            "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "f32" if args.config == 1 else "bf16", "data": "synthetic",
            "config": {"workload": desc},
-           "roofline": roofline, "kernels": kernels, "buffer_sets": n_sets}
+           "roofline": roofline, "kernels": kernels, "buffer_sets": n_sets, "hip_graph_replay_ms_per_step": graph_ms}
     if not args.no_ceilings:
         out["measured_ceilings"] = ceilings()
         if dom == "contract_mfma" and args.config != 1:
@@ -306,10 +332,10 @@ def main():
         # the other full-size workloads, a few steps each, so that their kernel families are measured in the same run
         others = {}
         for c, alt in ((3, False), (4, False), (5, False), (4, True)):
-            ms, ks, fl, d, dv, _, _ = measure(c, DEFAULT_PART[c], 5, 2, fuse_attention=alt)
+            ms, ks, fl, d, dv, _, (_, gms) = measure(c, DEFAULT_PART[c], 5, 2, fuse_attention=alt)
             del dv
             torch.cuda.empty_cache()
-            others[f"c{c}" + ("_attention_as_one_pass" if alt else "")] = {"workload": d, "ms_per_step": ms, "contraction_tflops_per_step": fl / (ms * 1e-3) / 1e12,
+            others[f"c{c}" + ("_attention_as_one_pass" if alt else "")] = {"workload": d, "ms_per_step": ms, "hip_graph_replay_ms_per_step": gms, "contraction_tflops_per_step": fl / (ms * 1e-3) / 1e12,
                                "kernels": {k: {f: v[f] for f in ("launches_per_step", "avg_launch_ms", "bound", "achieved", "peak", "unit", "frac", "traffic")}
                                            for k, v in ks.items()}}
         out["other_workloads"] = others
