@@ -103,7 +103,8 @@ typedef enum {
     EG_KERNEL_GENERIC = 4,         /* any EinSum: one output element per lane, loop over l_agg       */
     EG_KERNEL_CONTRACT_ALU = 5,    /* contraction-shaped EinSum with another (x)/(+) pair (squared L2, L-infinity, ...): LDS tiles, vector ALU */
     EG_KERNEL_SOFTMAX_FUSED = 6,   /* the softmax vertices max, exp(x - max), sum, division (and a preceding alpha*x + y) in one pass per row */
-    EG_KERNEL_ATTENTION_FUSED = 7  /* Section 3's attention, scores contraction to weighted sum, in one pass (tr_set_fused_attention) */
+    EG_KERNEL_ATTENTION_FUSED = 7, /* Section 3's attention, scores contraction to weighted sum, in one pass (tr_set_fused_attention) */
+    EG_KERNEL_AGGREGATE_TILES = 8  /* reported for an aggregation launch that read tile-ordered partial slabs (tr_set_tiled_partials) */
 } eg_kernel_kind;
 
 /* Read-only view of one vertex's plan.  All pointers are host memory owned by the graph and stay
@@ -242,6 +243,14 @@ int tr_set_fusion(eg_graph *g, int enable);
  * contraction.  Other vertices are not affected.  Changes the workspace size. */
 int tr_set_fused_aggregation(eg_graph *g, int enable);
 
+/* How a contraction on the direct-to-LDS kernel lays out the fp32 partial blocks that the aggregation stage sums (Section
+ * 4.3's two stages, unchanged).  enable != 0 (the default): when the vertex's blocks are whole output tiles of that kernel,
+ * a partial slab holds the tiles one after the other, each in the order the kernel's accumulators lie in registers, and
+ * the aggregation kernel that follows undoes the order; same workspace size, same sums in the same order, results equal
+ * bit for bit.  enable = 0: every slab is the dense row-major tensor (what tr_aggregate takes).  For comparisons and
+ * tests.  Takes effect at the next tr_execute. */
+int tr_set_tiled_partials(eg_graph *g, int enable);
+
 /* Another alternative for comparison, off by default.  Section 3 writes attention as a contraction Q x K^T over the head
  * dimension, the softmax chain over the key label (with alpha * x + mask in front when the graph has it) and a second
  * contraction with V over the key label.  With enable != 0 (and tr_set_fusion on) tr_execute runs such a group as one
@@ -282,7 +291,7 @@ int tr_profile_reset(eg_graph *g);
 int tr_profile_count(eg_graph *g);
 
 /* Recorded launch i: its vertex, whether it was the join kernel (0) or the aggregation (1), its
- * eg_kernel_kind (EG_KERNEL_NONE for the aggregation) and elapsed milliseconds.  The caller must have
+ * eg_kernel_kind (for the aggregation EG_KERNEL_NONE, or EG_KERNEL_AGGREGATE_TILES) and elapsed milliseconds.  The caller must have
  * synchronised the stream.  Host outputs, any may be NULL. */
 int tr_profile_get(eg_graph *g, int i, int *vertex, int *stage, int *kernel, float *ms);
 

@@ -56,6 +56,7 @@ EXPORTS = {
     "tr_aggregate": (ctypes.c_int, [ctypes.c_int, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]),
     "tr_set_fusion": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int]),
     "tr_set_fused_attention": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int]),
+    "tr_set_tiled_partials": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int]),
     "tr_set_fused_aggregation": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int]),
     "tr_set_contract_variant": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int]),
     "tr_profile_enable": (ctypes.c_int, [ctypes.c_void_p, ctypes.c_int]),

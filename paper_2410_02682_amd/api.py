@@ -17,7 +17,7 @@ DTYPE = {"f32": 0, "bf16": 1}
 OPLUS = {"none": 0, "sum": 1, "max": 2}
 OTIMES = {"mul": 0, "add": 1, "sub": 2, "div": 3, "sqdiff": 4, "absdiff": 5, "exp_sub": 6, "relu_grad": 7,
           "silu_mul": 8, "ident": 32, "scale": 33, "relu": 34, "exp": 35, "log": 36}
-KERNEL_NAMES = {0: "none", 1: "contract_mfma", 2: "map", 3: "reduce_row", 4: "generic", 5: "contract_alu", 6: "softmax_fused", 7: "attention_fused"}
+KERNEL_NAMES = {0: "none", 1: "contract_mfma", 2: "map", 3: "reduce_row", 4: "generic", 5: "contract_alu", 6: "softmax_fused", 7: "attention_fused", 8: "aggregate_tiles"}
 
 
 class EgError(RuntimeError):
@@ -142,6 +142,10 @@ def tr_aggregate(oplus: str, partials_ptr: int, n_agg: int, slab_elems: int, out
 
 def tr_set_fusion(g, enable: bool) -> None:
     _check(_lib.load().tr_set_fusion(g, 1 if enable else 0))
+
+
+def tr_set_tiled_partials(g, enable: bool) -> None:
+    _check(_lib.load().tr_set_tiled_partials(g, 1 if enable else 0))
 
 
 def tr_set_fused_attention(g, enable: bool) -> None:

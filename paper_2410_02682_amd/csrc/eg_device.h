@@ -140,6 +140,35 @@ __device__ __forceinline__ void decode_tuple(const TupleSpace &ts, int64_t t, in
     }
 }
 
+// Tuple t -> index of its output block (row-major over the partitioned labels that are not aggregated).
+__device__ __forceinline__ int64_t tuple_group(const TupleSpace &ts, int64_t t)
+{
+    int64_t g = 0;
+    uint32_t rem = (uint32_t)t;
+    for (int l = ts.n - 1; l >= 0; l--) {
+        uint32_t dd = (uint32_t)ts.d[l];
+        uint32_t q = rem / dd, k = rem - q * dd;
+        rem = q;
+        g += (int64_t)k * ts.grp_w[l];
+    }
+    return g;
+}
+
+// ... and back: output block index -> Z offset of the block.
+__device__ __forceinline__ int64_t group_offset_z(const TupleSpace &ts, int64_t g)
+{
+    int64_t oz = 0;
+    uint32_t rem = (uint32_t)g;
+    for (int l = ts.n - 1; l >= 0; l--) {
+        if (ts.grp_w[l] == 0) continue;                // an aggregated label: no part of the block index
+        uint32_t dd = (uint32_t)ts.d[l];
+        uint32_t q = rem / dd, k = rem - q * dd;
+        rem = q;
+        oz += (int64_t)k * ts.step_z[l];
+    }
+    return oz;
+}
+
 // Flat index within a collapsed index space -> offsets in X / Y / Z.
 __device__ __forceinline__ void decode_dims(const StridedDims &d, int64_t e, int64_t &ox, int64_t &oy, int64_t &oz)
 {

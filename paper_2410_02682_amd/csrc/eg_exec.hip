@@ -75,6 +75,13 @@ static TupleSpace tuple_space(const Vertex &v, const LabelInfo &li)
         aggw[v.agg[i]] = (int32_t)w;
         w *= v.d[v.agg[i]];
     }
+    int32_t grpw[kMaxLabels] = {0};
+    w = 1;
+    for (int l = li.nl - 1; l >= 0; l--) {
+        if (v.d[l] <= 1 || aggw[l] > 0) continue;
+        grpw[l] = (int32_t)w;
+        w *= v.d[l];
+    }
     int n = 0;
     for (int l = 0; l < li.nl; l++) {
         if (v.d[l] <= 1) continue;
@@ -83,6 +90,7 @@ static TupleSpace tuple_space(const Vertex &v, const LabelInfo &li)
         ts.step_y[n] = li.ext[l] * li.sy[l];
         ts.step_z[n] = li.ext[l] * li.sz[l];
         ts.agg_w[n] = aggw[l];
+        ts.grp_w[n] = grpw[l];
         n++;
     }
     ts.n = n;
@@ -247,6 +255,7 @@ static bool build_contract(const Vertex &v, const LabelInfo &li, const Operand &
 // ------------------------------------------------------------------------------------------------
 struct Routed {
     int kind = EG_KERNEL_NONE;
+    bool swapped = false;          // contraction: X and Y changed places (see route)
     ContractParams cp;
     MapParams mp;
     ReduceParams rp;
@@ -345,6 +354,7 @@ static int route(const Vertex &v, const Operand &X, const Operand *Y, const std:
         r.cp.ts = tc;
         r.cp.out = out;
         r.cp.n_tuples = n_tuples;
+        r.swapped = swap;
         r.kind = v.otimes == EG_MUL && v.oplus == EG_AGG_SUM ? EG_KERNEL_CONTRACT_MFMA : EG_KERNEL_CONTRACT_ALU;
         return EG_OK;
     }
@@ -899,6 +909,25 @@ static int launch_routed(Routed &r, void *stream)
     }
 }
 
+// What the aggregation of tile-ordered partial slabs needs to know about the destination: the contraction's role groups
+// once more, with the destination's strides in place of the dense slab's (same labels in the same order, so row, column
+// and batch indices mean the same; only which neighbours fuse may differ).
+static bool tiles_params(const Vertex &v, const Operand &X, const Operand &Y, const std::vector<int64_t> &zdest, const Routed &r, AggTilesParams &tp)
+{
+    LabelInfo li = label_info(v, X, &Y, zdest);
+    LabelInfo lc = li;
+    if (r.swapped)
+        for (int l = 0; l < li.nl; l++) { std::swap(lc.inx[l], lc.iny[l]); std::swap(lc.sx[l], lc.sy[l]); }
+    ContractParams c2;
+    if (!build_contract(v, lc, r.swapped ? Y : X, r.swapped ? X : Y, c2)) return false;
+    if (c2.M != r.cp.M || c2.N != r.cp.N || c2.n_batch != r.cp.n_batch) return false;
+    memset(&tp, 0, sizeof tp);
+    tp.ts = tuple_space(v, li);
+    tp.batch = c2.batch; tp.m = c2.m; tp.n = c2.n;
+    tp.n_batch = c2.n_batch;
+    return true;
+}
+
 static int aggregate_into(int oplus, const void *partials, int64_t n_agg, int64_t slab_elems, int64_t slab_stride, void *out, int out_dtype,
                           const std::vector<int64_t> &bound, const std::vector<int64_t> &stride, void *stream)
 {
@@ -944,6 +973,13 @@ int tr_set_fused_aggregation(eg_graph *g, int enable)
 {
     if (!g) return fail(EG_ERR_NULL, "graph is NULL");
     g->agg_in_kernel = enable != 0;
+    return EG_OK;
+}
+
+int tr_set_tiled_partials(eg_graph *g, int enable)
+{
+    if (!g) return fail(EG_ERR_NULL, "graph is NULL");
+    g->tiled_partials = enable != 0;
     return EG_OK;
 }
 
@@ -1077,7 +1113,7 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
 
     // route everything first so that a failure launches nothing
     struct Step { int vertex; Routed r; bool agg; int64_t slabs, stride; const void *partials; void *dst; std::vector<int64_t> dst_stride;
-                  bool fused = false; SoftmaxParams sp; bool attn = false; AttnParams ap; };
+                  bool fused = false; SoftmaxParams sp; bool attn = false; AttnParams ap; bool tiled = false; AggTilesParams tp; };
     std::vector<Step> steps;
     auto operand_of = [&](int u) {
         Operand o;
@@ -1245,6 +1281,7 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
         }
         int rc = route(vr, X, v.n_in > 1 ? &Y : nullptr, zstride, out, s.r, refined ? 1 : L.split[i]);
         if (rc) return rc;
+        const Vertex *routed = &vr;
         if (merged && s.r.kind != EG_KERNEL_CONTRACT_MFMA && s.r.kind != EG_KERNEL_CONTRACT_ALU)
             return fail(EG_ERR_LIMIT, "vertex %d: the bound relations' strides leave no contraction kernel for the merged aggregation; turn tr_set_fused_aggregation off", i);
         if (L.split[i] > 1 && s.r.kind != EG_KERNEL_REDUCE_ROW &&
@@ -1256,6 +1293,7 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
             if (!s.agg) { out.ptr = s.dst; out.slab_elems = 0; out.dtype = v.dtype; zstride = Z.stride; }
             rc = route(v, X, v.n_in > 1 ? &Y : nullptr, zstride, out, s.r, 1);
             if (rc) return rc;
+            routed = &v;
         }
         if (s.r.kind == EG_KERNEL_REDUCE_ROW && !refined && s.r.rp.split != L.split[i]) s.r.rp.split = L.split[i];
         s.stride = out.slab_elems;                 // what the join kernel was given
@@ -1264,6 +1302,27 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
             s.r.cp.force_tile_m = g->contract_tile_m;
             s.r.cp.force_tile_n = g->contract_tile_n;
             s.r.cp.force_waves = g->contract_waves;
+        }
+        // Partial slabs of the direct-to-LDS contraction kernel in tile order when its tiles are whole: the slab has the same
+        // size, only the order of its elements is a matter between that kernel and the aggregation that follows it.
+        if (s.agg && g->tiled_partials && s.r.kind == EG_KERNEL_CONTRACT_MFMA && contract_takes_dma(s.r.cp)) {
+            const Vertex &vu = *routed;
+            int tm = 0, tn = 0, nw = 0;
+            contract_dma_variant(s.r.cp, tm, tn, nw);
+            const ContractParams &cp = s.r.cp;
+            if (tm > 0 && cp.M % tm == 0 && cp.N % tn == 0 && vu.plan.n_tuples % s.slabs == 0 && v.n_in == 2 &&
+                tiles_params(vu, X, Y, Z.stride, s.r, s.tp)) {
+                AggTilesParams &tp = s.tp;
+                tp.tm = tm; tp.tn = tn; tp.nw = nw;
+                tp.tiles_m = (int32_t)(cp.M / tm); tp.tiles_n = (int32_t)(cp.N / tn);
+                tp.tiles = vu.plan.n_tuples / s.slabs * cp.n_batch * tp.tiles_m * tp.tiles_n;
+                tp.partials = (const float *)s.partials; tp.n_agg = s.slabs; tp.slab_stride = s.stride;
+                tp.out = s.dst; tp.out_dtype = v.dtype;
+                if (tp.tiles * tm * tn == numel(v.bound)) {
+                    s.tiled = true;
+                    s.r.cp.tile_order = 1;
+                }
+            }
         }
         steps.push_back(std::move(s));
     }
@@ -1289,7 +1348,8 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
             int rc = s.attn ? launch_attention(s.ap, hip_stream) : s.fused ? launch_softmax_rows(s.sp, hip_stream) : launch_routed(s.r, hip_stream);
             if (rc) return rc;
             if (s.agg) {
-                rc = aggregate_into(v.oplus, s.partials, s.slabs, numel(v.bound), s.stride, s.dst, v.dtype, v.bound, s.dst_stride, hip_stream);
+                rc = s.tiled ? launch_aggregate_tiles(s.tp, hip_stream)
+                             : aggregate_into(v.oplus, s.partials, s.slabs, numel(v.bound), s.stride, s.dst, v.dtype, v.bound, s.dst_stride, hip_stream);
                 if (rc) return rc;
             }
         }
@@ -1301,8 +1361,9 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
                          : timed(s.vertex, 0, s.r.kind, s.agg ? s.slabs : 0, [&] { return launch_routed(s.r, hip_stream); });
         if (rc) return rc;
         if (s.agg) {
-            rc = timed(s.vertex, 1, EG_KERNEL_NONE, s.slabs, [&] {
-                return aggregate_into(v.oplus, s.partials, s.slabs, numel(v.bound), s.stride, s.dst, v.dtype, v.bound, s.dst_stride, hip_stream);
+            rc = timed(s.vertex, 1, s.tiled ? EG_KERNEL_AGGREGATE_TILES : EG_KERNEL_NONE, s.slabs, [&] {
+                return s.tiled ? launch_aggregate_tiles(s.tp, hip_stream)
+                               : aggregate_into(v.oplus, s.partials, s.slabs, numel(v.bound), s.stride, s.dst, v.dtype, v.bound, s.dst_stride, hip_stream);
             });
             if (rc) return rc;
         }

@@ -24,11 +24,13 @@ constexpr int kMaxDims = 8;      // collapsed dimensions in the map / reduce ker
 
 // The join's tuple space (Section 4.3 of the paper): tuple t is the key over the schema in row-major
 // order of I(d).  step_* = block extent * element stride of the label in X / Y / Z (0 when absent), so a
-// block's base offset is sum_l key[l] * step[l].  agg_w[l] is the weight of key[l] in aggIdx.
+// block's base offset is sum_l key[l] * step[l].  agg_w[l] is the weight of key[l] in aggIdx, grp_w[l] its weight in
+// the row-major index of the output block over the labels that are not aggregated.
 struct TupleSpace {
     int32_t n;
     int32_t d[kMaxLabels];
     int32_t agg_w[kMaxLabels];
+    int32_t grp_w[kMaxLabels];    // weight of key[l] in the index of the tuple's output block (0 for aggregated labels)
     int64_t step_x[kMaxLabels];
     int64_t step_y[kMaxLabels];
     int64_t step_z[kMaxLabels];
@@ -71,6 +73,27 @@ struct ContractParams {
     int32_t force_kernel;         // 0: the launcher chooses; 1: register-staged kernel; 2: direct-to-LDS kernel wherever the layout allows (tr_set_contract_variant)
     int32_t force_tile_m, force_tile_n;   // 0: the launcher chooses; 128 x 128, 256 x 128 or 256 x 256: tile of the direct-to-LDS kernel
     int32_t force_waves;          // 0: the launcher chooses; 4 / 8: waves per workgroup of the 256 x 256 direct-to-LDS kernel
+    int32_t tile_order;           // 1: partial slabs are written tile after tile in the accumulators' order (see AggTilesParams)
+};
+
+// Aggregation of partial slabs that the direct-to-LDS contraction kernel wrote in tile order: a slab then holds the
+// output tiles one after the other (output block, batch entry, tile row, tile column), each tile as the waves'
+// accumulators lie in registers: 16-byte chunk (((wave * RT + i) * NT + j) * 4 + g) * 64 + lane holds rows
+// 32 i + 8 g + 4 (lane / 32) .. + 3 and column 32 j + lane % 32 of the wave's patch, so the join kernel stores whole
+// registers, 1 KiB per instruction, without a round trip through LDS, and the layout is undone here, where the
+// kernel waits for memory anyway.  Same sums in the same order as the dense layout.
+struct AggTilesParams {
+    TupleSpace ts;                // step_z: the destination's
+    DimList batch, m, n;          // batch.s2, m.s1, n.s1: the destination's element strides
+    int64_t n_batch;
+    int32_t tm, tn, nw;           // tile and waves of the join kernel
+    int32_t tiles_m, tiles_n;
+    int64_t tiles;                // per slab
+    const float *partials;
+    int64_t n_agg, slab_stride;   // slabs and the element stride between them
+    void *out;
+    int32_t out_dtype;
+    int32_t vec;                  // filled by the launcher: the destination takes 16-byte stores along its rows
 };
 
 struct StridedDims {              // collapsed index space with per-operand element strides
@@ -198,6 +221,9 @@ int launch_generic(const GenericParams &p, void *stream);
 int launch_aggregate(const AggregateParams &p, void *stream);
 int launch_softmax_rows(SoftmaxParams &p, void *stream);
 int launch_attention(AttnParams &p, void *stream);
+int launch_aggregate_tiles(AggTilesParams &p, void *stream);
+bool contract_takes_dma(const ContractParams &p);                              // launch_contract will hand p to the direct-to-LDS kernel
+void contract_dma_variant(const ContractParams &p, int &tm, int &tn, int &nw);   // ... which will run this tile shape and wave count
 size_t attention_mask_class_bytes(int64_t S, int64_t T);
 
 // ------------------------------------------------------------------------------------------------
@@ -238,6 +264,7 @@ struct eg_graph {
     // executor state
     bool fuse = true;                               // fuse softmax chains where the partitioning allows (tr_set_fusion)
     bool fuse_attention = false;                    // scores, softmax chain and weighted sum as one pass (tr_set_fused_attention)
+    bool tiled_partials = true;                     // partial slabs of whole-tile contractions in tile order (tr_set_tiled_partials)
     bool agg_in_kernel = false;                     // contractions sum over partitioned contracted labels inside the kernel (tr_set_fused_aggregation)
     int contract_kernel = 0, contract_tile_m = 0, contract_tile_n = 0, contract_waves = 0;   // tr_set_contract_variant (0: the launchers choose)
     bool profile = false;

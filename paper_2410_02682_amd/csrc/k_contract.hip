@@ -474,6 +474,20 @@ static int launch_cfg(ContractParams &p, void *stream)
     return EG_OK;
 }
 
+// Blocks with at least 128 rows or columns take the direct-to-LDS kernel when their layout allows; force_kernel
+// (tr_set_contract_variant) forces one of the two.  A handful of small fp32 blocks (configuration 1: eight blocks of
+// 128^3) is a latency chain of slow MFMAs on as many compute units, which 64 x 64 tiles of the register-staged kernel
+// spread over four times as many.  (Skinny products included: with 8192 x 4096 x 32..96 the half-empty tiles of that
+// kernel still finish in 0.045 ms against 0.105-0.124 ms here.)
+bool contract_takes_dma(const ContractParams &p)
+{
+    if (p.otimes != EG_MUL || p.oplus != EG_AGG_SUM) return false;
+    const int64_t tiles128 = p.n_tuples * p.n_batch * ((p.M + 127) / 128) * ((p.N + 127) / 128);
+    const bool tiny_f32 = p.in_dtype == EG_F32 && tiles128 <= 64;
+    const bool want_dma = p.force_kernel ? p.force_kernel == 2 : ((p.M >= 128 || p.N >= 128) && !tiny_f32);
+    return want_dma && contract_dma_eligible(p);
+}
+
 int launch_contract(ContractParams &p, void *stream)
 {
     // what the kernel assumes, re-checked here so that a wrong table can never reach the device
@@ -492,16 +506,8 @@ int launch_contract(ContractParams &p, void *stream)
         if (p.in_dtype == EG_BF16) return launch_alu_ops<Cfg<128, 128, 64, 64, true>>(p, stream);
         return launch_alu_ops<Cfg<128, 128, 64, 64, false>>(p, stream);
     }
-    // Blocks with at least 128 rows or columns take the direct-to-LDS kernel when their layout allows; force_kernel
-    // (tr_set_contract_variant) forces one of the two.  A handful of small fp32 blocks (configuration 1:
-    // eight blocks of 128^3) is a latency chain of slow MFMAs on as many compute units, which 64 x 64 tiles of the
-    // register-staged kernel spread over four times as many.
     const int64_t tiles128 = p.n_tuples * p.n_batch * ((p.M + 127) / 128) * ((p.N + 127) / 128);
-    const bool tiny_f32 = p.in_dtype == EG_F32 && tiles128 <= 64;
-    // (skinny products included: with 8192 x 4096 x 32..96 the half-empty tiles of that kernel still finish in 0.045 ms
-    // against 0.105-0.124 ms here)
-    const bool want_dma = p.force_kernel ? p.force_kernel == 2 : ((p.M >= 128 || p.N >= 128) && !tiny_f32);
-    if (want_dma && contract_dma_eligible(p)) return launch_contract_dma(p, stream);
+    if (contract_takes_dma(p)) return launch_contract_dma(p, stream);
     if (tiles128 <= 64) {
         if (p.in_dtype == EG_BF16) return launch_cfg<Cfg<64, 64, 32, 32, true>>(p, stream);
         return launch_cfg<Cfg<64, 64, 32, 32, false>>(p, stream);

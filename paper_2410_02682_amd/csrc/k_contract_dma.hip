@@ -205,6 +205,7 @@ struct TileInfo {
     const char *xb, *yb;     // X and Y at the tuple's blocks, the batch entry and the tile's first row / column
     int64_t ox0, oy0;        // element offsets of that first row / column inside the block (what lane offsets are relative to)
     int64_t bz, agg;         // Z element offset of the tuple's block and batch entry; aggIdx of the tuple
+    int64_t slab_tile;       // with tile-ordered partial slabs: the tile's place in its slab
 };
 
 // Output tiles are TM x TN; the NW waves of a workgroup form a 2 x NW/2 grid of patches; a stage holds KB bytes of k per row.
@@ -311,6 +312,7 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW, NS) <= 160 *
         t.yb = uniform_ptr((const char *)p.y + (by + t.oy0) * ES);
         t.bz = bz;
         t.agg = agg;
+        t.slab_tile = p.tile_order ? ((tuple_group(p.ts, tuple) * nb + bidx) * (int64_t)p.tiles_m + tile_m) * (int64_t)p.tiles_n + tile_n : 0;
     };
     const int kin = p.k.n - 1;                        // innermost K label: every stage lies inside one run of it
     const int64_t run = p.k.n == 1 ? p.K : p.k.ext[kin];            // k of one run of the innermost K label
@@ -554,7 +556,20 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW, NS) <= 160 *
         const bool slab = p.out.slab_elems != 0;
         const int mrem = (int)(p.M - cur.m0 < TM ? p.M - cur.m0 : TM);     // rows / columns of the tile inside the block
         const int nrem = (int)(p.N - cur.n0 < TN ? p.N - cur.n0 : TN);
-        if (p.out_vec) {
+        if (p.tile_order) {
+            // Partial slabs in tile order (the launcher set this only for whole tiles): every accumulator register group goes out
+            // as it is, 16 bytes per lane and 1 KiB per instruction, no staging; the aggregation kernel undoes the layout.
+            float *tb = (float *)zb + cur.slab_tile * (TM * TN) + (int64_t)wave_u * (RT * NT * 4 * 64 * 4);
+#pragma unroll
+            for (int i = 0; i < RT; i++)
+#pragma unroll
+                for (int j = 0; j < NT; j++)
+#pragma unroll
+                    for (int g = 0; g < 4; g++) {
+                        const f32x4 val = {p.alpha * acc[i][j][4 * g], p.alpha * acc[i][j][4 * g + 1], p.alpha * acc[i][j][4 * g + 2], p.alpha * acc[i][j][4 * g + 3]};
+                        __builtin_nontemporal_store(val, (f32x4 *)(tb + (((i * NT + j) * 4 + g) * 64 + elane) * 4));
+                    }
+        } else if (p.out_vec) {
             // Z is contiguous along the tile's columns: each wave stages 8 rows x CW columns of its patch at a time
             // in LDS (the row pitch leaves 32 bytes of padding, which keeps the two half-waves on different banks)
             // and writes them out as whole row segments, 16 bytes per lane.  LDS operations of one wave execute
@@ -741,17 +756,22 @@ bool contract_dma_eligible(const ContractParams &p)
     return true;
 }
 
-int launch_contract_dma(ContractParams &p, void *stream)
+// compute units of the current device, rounded down to whole XCD rounds (0: the device cannot be queried)
+static int dma_cu_count()
 {
-    if (!p.x || !p.y || !p.out.ptr) return fail(EG_ERR_NULL, "contraction: NULL operand");
-    if (!contract_dma_eligible(p)) return fail(EG_ERR_LIMIT, "contraction: shape not eligible for the direct-to-LDS kernel");
     static int n_cu = 0;
     if (!n_cu) {
         int dev = 0;
         hipDeviceProp_t prop;
-        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return fail(EG_ERR_HIP, "cannot query the device");
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return 0;
         n_cu = prop.multiProcessorCount > 8 ? prop.multiProcessorCount / 8 * 8 : 8;
     }
+    return n_cu;
+}
+
+void contract_dma_variant(const ContractParams &p, int &tm, int &tn, int &nw)
+{
+    const int n_cu = dma_cu_count();
     // Tile shape.  256 x 256, one workgroup per compute unit, is the fastest per flop on long reductions (fewest bytes into LDS per
     // flop, full 128-byte lines from operands contiguous along K).  256 x 128 with half-depth stages runs two workgroups per unit,
     // one's per-tile phases under the other's MFMAs; its main loop is a fifth slower (64-byte requests for operands contiguous
@@ -766,16 +786,28 @@ int launch_contract_dma(ContractParams &p, void *stream)
     auto count = [&](int tm, int tn) { return tuples * ((p.M + tm - 1) / tm) * ((p.N + tn - 1) / tn); };
     const int64_t small = count(128, 128);
     const int64_t ntail = p.N % 256;
-    int tm, tn;
     if (small <= 2 * n_cu) tm = tn = 128;
     else if (!f32 && (p.K <= 128 || (ntail > 0 && ntail <= 128 && p.N < 1024))) { tm = 256; tn = 128; }
     else if (4 * count(256, 256) * 10 > small * 14) tm = tn = 128;
     else tm = tn = 256;
     if (p.force_tile_m && p.force_tile_n) { tm = p.force_tile_m; tn = p.force_tile_n; }   // tr_set_contract_variant: comparisons and tests
     if (f32 && tm != tn) tn = tm;
+    nw = (tm == 256 && tn == 256 && (f32 || p.force_waves != 4)) ? 8 : 4;
+}
+
+int launch_contract_dma(ContractParams &p, void *stream)
+{
+    if (!p.x || !p.y || !p.out.ptr) return fail(EG_ERR_NULL, "contraction: NULL operand");
+    if (!contract_dma_eligible(p)) return fail(EG_ERR_LIMIT, "contraction: shape not eligible for the direct-to-LDS kernel");
+    const int n_cu = dma_cu_count();
+    if (!n_cu) return fail(EG_ERR_HIP, "cannot query the device");
+    const bool f32 = p.in_dtype == EG_F32;
+    const int64_t tuples = p.n_tuples * p.n_batch;
+    int tm, tn, nw;
+    contract_dma_variant(p, tm, tn, nw);
+    if (p.tile_order && (p.M % tm || p.N % tn || !p.out.slab_elems)) return fail(EG_ERR_LIMIT, "contraction: tile-ordered partial slabs need whole tiles");
     // the variant: stage depth and waves follow from the tile shape
     const int kb = (tm == 256 && tn == 128) ? 64 : 128;
-    const int nw = (tm == 256 && tn == 256 && (f32 || p.force_waves != 4)) ? 8 : 4;
     p.tiles_m = (int32_t)((p.M + tm - 1) / tm);
     p.tiles_n = (int32_t)((p.N + tn - 1) / tn);
     const int64_t wgs = tuples * p.tiles_m * p.tiles_n;
@@ -797,6 +829,129 @@ int launch_contract_dma(ContractParams &p, void *stream)
     if (tn == 128) return dma::launch_layout<256, 128, 64, 3, 4, false>(p, stream);
     if (nw == 4) return dma::launch_layout<256, 256, 128, 2, 4, false>(p, stream);
     return dma::launch_layout<256, 256, 128, 2, 8, false>(p, stream);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Aggregation of tile-ordered partial slabs (AggTilesParams): one workgroup per wave patch of an output tile.
+// The sums run over the slabs in ascending order in fp32 with one final cast, as in the dense-layout kernels
+// (Section 4.2: the aggregation operator over the tuples that share an output block).
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ int64_t agg_tiles_offset(const DimList &g, int64_t idx, bool batch)
+{
+    int64_t o = 0;
+    uint32_t rem = (uint32_t)idx;
+    for (int i = g.n - 1; i >= 0; i--) {
+        const uint32_t e = (uint32_t)g.ext[i], q = rem / e, k = rem - q * e;
+        rem = q;
+        o += (int64_t)k * (batch ? g.s2[i] : g.s1[i]);
+    }
+    return o;
+}
+
+template <int N>
+__global__ __launch_bounds__(256) void k_aggregate_tiles(const AggTilesParams p)
+{
+    __shared__ int64_t zr[128], zc[128];               // Z offsets of the patch's rows and columns
+    __shared__ __attribute__((aligned(16))) float rows[32 * (128 + 4)];    // 32 rows of the patch on their way from register order to row order
+    const int tid = threadIdx.x;
+    const int WN = p.nw / 2, RT = p.tm / 64, NT = p.tn / WN / 32;
+    const int PR = 32 * RT, PC = 32 * NT, pitch = PC + 4;
+    // workgroup -> (output block, batch entry, tile row, tile column, wave of the join kernel)
+    const uint32_t wave = blockIdx.x % (uint32_t)p.nw;
+    int64_t T = blockIdx.x / (uint32_t)p.nw;
+    const int64_t tile = T;
+    const int64_t tile_n = T % p.tiles_n; T /= p.tiles_n;
+    const int64_t tile_m = T % p.tiles_m; T /= p.tiles_m;
+    const int64_t bidx = T % p.n_batch, grp = T / p.n_batch;
+    const int64_t bz = group_offset_z(p.ts, grp) + agg_tiles_offset(p.batch, bidx, true);
+    const int64_t row0 = tile_m * p.tm + (wave / WN) * PR, col0 = tile_n * p.tn + (wave % WN) * PC;
+    if (tid < PR) zr[tid] = agg_tiles_offset(p.m, row0 + tid, false);
+    else if (tid - PR < PC) zc[tid - PR] = agg_tiles_offset(p.n, col0 + (tid - PR), false);
+    const float *src = p.partials + tile * ((int64_t)p.tm * p.tn) + (int64_t)wave * (RT * NT * 1024);
+    const int lane = tid & 63, g4 = tid >> 6;          // chunk (k * 4 + g4) * 64 + lane of the patch, k = i * NT + j
+    const int64_t slab4 = p.slab_stride / 4;
+    const int orow = tid >> 3, oc0 = (tid & 7) * (PC / 8);    // on the way out: 8 threads per row, PC / 8 consecutive columns each
+    // the sums of row tile i (NT chunks per thread); the loads of tile i + 1 are issued before tile i's rows are written out
+    auto sums = [&](int i, f32x4 (&acc)[4]) {
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            if (j >= NT) break;
+            const f32x4 *s4 = (const f32x4 *)src + ((i * NT + j) * 4 + g4) * 64 + lane;
+            if (N > 0) {
+                f32x4 v[N > 0 ? N : 1];
+#pragma unroll
+                for (int a = 0; a < N; a++) v[a] = __builtin_nontemporal_load(s4 + a * slab4);
+                acc[j] = v[0];
+#pragma unroll
+                for (int a = 1; a < N; a++) acc[j] += v[a];
+            } else {
+                acc[j] = __builtin_nontemporal_load(s4);
+                for (int64_t a = 1; a < p.n_agg; a++) acc[j] += __builtin_nontemporal_load(s4 + a * slab4);
+            }
+        }
+    };
+    f32x4 cur[4], nxt[4];
+    sums(0, cur);
+    for (int i = 0; i < RT; i++) {
+        __syncthreads();                               // the tables are there; the previous rows have been read
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            if (j >= NT) break;
+            float *d = rows + (8 * g4 + 4 * (lane >> 5)) * pitch + j * 32 + (lane & 31);
+            d[0] = cur[j].x; d[pitch] = cur[j].y; d[2 * pitch] = cur[j].z; d[3 * pitch] = cur[j].w;
+        }
+        if (i + 1 < RT) sums(i + 1, nxt);
+        __syncthreads();
+        const float *r = rows + orow * pitch + oc0;
+        const int64_t zb = bz + zr[i * 32 + orow];
+        if (p.vec) {                                    // Z runs along the columns: whole 16-byte pieces
+            if (p.out_dtype == EG_BF16) {
+                for (int c = 0; c < PC / 8; c += 8) {
+                    const f32x4 a = *(const f32x4 *)(r + c), b = *(const f32x4 *)(r + c + 4);
+                    uint4 o;
+                    o.x = pack_bf16x2(a.x, a.y); o.y = pack_bf16x2(a.z, a.w); o.z = pack_bf16x2(b.x, b.y); o.w = pack_bf16x2(b.z, b.w);
+                    *(uint4 *)((uint16_t *)p.out + zb + zc[oc0 + c]) = o;
+                }
+            } else {
+                for (int c = 0; c < PC / 8; c += 4) *(f32x4 *)((float *)p.out + zb + zc[oc0 + c]) = *(const f32x4 *)(r + c);
+            }
+        } else {
+            for (int c = 0; c < PC / 8; c++) store_elem(p.out, p.out_dtype, zb + zc[oc0 + c], r[c]);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; j++) cur[j] = nxt[j];
+    }
+}
+
+int launch_aggregate_tiles(AggTilesParams &p, void *stream)
+{
+    if (!p.partials || !p.out) return fail(EG_ERR_NULL, "aggregation of tiles: NULL operand");
+    const bool shape = (p.tm == 256 && p.tn == 256 && (p.nw == 8 || p.nw == 4)) || (p.tm == 256 && p.tn == 128 && p.nw == 4) || (p.tm == 128 && p.tn == 128 && p.nw == 4);
+    if (!shape) return fail(EG_ERR_LIMIT, "aggregation of tiles: no join kernel writes %d x %d tiles with %d waves", p.tm, p.tn, p.nw);
+    if (p.n_agg < 1 || p.tiles < 1 || p.tiles_m < 1 || p.tiles_n < 1 || p.n_batch < 1) return fail(EG_ERR_LIMIT, "aggregation of tiles: empty input");
+    if (p.tiles % ((int64_t)p.tiles_m * p.tiles_n * p.n_batch)) return fail(EG_ERR_LIMIT, "aggregation of tiles: the tile count is no whole number of output blocks");
+    if (p.slab_stride < p.tiles * p.tm * p.tn || p.slab_stride % 4 || ((uintptr_t)p.partials & 15)) return fail(EG_ERR_LIMIT, "aggregation of tiles: slabs overlap or are not 16-byte aligned");
+    if (p.out_dtype != EG_F32 && p.out_dtype != EG_BF16) return fail(EG_ERR_DTYPE, "aggregation of tiles: result dtype");
+    const int64_t wgs = p.tiles * p.nw;
+    if (wgs >= (1ll << 31)) return fail(EG_ERR_LIMIT, "aggregation of tiles: %lld workgroups", (long long)wgs);
+    // 16-byte stores along the rows: Z contiguous along the innermost column label in runs of whole pieces, everything else 8-aligned
+    bool vec = p.n.s1[p.n.n - 1] == 1 && p.n.ext[p.n.n - 1] % 8 == 0 && ((uintptr_t)p.out & 15) == 0;
+    for (int i = 0; i < p.m.n; i++) vec = vec && p.m.s1[i] % 8 == 0;
+    for (int i = 0; i + 1 < p.n.n; i++) vec = vec && p.n.s1[i] % 8 == 0;
+    for (int i = 0; i < p.batch.n; i++) vec = vec && p.batch.s2[i] % 8 == 0;
+    for (int l = 0; l < p.ts.n; l++) vec = vec && p.ts.step_z[l] % 8 == 0;
+    p.vec = vec ? 1 : 0;
+    hipStream_t st = (hipStream_t)stream;
+    switch (p.n_agg) {
+    case 2: EG_LAUNCH(k_aggregate_tiles<2>, dim3((unsigned)wgs), dim3(256), 0, st, p); break;
+    case 4: EG_LAUNCH(k_aggregate_tiles<4>, dim3((unsigned)wgs), dim3(256), 0, st, p); break;
+    case 8: EG_LAUNCH(k_aggregate_tiles<8>, dim3((unsigned)wgs), dim3(256), 0, st, p); break;
+    case 16: EG_LAUNCH(k_aggregate_tiles<16>, dim3((unsigned)wgs), dim3(256), 0, st, p); break;
+    default: EG_LAUNCH(k_aggregate_tiles<0>, dim3((unsigned)wgs), dim3(256), 0, st, p); break;
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(EG_ERR_HIP, "k_aggregate_tiles launch failed: %s", hipGetErrorString(e));
+    return EG_OK;
 }
 
 }  // namespace eg

@@ -34,9 +34,10 @@ def to_host(x: torch.Tensor) -> HostTensor:
 class GraphRunner:
     def __init__(self, w: Workload, partitioning: str, outputs: Optional[Iterable[str]] = None, device="cuda",
                  contract: Optional[dict] = None, fuse: Optional[bool] = None, fuse_aggregation: Optional[bool] = None,
-                 fuse_attention: Optional[bool] = None):
+                 fuse_attention: Optional[bool] = None, tiled_partials: Optional[bool] = None):
         """contract: arguments of tr_set_contract_variant (kernel / tile / waves); fuse, fuse_aggregation, fuse_attention:
-        arguments of tr_set_fusion, tr_set_fused_aggregation and tr_set_fused_attention.  None leaves the library's defaults."""
+        arguments of tr_set_fusion, tr_set_fused_aggregation and tr_set_fused_attention; tiled_partials: of
+        tr_set_tiled_partials.  None leaves the library's defaults."""
         self.w = w
         self.device = device
         self.g = api.einsum_graph_create()
@@ -48,6 +49,8 @@ class GraphRunner:
             api.tr_set_fused_aggregation(self.g, fuse_aggregation)
         if fuse_attention is not None:
             api.tr_set_fused_attention(self.g, fuse_attention)
+        if tiled_partials is not None:
+            api.tr_set_tiled_partials(self.g, tiled_partials)
         self.vid: Dict[str, int] = {}
         # "eindecomp:<p>": let the library choose the partitioning vectors (p join results per vertex)
         planned = partitioning.startswith("eindecomp:")
