@@ -145,7 +145,7 @@ KERNEL_TEXT = {"contract_mfma": "k_contract_dma / k_contract (block contraction 
                "attention_fused": "k_attention (scores contraction, softmax chain and weighted sum in one pass; alternative, off by default)"}
 
 
-def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None, fuse_attention=False):
+def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None, fuse_attention=False, dense_partials=False):
     """Times `steps` passes of one workload under one partitioning: (per-step ms, per-family kernel records, flops per step,
     workload description, device inputs, the workload)."""
     import torch
@@ -155,7 +155,7 @@ def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None,
 
     w = build_config(config)
     dev = {v.name: prng_torch.make_tensor(v.recipe, v.bound, v.dtype, w.seed, w.tensor_id(v.name)) for v in w.vertices if v.is_input}
-    r = GraphRunner(w, pname, contract=contract, fuse_aggregation=True if fuse_aggregation else None, fuse_attention=True if fuse_attention else None)
+    r = GraphRunner(w, pname, contract=contract, fuse_aggregation=True if fuse_aggregation else None, fuse_attention=True if fuse_attention else None, tiled_partials=False if dense_partials else None)
     r.bind(dev)
     stream = torch.cuda.current_stream()
     # A working set that the 256 MiB Infinity Cache could hold between steps is rotated over three copies (inputs,
@@ -166,7 +166,7 @@ def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None,
     runners = [r]
     if working_set < (512 << 20):
         for _ in range(2):
-            r2 = GraphRunner(w, pname, contract=contract, fuse_aggregation=True if fuse_aggregation else None, fuse_attention=True if fuse_attention else None)
+            r2 = GraphRunner(w, pname, contract=contract, fuse_aggregation=True if fuse_aggregation else None, fuse_attention=True if fuse_attention else None, tiled_partials=False if dense_partials else None)
             r2.bind({k: t.clone() for k, t in dev.items()})
             runners.append(r2)
     for i in range(warmup * len(runners)):
@@ -268,7 +268,8 @@ def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None,
         print(f"bench.py: HIP graph replay not measured ({e})", file=sys.stderr)
     desc = f"{w.name} dims {json.dumps(w.dims)}, partitioning '{pname}': {json.dumps(r.part)}" \
         + (" [alternative method: aggregation inside the contraction kernels]" if fuse_aggregation else "") \
-        + (" [alternative: attention as one pass]" if fuse_attention else "")
+        + (" [alternative: attention as one pass]" if fuse_attention else "") \
+        + (" [comparison: dense partial slabs]" if dense_partials else "")
     n_sets = len(runners)
     for q in runners[1:]:
         q.close()
@@ -287,6 +288,8 @@ def main():
                     help="alternative method, reported separately: contractions reduce over partitioned contracted labels inside the kernel (no partial slabs, no aggregation launch)")
     ap.add_argument("--fuse-attention", action="store_true",
                     help="alternative, reported separately: attention groups (scores contraction, softmax chain, weighted sum) run as one kernel")
+    ap.add_argument("--dense-partials", action="store_true",
+                    help="for comparisons: partial slabs as dense row-major tensors instead of in the contraction kernel's tile order")
     ap.add_argument("--contract-tile", default=None, help="for comparisons: output tile of the block-contraction kernel, e.g. 256x256, 256x128, 128 (default: the library chooses)")
     ap.add_argument("--contract-waves", type=int, default=0, help="for comparisons: 4 or 8 waves per workgroup of the 256 x 256 tile")
     ap.add_argument("--no-other-workloads", action="store_true", help="skip the short runs of configs 3, 4 and 5 that follow the headline workload")
@@ -305,7 +308,7 @@ def main():
     if args.contract_tile:
         t = [int(x) for x in args.contract_tile.split("x")]
         contract = dict(tile=(t[0], t[-1]), waves=args.contract_waves)
-    ms_per_step, kernels, flops_per_step, desc, dev, w, (n_sets, graph_ms) = measure(args.config, pname, args.steps, args.warmup, args.fuse_aggregation, contract, args.fuse_attention)
+    ms_per_step, kernels, flops_per_step, desc, dev, w, (n_sets, graph_ms) = measure(args.config, pname, args.steps, args.warmup, args.fuse_aggregation, contract, args.fuse_attention, args.dense_partials)
     value = flops_per_step / (ms_per_step * 1e-3) / 1e12
 
     dom = "contract_mfma" if "contract_mfma" in kernels else max(kernels, key=lambda k: kernels[k]["share_of_step"])
@@ -328,7 +331,7 @@ def main():
         out["cpu_baseline"] = cpu_baseline(w, dev)
     del dev
     torch.cuda.empty_cache()
-    if not args.no_other_workloads and args.config == 2 and not args.fuse_aggregation and not args.fuse_attention and contract is None:
+    if not args.no_other_workloads and args.config == 2 and not args.fuse_aggregation and not args.fuse_attention and not args.dense_partials and contract is None:
         # the other full-size workloads, a few steps each, so that their kernel families are measured in the same run
         others = {}
         for c, alt in ((3, False), (4, False), (5, False), (4, True)):

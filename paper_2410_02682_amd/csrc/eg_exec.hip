@@ -1304,8 +1304,11 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
             s.r.cp.force_waves = g->contract_waves;
         }
         // Partial slabs of the direct-to-LDS contraction kernel in tile order when its tiles are whole: the slab has the same
-        // size, only the order of its elements is a matter between that kernel and the aggregation that follows it.
-        if (s.agg && g->tiled_partials && s.r.kind == EG_KERNEL_CONTRACT_MFMA && contract_takes_dma(s.r.cp)) {
+        // size, only the order of its elements is a matter between that kernel and the aggregation that follows it.  The join
+        // kernel saves some 5 us per tile (no staging through LDS), the aggregation of tile-ordered slabs runs at 0.70 of the
+        // memory rate where the dense one reaches up to 0.84: taken where a tile's reduction is short enough for the 5 us to
+        // count (up to 4096; config 6's product with 12800 per tile lost 0.5 % per step with it).
+        if (s.agg && g->tiled_partials && s.r.kind == EG_KERNEL_CONTRACT_MFMA && s.r.cp.K <= 4096 && contract_takes_dma(s.r.cp)) {
             const Vertex &vu = *routed;
             int tm = 0, tn = 0, nw = 0;
             contract_dma_variant(s.r.cp, tm, tn, nw);
