@@ -31,19 +31,19 @@ DEFAULT_PART = {1: "d222", 2: "mix", 3: "batch8", 4: "heads8", 5: "k16", 6: "spl
 # file, scaled by what the same counters read for the plain 1 GiB copy kernel (see profiles/); a family that is not listed
 # reports null.  Keys: (workload, partitioning, kernel family).
 MEASURED_TRAFFIC = {
-    ("c2", "mix", "contract_mfma"): 2218699795,    # 1604 MiB fetched + 512 MiB written per launch (1617-1690 MiB fetched over the pool's boxes)
-    ("c2", "mix", "aggregate"): 738161306,         # 512 MiB fetched + 192 MiB written
-    ("c3", "batch8", "contract_mfma"): 517133088,  # 247 MiB fetched + 246 MiB written (mean over the step's five contractions)
+    ("c2", "mix", "contract_mfma"): 2189732864,    # 1575 MiB fetched + 513 MiB written per launch (1575-1690 MiB fetched over the pool's boxes)
+    ("c2", "mix", "aggregate"): 739217408,         # 512 MiB fetched + 193 MiB written
+    ("c3", "batch8", "contract_mfma"): 481092000,  # 212 MiB fetched + 247 MiB written (mean over the step's five contractions)
     ("c3", "batch8", "map"): 44803018,             # 25 MiB fetched + 17 MiB written
     ("c3", "batch8", "softmax_fused"): 33701239,   # 16 MiB fetched + 16 MiB written
     ("c3", "batch8", "reduce_row"): 25293930,      # 24 MiB fetched
-    ("c3", "batch8", "aggregate"): 452967563,      # 384 MiB fetched + 48 MiB written (mean over the step's three aggregations)
-    ("c4", "heads8", "contract_mfma"): 1311156099, # 842 MiB fetched + 408 MiB written (mean over the step's nine contractions)
+    ("c3", "batch8", "aggregate"): 453230000,      # 384 MiB fetched + 48 MiB written (mean over the step's three aggregations)
+    ("c4", "heads8", "contract_mfma"): 1280241700, # 812 MiB fetched + 409 MiB written (mean over the step's nine contractions)
     ("c4", "heads8", "softmax_fused"): 2281005450, # 1152 MiB fetched (scores + the mask rows) + 1023 MiB written
-    ("c4", "heads8", "aggregate"): 1174343587,     # 1024 MiB fetched + 96 MiB written
+    ("c4", "heads8", "aggregate"): 1174699000,     # 1024 MiB fetched + 96 MiB written
     ("c4", "heads8", "map"): 549389600,            # 352 MiB fetched + 172 MiB written
-    ("c5", "k16", "contract_mfma"): 42339511874,   # 24006 MiB fetched (L2 misses; the re-reads of X are served by the Infinity Cache) + 16372 MiB written
-    ("c5", "k16", "aggregate"): 18252583418,       # 16384 MiB fetched + 1023 MiB written
+    ("c5", "k16", "contract_mfma"): 31395302400,   # 13556 MiB fetched (L2 misses; the re-reads of X are served by the Infinity Cache) + 16385 MiB written
+    ("c5", "k16", "aggregate"): 18253883392,       # 16384 MiB fetched + 1024 MiB written
 }
 
 
@@ -139,7 +139,7 @@ def ceilings():
 
 
 KERNEL_TEXT = {"contract_mfma": "k_contract_dma / k_contract (block contraction on MFMA, all tuples of a vertex per launch)",
-               "aggregate": "k_aggregate_vec4", "map": "k_map", "reduce_row": "k_reduce_row", "generic": "k_generic",
+               "aggregate": "k_aggregate_patches (tile-ordered partial slabs) / k_aggregate_vec4 (dense ones)", "map": "k_map", "reduce_row": "k_reduce_row", "generic": "k_generic",
                "contract_alu": "k_contract_alu (contraction-shaped vertex with another scalar function, vector ALU)",
                "softmax_fused": "k_softmax_rows",
                "attention_fused": "k_attention (scores contraction, softmax chain and weighted sum in one pass; alternative, off by default)"}
