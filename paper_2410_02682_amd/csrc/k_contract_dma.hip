@@ -483,6 +483,7 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW, NS) <= 160 *
         // (256 rows, 256 columns; two sets in turn, so a wave already in the next tile cannot disturb a slower one)
         if (more) tile_info(first + (it + 1) * stride, nxt);
         int64_t *zrow = (int64_t *)(ldsx + (it & 1) * TBL), *zcol = zrow + TM;
+        if (!p.tile_order)                            // (tile-ordered partial slabs need no Z offsets)
         for (int e = tid; e < TM + TN; e += NW * 64) {
             int64_t unused, z;
             if (e < TM) {
