@@ -74,6 +74,8 @@ struct ContractParams {
     int32_t force_tile_m, force_tile_n;   // 0: the launcher chooses; 128 x 128, 256 x 128 or 256 x 256: tile of the direct-to-LDS kernel
     int32_t force_waves;          // 0: the launcher chooses; 4 / 8: waves per workgroup of the 256 x 256 direct-to-LDS kernel
     int32_t tile_order;           // 1: partial slabs are written tile after tile in the accumulators' order (see AggTilesParams)
+    int32_t k_stages;             // filled by the launcher of the direct-to-LDS kernel: stages per output tile
+    int32_t k_align;              // filled by that launcher: 0: a tile's stages start at its block's first k; 1 / 2: on the 128-byte line of X / Y below it
 };
 
 // Aggregation of partial slabs that the direct-to-LDS contraction kernel wrote in tile order: a slab then holds the

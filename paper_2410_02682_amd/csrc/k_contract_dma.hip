@@ -113,11 +113,12 @@ struct Src {
                 boff[i] = (uint32_t)((o0 - origin + (KR * NW * i + kl) * k_inner_stride) * ES);
         }
     }
-    // offset handed to load i of a stage that has `krem` valid k left: beyond the descriptor when the chunk's k is past the end
-    __device__ __forceinline__ uint32_t voff(int i, int krem) const
+    // offset handed to load i of a stage whose valid k are kmin .. krem-1: beyond the descriptor when the chunk's k is outside
+    // (past the end of the reduction, or, in a tile's first stage, before its start)
+    __device__ __forceinline__ uint32_t voff(int i, int krem, int kmin) const
     {
         const int k = KC ? kl : kl + KR * NW * i;
-        return k < krem ? boff[i] : 0x80000000u;
+        return (uint32_t)(k - kmin) < (uint32_t)(krem - kmin) ? boff[i] : 0x80000000u;
     }
 };
 
@@ -315,7 +316,7 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW, NS) <= 160 *
     };
     const int kin = p.k.n - 1;                        // innermost K label: every stage lies inside one run of it
     const int64_t run = p.k.n == 1 ? p.K : p.k.ext[kin];            // k of one run of the innermost K label
-    const int64_t nk = (p.K / run) * ((run + BK - 1) / BK);          // stages: every run starts a stage of its own
+    const int64_t nk = p.k_stages;                    // stages per tile: every run starts a stage of its own
 
     TileInfo cur, nxt;
     Src<A_KC, NW, TM, KB, F32> sa;
@@ -328,13 +329,25 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW, NS) <= 160 *
     // next stage starts the next run and its offsets are decoded afresh, so a stage never straddles two runs and the
     // main loop's scalar work per stage is two additions almost always.
     const int64_t dka = (int64_t)BK * p.k.s0[kin] * ES, dkb = (int64_t)BK * p.k.s1[kin] * ES;
+    // With p.k_align (one K label, an operand contiguous along it whose rows all start at the same offset inside a 128-byte
+    // line) a tile's stages are laid on that operand's lines: the first one starts `kskip` elements before the block's
+    // first k, those elements are not fetched (zeros), and every later stage fetches whole lines instead of the halves of two.
     const char *ga_n, *gb_n;
     int64_t k_n, run_left;
-    auto first_stage = [&]() { k_n = 0; ga_n = xb; gb_n = yb; run_left = run; };
-    auto next_stage = [&](const char *&ga, const char *&gb, int &krem) {
+    int kskip = 0, kmin_n = 0;
+    auto first_stage = [&]() {
+        k_n = -kskip;
+        ga_n = xb - (int64_t)kskip * p.k.s0[kin] * ES;
+        gb_n = yb - (int64_t)kskip * p.k.s1[kin] * ES;
+        run_left = run + kskip;
+        kmin_n = kskip;
+    };
+    auto next_stage = [&](const char *&ga, const char *&gb, int &krem, int &kmin) {
         ga = ga_n;
         gb = gb_n;
         krem = k_n >= p.K ? 0 : (run_left < BK ? (int)run_left : BK);
+        kmin = kmin_n;
+        kmin_n = 0;
         if (run_left > BK) {
             k_n += BK;
             run_left -= BK;
@@ -354,20 +367,20 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW, NS) <= 160 *
     // direct load i (0..LDA-1: X tile, LDA..NLD-1: Y tile) of a stage into the LDS stage at `dst`: a 2 GiB buffer descriptor
     // on the uniform stage base + a 32-bit lane offset (in-block offsets are below 2^31; 2^31 itself means "no fetch, zeros")
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    auto dma = [&](int i, const char *ga, const char *gb, int krem, char *dst) {
+    auto dma = [&](int i, const char *ga, const char *gb, int krem, int kmin, char *dst) {
         if (i < LDA) {
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)ga, 0, (int)0x80000000u, 0x00020000);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, EG_LDS(dst + (NW * i + wave_u) * 1024), 16, (int)sa.voff(i, krem), 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, EG_LDS(dst + (NW * i + wave_u) * 1024), 16, (int)sa.voff(i, krem, kmin), 0, 0, 0);
         } else {
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void *)gb, 0, (int)0x80000000u, 0x00020000);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, EG_LDS(dst + TILE_BYTES + (NW * (i - LDA) + wave_u) * 1024), 16, (int)sb.voff(i - LDA, krem), 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, EG_LDS(dst + TILE_BYTES + (NW * (i - LDA) + wave_u) * 1024), 16, (int)sb.voff(i - LDA, krem, kmin), 0, 0, 0);
         }
     };
     // The same load written out by hand, for the loads that travel during an epilogue: the compiler keeps track of
     // direct loads it issued itself and would hold the epilogue's first LDS access until they have landed.  These
     // are waited for by the explicit vmcnt(0) and barrier at the head of the tile loop.  M0 (the LDS base of a
     // direct load) is put back, so the compiler's own picture of it stays right.
-    auto dma_untracked = [&](int i, const char *ga, const char *gb, int krem, char *dst) {
+    auto dma_untracked = [&](int i, const char *ga, const char *gb, int krem, int kmin, char *dst) {
         const bool isa = i < LDA;
         const uint64_t base = (uint64_t)(isa ? ga : gb);
         u32x4 rs;
@@ -376,28 +389,29 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW, NS) <= 160 *
         rs.z = 0x80000000u;
         rs.w = 0x00020000u;
         const uint32_t l = (uint32_t)(uintptr_t)EG_LDS(dst + (isa ? 0 : TILE_BYTES) + (NW * (isa ? i : i - LDA) + wave_u) * 1024);
-        const uint32_t off = isa ? sa.voff(i, krem) : sb.voff(i - LDA, krem);
+        const uint32_t off = isa ? sa.voff(i, krem, kmin) : sb.voff(i - LDA, krem, kmin);
         uint32_t keep;
         asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
                      : "=&s"(keep) : "s"(l), "v"(off), "s"(rs) : "memory");
     };
-    auto issue = [&](const char *ga, const char *gb, int krem, char *dst) {
+    auto issue = [&](const char *ga, const char *gb, int krem, int kmin, char *dst) {
 #pragma unroll
-        for (int i = 0; i < NLD; i++) dma_untracked(i, ga, gb, krem, dst);
+        for (int i = 0; i < NLD; i++) dma_untracked(i, ga, gb, krem, kmin, dst);
     };
     const char *ga2, *gb2;
-    int kr2;
+    int kr2, km2;
     // per-lane addressing of tile t, then its first two stages on their way (both LDS stages must be free)
     auto start_tile = [&](const TileInfo &t) {
         sa.init(p.m, t.m0, p.M, t.ox0, p.k.s0[kin], wave, lane);
         sb.init(p.n, t.n0, p.N, t.oy0, p.k.s1[kin], wave, lane);
         xb = uniform_ptr(t.xb);
         yb = uniform_ptr(t.yb);
+        kskip = p.k_align ? (int)(((uint32_t)(uintptr_t)(p.k_align == 1 ? xb : yb) & 127u) / ES) : 0;
         first_stage();
-        next_stage(ga2, gb2, kr2);
-        issue(ga2, gb2, kr2, lds0);
-        next_stage(ga2, gb2, kr2);
-        if (nk > 1) issue(ga2, gb2, kr2, lds1);
+        next_stage(ga2, gb2, kr2, km2);
+        issue(ga2, gb2, kr2, km2, lds0);
+        next_stage(ga2, gb2, kr2, km2);
+        if (nk > 1) issue(ga2, gb2, kr2, km2, lds1);
     };
 
     // Software pipeline.  Fragment registers alternate between two sets (f0 = a0/b0, f1 = a1/b1).  Each k-step
@@ -415,12 +429,12 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW, NS) <= 160 *
     mfma_rows<1, RT, RT, NT, F32>(FA, FB, acc); EG_PIN();
     // the direct loads of a stage are spread over the RT * NT MFMAs of a k-step: those that follow MFMA q
 #define EG_DMA_AFTER(Q, C)                                                                        \
-    if (has2) { _Pragma("unroll") for (int d = (Q) * NLD / (RT * NT); d < ((Q) + 1) * NLD / (RT * NT); d++) dma(d, ga2, gb2, kr2, C); }
+    if (has2) { _Pragma("unroll") for (int d = (Q) * NLD / (RT * NT); d < ((Q) + 1) * NLD / (RT * NT); d++) dma(d, ga2, gb2, kr2, km2, C); }
 #define EG_STAGE_NEXT(C, O, HAS_NEXT2) /* one stage; its successor is already in flight into O */     \
     do {                                                                                          \
         mfma_rows<0, 1, RT, NT, F32>(a0, b0, acc); EG_PIN();                                               \
         const bool has2 = (HAS_NEXT2);                                                            \
-        next_stage(ga2, gb2, kr2);          /* scalar work rides under the MFMAs */               \
+        next_stage(ga2, gb2, kr2, km2);          /* scalar work rides under the MFMAs */               \
         EG_FRAGS(C, 1, a1, b1); EG_PIN();                                                         \
         mfma_rows<1, RT, RT, NT, F32>(a0, b0, acc); EG_PIN();                                               \
         if constexpr (KS == 4) {                                                                  \
@@ -451,7 +465,7 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW, NS) <= 160 *
     do {                                                                                          \
         mfma_rows<0, 1, RT, NT, F32>(a0, b0, acc); EG_PIN();                                               \
         const bool has2 = (HAS_NEXT3);      /* what EG_DMA_AFTER issues: stage s+3 into C */      \
-        next_stage(ga2, gb2, kr2);                                                                \
+        next_stage(ga2, gb2, kr2, km2);                                                                \
         EG_FRAGS(C, 1, a1, b1); EG_PIN();                                                         \
         mfma_rows<1, RT, RT, NT, F32>(a0, b0, acc); EG_PIN();                                               \
         /* vmcnt(NLD): stage s+1 has landed, stage s+2 may still travel; lgkmcnt(0): this wave's reads of C have returned. */ \
@@ -505,10 +519,10 @@ __global__ __launch_bounds__(NW * 64, 2 * lds_bytes(TM, TN, KB, NW, NS) <= 160 *
         __syncthreads();
         if constexpr (NS == 3) {
             // the third buffer held the previous tile's staging rows until this barrier: its stage goes out now
-            next_stage(ga2, gb2, kr2);
+            next_stage(ga2, gb2, kr2, km2);
             if (nk > 2) {
 #pragma unroll
-                for (int i = 0; i < NLD; i++) dma(i, ga2, gb2, kr2, lds2);
+                for (int i = 0; i < NLD; i++) dma(i, ga2, gb2, kr2, km2, lds2);
             }
         }
         EG_FRAGS(lds0, 0, a0, b0);
@@ -696,9 +710,7 @@ static int launch_one(ContractParams &p, void *stream)
 template <int TM, int TN, int KB, int NS, int NW, bool A_KC, bool B_KC, bool F32>
 static int launch_rem(ContractParams &p, void *stream)
 {
-    constexpr int BK = KB / Elem<F32>::ES;
-    const int64_t run = p.k.n == 1 ? p.K : p.k.ext[p.k.n - 1];
-    const int rem = (int)(((p.K / run) * ((run + BK - 1) / BK)) % NS);
+    const int rem = (int)(p.k_stages % NS);
     if (rem == 0) return launch_one<TM, TN, KB, NS, NW, A_KC, B_KC, 0, F32>(p, stream);
     if (rem == 1) return launch_one<TM, TN, KB, NS, NW, A_KC, B_KC, 1, F32>(p, stream);
     if constexpr (NS == 3) return launch_one<TM, TN, KB, NS, NW, A_KC, B_KC, 2, F32>(p, stream);
@@ -824,6 +836,50 @@ int launch_contract_dma(ContractParams &p, void *stream)
     for (int i = 0; i < p.batch.n; i++) vec = vec && p.batch.s2[i] % 8 == 0;
     for (int l = 0; l < p.ts.n; l++) vec = vec && p.ts.step_z[l] % 8 == 0;
     p.out_vec = vec ? 1 : 0;
+    // Stages per tile.  Where an operand is contiguous along the one K label and its blocks start inside a 128-byte line
+    // (a slice of 1376 bf16: every other block starts 64 bytes into a line), stages that start at the block's first k fetch
+    // two half lines per row and stage (config 4's down projection: 830 against 1030-1090 TFLOP/s with aligned slices).
+    // k_align lays the stages on that operand's lines instead; the set of offsets the tuples' blocks can have decides how
+    // many stages that takes, and a tile whose own offset needs one fewer runs an empty last stage.
+    const int64_t es = f32 ? 4 : 2, bk = kb / es, run = p.k.n == 1 ? p.K : p.k.ext[p.k.n - 1];
+    const int64_t stages0 = (p.K / run) * ((run + bk - 1) / bk);
+    p.k_align = 0;
+    p.k_stages = (int32_t)stages0;
+    if (kb == 128 && p.k.n == 1 && stages0 >= 8) {
+        // largest offset (in 16-byte chunks, 0..7) of a block's first row inside its line; -1: rows differ among themselves
+        auto worst = [&](const void *base, int which) -> int {
+            auto bytes = [&](int64_t elems) { return (uint64_t)(elems * es); };
+            const DimList &rows = which == 0 ? p.m : p.n;
+            for (int i = 0; i < rows.n; i++)
+                if (rows.ext[i] > 1 && bytes(rows.s0[i]) % 128) return -1;
+            for (int i = 0; i < p.batch.n; i++)
+                if (p.batch.ext[i] > 1 && bytes(which == 0 ? p.batch.s0[i] : p.batch.s1[i]) % 128) return -1;
+            unsigned set = 1u << (((uintptr_t)base % 128) / 16);
+            for (int l = 0; l < p.ts.n; l++) {
+                const uint64_t st = bytes(which == 0 ? p.ts.step_x[l] : p.ts.step_y[l]);
+                if (st % 16) return -1;
+                unsigned next = 0;
+                for (int i = 0; i < p.ts.d[l] && i < 8; i++)
+                    for (int r = 0; r < 8; r++)
+                        if (set >> r & 1) next |= 1u << ((r + i * (st / 16)) % 8);
+                set = next;
+            }
+            int w = 0;
+            for (int r = 0; r < 8; r++)
+                if (set >> r & 1) w = r;
+            return w;
+        };
+        const int wx = p.a_kcontig ? worst(p.x, 0) : 0, wy = p.b_kcontig ? worst(p.y, 1) : 0;
+        const int which = wx > 0 ? 1 : (wy > 0 ? 2 : 0);
+        if (which) {
+            const int64_t skip = (which == 1 ? wx : wy) * (16 / es);
+            const int64_t stages = (p.K + skip + bk - 1) / bk;
+            if (stages == stages0 || (stages == stages0 + 1 && stages0 >= 32)) {     // (an extra stage in 22 costs what whole lines gain)
+                p.k_align = which;
+                p.k_stages = (int32_t)stages;
+            }
+        }
+    }
     if (f32) return tm == 128 ? dma::launch_layout<128, 128, 128, 2, 4, true>(p, stream) : dma::launch_layout<256, 256, 128, 2, 8, true>(p, stream);
     if (tm == 128) return dma::launch_layout<128, 128, 128, 2, 4, false>(p, stream);
     if (tn == 128) return dma::launch_layout<256, 128, 64, 3, 4, false>(p, stream);
