@@ -295,44 +295,59 @@ static int route(const Vertex &v, const Operand &X, const Operand *Y, const std:
     const bool binary = v.n_in == 2;
 
     if (v.agg.empty()) {                                        // element-wise: no aggregated label
-        MapParams &p = r.mp;
-        memset(&p, 0, sizeof p);
-        std::vector<int> zl(v.lz.begin(), v.lz.end());
-        if (!collapse(li, zl, p.dims)) return fail(EG_ERR_LIMIT, "map: too many dimensions after collapsing");
-        if (p.dims.n == 0) { p.dims.n = 1; p.dims.ext[0] = 1; }
-        p.ts = ts; p.binary = binary; p.otimes = v.otimes; p.alpha = (float)v.alpha;
-        p.dtx = X.dtype; p.dty = Y ? Y->dtype : EG_F32;
-        p.x = X.ptr; p.y = Y ? Y->ptr : nullptr; p.out = out; p.n_tuples = n_tuples;
-        const int vd = p.dims.n - 1;
-        // whole 16-byte vectors, except in a dense one-dimensional space that is not cut: there the last vector may be partial
-        const bool flat = p.dims.n == 1 && ts.n == 0;
-        bool vz = p.dims.sz[vd] == 1 && aligned16(out.ptr) && (p.dims.ext[vd] % 8 == 0 || flat);
-        for (int i = 0; i < p.dims.n && vz; i++)
-            if (i != vd && p.dims.sz[i] % 8) vz = false;
-        for (int l = 0; l < ts.n && vz; l++)
-            if (ts.step_z[l] % 8) vz = false;
-        if (out.slab_elems % 8) vz = false;
-        bool vx = vec_ok(p.dims, 0, vd, 8, X.ptr, ts, true);
-        bool vy = !binary || vec_ok(p.dims, 1, vd, 8, Y->ptr, ts, true);
-        p.vec = (vz && vx && vy) ? 8 : 1;
-        // one operand contiguous along another dimension than Z's last (a transpose): tiles through LDS
-        if (p.vec == 1 && vz && p.dims.n >= 2 && (!binary || vx != vy) && (binary || !vx)) {
-            const bool xt = !vx;
-            const int64_t *s = xt ? p.dims.sx : p.dims.sy;
-            const int64_t *step = xt ? ts.step_x : ts.step_y;
-            int td = -1;
-            for (int i = 0; i < vd; i++)
-                if (s[i] == 1 && p.dims.ext[i] % 8 == 0) td = i;
-            bool ok = td >= 0 && aligned16(xt ? X.ptr : Y->ptr);
-            for (int i = 0; i < p.dims.n && ok; i++)
-                if (i != td && s[i] % 8) ok = false;
-            for (int l = 0; l < ts.n && ok; l++)
-                if (step[l] % 8) ok = false;
-            if (ok) { p.tr = xt ? 1 : 2; p.td = td; p.vec = 8; }
+        auto build = [&](const LabelInfo &li, const TupleSpace &ts, int64_t n_tuples) -> bool {
+            MapParams &p = r.mp;
+            memset(&p, 0, sizeof p);
+            std::vector<int> zl(v.lz.begin(), v.lz.end());
+            if (!collapse(li, zl, p.dims)) return false;
+            if (p.dims.n == 0) { p.dims.n = 1; p.dims.ext[0] = 1; }
+            p.ts = ts; p.binary = binary; p.otimes = v.otimes; p.alpha = (float)v.alpha;
+            p.dtx = X.dtype; p.dty = Y ? Y->dtype : EG_F32;
+            p.x = X.ptr; p.y = Y ? Y->ptr : nullptr; p.out = out; p.n_tuples = n_tuples;
+            const int vd = p.dims.n - 1;
+            // whole 16-byte vectors, except in a dense one-dimensional space that is not cut: there the last vector may be partial
+            const bool flat = p.dims.n == 1 && ts.n == 0;
+            bool vz = p.dims.sz[vd] == 1 && aligned16(out.ptr) && (p.dims.ext[vd] % 8 == 0 || flat);
+            for (int i = 0; i < p.dims.n && vz; i++)
+                if (i != vd && p.dims.sz[i] % 8) vz = false;
+            for (int l = 0; l < ts.n && vz; l++)
+                if (ts.step_z[l] % 8) vz = false;
+            if (out.slab_elems % 8) vz = false;
+            bool vx = vec_ok(p.dims, 0, vd, 8, X.ptr, ts, true);
+            bool vy = !binary || vec_ok(p.dims, 1, vd, 8, Y->ptr, ts, true);
+            p.vec = (vz && vx && vy) ? 8 : 1;
+            // one operand contiguous along another dimension than Z's last (a transpose): tiles through LDS
+            if (p.vec == 1 && vz && p.dims.n >= 2 && (!binary || vx != vy) && (binary || !vx)) {
+                const bool xt = !vx;
+                const int64_t *s = xt ? p.dims.sx : p.dims.sy;
+                const int64_t *step = xt ? ts.step_x : ts.step_y;
+                int td = -1;
+                for (int i = 0; i < vd; i++)
+                    if (s[i] == 1 && p.dims.ext[i] % 8 == 0) td = i;
+                bool ok = td >= 0 && aligned16(xt ? X.ptr : Y->ptr);
+                for (int i = 0; i < p.dims.n && ok; i++)
+                    if (i != td && s[i] % 8) ok = false;
+                for (int l = 0; l < ts.n && ok; l++)
+                    if (step[l] % 8) ok = false;
+                if (ok) { p.tr = xt ? 1 : 2; p.td = td; p.vec = 8; }
+            }
+            int64_t rows = 1;
+            for (int i = 0; i < vd; i++) rows *= p.dims.ext[i];
+            p.vecs_per_block = rows * ((p.dims.ext[vd] + p.vec - 1) / p.vec);
+            return true;
+        };
+        // A scalar function applied block by block is the same function applied to the whole tensors, and the blocks of
+        // every operand under one key lie where the whole tensor has them, so the tuples are walked as one index space
+        // in memory order (a tensor cut eight ways along its rows or inside them streams like an uncut one); the tuple
+        // by tuple launch remains for spaces too large for one and for those without 16-byte accesses.
+        if (ts.n > 0) {
+            LabelInfo whole = li;
+            for (int l = 0; l < li.nl; l++) whole.ext[l] = v.lbound[l];
+            TupleSpace none;
+            memset(&none, 0, sizeof none);
+            if (build(whole, none, 1) && r.mp.vec == 8 && r.mp.vecs_per_block < (1ll << 32)) { r.kind = EG_KERNEL_MAP; return EG_OK; }
         }
-        int64_t rows = 1;
-        for (int i = 0; i < vd; i++) rows *= p.dims.ext[i];
-        p.vecs_per_block = rows * ((p.dims.ext[vd] + p.vec - 1) / p.vec);
+        if (!build(li, ts, n_tuples)) return fail(EG_ERR_LIMIT, "map: too many dimensions after collapsing");
         r.kind = EG_KERNEL_MAP;
         return EG_OK;
     }
