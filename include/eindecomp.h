@@ -102,7 +102,7 @@ typedef enum {
     EG_KERNEL_REDUCE_ROW = 3,      /* aggregated labels are the contiguous tail of X: wave reductions */
     EG_KERNEL_GENERIC = 4,         /* any EinSum: one output element per lane, loop over l_agg       */
     EG_KERNEL_CONTRACT_ALU = 5,    /* contraction-shaped EinSum with another (x)/(+) pair (squared L2, L-infinity, ...): LDS tiles, vector ALU */
-    EG_KERNEL_SOFTMAX_FUSED = 6,   /* the softmax vertices max, exp(x - max), sum, division (and a preceding alpha*x + y) in one pass per row */
+    EG_KERNEL_SOFTMAX_FUSED = 6,   /* the softmax vertices max, exp(x - max), sum, division (a preceding alpha*x + y, element-wise vertices behind it) in one pass per row */
     EG_KERNEL_ATTENTION_FUSED = 7, /* Section 3's attention, scores contraction to weighted sum, in one pass (tr_set_fused_attention) */
     EG_KERNEL_AGGREGATE_TILES = 8  /* reported for an aggregation launch that read tile-ordered partial slabs (tr_set_tiled_partials) */
 } eg_kernel_kind;
@@ -233,7 +233,12 @@ int tr_aggregate(eg_agg oplus, const void *partials, int64_t n_agg, int64_t slab
  * vertices carry the same partitioning vector and the intermediate tensors have no other consumer, tr_execute
  * runs it as one pass over the rows (the preceding alpha * x + y vertex included when it feeds only the chain),
  * rounding where the separate vertices would have rounded.  Row maxima and sums that other vertices consume are
- * still written.  Enabled by default; enable = 0 makes every vertex run on its own.  Changes the workspace size. */
+ * still written.  Up to four element-wise vertices behind the division join the pass as well when their operands are
+ * the chain's own values (its source, row maximum, exponentials, row sum, quotient), earlier such vertices, or at most
+ * two tensors of the result's shape that exist before the pass runs (the log-probabilities and the cross-entropy
+ * gradient of a training step); each is evaluated and rounded as its own vertex would, and only those that something
+ * outside the pass reads, or that are outputs, are written.  The pass is reported at the division's vertex.
+ * Enabled by default; enable = 0 makes every vertex run on its own.  Changes the workspace size. */
 int tr_set_fusion(eg_graph *g, int enable);
 
 /* The alternative to the two-stage path, for comparison (off by default: the method of Section 4.3 is join, then

@@ -566,7 +566,11 @@ struct FuseGroup {
     int add = -1;              // the alpha * x + y vertex in front of the chain, or -1
     int vmax = -1, vexp = -1, vsum = -1, vdiv = -1;
     int src = -1, addend = -1; // what the chain reads: the source tensor and the added operand (or -1)
-    bool emit_max = false, emit_sum = false;
+    bool emit_max = false, emit_sum = false, emit_div = true;
+    // element-wise vertices behind the chain that its pass evaluates as well (see SoftmaxTail): the vertices, their operand
+    // slots, whether each is still written, and the tensors of full rank they read from outside the group
+    std::vector<int> tails, tail_a, tail_b, ext;
+    std::vector<char> tail_row, tail_emit;
     // attention as one pass (tr_set_fused_attention): the contraction that produces the chain's source and the contraction
     // that consumes its result join the group; the pass then stands at the second contraction
     int qk = -1, pv = -1;
@@ -579,21 +583,25 @@ struct FuseGroup {
         std::vector<int> m;
         for (int u : {qk, add, vmax, vexp, vsum, vdiv, pv})
             if (u >= 0) m.push_back(u);
+        m.insert(m.end(), tails.begin(), tails.end());
         return m;
     }
     std::vector<int> reads() const
     {
         std::vector<int> r;
         if (pv >= 0) { r = {q, k}; if (addend >= 0) r.push_back(addend); r.push_back(v); }
-        else { r.push_back(src); if (addend >= 0) r.push_back(addend); }
+        else { r.push_back(src); if (addend >= 0) r.push_back(addend); r.insert(r.end(), ext.begin(), ext.end()); }
         return r;
     }
     std::vector<int> writes() const
     {
         if (pv >= 0) return {pv};
-        std::vector<int> w = {vdiv};
+        std::vector<int> w;
+        if (emit_div) w.push_back(vdiv);
         if (emit_max) w.push_back(vmax);
         if (emit_sum) w.push_back(vsum);
+        for (size_t k = 0; k < tails.size(); k++)
+            if (tail_emit[k]) w.push_back(tails[k]);
         return w;
     }
 };
@@ -672,11 +680,89 @@ static std::vector<FuseGroup> find_fusions(const eg_graph *g)
             if (u >= 0) taken[u] = 1;
         out.push_back(grp);
     }
+    // Tails: element-wise vertices after the division whose operands are the chain's own values (the source as the chain sees
+    // it, the row maximum, the exponentials, the row sum, the quotient), earlier tails, or tensors of the result's shape that
+    // exist before the pass runs.  The pass evaluates them on the spot; the chain's values and the tails that nobody else
+    // reads are then never stored.  Structural conditions only.
+    for (FuseGroup &f : out) {
+        const int p = f.vdiv, tsrc = g->v[f.vexp].in[0];
+        const Vertex &P = g->v[p];
+        const size_t r = P.lz.size();
+        std::vector<int> slot_of(nv, -1), per_row(nv, 0);
+        slot_of[tsrc] = 0; slot_of[f.vmax] = 1; slot_of[f.vexp] = 2; slot_of[f.vsum] = 3; slot_of[p] = 4;
+        per_row[f.vmax] = per_row[f.vsum] = 1;
+        for (int j = p + 1; j < nv && j <= p + 12 && (int)f.tails.size() < kSoftmaxTails; j++) {
+            const Vertex &T = g->v[j];
+            if (T.is_input || taken[j] || !T.agg.empty() || T.n_in < 1 || T.n_in > 2) continue;
+            if (T.n_in == 2 && T.in[0] == T.in[1]) continue;
+            switch (T.otimes) {                      // the scalar functions the element-wise kernel knows
+            case EG_MUL: case EG_ADD: case EG_SUB: case EG_DIV: case EG_SQDIFF: case EG_ABSDIFF: case EG_EXP_SUB: case EG_RELU_GRAD:
+            case EG_SILU_MUL: case EG_IDENT: case EG_SCALE: case EG_RELU: case EG_EXP: case EG_LOG: break;
+            default: continue;
+            }
+            const bool row = is_iota(T.lz, r - 1) && r >= 2;
+            if (!row && !is_iota(T.lz, r)) continue;
+            bool ok = true, inside = false;
+            int sl[2] = {-1, -1};
+            std::vector<int> ext = f.ext;
+            for (int k = 0; k < T.n_in && ok; k++) {
+                const int u = T.in[k];
+                const std::vector<int> &lab = k == 0 ? T.lx : T.ly;
+                if (slot_of[u] >= 0) {
+                    ok = per_row[u] ? is_iota(lab, r - 1) : (!row && is_iota(lab, r));
+                    sl[k] = slot_of[u];
+                    inside = true;
+                } else {
+                    // a tensor of the result's shape that exists when the pass runs: a graph input or an earlier vertex outside the group
+                    ok = !row && is_iota(lab, r) && (g->v[u].is_input || u < p) && g->v[u].bound == P.bound;
+                    for (int m : f.members()) ok = ok && u != m;
+                    if (!ok) break;
+                    size_t e = std::find(ext.begin(), ext.end(), u) - ext.begin();
+                    if (e == ext.size()) ext.push_back(u);
+                    ok = (int)ext.size() <= kSoftmaxExt;
+                    sl[k] = 5 + (int)e;
+                }
+            }
+            if (!ok || !inside) continue;
+            for (size_t l = 0; l < T.lz.size() && ok; l++) ok = T.lbound[l] == P.lbound[l];      // same extents, label by label
+            if (!ok) continue;
+            slot_of[j] = 8 + (int)f.tails.size();
+            per_row[j] = row;
+            f.tails.push_back(j); f.tail_a.push_back(sl[0]); f.tail_b.push_back(sl[1]); f.tail_row.push_back(row); f.tail_emit.push_back(1);
+            f.ext = ext;
+            taken[j] = 1;
+        }
+        if (f.tails.empty()) continue;
+        // alpha * x + y in front once more: with tails that read its sum it may now feed nothing but the group
+        if (f.add < 0 && !g->v[tsrc].is_input && !taken[tsrc]) {
+            const Vertex &T = g->v[tsrc];
+            bool inside = T.n_in == 2 && T.otimes == EG_ADD && T.agg.empty() && !T.is_output && T.in[0] != T.in[1] && is_iota(T.lx, r) && is_iota(T.lz, r);
+            const std::vector<int> mem0 = f.members();
+            for (int c : cons[tsrc]) inside = inside && std::find(mem0.begin(), mem0.end(), c) != mem0.end();
+            for (int e : f.ext) inside = inside && e != T.in[0] && e != T.in[1];
+            if (inside) {
+                f.add = tsrc; f.src = T.in[0]; f.addend = T.in[1];
+                taken[tsrc] = 1;
+            }
+        }
+        // what is still written: whatever somebody outside the group reads, or the caller asked for
+        std::vector<int> mem = f.members();
+        auto wanted = [&](int u) {
+            if (g->v[u].is_output) return true;
+            for (int c : cons[u])
+                if (std::find(mem.begin(), mem.end(), c) == mem.end()) return true;
+            return false;
+        };
+        f.emit_max = wanted(f.vmax);
+        f.emit_sum = wanted(f.vsum);
+        f.emit_div = wanted(p);
+        for (size_t k = 0; k < f.tails.size(); k++) f.tail_emit[k] = wanted(f.tails[k]);
+    }
     if (!g->fuse_attention) return out;
     // Attention (Section 3): scores = a contraction whose result [batch.., s, t] feeds nothing but the chain, and a
     // contraction of the chain's result with V over t.  Structural conditions only, as above.
     for (FuseGroup &f : out) {
-        if (f.emit_max || f.emit_sum) continue;
+        if (f.emit_max || f.emit_sum || !f.tails.empty()) continue;
         const int t1 = f.src, p = f.vdiv;
         if (t1 < 0 || g->v[t1].is_input || taken[t1]) continue;
         const Vertex &T1 = g->v[t1], &P = g->v[p];
@@ -1261,8 +1347,40 @@ static int execute_graph(eg_graph *g, eg_relation *const *inputs, int n_inputs, 
             sp.dt_src = src.dtype; sp.dt_e = E.dtype; sp.dt_p = res.dtype;
             sp.dt_max = g->v[f.vmax].dtype; sp.dt_sum = g->v[f.vsum].dtype;     // the statistics are rounded as their vertices store them, written or not
             if (!sp.has_add) sp.dt_t = src.dtype;
-            sp.src = src.ptr; sp.p = (void *)res.ptr;
+            sp.src = src.ptr; sp.p = f.emit_div ? (void *)res.ptr : nullptr;
+            sp.emit_p = f.emit_div ? 1 : 0;
             sp.n_tuples = P.plan.n_tuples;
+            if (!f.tails.empty()) {
+                // strides, label by label, of the tensors the tails read (entries 0, 1) and write (2 + k); row tensors lack the last label
+                std::vector<std::vector<int64_t>> st(kSoftmaxMore, std::vector<int64_t>(r, 0));
+                sp.n_ext = (int32_t)f.ext.size();
+                sp.n_tail = (int32_t)f.tails.size();
+                for (size_t e = 0; e < f.ext.size(); e++) {
+                    const Operand o = operand_of(f.ext[e]);
+                    sp.ext[e] = o.ptr; sp.dt_ext[e] = o.dtype;
+                    for (int l = 0; l < r; l++) st[e][l] = o.stride[l];
+                }
+                for (size_t k = 0; k < f.tails.size(); k++) {
+                    const Vertex &T = g->v[f.tails[k]];
+                    SoftmaxTail &tl = sp.tail[k];
+                    tl.op = T.otimes; tl.alpha = (float)T.alpha;
+                    tl.a = f.tail_a[k]; tl.b = T.n_in == 2 ? f.tail_b[k] : -1;
+                    tl.row = f.tail_row[k]; tl.dt = T.dtype; tl.emit = f.tail_emit[k];
+                    if (tl.emit) {
+                        const Operand o = operand_of(f.tails[k]);
+                        tl.out = (void *)o.ptr;
+                        for (size_t l = 0; l < o.stride.size() && l < (size_t)r; l++) st[kSoftmaxExt + k][l] = o.stride[l];
+                    }
+                }
+                for (int e = 0; e < kSoftmaxMore; e++) {
+                    sp.more_last[e] = (e >= kSoftmaxExt && e - kSoftmaxExt < sp.n_tail && sp.tail[e - kSoftmaxExt].row) ? 0 : st[e][r - 1];
+                    int k = 0, n = 0;
+                    for (int l : order)
+                        if (li.ext[l] > 1) sp.more_rows[e][k++] = st[e][l];
+                    for (int l = 0; l < r; l++)
+                        if (P.d[l] > 1) sp.more_step[e][n++] = li.ext[l] * st[e][l];
+                }
+            }
             steps.push_back(std::move(s));
             continue;
         }

@@ -156,6 +156,21 @@ struct GenericParams {            // any EinSum: one output element per lane, se
 
 // A softmax over the last label, optionally preceded by alpha * x + y, computed row by row in one pass
 // (the vertices max, exp(x - max), sum and division of Section 3's softmax, fused where the partitioning allows).
+// An element-wise vertex behind a softmax chain that the chain's pass evaluates on the spot (D = L - max, log of the row sum,
+// log-probabilities, the gradient P - Y, ...).  Operands are slots: 0 the chain's source value (after alpha * x + y, as its
+// vertex stores it), 1 the row maximum, 2 the exponential, 3 the row sum, 4 the quotient, 5 / 6 a tensor of the result's
+// shape read from memory, 8 + k the value of tail k (an earlier one).  Slots 1, 3 and row tails hold one value per row.
+constexpr int kSoftmaxTails = 4, kSoftmaxExt = 2, kSoftmaxMore = kSoftmaxTails + kSoftmaxExt;
+struct SoftmaxTail {
+    int32_t op;                   // the vertex's scalar function
+    float alpha;
+    int32_t a, b;                 // operand slots (b = -1: one operand)
+    int32_t row;                  // 1: one value per row (all operands are per-row slots)
+    int32_t dt;                   // the vertex's dtype: values are rounded to it before anything uses them
+    int32_t emit;                 // 1: the tensor is written (somebody outside the pass reads it, or it is an output)
+    void *out;
+};
+
 struct SoftmaxParams {
     TupleSpace ts;                // steps of the source (x), of the added operand (y) and of the result (z)
     TupleSpace ts2;               // steps of the row maxima (x) and of the row sums (y) when those are written
@@ -174,6 +189,15 @@ struct SoftmaxParams {
     int64_t n_tuples, rows_per_block;
     int32_t vec;                  // filled by the launcher: 8 (16-byte accesses along the rows) or 1
     int32_t share_add;            // filled by the launcher: the rows of a workgroup take the same row of the added operand
+    int32_t emit_p;               // 0: the quotient is not stored (only tails read it)
+    // tails, and the addressing of the tensors they bring: entries 0 / 1 the tensors read (slots 5 / 6), 2 + k what tail k writes
+    int32_t n_tail, n_ext;
+    SoftmaxTail tail[kSoftmaxTails];
+    const void *ext[kSoftmaxExt];
+    int32_t dt_ext[kSoftmaxExt];
+    int64_t more_last[kSoftmaxMore];                  // element stride along the last label
+    int64_t more_rows[kSoftmaxMore][kMaxDims];        // ... along the entries of `rows`
+    int64_t more_step[kSoftmaxMore][kMaxLabels];      // ... per block of the entries of `ts`
 };
 
 // Attention as one pass (see k_attention.hip): O[b.., q, :] = softmax_t(alpha * (alpha_qk * Q K^T) + mask) V per batch entry.

@@ -7,6 +7,8 @@
 // tuple of the join: the workgroup index selects (tuple, piece of that tuple's block).
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "eg_device.h"
 
 namespace eg {
@@ -849,12 +851,126 @@ __device__ __forceinline__ void softmax_row_offsets(const SoftmaxParams &p, int6
     }
 }
 
+// Element offsets of the row in the tensors that tails bring (read: entries 0, 1; written by tail k: 2 + k).  One walk over the
+// tuple's and the row's keys for all entries, so that an iteration's stride loads go out together.
+__device__ __forceinline__ void softmax_more_offsets(const SoftmaxParams &p, int64_t t, uint32_t row, int64_t (&o)[kSoftmaxMore])
+{
+#pragma unroll
+    for (int e = 0; e < kSoftmaxMore; e++) o[e] = 0;
+    uint32_t rem = (uint32_t)t;
+    for (int l = p.ts.n - 1; l >= 0; l--) {
+        const uint32_t dd = (uint32_t)p.ts.d[l], q = rem / dd;
+        const int64_t k = rem - q * dd;
+        rem = q;
+#pragma unroll
+        for (int e = 0; e < kSoftmaxMore; e++) o[e] += k * p.more_step[e][l];
+    }
+    uint32_t r = row;
+    for (int i = p.rows.n - 1; i >= 0; i--) {
+        const uint32_t ext = (uint32_t)p.rows.ext[i], q = r / ext;
+        const int64_t k = r - q * ext;
+        r = q;
+#pragma unroll
+        for (int e = 0; e < kSoftmaxMore; e++) o[e] += k * p.more_rows[e][i];
+    }
+}
+
+// A tail's scalar function as its own vertex would evaluate it (hardware exponential and reciprocal where the result is
+// stored as bf16), rounded to the vertex's dtype.
+__device__ __noinline__ float softmax_tail_eval(int op, float alpha, int dt, float a, float b)
+{
+    const float v = dt == EG_BF16 ? otimes_t<-1, true>(op, a, b, alpha) : otimes_t<-1, false>(op, a, b, alpha);
+    return round_as(v, dt);
+}
+
+// The same for the 8 elements of a lane's vector.  One copy of the code for all tails and vectors (a call, not inlined: inlined
+// into every tail of every vector the scalar functions' switch made a kernel of 45 000 instructions that ran four times as long).
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+__device__ __noinline__ f32x8 softmax_tail_eval8(int op, float alpha, int dt, f32x8 a, f32x8 b)
+{
+    f32x8 r;
+    if (dt == EG_BF16) {
+#pragma unroll
+        for (int i = 0; i < 8; i++) r[i] = otimes_t<-1, true>(op, a[i], b[i], alpha);
+#pragma unroll
+        for (int i = 0; i < 8; i += 2) { float x = r[i], y = r[i + 1]; round_pair_bf16(x, y); r[i] = x; r[i + 1] = y; }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; i++) r[i] = otimes_t<-1, false>(op, a[i], b[i], alpha);
+    }
+    return r;
+}
+
+// A pass's tail descriptors in registers: read from the kernel arguments once, all loads issued together (read where they
+// are used, every access was a scalar load of its own with its own wait, some hundred per wave, and the pass took 60 us
+// on rows that the chain alone covers in 15).
+struct SoftmaxTailRegs {
+    int op[kSoftmaxTails], a[kSoftmaxTails], b[kSoftmaxTails], row[kSoftmaxTails], dt[kSoftmaxTails], emit[kSoftmaxTails];
+    float alpha[kSoftmaxTails];
+    void *out[kSoftmaxTails];
+    const void *ext[kSoftmaxExt];
+    int dt_ext[kSoftmaxExt];
+    int n_tail, n_ext;
+};
+__device__ __forceinline__ void softmax_tail_regs(const SoftmaxParams &p, SoftmaxTailRegs &r)
+{
+    r.n_tail = p.n_tail; r.n_ext = p.n_ext;
+#pragma unroll
+    for (int k = 0; k < kSoftmaxTails; k++) {
+        r.op[k] = p.tail[k].op; r.a[k] = p.tail[k].a; r.b[k] = p.tail[k].b; r.row[k] = p.tail[k].row;
+        r.dt[k] = p.tail[k].dt; r.emit[k] = p.tail[k].emit; r.alpha[k] = p.tail[k].alpha; r.out[k] = p.tail[k].out;
+    }
+    // the values are wanted here, in scalar registers: keeps the compiler from moving each load to its first use
+#pragma unroll
+    for (int k = 0; k < kSoftmaxTails; k++) {
+        asm volatile("" : "+s"(r.op[k]), "+s"(r.a[k]), "+s"(r.b[k]), "+s"(r.row[k]), "+s"(r.dt[k]), "+s"(r.emit[k]), "+s"(r.alpha[k]), "+s"(r.out[k]));
+    }
+#pragma unroll
+    for (int e = 0; e < kSoftmaxExt; e++) {
+        r.ext[e] = p.ext[e]; r.dt_ext[e] = p.dt_ext[e];
+        asm volatile("" : "+s"(r.ext[e]), "+s"(r.dt_ext[e]));
+    }
+    asm volatile("" : "+s"(r.n_tail), "+s"(r.n_ext));
+}
+
+// The per-row tails (operands: the row maximum, the row sum, earlier per-row tails), evaluated by every lane alike.
+__device__ __forceinline__ void softmax_row_tails(const SoftmaxTailRegs &td, float m, float sum, float (&rowv)[kSoftmaxTails])
+{
+#pragma unroll
+    for (int k = 0; k < kSoftmaxTails; k++) {
+        rowv[k] = 0.f;
+        if (k < td.n_tail && td.row[k]) {
+            auto slot = [&](int s) {
+                switch (s) {
+                case 1: return m;
+                case 3: return sum;
+                case 8: return rowv[0];
+                case 9: return rowv[1];
+                case 10: return rowv[2];
+                default: return 0.f;
+                }
+            };
+            rowv[k] = softmax_tail_eval(td.op[k], td.alpha[k], td.dt[k], slot(td.a[k]), td.b[k] >= 0 ? slot(td.b[k]) : 0.f);
+        }
+    }
+}
+
+template <int U, int N, class F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (U < N) {
+        f(std::integral_constant<int, U>{});
+        static_for<U + 1, N>(f);
+    }
+}
+
 // One wave per row, VPL vectors of 8 elements per lane held in registers (rows of up to 512 * VPL elements).
 // MODE fixes the storage dtypes of the chain at compile time (0: sum, exponentials and result all bf16; 1: all
 // fp32; 2: read from the parameters): with run-time dtypes every element pays for both variants of each step.
-template <int VPL, int MODE>
+template <int VPL, int MODE, bool TAIL>
 __global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p)
 {
+    static_assert(!TAIL || MODE == 2, "tails come with run-time dtypes");
     const int dt_t = MODE == 0 ? EG_BF16 : MODE == 1 ? EG_F32 : p.dt_t;
     const int dt_e = MODE == 0 ? EG_BF16 : MODE == 1 ? EG_F32 : p.dt_e;
     const int dt_p = MODE == 0 ? EG_BF16 : MODE == 1 ? EG_F32 : p.dt_p;
@@ -876,6 +992,7 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p
         __syncthreads();
     }
     float v[VPL][8];
+    float tsrc[TAIL ? VPL : 1][8];                      // the chain's source values, for tails that read them
     float m = -INFINITY;
 #pragma unroll
     for (int u = 0; u < VPL; u++) {
@@ -898,6 +1015,10 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p
             }
 #pragma unroll
             for (int i = 0; i < 8; i++) m = fmaxf(m, v[u][i]);
+            if (TAIL) {
+#pragma unroll
+                for (int i = 0; i < 8; i++) tsrc[u][i] = v[u][i];
+            }
         }
     }
     m = round_as(wave_reduce<EG_AGG_MAX>(EG_AGG_MAX, m), p.dt_max);       // the exponentials see the maximum as its vertex stores it
@@ -919,19 +1040,76 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p
     }
     sum = round_as(wave_reduce<EG_AGG_SUM>(EG_AGG_SUM, sum), p.dt_sum);   // ... and the division the sum as its vertex stores it
     const float inv = __frcp_rn(sum);
-#pragma unroll
-    for (int u = 0; u < VPL; u++) {
+    float rowv[kSoftmaxTails];
+    int64_t omore[kSoftmaxMore];
+    SoftmaxTailRegs td;
+    if (TAIL) {
+        static_assert(kSoftmaxMore == 6 && kSoftmaxExt == 2, "one statement per entry: the array must stay in registers");
+        softmax_tail_regs(p, td);
+        softmax_row_tails(td, m, sum, rowv);
+        softmax_more_offsets(p, t, row, omore);
+    }
+    // (unrolled by recursion over the vector's index: with the tails inside, the loop form was left rolled, and its arrays went to scratch memory)
+    static_for<0, VPL>([&](auto U) {
+        constexpr int u = decltype(U)::value;
         const int c = (u * 64 + lane) * 8;
         if (c < p.n) {
             float z[8];
 #pragma unroll
             for (int i = 0; i < 8; i++) z[i] = fast_p ? v[u][i] * inv : v[u][i] / sum;
-            store8(p.p, dt_p, oz + c, z);
+            if (!TAIL || p.emit_p) store8(p.p, dt_p, oz + c, z);
+            if (TAIL) {
+                float e0[8], e1[8], tv[kSoftmaxTails][8];
+#pragma unroll
+                for (int i = 0; i < 8; i++) { e0[i] = e1[i] = 0.f; z[i] = round_as(z[i], dt_p); }      // tails see the quotient as its vertex stores it
+                if (td.n_ext > 0) load8(td.ext[0], td.dt_ext[0], omore[0] + c, e0);
+                if (td.n_ext > 1) load8(td.ext[1], td.dt_ext[1], omore[1] + c, e1);
+                // the 8 values of an operand slot
+                auto fetch = [&](int sl, float (&dst)[8]) {
+#define EG_SLOT(EXPR) { _Pragma("unroll") for (int i = 0; i < 8; i++) dst[i] = (EXPR); } break
+                    switch (sl) {
+                    case 0: EG_SLOT(tsrc[TAIL ? u : 0][i]);
+                    case 1: EG_SLOT(m);
+                    case 2: EG_SLOT(v[u][i]);
+                    case 3: EG_SLOT(sum);
+                    case 4: EG_SLOT(z[i]);
+                    case 5: EG_SLOT(e0[i]);
+                    case 6: EG_SLOT(e1[i]);
+                    case 8: EG_SLOT(td.row[0] ? rowv[0] : tv[0][i]);
+                    case 9: EG_SLOT(td.row[1] ? rowv[1] : tv[1][i]);
+                    case 10: EG_SLOT(td.row[2] ? rowv[2] : tv[2][i]);
+                    default: EG_SLOT(0.f);
+                    }
+#undef EG_SLOT
+                };
+#pragma unroll
+                for (int k = 0; k < kSoftmaxTails; k++) {
+#pragma unroll
+                    for (int i = 0; i < 8; i++) tv[k][i] = 0.f;
+                    if (k < td.n_tail && !td.row[k]) {
+                        float a[8], b[8];
+                        fetch(td.a[k], a);
+                        fetch(td.b[k], b);                 // (slot -1: zeros)
+                        f32x8 av, bv;
+#pragma unroll
+                        for (int i = 0; i < 8; i++) { av[i] = a[i]; bv[i] = b[i]; }
+                        const f32x8 rv = softmax_tail_eval8(td.op[k], td.alpha[k], td.dt[k], av, bv);
+#pragma unroll
+                        for (int i = 0; i < 8; i++) tv[k][i] = rv[i];
+                        if (td.emit[k]) store8(td.out[k], td.dt[k], omore[2 + k] + c, tv[k]);
+                    }
+                }
+            }
         }
-    }
+    });
     if (lane == 0) {
         if (p.emit_max) store_elem(p.row_max, p.dt_max, oc, m);
         if (p.emit_sum) store_elem(p.row_sum, p.dt_sum, os, sum);
+        if (TAIL) {
+#pragma unroll
+            for (int k = 0; k < kSoftmaxTails; k++)
+                if (k < td.n_tail && td.row[k] && td.emit[k]) store_elem(td.out[k], td.dt[k], omore[2 + k], rowv[k]);
+        }
     }
 }
 
@@ -975,26 +1153,90 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows_scalar(const SoftmaxP
     }
     sum = round_as(block_reduce(sum, EG_AGG_SUM, red), p.dt_sum);
     const float inv = __frcp_rn(sum);
-    for (int c = threadIdx.x; c < p.n; c += kThreads) store_elem(p.p, p.dt_p, oz + c * p.sz_last, fast_p ? buf[c] * inv : buf[c] / sum);
+    const bool tails = p.n_tail > 0;
+    float rowv[kSoftmaxTails];
+    int64_t omore[kSoftmaxMore];
+    SoftmaxTailRegs td;
+    if (tails) {
+        softmax_tail_regs(p, td);
+        softmax_row_tails(td, m, sum, rowv);
+        softmax_more_offsets(p, t, row, omore);
+    }
+    for (int c = threadIdx.x; c < p.n; c += kThreads) {
+        const float q = fast_p ? buf[c] * inv : buf[c] / sum;
+        if (p.emit_p) store_elem(p.p, p.dt_p, oz + c * p.sz_last, q);
+        if (tails) {
+            float x = load_elem(p.src, p.dt_src, ox + c * p.sx_last);                 // the chain's source value, as in the first sweep
+            if (p.has_add) x = round_as(p.alpha * x + load_elem(p.add, p.dt_add, oy + c * p.sy_last), p.dt_t);
+            const float e0 = td.n_ext > 0 ? load_elem(p.ext[0], p.dt_ext[0], omore[0] + c * p.more_last[0]) : 0.f;
+            const float e1 = td.n_ext > 1 ? load_elem(p.ext[1], p.dt_ext[1], omore[1] + c * p.more_last[1]) : 0.f;
+            const float qz = round_as(q, p.dt_p);
+            float tv[kSoftmaxTails] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int k = 0; k < kSoftmaxTails; k++) {
+                if (k < td.n_tail && !td.row[k]) {
+                    auto slot = [&](int sl) {
+                        switch (sl) {
+                        case 0: return x;
+                        case 1: return m;
+                        case 2: return buf[c];
+                        case 3: return sum;
+                        case 4: return qz;
+                        case 5: return e0;
+                        case 6: return e1;
+                        case 8: return td.row[0] ? rowv[0] : tv[0];
+                        case 9: return td.row[1] ? rowv[1] : tv[1];
+                        case 10: return td.row[2] ? rowv[2] : tv[2];
+                        default: return 0.f;
+                        }
+                    };
+                    tv[k] = softmax_tail_eval(td.op[k], td.alpha[k], td.dt[k], slot(td.a[k]), td.b[k] >= 0 ? slot(td.b[k]) : 0.f);
+                    if (td.emit[k]) store_elem(td.out[k], td.dt[k], omore[2 + k] + c * p.more_last[2 + k], tv[k]);
+                }
+            }
+        }
+    }
     if (threadIdx.x == 0) {
         if (p.emit_max) store_elem(p.row_max, p.dt_max, oc, m);
         if (p.emit_sum) store_elem(p.row_sum, p.dt_sum, os, sum);
+        if (tails) {
+#pragma unroll
+            for (int k = 0; k < kSoftmaxTails; k++)
+                if (k < td.n_tail && td.row[k] && td.emit[k]) store_elem(td.out[k], td.dt[k], omore[2 + k], rowv[k]);
+        }
     }
 }
 
 int launch_softmax_rows(SoftmaxParams &p, void *stream)
 {
-    if (!p.src || !p.p || (p.has_add && !p.add) || (p.emit_max && !p.row_max) || (p.emit_sum && !p.row_sum))
+    if (!p.src || (p.emit_p && !p.p) || (p.has_add && !p.add) || (p.emit_max && !p.row_max) || (p.emit_sum && !p.row_sum))
         return fail(EG_ERR_NULL, "softmax kernel: NULL operand");
+    if (p.n_tail < 0 || p.n_tail > kSoftmaxTails || p.n_ext < 0 || p.n_ext > kSoftmaxExt) return fail(EG_ERR_LIMIT, "softmax kernel: %d tails, %d tensors read by them", p.n_tail, p.n_ext);
+    for (int e = 0; e < p.n_ext; e++)
+        if (!p.ext[e]) return fail(EG_ERR_NULL, "softmax kernel: NULL operand of a tail");
+    for (int k = 0; k < p.n_tail; k++)
+        if (p.tail[k].emit && !p.tail[k].out) return fail(EG_ERR_NULL, "softmax kernel: NULL result of a tail");
     if (p.n < 1 || p.n > kSoftmaxMaxRow) return fail(EG_ERR_LIMIT, "softmax kernel: row length %d", p.n);
     if (p.rows_per_block < 1 || p.n_tuples < 1) return fail(EG_ERR_LIMIT, "softmax kernel: empty index space");
     // 16-byte accesses along the rows need unit stride, whole vectors, and every other offset a multiple of 8 elements
-    bool vec = p.n % 8 == 0 && p.sx_last == 1 && p.sz_last == 1 && (!p.has_add || p.sy_last == 1 || p.sy_last == 0) &&
-               ((uintptr_t)p.src & 15) == 0 && ((uintptr_t)p.p & 15) == 0 && (!p.has_add || ((uintptr_t)p.add & 15) == 0);
+    bool vec = p.n % 8 == 0 && p.sx_last == 1 && (!p.emit_p || p.sz_last == 1) && (!p.has_add || p.sy_last == 1 || p.sy_last == 0) &&
+               ((uintptr_t)p.src & 15) == 0 && (!p.emit_p || ((uintptr_t)p.p & 15) == 0) && (!p.has_add || ((uintptr_t)p.add & 15) == 0);
     for (int i = 0; i < p.rows.n && vec; i++)
-        if (p.rows.sx[i] % 8 || p.rows.sz[i] % 8 || (p.has_add && p.sy_last == 1 && p.rows.sy[i] % 8)) vec = false;
+        if (p.rows.sx[i] % 8 || (p.emit_p && p.rows.sz[i] % 8) || (p.has_add && p.sy_last == 1 && p.rows.sy[i] % 8)) vec = false;
     for (int l = 0; l < p.ts.n && vec; l++)
-        if (p.ts.step_x[l] % 8 || p.ts.step_z[l] % 8 || (p.has_add && p.sy_last == 1 && p.ts.step_y[l] % 8)) vec = false;
+        if (p.ts.step_x[l] % 8 || (p.emit_p && p.ts.step_z[l] % 8) || (p.has_add && p.sy_last == 1 && p.ts.step_y[l] % 8)) vec = false;
+    // the tensors of full rank that tails read or write take 16-byte accesses too, or the whole pass goes element by element
+    for (int e = 0; e < kSoftmaxMore && vec; e++) {
+        const bool used = e < kSoftmaxExt ? e < p.n_ext : (e - kSoftmaxExt < p.n_tail && p.tail[e - kSoftmaxExt].emit && !p.tail[e - kSoftmaxExt].row);
+        if (!used) continue;
+        const void *q = e < kSoftmaxExt ? p.ext[e] : p.tail[e - kSoftmaxExt].out;
+        if (p.more_last[e] != 1 || ((uintptr_t)q & 15)) vec = false;
+        for (int i = 0; i < p.rows.n && vec; i++)
+            if (p.more_rows[e][i] % 8) vec = false;
+        for (int l = 0; l < p.ts.n && vec; l++)
+            if (p.more_step[e][l] % 8) vec = false;
+    }
+    if (p.n_tail > 0 && p.n > 2048) vec = false;      // the register-resident pass carries tails for rows of up to 2048 elements
     p.vec = vec ? 8 : 1;
     // rows of a workgroup are kThreads / 64 consecutive ones; if the innermost row labels that the added operand
     // lacks span a multiple of that many rows, the workgroup's rows share one row of the added operand
@@ -1013,12 +1255,18 @@ int launch_softmax_rows(SoftmaxParams &p, void *stream)
     int rc = tuple_grid(p.rows_per_block, kThreads / 64, p.n_tuples, grid);
     if (rc) return rc;
     const int vpl = (p.n + 511) / 512;
+    if (p.n_tail > 0) {                                // tails: only with run-time dtypes, rows of up to 2048 elements in registers
+        if (vpl <= 1) EG_LAUNCH((k_softmax_rows<1, 2, true>), grid, dim3(kThreads), 0, st, p);
+        else if (vpl <= 2) EG_LAUNCH((k_softmax_rows<2, 2, true>), grid, dim3(kThreads), 0, st, p);
+        else EG_LAUNCH((k_softmax_rows<4, 2, true>), grid, dim3(kThreads), 0, st, p);
+        return check_launch("k_softmax_rows");
+    }
     const bool all_bf16 = p.dt_src == EG_BF16 && p.dt_t == EG_BF16 && p.dt_e == EG_BF16 && p.dt_p == EG_BF16;
     const bool all_f32 = p.dt_src == EG_F32 && p.dt_t == EG_F32 && p.dt_e == EG_F32 && p.dt_p == EG_F32;
     const int mode = all_bf16 ? 0 : all_f32 ? 1 : 2;
-#define EG_SM(V) do { if (mode == 0) EG_LAUNCH((k_softmax_rows<V, 0>), grid, dim3(kThreads), 0, st, p); \
-                      else if (mode == 1) EG_LAUNCH((k_softmax_rows<V, 1>), grid, dim3(kThreads), 0, st, p); \
-                      else EG_LAUNCH((k_softmax_rows<V, 2>), grid, dim3(kThreads), 0, st, p); } while (0)
+#define EG_SM(V) do { if (mode == 0) EG_LAUNCH((k_softmax_rows<V, 0, false>), grid, dim3(kThreads), 0, st, p); \
+                      else if (mode == 1) EG_LAUNCH((k_softmax_rows<V, 1, false>), grid, dim3(kThreads), 0, st, p); \
+                      else EG_LAUNCH((k_softmax_rows<V, 2, false>), grid, dim3(kThreads), 0, st, p); } while (0)
     if (vpl <= 1) EG_SM(1);
     else if (vpl <= 2) EG_SM(2);
     else if (vpl <= 4) EG_SM(4);

@@ -328,3 +328,53 @@ def test_attention_as_one_pass_keeps_no_intermediate_tensor_where_it_applies():
     with pytest.raises(E.EgError):
         E.tr_set_fused_attention(None, True)
 
+
+
+def _xent_graph(fuse=True, outputs=("loss", "dL"), row_cut=1, class_cut=1, late_y=False):
+    """Softmax over c followed by log-probabilities, loss and gradient (config 3's vertices around the loss) on 64 x 512."""
+    g = E.einsum_graph_create()
+    E.tr_set_fusion(g, fuse)
+    vid = {"L": E.einsum_graph_add_input(g, [64, 512], "f32"), "Y0": E.einsum_graph_add_input(g, [64, 512], "bf16")}
+    specs = [("C", "bc->b", "ident", "max", 1.0, ("L",), "f32"),
+             ("E", "bc,b->bc", "exp_sub", "none", 1.0, ("L", "C"), "f32"),
+             ("S", "bc->b", "ident", "sum", 1.0, ("E",), "f32"),
+             ("P", "bc,b->bc", "div", "none", 1.0, ("E", "S"), "f32"),
+             ("D", "bc,b->bc", "sub", "none", 1.0, ("L", "C"), "f32"),
+             ("logS", "b->b", "log", "none", 1.0, ("S",), "f32"),
+             ("logP", "bc,b->bc", "sub", "none", 1.0, ("D", "logS"), "f32"),
+             ("Y", "bc->bc", "scale", "none", 1.0, ("Y0",), "bf16"),
+             ("loss", "bc,bc->", "mul", "sum", -1.0 / 64, ("Y", "logP"), "f32"),
+             ("dL", "bc,bc->bc", "sub", "none", 1.0 / 64, ("P", "Y"), "bf16")]
+    if not late_y:                                  # the labels as a vertex in front of the chain: a tensor the pass can read
+        specs.insert(0, specs.pop(7))
+    for name, spec, ot, op, alpha, ins, dt in specs:
+        vid[name] = E.einsum_graph_add_einsum(g, spec, ot, op, alpha, [vid[i] for i in ins], dt)
+        cut = {"b": row_cut, "c": class_cut if name in ("C", "E", "S", "P") else 1}
+        E.einsum_graph_set_partition(g, vid[name], d_vector(spec, {l: c for l, c in cut.items() if l in spec and c > 1}))
+    for o in outputs:
+        E.einsum_graph_mark_output(g, vid[o])
+    return g, vid
+
+
+def test_tails_of_a_softmax_chain_are_laid_out_only_where_somebody_reads_them():
+    """Which element-wise vertices the softmax pass evaluates itself shows in the workspace size without a GPU: D, log S and
+    the probabilities exist nowhere when only tails read them; the log-probabilities are kept for the loss; a vertex whose
+    operand is produced after the chain, or a chain whose softmax label is cut, runs as before."""
+    def size(**kw):
+        g, _ = _xent_graph(**kw)
+        n = E.tr_workspace_bytes(g)
+        E.einsum_graph_destroy(g)
+        return n
+    full, labels = 64 * 512 * 4, 64 * 512 * 2
+    def about(n, expected):                                                   # (+ the few partial sums the loss is cut into)
+        return expected <= n < expected + 8192
+    assert about(size(), labels + full)                                       # Y (a vertex of its own) and logP, nothing else
+    assert about(size(row_cut=8), labels + full)                              # cuts of the row label are views
+    assert about(size(outputs=("loss", "dL", "logP")), labels)                # an output lives in the caller's relation
+    assert about(size(outputs=("loss", "dL", "P", "D")), labels + full)       # asked for: written to the caller's relations
+    separate = size(fuse=False)
+    assert separate >= labels + 3 * full                                      # E, P (or D) and logP at the least
+    # the labels produced after the division: dL cannot join the pass, so the probabilities are stored for it
+    assert size(late_y=True) >= labels + 2 * full
+    # the softmax label cut: no chain, no tails
+    assert size(class_cut=2) == size(class_cut=2, fuse=False)

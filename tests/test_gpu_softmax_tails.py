@@ -1,0 +1,112 @@
+"""Element-wise vertices behind a softmax chain that the chain's pass evaluates as well (Section 3 writes softmax as row
+maximum, exp(x - maximum), row sum and division; what follows it in a training step, the log-probabilities and the gradient
+of the cross-entropy, are EinSums without aggregated labels over the same rows): D = T - max, log S, log P = D - log S,
+dL = alpha (P - Y), and whatever else reads only the chain's values, earlier such vertices or tensors of the same shape.
+The pass must give what the separate vertices give (same roundings; the row sum's order aside) and what the oracle gives,
+write only what somebody still reads, and fall back to separate launches where a vertex does not qualify."""
+import numpy as np
+import pytest
+
+from tests._parity import rtol_for, violations
+from oracle.graph_ref import make_inputs, run_graph
+
+pytestmark = pytest.mark.gpu
+
+
+def _workload(bound, dtype, stat_dtype, with_add, variant):
+    from synth_inputs.workloads import Vertex, Workload
+    labs = "bhc"[3 - len(bound):]
+    row = labs[:-1]
+    full, rs = f"{labs},{row}->{labs}", f"{labs}->{row}"
+    vs = [Vertex("T", dtype, bound=tuple(bound), recipe={"dist": "normal", "std": 2.0}),
+          Vertex("Y", "bf16", bound=tuple(bound), recipe={"dist": "onehot"} if len(bound) == 2 else {"dist": "ints", "lo": 0, "hi": 1})]
+    src = "T"
+    if with_add:
+        vs.append(Vertex("B", "f32", bound=tuple(bound[-1:]), recipe={"dist": "normal", "std": 0.5}))
+        vs.append(Vertex("T2", dtype, spec=f"{labs},{labs[-1]}->{labs}", otimes="add", oplus="none", alpha=0.5, inputs=("T", "B")))
+        src = "T2"
+    vs += [
+        Vertex("C", stat_dtype, spec=rs, otimes="ident", oplus="max", inputs=(src,)),
+        Vertex("E", dtype, spec=full, otimes="exp_sub", oplus="none", inputs=(src, "C")),
+        Vertex("S", stat_dtype, spec=rs, otimes="ident", oplus="sum", inputs=("E",)),
+        Vertex("P", dtype, spec=full, otimes="div", oplus="none", inputs=("E", "S")),
+        Vertex("D", "f32", spec=full, otimes="sub", oplus="none", inputs=(src, "C")),
+        Vertex("logS", "f32", spec=f"{row}->{row}", otimes="log", oplus="none", inputs=("S",)),
+        Vertex("logP", "f32", spec=full, otimes="sub", oplus="none", inputs=("D", "logS")),
+    ]
+    outs = ["loss", "dL"]
+    if variant == "xent":
+        # the training step's shape: the probabilities and D are read by tails only and must not be stored
+        vs.append(Vertex("loss", "f32", spec=f"{labs},{labs}->", otimes="mul", oplus="sum", alpha=-1.0 / bound[0], inputs=("Y", "logP")))
+        vs.append(Vertex("dL", "bf16", spec=f"{labs},{labs}->{labs}", otimes="sub", oplus="none", alpha=1.0 / bound[0], inputs=("P", "Y")))
+    elif variant == "outputs":
+        # tails and chain values that the caller asks for: everything is written
+        vs.append(Vertex("dL", "bf16", spec=f"{labs},{labs}->{labs}", otimes="sub", oplus="none", alpha=0.25, inputs=("P", "Y")))
+        vs.append(Vertex("loss", "f32", spec=f"{labs},{labs}->", otimes="mul", oplus="sum", inputs=("Y", "logP")))
+        outs = ["loss", "dL", "P", "D", "logS", "logP", "C", "S"]
+    elif variant == "more":
+        # five candidates (the pass takes four), one of them a function of two tails, one with a bf16 result of an exponential
+        vs.append(Vertex("dL", "bf16", spec=f"{labs},{labs}->{labs}", otimes="sub", oplus="none", alpha=1.0, inputs=("P", "Y")))
+        vs.append(Vertex("Pe", "bf16", spec=f"{labs}->{labs}", otimes="exp", oplus="none", inputs=("logP",)))
+        vs.append(Vertex("loss", "f32", spec=f"{labs},{labs}->", otimes="mul", oplus="sum", inputs=("Pe", "dL")))
+        outs = ["loss", "dL", "Pe", "logP"]
+    first = labs[0]
+    parts = {"whole": {}, "rows2": {v.name: ({first: 2} if first in v.spec.split("->")[1] or v.name == "loss" else {}) for v in vs if v.spec}}
+    return Workload("softmax_tails", 91, vs, outs, parts, {})
+
+
+_CASES = [((64, 1024), "f32", "f32", False, "xent"), ((64, 1024), "f32", "f32", False, "outputs"), ((64, 1024), "f32", "f32", False, "more"),
+          ((6, 10, 2048), "bf16", "f32", True, "xent"), ((6, 10, 2048), "bf16", "bf16", True, "outputs"),
+          ((40, 100), "f32", "f32", False, "xent"),            # element by element: rows of 100
+          ((8, 4096), "bf16", "f32", True, "more"),            # rows too long for the register-resident pass with tails
+          ((24, 520), "bf16", "f32", False, "outputs"), ((4, 8), "f32", "f32", True, "xent")]
+
+
+@pytest.mark.parametrize("bound,dtype,stat_dtype,with_add,variant", _CASES)
+def test_tails_of_a_softmax_chain_match_the_oracle_and_the_separate_vertices(bound, dtype, stat_dtype, with_add, variant):
+    import torch
+    import paper_2410_02682_amd as E
+    from paper_2410_02682_amd.runner import GraphRunner, to_device, to_host
+    w = _workload(bound, dtype, stat_dtype, with_add, variant)
+    inp = make_inputs(w)
+    ref = run_graph(w, inp)
+    for pname in ("whole", "rows2"):
+        print(f"softmax tails {bound} {dtype} statistics {stat_dtype} add={with_add} {variant} {pname}", flush=True)
+        res, launches = {}, {}
+        for fuse in (True, False):
+            r = GraphRunner(w, pname)
+            try:
+                E.tr_set_fusion(r.g, fuse)
+                r.bind({k: to_device(t) for k, t in inp.items()})
+                E.tr_profile_enable(r.g, 64)
+                r.run()
+                torch.cuda.synchronize()
+                launches[fuse] = [(r_["vertex"], r_["stage"], r_["kernel"]) for r_ in E.tr_profile_read(r.g)]
+                res[fuse] = {n: to_host(r.output(n)) for n in r.out_names}
+                ws = r.workspace_bytes
+            finally:
+                r.close()
+            if fuse:
+                ws_fused = ws
+            else:
+                assert ws_fused < ws or variant == "outputs", (ws_fused, ws)     # tensors that only the pass reads are never laid out
+        kinds = [k for _, _, k in launches[True]]
+        assert kinds.count("softmax_fused") == 1
+        # the pass takes the place of the chain, of the add in front and of the tails: what is left are the loss (a reduction,
+        # with the aggregation of its pieces where it is cut) and, with five candidates, the one the pass had no room for
+        own = {"xent": 1, "outputs": 1, "more": 2}[variant]
+        left = [v for v, st, k in launches[True] if k != "softmax_fused" and st == "join"]
+        assert len(left) == own, launches[True]
+        for n in w.outputs:
+            rt = rtol_for(w, n)
+            bad, worst = violations(res[True][n].as_f64(), ref[n].as_f64(), rt)
+            assert bad == 0, f"{n} fused: {bad} elements out of tolerance (worst {worst:.2f}x)"
+            a, b = res[True][n].as_f64(), res[False][n].as_f64()
+            if n == "loss":
+                assert abs(a - b) <= 1e-4 * (abs(b) + 1.0), (a, b)
+                continue
+            # the same roundings as the separate vertices; the row sum may differ in its last place, and what depends on it with it
+            ulp = np.abs(b) * 2.0 ** -7 + 2.0 ** -20 if w.vertex(n).dtype == "bf16" else (np.abs(b) + 1.0) * 2.0 ** -19
+            if stat_dtype == "bf16" and n in ("logS", "logP", "Pe", "dL", "P"):
+                ulp = ulp + 2.0 ** -6 * (np.abs(b) + 1.0)     # a row sum that differs by one bf16 unit
+            assert np.all(np.abs(a - b) <= ulp), f"{n}: fused and separate results differ by more than a unit in the last place ({np.abs(a - b).max()})"
