@@ -135,6 +135,21 @@ def ceilings():
     b.record()
     torch.cuda.synchronize()
     out["copy_read_plus_write_gbs"] = 2 * n * 5 / a.elapsed_time(b) / 1e6
+    del src, dst
+    # read-mostly streams with the traffic shape of an aggregation of 2, 8 and 16 partial slabs (256 MiB pieces)
+    piece = 1 << 28
+    src = torch.empty(16 * piece, dtype=torch.uint8, device="cuda")
+    dst = torch.empty(piece, dtype=torch.uint8, device="cuda")
+    for streams in (2, 8, 16):
+        E.eg_ceiling_read(dst.data_ptr(), src.data_ptr(), streams, piece, s)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(5):
+            E.eg_ceiling_read(dst.data_ptr(), src.data_ptr(), streams, piece, s)
+        b.record()
+        torch.cuda.synchronize()
+        out[f"read_{streams}_pieces_write_1_gbs"] = (streams + 1) * piece * 5 / a.elapsed_time(b) / 1e6
     return out
 
 

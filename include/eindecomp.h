@@ -364,6 +364,11 @@ int eg_ceiling_valu_f32(void *sink, int cus, int waves_per_simd, int iters, doub
 /* Enqueues a plain device-to-device copy of `bytes` (multiple of 16; dst/src device, 16-byte aligned). */
 int eg_ceiling_copy(void *dst, const void *src, int64_t bytes, void *hip_stream);
 
+/* Enqueues a read-mostly stream with the traffic shape of an aggregation of partial slabs (Section 4.3's second stage):
+ * `streams` (2, 8 or 16) consecutive pieces of `bytes` each are read from src, combined without arithmetic and written
+ * as one piece of `bytes` to dst (bytes: multiple of 16; dst/src device, 16-byte aligned; src holds streams * bytes). */
+int eg_ceiling_read(void *dst, const void *src, int streams, int64_t bytes, void *hip_stream);
+
 /* Message for the last error on this thread (host, valid until the next failing call on the thread). */
 const char *eg_last_error(void);
 

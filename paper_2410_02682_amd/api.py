@@ -254,3 +254,7 @@ def eg_ceiling_valu_f32(sink_ptr: int, cus: int, waves_per_simd: int, iters: int
 
 def eg_ceiling_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream: int = 0) -> None:
     _check(_lib.load().eg_ceiling_copy(ctypes.c_void_p(dst_ptr), ctypes.c_void_p(src_ptr), nbytes, ctypes.c_void_p(stream)))
+
+
+def eg_ceiling_read(dst_ptr: int, src_ptr: int, streams: int, nbytes: int, stream: int = 0) -> None:
+    _check(_lib.load().eg_ceiling_read(ctypes.c_void_p(dst_ptr), ctypes.c_void_p(src_ptr), streams, nbytes, ctypes.c_void_p(stream)))

@@ -1,5 +1,6 @@
 // Measured ceilings of the box, reported next to the datasheet peaks: a register-resident bf16 MFMA loop
-// (no memory traffic at all) and a plain streaming copy, 16 bytes per lane.  Neither is part of the einsum path.
+// (no memory traffic at all), a plain streaming copy, 16 bytes per lane, and a read-mostly stream (N pieces in, one out).
+// None is part of the einsum path.
 #include <hip/hip_runtime.h>
 
 #include "eg_internal.h"
@@ -89,6 +90,23 @@ __global__ __launch_bounds__(256) void k_copy_ceiling(u32x4 *dst, const u32x4 *s
     if (i < n16) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
+
+// N streams read, one written, 16 bytes per lane and stream: the traffic shape of an aggregation of N partial slabs, without
+// its arithmetic (the vectors are combined with exclusive-or).  What memory gives to a read-mostly kernel.
+template <int N>
+__global__ __launch_bounds__(256) void k_read_ceiling(u32x4 *dst, const u32x4 *src, int64_t n16)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n16) return;
+    u32x4 v[N];
+#pragma unroll
+    for (int k = 0; k < N; k++) v[k] = __builtin_nontemporal_load(src + k * n16 + i);
+    u32x4 r = v[0];
+#pragma unroll
+    for (int k = 1; k < N; k++) r ^= v[k];
+    __builtin_nontemporal_store(r, dst + i);
+}
+
 }  // namespace eg
 
 extern "C" {
@@ -141,6 +159,24 @@ int eg_ceiling_copy(void *dst, const void *src, int64_t bytes, void *hip_stream)
     if (wgs >= (1ll << 31)) return eg::fail(EG_ERR_LIMIT, "eg_ceiling_copy: too large for one launch");
     hipLaunchKernelGGL(eg::k_copy_ceiling, dim3((unsigned)wgs), dim3(256), 0, (hipStream_t)hip_stream, (eg::u32x4 *)dst, (const eg::u32x4 *)src, n16);
     if (hipGetLastError() != hipSuccess) return eg::fail(EG_ERR_HIP, "k_copy_ceiling launch failed");
+    return EG_OK;
+}
+
+
+// Reads `streams` (2, 8 or 16) consecutive pieces of `bytes` each from src and writes one piece of `bytes` to dst
+// (bytes: a multiple of 16; pointers device, 16-byte aligned; src holds streams * bytes).
+int eg_ceiling_read(void *dst, const void *src, int streams, int64_t bytes, void *hip_stream)
+{
+    if (!dst || !src) return eg::fail(EG_ERR_NULL, "eg_ceiling_read: NULL argument");
+    if (bytes < 16 || bytes % 16 || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return eg::fail(EG_ERR_LIMIT, "eg_ceiling_read: size/alignment");
+    const int64_t n16 = bytes / 16, wgs = (n16 + 255) / 256;
+    if (wgs >= (1ll << 31)) return eg::fail(EG_ERR_LIMIT, "eg_ceiling_read: too large for one launch");
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (streams == 2) hipLaunchKernelGGL(eg::k_read_ceiling<2>, dim3((unsigned)wgs), dim3(256), 0, st, (eg::u32x4 *)dst, (const eg::u32x4 *)src, n16);
+    else if (streams == 8) hipLaunchKernelGGL(eg::k_read_ceiling<8>, dim3((unsigned)wgs), dim3(256), 0, st, (eg::u32x4 *)dst, (const eg::u32x4 *)src, n16);
+    else if (streams == 16) hipLaunchKernelGGL(eg::k_read_ceiling<16>, dim3((unsigned)wgs), dim3(256), 0, st, (eg::u32x4 *)dst, (const eg::u32x4 *)src, n16);
+    else return eg::fail(EG_ERR_LIMIT, "eg_ceiling_read: 2, 8 or 16 streams");
+    if (hipGetLastError() != hipSuccess) return eg::fail(EG_ERR_HIP, "k_read_ceiling launch failed");
     return EG_OK;
 }
 
