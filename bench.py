@@ -34,8 +34,8 @@ MEASURED_TRAFFIC = {
     ("c2", "mix", "contract_mfma"): 2189732864,    # 1575 MiB fetched + 513 MiB written per launch (1575-1690 MiB fetched over the pool's boxes)
     ("c2", "mix", "aggregate"): 739217408,         # 512 MiB fetched + 193 MiB written
     ("c3", "batch8", "contract_mfma"): 481092000,  # 212 MiB fetched + 247 MiB written (mean over the step's five contractions)
-    ("c3", "batch8", "map"): 44803018,             # 25 MiB fetched + 17 MiB written
-    ("c3", "batch8", "softmax_fused"): 33701239,   # 16 MiB fetched + 16 MiB written
+    ("c3", "batch8", "map"): 83944448,             # 48 MiB fetched + 32 MiB written (mean over the ReLU and its gradient; the other maps run inside the softmax pass)
+    ("c3", "batch8", "softmax_fused"): 51062784,   # 24.7 MiB fetched (logits and labels) + 24 MiB written (log-probabilities and the gradient dL)
     ("c3", "batch8", "reduce_row"): 25293930,      # 24 MiB fetched
     ("c3", "batch8", "aggregate"): 453230000,      # 384 MiB fetched + 48 MiB written (mean over the step's three aggregations)
     ("c4", "heads8", "contract_mfma"): 1280241700, # 812 MiB fetched + 409 MiB written (mean over the step's nine contractions)
