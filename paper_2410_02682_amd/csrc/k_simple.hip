@@ -1113,6 +1113,131 @@ __global__ __launch_bounds__(kThreads) void k_softmax_rows(const SoftmaxParams p
     }
 }
 
+// The all-bf16 chain (source, sum in front, exponentials and result stored as bf16) with R consecutive rows per wave: the
+// row's offsets are decoded once and advanced by the innermost row label's strides, and the next row's 16-byte loads are
+// issued before the current row is worked on, so a wave always has loads in flight (with one row per wave a wave spent
+// three quarters of its life waiting: for its scalar loads, then for its row, then for its stores).  Same arithmetic, in the
+// same order, as k_softmax_rows<VPL, 0, false>.  The launcher takes it when R divides the innermost row label's extent.
+// ADD: 0 no added operand; 1 its row is shared by the workgroup's rows and staged in LDS; 2 read from memory row by row.
+// (A template parameter: with the choice made at run time the compiler waited, where the paths meet again, for every load
+// in flight, the next row's included.)
+template <int VPL, int R, int ADD>
+__global__ __launch_bounds__(kThreads) void k_softmax_rows_bf16(const SoftmaxParams p)
+{
+    typedef uint32_t raw4 __attribute__((ext_vector_type(4)));
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t t = tuple_of_block();
+    const uint32_t row0 = (pos_of_block() * (kThreads / 64) + wave) * R;
+    if (t >= p.n_tuples || row0 >= (uint32_t)p.rows_per_block) return;         // whole waves leave
+    int64_t ox, oy, oz, oc, os;
+    softmax_row_offsets(p, t, row0, ox, oy, oz, oc, os);
+    const int last = p.rows.n - 1;
+    const int64_t dx = p.rows.sx[last], dy = p.rows.sy[last], dz = p.rows.sz[last], dc = p.stats.sx[last], dsum = p.stats.sy[last];
+    __shared__ uint4 addrow[ADD == 1 ? VPL * 128 : 1];
+    if (ADD == 1) {                                     // one row of the added operand for all rows of the workgroup
+        const int es = p.dt_add == EG_BF16 ? 2 : 4, chunks = p.n * es / 16;
+        const uint4 *g = (const uint4 *)((const char *)p.add + oy * es);
+#pragma unroll
+        for (int j = 0; j < (VPL + 1) / 2; j++) { const int c = j * kThreads + threadIdx.x; if (c < chunks) addrow[c] = g[c]; }
+    }
+    raw4 nxt[VPL];
+#pragma unroll
+    for (int u = 0; u < VPL; u++) {
+        const int c = (u * 64 + lane) * 8;
+        if (c < p.n) nxt[u] = *(const raw4 *)((const uint16_t *)p.src + ox + c);
+    }
+    if (ADD == 1) __syncthreads();
+    // A row's results stay in registers until the next row's data has arrived and go out then, in front of the loads of the
+    // row after: loads and stores share one in-order counter, and stores issued right before the wait for the next row's
+    // data would have to be waited for as well.
+    raw4 held[VPL];
+    float held_m = 0.f, held_sum = 0.f;
+    auto store_row = [&](int j) {
+#pragma unroll
+        for (int u = 0; u < VPL; u++) {
+            const int c = (u * 64 + lane) * 8;
+            if (c < p.n) *(raw4 *)((uint16_t *)p.p + oz + j * dz + c) = held[u];
+        }
+        if (lane == 0) {
+            if (p.emit_max) store_elem(p.row_max, p.dt_max, oc + j * dc, held_m);
+            if (p.emit_sum) store_elem(p.row_sum, p.dt_sum, os + j * dsum, held_sum);
+        }
+    };
+#pragma unroll
+    for (int j = 0; j < R; j++) {
+        // this row's data has arrived (and with it everything older); only then the previous row's stores and the next row's loads
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __builtin_amdgcn_sched_barrier(0);
+        raw4 cur[VPL];
+#pragma unroll
+        for (int u = 0; u < VPL; u++) cur[u] = nxt[u];
+        if (j > 0) store_row(j - 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (j + 1 < R) {
+#pragma unroll
+            for (int u = 0; u < VPL; u++) {
+                const int c = (u * 64 + lane) * 8;
+                if (c < p.n) nxt[u] = *(const raw4 *)((const uint16_t *)p.src + ox + (j + 1) * dx + c);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        float v[VPL][8];
+        float m = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < VPL; u++) {
+            const int c = (u * 64 + lane) * 8;
+            if (c < p.n) {
+                const raw4 r = cur[u];
+                v[u][0] = __uint_as_float(r.x << 16); v[u][1] = __uint_as_float(r.x & 0xffff0000u);
+                v[u][2] = __uint_as_float(r.y << 16); v[u][3] = __uint_as_float(r.y & 0xffff0000u);
+                v[u][4] = __uint_as_float(r.z << 16); v[u][5] = __uint_as_float(r.z & 0xffff0000u);
+                v[u][6] = __uint_as_float(r.w << 16); v[u][7] = __uint_as_float(r.w & 0xffff0000u);
+                if (ADD != 0) {
+                    float y[8];
+                    if (ADD == 1) load8(addrow, p.dt_add, c, y);
+                    else if (p.sy_last == 1) load8(p.add, p.dt_add, oy + j * dy + c, y);
+                    else { const float s = load_elem(p.add, p.dt_add, oy + j * dy);
+#pragma unroll
+                        for (int i = 0; i < 8; i++) y[i] = s; }
+#pragma unroll
+                    for (int i = 0; i < 8; i++) v[u][i] = p.alpha * v[u][i] + y[i];
+#pragma unroll
+                    for (int i = 0; i < 8; i += 2) round_pair_bf16(v[u][i], v[u][i + 1]);
+                }
+#pragma unroll
+                for (int i = 0; i < 8; i++) m = fmaxf(m, v[u][i]);
+            }
+        }
+        m = round_as(wave_reduce<EG_AGG_MAX>(EG_AGG_MAX, m), p.dt_max);
+        const float neg_m_log2e = -(m * kLog2e);
+        float sum = 0.f;
+#pragma unroll
+        for (int u = 0; u < VPL; u++) {
+            if ((u * 64 + lane) * 8 < p.n) {
+#pragma unroll
+                for (int i = 0; i < 8; i++) v[u][i] = exp_sub_scaled(v[u][i], neg_m_log2e);
+#pragma unroll
+                for (int i = 0; i < 8; i += 2) round_pair_bf16(v[u][i], v[u][i + 1]);
+#pragma unroll
+                for (int i = 0; i < 8; i++) sum += v[u][i];
+            }
+        }
+        sum = round_as(wave_reduce<EG_AGG_SUM>(EG_AGG_SUM, sum), p.dt_sum);
+        const float inv = __frcp_rn(sum);
+#pragma unroll
+        for (int u = 0; u < VPL; u++) {
+            raw4 o;
+            o.x = pack_bf16x2(v[u][0] * inv, v[u][1] * inv); o.y = pack_bf16x2(v[u][2] * inv, v[u][3] * inv);
+            o.z = pack_bf16x2(v[u][4] * inv, v[u][5] * inv); o.w = pack_bf16x2(v[u][6] * inv, v[u][7] * inv);
+            held[u] = o;
+        }
+        held_m = m;
+        held_sum = sum;
+    }
+    store_row(R - 1);
+}
+
 // Any strides and alignments: one workgroup per row, the row staged in LDS between the three sweeps.
 constexpr int kSoftmaxMaxRow = 8192;
 
@@ -1243,7 +1368,14 @@ int launch_softmax_rows(SoftmaxParams &p, void *stream)
     constexpr int rpw = kThreads / 64;
     int64_t lacking = 1;
     for (int i = p.rows.n - 1; i >= 0 && p.rows.sy[i] == 0; i--) lacking *= p.rows.ext[i];
-    p.share_add = vec && p.has_add && p.sy_last == 1 && p.rows.n >= 1 && lacking % rpw == 0;
+    // the all-bf16 chain on rows of up to 2048 elements, four rows per wave: when the innermost row label holds whole
+    // groups of four and every workgroup is full
+    constexpr int kRowsPerWave = 4;
+    const bool bf16_chain = p.dt_src == EG_BF16 && p.dt_t == EG_BF16 && p.dt_e == EG_BF16 && p.dt_p == EG_BF16;
+    const bool multi = vec && bf16_chain && p.n_tail == 0 && p.emit_p && p.n <= 2048 && p.rows.n >= 1 &&
+                       p.rows.ext[p.rows.n - 1] % kRowsPerWave == 0 && p.rows_per_block % (rpw * kRowsPerWave) == 0 &&
+                       (!(p.has_add && p.sy_last == 1 && lacking % rpw == 0) || lacking % (rpw * kRowsPerWave) == 0);   // (never at the price of a shared row)
+    p.share_add = vec && p.has_add && p.sy_last == 1 && p.rows.n >= 1 && lacking % (multi ? rpw * kRowsPerWave : rpw) == 0;
     hipStream_t st = (hipStream_t)stream;
     dim3 grid;
     if (!vec) {
@@ -1252,9 +1384,20 @@ int launch_softmax_rows(SoftmaxParams &p, void *stream)
         EG_LAUNCH(k_softmax_rows_scalar, grid, dim3(kThreads), 0, st, p);
         return check_launch("k_softmax_rows_scalar");
     }
-    int rc = tuple_grid(p.rows_per_block, kThreads / 64, p.n_tuples, grid);
+    int rc = tuple_grid(p.rows_per_block, multi ? rpw * kRowsPerWave : rpw, p.n_tuples, grid);
     if (rc) return rc;
     const int vpl = (p.n + 511) / 512;
+    if (multi) {
+        const int add = !p.has_add ? 0 : p.share_add ? 1 : 2;
+#define EG_SMB(V) do { if (add == 0) EG_LAUNCH((k_softmax_rows_bf16<V, kRowsPerWave, 0>), grid, dim3(kThreads), 0, st, p); \
+                       else if (add == 1) EG_LAUNCH((k_softmax_rows_bf16<V, kRowsPerWave, 1>), grid, dim3(kThreads), 0, st, p); \
+                       else EG_LAUNCH((k_softmax_rows_bf16<V, kRowsPerWave, 2>), grid, dim3(kThreads), 0, st, p); } while (0)
+        if (vpl <= 1) EG_SMB(1);
+        else if (vpl <= 2) EG_SMB(2);
+        else EG_SMB(4);
+#undef EG_SMB
+        return check_launch("k_softmax_rows_bf16");
+    }
     if (p.n_tail > 0) {                                // tails: only with run-time dtypes, rows of up to 2048 elements in registers
         if (vpl <= 1) EG_LAUNCH((k_softmax_rows<1, 2, true>), grid, dim3(kThreads), 0, st, p);
         else if (vpl <= 2) EG_LAUNCH((k_softmax_rows<2, 2, true>), grid, dim3(kThreads), 0, st, p);

@@ -552,7 +552,10 @@ _SOFTMAX_CASES = [((6, 40, 2048), "bf16", True, False), ((2, 3, 24, 1024), "bf16
                   # rows of a workgroup share the added row (4, 8 or 16 rows lack its labels)
                   ((4, 2, 16, 512), "bf16", True, False), ((8, 24, 2048), "bf16", True, True),
                   ((4, 8, 4096), "bf16", True, False), ((4, 16, 1024), "f32", True, True),
-                  ((16, 8, 8192), "bf16", True, False)]
+                  ((16, 8, 8192), "bf16", True, False),
+                  # all-bf16 chains with whole groups of four rows per wave: no added operand, a shared row of it, its rows one by one
+                  ((32, 1024), "bf16", False, True), ((16, 4, 32, 1024), "bf16", True, False), ((4, 4, 8, 2048), "bf16", True, True),
+                  ((2, 6, 16, 256), "bf16", True, True)]
 # ... and the bf16 chains with rows of up to 2048 elements once more with row maxima and row sums stored as bf16: the
 # exponentials and the division then see them rounded, written or not
 _SOFTMAX_CASES = [c + ("f32",) for c in _SOFTMAX_CASES] + [c + ("bf16",) for c in _SOFTMAX_CASES if c[1] == "bf16" and c[0][-1] <= 2048]
