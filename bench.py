@@ -156,7 +156,7 @@ def ceilings():
 KERNEL_TEXT = {"contract_mfma": "k_contract_dma / k_contract (block contraction on MFMA, all tuples of a vertex per launch)",
                "aggregate": "k_aggregate_patches (tile-ordered partial slabs) / k_aggregate_vec4 (dense ones)", "map": "k_map", "reduce_row": "k_reduce_row", "generic": "k_generic",
                "contract_alu": "k_contract_alu (contraction-shaped vertex with another scalar function, vector ALU)",
-               "softmax_fused": "k_softmax_rows",
+               "softmax_fused": "k_softmax_rows / k_softmax_rows_bf16 (softmax chain, the sum in front and the element-wise vertices behind it in one pass per row)",
                "attention_fused": "k_attention (scores contraction, softmax chain and weighted sum in one pass; alternative, off by default)"}
 
 
