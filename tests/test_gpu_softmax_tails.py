@@ -110,3 +110,34 @@ def test_tails_of_a_softmax_chain_match_the_oracle_and_the_separate_vertices(bou
             if stat_dtype == "bf16" and n in ("logS", "logP", "Pe", "dL", "P"):
                 ulp = ulp + 2.0 ** -6 * (np.abs(b) + 1.0)     # a row sum that differs by one bf16 unit
             assert np.all(np.abs(a - b) <= ulp), f"{n}: fused and separate results differ by more than a unit in the last place ({np.abs(a - b).max()})"
+
+
+@pytest.mark.parametrize("pad", [8, 3])
+def test_tails_written_into_strided_relations(pad):
+    """The tensors a pass writes for its tails are relations like any other: views with padded rows (a multiple of 8 elements:
+    16-byte accesses; 3: element by element) inside larger tensors whose other elements must stay untouched."""
+    import torch
+    from paper_2410_02682_amd.runner import GraphRunner, to_device, to_host
+    print(f"softmax tails into views with rows padded by {pad}", flush=True)
+    bound = (48, 512)
+    w = _workload(bound, "f32", "f32", False, "outputs")
+    inp = make_inputs(w)
+    ref = run_graph(w, inp)
+    r = GraphRunner(w, "whole")
+    try:
+        big = {n: torch.full((bound[0] + 2, bound[1] + pad), 7.0, dtype=torch.bfloat16 if w.vertex(n).dtype == "bf16" else torch.float32, device="cuda")
+               for n in ("dL", "P", "D", "logP")}
+        views = {n: t[1:1 + bound[0], :bound[1]] for n, t in big.items()}
+        r.bind({k: to_device(t) for k, t in inp.items()}, outputs=views)
+        r.run()
+        torch.cuda.synchronize()
+        for n in w.outputs:
+            got = to_host(r.output(n).contiguous())
+            bad, worst = violations(got.as_f64(), ref[n].as_f64(), rtol_for(w, n))
+            assert bad == 0, f"{n}: {bad} elements out of tolerance (worst {worst:.2f}x)"
+        for n, t in big.items():
+            mask = torch.ones_like(t, dtype=torch.bool)
+            mask[1:1 + bound[0], :bound[1]] = False
+            assert bool((t[mask] == 7.0).all()), n
+    finally:
+        r.close()
