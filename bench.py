@@ -217,6 +217,20 @@ def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None,
     ms_per_step = (t1 - t0) * 1e3 / steps
     flops_per_step = sum(a["flops"] for a in acct.values())
 
+    # A fused softmax pass is recorded at its division; the vertices it absorbed (the chain, a sum in front, element-wise
+    # vertices behind) have no launch of their own.  Its algorithmic bytes: what those vertices read from outside their
+    # set + what of theirs anything outside the set reads (or the caller asked for), each tensor once.  (With the one-pass
+    # attention in the same graph the absorbed sets cannot be told apart this way and the chain alone is credited.)
+    launched = {x["vertex"] for x in rec}
+    fused_pass_bytes = None
+    if any(x["kernel"] == "softmax_fused" for x in rec) and not any(x["kernel"] == "attention_fused" for x in rec):
+        absorbed = {v.name for v in w.einsum_vertices() if r.vid[v.name] not in launched}
+        absorbed |= {a["name"] for vid_, a in acct.items() if any(x["vertex"] == vid_ and x["kernel"] == "softmax_fused" for x in rec)}
+        size = lambda name: prod(w.vertex(name).bound if w.vertex(name).is_input else r.plan(name)["bound_z"]) * esz[w.vertex(name).dtype]
+        reads = {i for v in w.einsum_vertices() if v.name in absorbed for i in v.inputs if i not in absorbed}
+        writes = {n for n in absorbed if n in w.outputs or any(n in v.inputs for v in w.einsum_vertices() if v.name not in absorbed)}
+        fused_pass_bytes = sum(size(n) for n in reads | writes)
+        n_fused_per_step = sum(1 for x in rec if x["kernel"] == "softmax_fused") / steps
     # aggregate the recorded launches by kernel family; bytes as the execution really ran them: a join launch reads its
     # inputs and writes `slabs` fp32 partial slabs (or its tensor), an aggregation reads `slabs` slabs and writes the tensor
     fam = {}
@@ -230,7 +244,7 @@ def measure(config, pname, steps, warmup, fuse_aggregation=False, contract=None,
         if x["stage"] == "aggregate":
             f["bytes"] += x["slabs"] * a["nz"] * 4 + a["nz"] * a["esz"]
         elif key == "softmax_fused":
-            f["bytes"] += a["fused_bytes"]
+            f["bytes"] += fused_pass_bytes / n_fused_per_step if fused_pass_bytes is not None else a["fused_bytes"]
         elif key == "attention_fused":
             # recorded at the second contraction; the first one runs over the same label combinations, so the launch
             # does twice that vertex's operations (no key block is skipped under a causal mask)
