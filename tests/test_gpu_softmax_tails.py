@@ -4,6 +4,9 @@ of the cross-entropy, are EinSums without aggregated labels over the same rows):
 dL = alpha (P - Y), and whatever else reads only the chain's values, earlier such vertices or tensors of the same shape.
 The pass must give what the separate vertices give (same roundings; the row sum's order aside) and what the oracle gives,
 write only what somebody still reads, and fall back to separate launches where a vertex does not qualify."""
+import os
+import random
+
 import numpy as np
 import pytest
 
@@ -141,3 +144,88 @@ def test_tails_written_into_strided_relations(pad):
             assert bool((t[mask] == 7.0).all()), n
     finally:
         r.close()
+
+
+N_RANDOM = int(os.environ.get("EINDECOMP_RANDOM_CHAINS", "60"))     # more chains on request, same generator
+
+
+def _random_chain(seed):
+    """A softmax chain over the last label (rank 2 or 3, rows of 8 to 4096 elements, with or without a scale-and-add in front)
+    followed by one to six element-wise vertices over the chain's values, the labels Y and each other: per-row vertices,
+    full-rank ones with a per-row operand, with two full-rank operands, with one; a random subset of them (and sometimes the
+    probabilities or the row sums) are the outputs."""
+    from synth_inputs.workloads import Vertex, Workload
+    r = random.Random(seed)
+    rank = r.choice([2, 3])
+    n = r.choice([8, 64, 100, 256, 520, 1024, 2048, 2056, 4096])
+    bound = tuple([r.choice([1, 2, 3, 4, 8, 12]) for _ in range(rank - 1)] + [n])
+    labs = "bhc"[3 - rank:]
+    row = labs[:-1]
+    dt = r.choice(["f32", "bf16"])
+    sdt = r.choice(["f32", "f32", "bf16"]) if dt == "bf16" else "f32"
+    vs = [Vertex("T", dt, bound=bound, recipe={"dist": "normal", "std": 1.5}),
+          Vertex("Y", r.choice(["bf16", "f32"]), bound=bound, recipe={"dist": "uniform"})]
+    src = "T"
+    if r.random() < 0.4:
+        vs.append(Vertex("B", "f32", bound=bound[-1:], recipe={"dist": "normal", "std": 0.5}))
+        vs.append(Vertex("T2", dt, spec=f"{labs},{labs[-1]}->{labs}", otimes="add", oplus="none", alpha=0.5, inputs=("T", "B")))
+        src = "T2"
+    full, rs = f"{labs},{row}->{labs}", f"{labs}->{row}"
+    vs += [Vertex("C", sdt, spec=rs, otimes="ident", oplus="max", inputs=(src,)),
+           Vertex("E", dt, spec=full, otimes="exp_sub", oplus="none", inputs=(src, "C")),
+           Vertex("S", sdt, spec=rs, otimes="ident", oplus="sum", inputs=("E",)),
+           Vertex("P", dt, spec=full, otimes="div", oplus="none", inputs=("E", "S"))]
+    elem, rowv, names = [src, "P", "Y"], ["C", "S"], []
+    for k in range(r.randint(1, 6)):
+        name, odt, kind = f"t{k}", r.choice(["f32", "bf16"]), r.random()
+        if kind < 0.2:
+            a = r.choice(rowv)
+            op = "log" if a == "S" else r.choice(["scale", "ident", "relu"])        # (the row sums are positive)
+            vs.append(Vertex(name, "f32", spec=f"{row}->{row}", otimes=op, oplus="none", alpha=0.5, inputs=(a,)))
+            rowv.append(name)
+        elif kind < 0.45:
+            vs.append(Vertex(name, odt, spec=full, otimes=r.choice(["sub", "add", "mul"]), oplus="none", alpha=r.choice([1.0, 0.25]),
+                             inputs=(r.choice(elem), r.choice(rowv))))
+            elem.append(name)
+        elif kind < 0.8:
+            a = r.choice(elem)
+            b = r.choice([e for e in elem if e != a])
+            vs.append(Vertex(name, odt, spec=f"{labs},{labs}->{labs}", otimes=r.choice(["sub", "add", "mul", "sqdiff", "absdiff", "relu_grad"]),
+                             oplus="none", alpha=r.choice([1.0, 0.5]), inputs=(a, b)))
+            elem.append(name)
+        else:
+            vs.append(Vertex(name, odt, spec=f"{labs}->{labs}", otimes=r.choice(["relu", "scale", "ident"]), oplus="none", alpha=0.5, inputs=(r.choice(elem),)))
+            elem.append(name)
+        names.append(name)
+    outs = [nm for nm in names if r.random() < 0.6] or [names[-1]]
+    if r.random() < 0.3:
+        outs.append("P")
+    if r.random() < 0.2:
+        outs.append("S")
+    first = labs[0]
+    parts = {"whole": {}, "rows2": {v.name: ({first: 2} if first in v.spec.split("->")[1] and bound[0] % 2 == 0 else {}) for v in vs if v.spec}}
+    return Workload("random_chain", 1000 + seed, vs, list(dict.fromkeys(outs)), parts, {})
+
+
+@pytest.mark.parametrize("seed", range(N_RANDOM))
+def test_random_chains_with_tails_match_the_oracle(seed):
+    import torch
+    from paper_2410_02682_amd.runner import GraphRunner, to_device, to_host
+    w = _random_chain(seed)
+    print(f"random chain {seed}: " + "; ".join(f"{v.name} {v.dtype} {v.otimes} {v.spec} {v.inputs}" for v in w.vertices if v.spec) + f" -> {w.outputs}", flush=True)
+    inp = make_inputs(w)
+    ref = run_graph(w, inp)
+    for pname in ("whole", "rows2"):
+        r = GraphRunner(w, pname)
+        try:
+            r.bind({k: to_device(t) for k, t in inp.items()})
+            r.run()
+            torch.cuda.synchronize()
+            for n in w.outputs:
+                got, want = to_host(r.output(n)).as_f64(), ref[n].as_f64()
+                fin = np.isfinite(want)
+                assert np.array_equal(np.isfinite(got), fin), f"{n} ({pname}): infinities / NaNs in other places than the oracle's"
+                bad, worst = violations(np.where(fin, got, 0.0), np.where(fin, want, 0.0), rtol_for(w, n))
+                assert bad == 0, f"{n} ({pname}): {bad} elements out of tolerance (worst {worst:.2f}x)"
+        finally:
+            r.close()
