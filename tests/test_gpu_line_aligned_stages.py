@@ -78,3 +78,49 @@ def test_operands_that_are_views_starting_inside_a_line(lead_x, lead_y):
     ref = run_graph(w, {"X": x, "Y": y})["Z"].as_f64()
     bad, worst = violations(to_host(got).as_f64(), ref, RTOL_F32)
     assert bad == 0, f"{bad} elements out of tolerance (worst {worst:.2f}x)"
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_slices_of_the_contracted_label_in_views(seed):
+    """Seeded shapes: the contracted label cut 2, 4 or 8 ways into slices of 512 to 1400 elements (whole 16-byte chunks, any
+    offset inside a line), the four operand layouts, bf16 and fp32, operands that are views starting 0 to 7 chunks into a
+    line of tensors filled with NaN, rows a whole number of lines apart (so that the stages do get laid on lines), under
+    the 256 x 256 tile, the 128 x 128 tile and the library's choice."""
+    import random
+    import torch
+    from paper_2410_02682_amd.runner import GraphRunner, to_device, to_host
+    r = random.Random(seed)
+    dt = r.choice(["bf16", "bf16", "f32"])
+    epc = 8 if dt == "bf16" else 4
+    d = r.choice([2, 4, 8])
+    kper = epc * r.randint(512 // epc, 1400 // epc)
+    K, M, N = d * kper, r.choice([128, 256, 384]), r.choice([128, 256, 320])
+    spec = r.choice(["ij,jk->ik", "ij,kj->ik", "ji,jk->ik", "ji,kj->ik"])
+    bx = (M, K) if spec.startswith("ij") else (K, M)
+    by = (K, N) if ",jk" in spec else (N, K)
+    out_dt = r.choice(["f32", "bf16"]) if dt == "bf16" else "f32"
+    lead_x, lead_y = epc * r.randint(0, 7), epc * r.randint(0, 7)
+    print(f"random slices {seed}: {spec} X{bx} Y{by} {dt}->{out_dt} j cut {d} ways, views start {lead_x} / {lead_y} elements into a line", flush=True)
+    x = HostTensor.from_f32(uniform_pm1(900 + seed, 0, int(np.prod(bx))).reshape(bx), dt)
+    y = HostTensor.from_f32(uniform_pm1(900 + seed, 1, int(np.prod(by))).reshape(by), dt)
+    w = single_vertex(spec, x, y, out_dt, parts={"d": {"j": d}})
+    ref = run_graph(w, {"X": x, "Y": y})["Z"].as_f64()
+    tdt = torch.bfloat16 if dt == "bf16" else torch.float32
+    bigx = torch.full((bx[0], bx[1] + 64 + (-bx[1]) % 64), float("nan"), dtype=tdt, device="cuda")
+    bigy = torch.full((by[0], by[1] + 64 + (-by[1]) % 64), float("nan"), dtype=tdt, device="cuda")
+    vx, vy = bigx[:, lead_x:lead_x + bx[1]], bigy[:, lead_y:lead_y + by[1]]
+    vx.copy_(to_device(x))
+    vy.copy_(to_device(y))
+    for tile in ("256", "128", ""):
+        got = _run(w, {"X": vx, "Y": vy}, tile) if tile else None
+        if got is None:
+            rr = GraphRunner(w, "d")
+            try:
+                rr.bind({"X": vx, "Y": vy})
+                rr.run()
+                torch.cuda.synchronize()
+                got = rr.output("Z").clone()
+            finally:
+                rr.close()
+        bad, worst = violations(to_host(got).as_f64(), ref, RTOL_BF16 if out_dt == "bf16" else RTOL_F32)
+        assert bad == 0, f"tile {tile or 'default'}: {bad} elements out of tolerance (worst {worst:.2f}x)"
