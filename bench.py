@@ -364,7 +364,7 @@ def main():
         # the other full-size workloads, a few steps each, so that their kernel families are measured in the same run
         others = {}
         for c, alt in ((3, False), (4, False), (5, False), (4, True)):
-            ms, ks, fl, d, dv, _, (_, gms) = measure(c, DEFAULT_PART[c], 5, 2, fuse_attention=alt)
+            ms, ks, fl, d, dv, _, (_, gms) = measure(c, DEFAULT_PART[c], 12 if c == 3 else 5, 3 if c == 3 else 2, fuse_attention=alt)   # (config 3's step is a millisecond)
             del dv
             torch.cuda.empty_cache()
             others[f"c{c}" + ("_attention_as_one_pass" if alt else "")] = {"workload": d, "ms_per_step": ms, "hip_graph_replay_ms_per_step": gms, "contraction_tflops_per_step": fl / (ms * 1e-3) / 1e12,
