@@ -599,7 +599,7 @@ def test_fused_softmax_matches_oracle_and_the_separate_vertices(bound, dtype, wi
 
 
 # ------------------------------------------------------------------ the whole step inside a HIP graph
-@pytest.mark.parametrize("n,pname", [(3, "mixed"), (4, "heads8"), (5, "k16")])
+@pytest.mark.parametrize("n,pname", [(3, "mixed"), (3, "batch8"), (4, "heads8"), (5, "k16")])
 def test_execute_can_be_captured_into_a_hip_graph_and_replayed(n, pname):
     # tr_execute only enqueues kernels on the caller's stream (no allocation, no synchronisation, no memset), so a
     # caller may capture it; every replay, with the program's own eager work in between, must give the eager result
